@@ -1,0 +1,215 @@
+"""ctypes front for the CPU oracle (oracle/brq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: nothing in the product package imports this module.  Only
+tests, the smoke entry and the benchmark's cpu_baseline leg use it.  It carries no
+arithmetic of its own: every function marshals numpy arrays into the C routines.
+
+bf16 tensors are numpy uint16 arrays holding the bit patterns; fp32 tensors are float32.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "brq_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_brq.so")
+
+F32, BF16 = 0, 1
+
+
+def build(force=False):
+    """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+
+def _bind(path):
+    L = ctypes.CDLL(path)
+    i64, vp, i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    L.oracle_set_threads.argtypes = [i32]
+    L.oracle_get_threads.restype = i32
+    L.oracle_bf16_to_f32.argtypes = [ctypes.c_uint16]
+    L.oracle_bf16_to_f32.restype = ctypes.c_float
+    L.oracle_bf16_to_f32_array.argtypes = [vp, i64, vp]
+    L.oracle_f32_to_bf16.argtypes = [ctypes.c_float]
+    L.oracle_f32_to_bf16.restype = ctypes.c_uint16
+    L.oracle_hadamard_entry.argtypes = [i32, i32, i32]
+    L.oracle_hadamard_entry.restype = i32
+    L.oracle_hadamard_sylvester.argtypes = [i32, vp]
+    L.oracle_rotate_dense_f64.argtypes = [vp, i64, i64, i64, vp]
+    L.oracle_rotation_norm.argtypes = [i64]
+    L.oracle_rotation_norm.restype = ctypes.c_float
+    L.oracle_block_rotate.argtypes = [vp, i32, i64, i64, i64, i64, vp, i32, i64]
+    L.oracle_e2m1_value.argtypes = [i32]
+    L.oracle_e2m1_value.restype = ctypes.c_double
+    L.oracle_e8m0_from_amax.argtypes = [ctypes.c_float]
+    L.oracle_e8m0_from_amax.restype = ctypes.c_uint8
+    L.oracle_e8m0_value.argtypes = [ctypes.c_uint8]
+    L.oracle_e8m0_value.restype = ctypes.c_double
+    L.oracle_e2m1_encode.argtypes = [ctypes.c_float, ctypes.c_uint8]
+    L.oracle_e2m1_encode.restype = ctypes.c_uint8
+    L.oracle_mxfp4_quantize.argtypes = [vp, i32, i64, i64, i64, vp, vp]
+    L.oracle_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp]
+    L.oracle_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, vp]
+    L.oracle_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp]
+    L.oracle_matmul_nt_f64.argtypes = [vp, vp, i64, i64, i64, vp]
+    return L
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError("oracle %s: bad arguments (rc=%d)" % (what, rc))
+
+
+def _dt(a):
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError("oracle takes float32, or uint16 holding bf16 bits; got %s" % a.dtype)
+
+
+def _rows(a):
+    """2-D array with contiguous rows -> (array, M, K, row pitch in elements)."""
+    if a.ndim != 2 or a.strides[1] != a.itemsize or a.strides[0] % a.itemsize:
+        raise ValueError("need a 2-D array with contiguous rows")
+    return a, a.shape[0], a.shape[1], a.strides[0] // a.itemsize
+
+
+class Oracle:
+    """One loaded build of the oracle library.  The default build is `oracle.default()`;
+    tests that plant a mistake in a copy of the C source load that copy through this class."""
+
+    def __init__(self, path):
+        self.L = _bind(path)
+
+    def set_threads(self, n):
+        self.L.oracle_set_threads(int(n))
+
+    def get_threads(self):
+        return int(self.L.oracle_get_threads())
+
+    def bf16_to_f32(self, bits):
+        """uint16 bf16 bit patterns -> float32 (exact widening, done by the C routine)."""
+        b = np.ascontiguousarray(bits, dtype=np.uint16)
+        out = np.empty(b.shape, dtype=np.float32)
+        self.L.oracle_bf16_to_f32_array(_p(b), b.size, _p(out))
+        return out
+
+    def f32_to_bf16(self, f):
+        return int(self.L.oracle_f32_to_bf16(float(np.float32(f))))
+
+    def hadamard_sylvester(self, B):
+        out = np.zeros((B, B), dtype=np.int32)
+        _check(self.L.oracle_hadamard_sylvester(B, _p(out)), "hadamard_sylvester")
+        return out
+
+    def hadamard_entry(self, B, i, j):
+        return int(self.L.oracle_hadamard_entry(B, i, j))
+
+    def rotate_dense_f64(self, x, B):
+        x = np.ascontiguousarray(x, dtype=np.float64)
+        y = np.empty_like(x)
+        _check(self.L.oracle_rotate_dense_f64(_p(x), x.shape[0], x.shape[1], B, _p(y)), "rotate_dense_f64")
+        return y
+
+    def rotation_norm(self, B):
+        return np.float32(self.L.oracle_rotation_norm(B))
+
+    def block_rotate(self, x, B, out_bf16=False):
+        x, M, K, ldx = _rows(x)
+        y = np.empty((M, K), dtype=np.uint16 if out_bf16 else np.float32)
+        _check(self.L.oracle_block_rotate(_p(x), _dt(x), M, K, ldx, B, _p(y), BF16 if out_bf16 else F32, K),
+               "block_rotate")
+        return y
+
+    def e2m1_value(self, code):
+        return float(self.L.oracle_e2m1_value(int(code)))
+
+    def e8m0_from_amax(self, amax):
+        return int(self.L.oracle_e8m0_from_amax(float(np.float32(amax))))
+
+    def e8m0_value(self, byte):
+        return float(self.L.oracle_e8m0_value(int(byte)))
+
+    def e2m1_encode(self, y, scale_byte):
+        return int(self.L.oracle_e2m1_encode(float(np.float32(y)), int(scale_byte)))
+
+    def mxfp4_quantize(self, x):
+        x, M, K, ldx = _rows(x)
+        codes = np.empty((M, K // 2), dtype=np.uint8)
+        scales = np.empty((M, K // 32), dtype=np.uint8)
+        _check(self.L.oracle_mxfp4_quantize(_p(x), _dt(x), M, K, ldx, _p(codes), _p(scales)), "mxfp4_quantize")
+        return codes, scales
+
+    def rotate_quantize_fused(self, x, B):
+        x, M, K, ldx = _rows(x)
+        codes = np.empty((M, K // 2), dtype=np.uint8)
+        scales = np.empty((M, K // 32), dtype=np.uint8)
+        _check(self.L.oracle_rotate_quantize_fused(_p(x), _dt(x), M, K, ldx, B, _p(codes), _p(scales)),
+               "rotate_quantize_fused")
+        return codes, scales
+
+    def mxfp4_dequantize(self, codes, scales):
+        codes = np.ascontiguousarray(codes, dtype=np.uint8)
+        scales = np.ascontiguousarray(scales, dtype=np.uint8)
+        M, K = codes.shape[0], codes.shape[1] * 2
+        out = np.empty((M, K), dtype=np.float64)
+        _check(self.L.oracle_mxfp4_dequantize(_p(codes), _p(scales), M, K, _p(out)), "mxfp4_dequantize")
+        return out
+
+    def mxfp4_gemm(self, aq, as_, wq, ws, rows=None, want_bound=True):
+        """fp64 product of the dequantized operands; returns (y, bound) for the chosen rows."""
+        aq = np.ascontiguousarray(aq, dtype=np.uint8)
+        as_ = np.ascontiguousarray(as_, dtype=np.uint8)
+        wq = np.ascontiguousarray(wq, dtype=np.uint8)
+        ws = np.ascontiguousarray(ws, dtype=np.uint8)
+        M, K = aq.shape[0], aq.shape[1] * 2
+        N = wq.shape[0]
+        if wq.shape[1] * 2 != K or as_.shape != (M, K // 32) or ws.shape != (N, K // 32):
+            raise ValueError("operand shapes disagree")
+        if rows is None:
+            rp, nrows = None, M
+        else:
+            rows = np.ascontiguousarray(rows, dtype=np.int64)
+            rp, nrows = _p(rows), rows.size
+        y = np.empty((nrows, N), dtype=np.float64)
+        bound = np.empty((nrows, N), dtype=np.float64) if want_bound else None
+        _check(self.L.oracle_mxfp4_gemm(_p(aq), _p(as_), _p(wq), _p(ws), M, N, K, rp, nrows, _p(y),
+                                        _p(bound) if want_bound else None), "mxfp4_gemm")
+        return y, bound
+
+    def matmul_nt_f64(self, a, w):
+        a = np.ascontiguousarray(a, dtype=np.float64)
+        w = np.ascontiguousarray(w, dtype=np.float64)
+        y = np.empty((a.shape[0], w.shape[0]), dtype=np.float64)
+        _check(self.L.oracle_matmul_nt_f64(_p(a), _p(w), a.shape[0], w.shape[0], a.shape[1], _p(y)), "matmul_nt")
+        return y
+
+
+_default = None
+
+
+def default():
+    """The oracle built from oracle/brq_oracle.c as committed."""
+    global _default
+    if _default is None:
+        _default = Oracle(build())
+    return _default
+
+
+def __getattr__(name):
+    # module-level shorthand: oracle.mxfp4_quantize(x) == oracle.default().mxfp4_quantize(x)
+    if name.startswith("_"):
+        raise AttributeError(name)
+    return getattr(default(), name)

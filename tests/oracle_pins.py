@@ -1,0 +1,352 @@
+"""Pins for the CPU oracle: checks against what the paper and the mathematics fix.
+
+Each pin is a plain function taking an `oracle.Oracle` build, so that the same pins run
+against the committed oracle (test_oracle_pins.py) and against copies of its source with
+a mistake planted in them (test_oracle_mutants.py, where at least one pin must fail).
+
+Nothing here re-types the oracle's own formulas: expected values are hand-worked text
+fixtures (tests/golden/), library routines the oracle does not call (scipy's Hadamard,
+numpy matmul, Python's float.hex / math.frexp on literals), closed forms and invariants.
+"""
+import math
+import os
+
+import numpy as np
+import scipy.linalg
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+E2M1_MAGS = None  # filled from the golden file
+
+
+def _golden_rows(name):
+    rows = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append(line.split())
+    return rows
+
+
+def golden_e2m1():
+    return {int(r[0]): float(r[1]) for r in _golden_rows("e2m1_values.txt")}
+
+
+def _f32bits(x):
+    return int(np.float32(x).view(np.uint32))
+
+
+def _group(x0, n=32):
+    g = np.zeros((1, n), dtype=np.float32)
+    g[0, 0] = x0
+    return g
+
+
+def _unpack(codes):
+    """[M, K/2] packed bytes -> [M, K] 4-bit codes, even element in the low nibble."""
+    out = np.empty((codes.shape[0], codes.shape[1] * 2), dtype=np.uint8)
+    out[:, 0::2] = codes & 0xF
+    out[:, 1::2] = codes >> 4
+    return out
+
+
+# --------------------------------------------------------------------------- Hadamard
+
+def pin_hadamard_matches_scipy_and_is_orthogonal(o):
+    for B in (1, 2, 4, 8, 32, 64, 128):
+        H = o.hadamard_sylvester(B).astype(np.int64)
+        assert np.array_equal(H, scipy.linalg.hadamard(B).astype(np.int64))  # Sylvester construction
+        assert np.array_equal(H @ H.T, B * np.eye(B, dtype=np.int64))        # R^T R = I after 1/sqrt(B)
+        assert np.array_equal(H, H.T)
+        for i in range(0, B, max(1, B // 8)):
+            for j in range(B):
+                assert o.hadamard_entry(B, i, j) == H[i, j]
+
+
+def pin_norm_constant_bits(o):
+    # 1/sqrt(B) rounded to fp32: sqrt(2)/2 = 0x3F3504F3, scaled by exact powers of two.
+    want = {2: 0x3F3504F3, 4: 0x3F000000, 8: 0x3EB504F3, 16: 0x3E800000, 32: 0x3E3504F3,
+            64: 0x3E000000, 128: 0x3DB504F3, 8192: 0x3C3504F3}
+    for B, bits in want.items():
+        assert _f32bits(o.rotation_norm(B)) == bits, B
+
+
+def pin_butterfly_exact_on_small_integers(o):
+    # small integers: every partial sum fits 24 bits, so fp32 is exact and the result
+    # must equal the integer matrix product (scipy's H) times fl32(1/sqrt(B)).
+    rng = np.random.default_rng(5)
+    for B in (32, 64, 128, 1024):
+        x = rng.integers(-64, 65, size=(3, 2 * B)).astype(np.float32)
+        y = o.block_rotate(x, B)
+        H = scipy.linalg.hadamard(B).astype(np.int64)
+        want = np.concatenate([x[:, :B].astype(np.int64) @ H, x[:, B:].astype(np.int64) @ H], axis=1)
+        c = np.float32(1.0 / math.sqrt(B))
+        assert np.array_equal(y, want.astype(np.float32) * c), B
+
+
+def pin_butterfly_stage_order(o):
+    # Hand-worked, B = 4 (norm 0.5, exact).  x = [2^24, 1, 1, 1].
+    # ascending stages: h=1 -> [2^24 (tie of 2^24+1 to even), 2^24-1, 2, 0]
+    #                   h=2 -> [2^24+2, 2^24-1, 2^24-2, 2^24-1]
+    # (a descending order would swap the values in positions 1 and 2).
+    x = np.array([[16777216.0, 1.0, 1.0, 1.0]], dtype=np.float32)
+    y = o.block_rotate(x, 4)
+    assert y.tolist() == [[8388609.0, 8388607.5, 8388607.0, 8388607.5]]
+    # B = 2: [a, b] -> [(a+b), (a-b)] / sqrt(2); sign convention of the second output.
+    y2 = o.block_rotate(np.array([[3.0, 1.0]], dtype=np.float32), 2)
+    c = np.float32(1.0 / math.sqrt(2))
+    assert y2.tolist() == [[float(np.float32(4.0) * c), float(np.float32(2.0) * c)]]
+
+
+def pin_one_hot_spreads_over_its_block_only(o):
+    # Sec. 4.3: an outlier is redistributed over its own block, nothing leaks outside.
+    B, K = 32, 128
+    cB = np.float32(1.0 / math.sqrt(B))
+    H = scipy.linalg.hadamard(B)
+    for j in (0, 1, 7, 31):
+        x = np.zeros((1, K), dtype=np.float32)
+        x[0, B + j] = 20.0
+        y = o.block_rotate(x, B)
+        assert np.array_equal(y[0, B:2 * B], (np.float32(20.0) * H[j]).astype(np.float32) * cB)
+        assert not y[0, :B].any() and not y[0, 2 * B:].any()
+
+
+def pin_rotation_invariants(o):
+    rng = np.random.default_rng(6)
+    for B in (32, 64, 256):
+        x = rng.standard_normal((4, 2 * B)).astype(np.float32)
+        y = o.block_rotate(x, B)
+        # Sec. 4.2: rotation leaves the L2 norm unchanged (per block)
+        for b in range(2):
+            nx = np.linalg.norm(x[:, b * B:(b + 1) * B].astype(np.float64), axis=1)
+            ny = np.linalg.norm(y[:, b * B:(b + 1) * B].astype(np.float64), axis=1)
+            assert np.allclose(nx, ny, rtol=1e-6)
+        # H/sqrt(B) is symmetric and orthogonal, hence an involution
+        assert np.allclose(o.block_rotate(y, B), x, atol=1e-5)
+        # block independence (Eq. 1): changing block 1 leaves block 0 bit-identical
+        x2 = x.copy()
+        x2[:, B:] += 1.0
+        y2 = o.block_rotate(x2, B)
+        assert np.array_equal(y2[:, :B], y[:, :B]) and not np.array_equal(y2[:, B:], y[:, B:])
+        # fp32 butterfly vs the fp64 definition: (log2 B + 1) half-ulps of c*sum|x|
+        yd = o.rotate_dense_f64(x.astype(np.float64), B)
+        H = scipy.linalg.hadamard(B).astype(np.float64) / math.sqrt(B)
+        assert np.allclose(yd[:, :B], x[:, :B].astype(np.float64) @ H, rtol=0, atol=1e-12)
+        assert np.allclose(yd[:, B:], x[:, B:].astype(np.float64) @ H, rtol=0, atol=1e-12)
+        for b in range(2):
+            s = np.abs(x[:, b * B:(b + 1) * B]).astype(np.float64).sum(axis=1, keepdims=True)
+            bound = (math.log2(B) + 1) * 2.0 ** -24 * s / math.sqrt(B) * 1.0001
+            assert (np.abs(y[:, b * B:(b + 1) * B] - yd[:, b * B:(b + 1) * B]) <= bound).all()
+
+
+def pin_bf16_conversions(o):
+    # widening is exact; narrowing is RNE (hand-worked bit patterns)
+    assert o.bf16_to_f32(np.array([0x3F80, 0xC000, 0x0001, 0x7F7F], dtype=np.uint16)).view(np.uint32).tolist() == \
+        [0x3F800000, 0xC0000000, 0x00010000, 0x7F7F0000]
+    assert o.f32_to_bf16(1.0) == 0x3F80
+    assert o.f32_to_bf16(np.uint32(0x3F808000).view(np.float32)) == 0x3F80   # tie -> even (down)
+    assert o.f32_to_bf16(np.uint32(0x3F808001).view(np.float32)) == 0x3F81   # just above the tie
+    assert o.f32_to_bf16(np.uint32(0x3F818000).view(np.float32)) == 0x3F82   # tie -> even (up)
+    assert o.f32_to_bf16(np.uint32(0xBF817FFF).view(np.float32)) == 0xBF81   # just below the tie
+    x = np.array([[1.0, 1.0]], dtype=np.float32)
+    # bf16 output of block_rotate is RNE of the fp32 value: 2/sqrt(2) = 1.41421354 -> 0x3FB5
+    assert o.block_rotate(x, 2, out_bf16=True).tolist() == [[0x3FB5, 0x0000]]
+    # bf16 input is widened, not reinterpreted
+    xb = np.array([[0x3F80, 0x3F80]], dtype=np.uint16)
+    assert np.array_equal(o.block_rotate(xb, 2), o.block_rotate(x, 2))
+
+
+# --------------------------------------------------------------------------- E2M1 / E8M0
+
+def pin_e2m1_table(o):
+    g = golden_e2m1()
+    assert len(g) == 16
+    for code, val in g.items():
+        got = o.e2m1_value(code)
+        assert got == val and math.copysign(1.0, got) == math.copysign(1.0, val), code
+    # encode(decode(c)) = c at scale 2^0 (code 8, "-0", is never produced: it maps to 0)
+    for code, val in g.items():
+        assert o.e2m1_encode(val, 127) == (0 if code == 8 else code)
+
+
+def pin_thresholds_and_ties(o):
+    for r, code in _golden_rows("threshold_cases.txt"):
+        r, code = float(r), int(code)
+        assert o.e2m1_encode(r, 127) == code, r
+        assert o.e2m1_encode(-r, 127) == (code | 8 if code else 0), r
+    # one fp32 step either side of each midpoint
+    mids = [(0.25, 0, 1), (0.75, 1, 2), (1.25, 2, 3), (1.75, 3, 4), (2.5, 4, 5), (3.5, 5, 6), (5.0, 6, 7)]
+    for m, lo, hi in mids:
+        dn = np.nextafter(np.float32(m), np.float32(0))
+        up = np.nextafter(np.float32(m), np.float32(10))
+        assert o.e2m1_encode(dn, 127) == lo and o.e2m1_encode(up, 127) == hi, m
+    # the same decisions under another scale: r = y / 2^e
+    for sb in (100, 120, 130, 200):
+        s = 2.0 ** (sb - 127)
+        for r, code in _golden_rows("threshold_cases.txt"):
+            assert o.e2m1_encode(float(r) * s, sb) == int(code), (r, sb)
+
+
+def pin_scale_rule(o):
+    g = golden_e2m1()
+    for x, sb, code, deq in _golden_rows("rne_cases.txt"):
+        x, sb, code, deq = float(x), int(sb), int(code), float(deq)
+        codes, scales = o.mxfp4_quantize(_group(x))
+        assert scales.shape == (1, 1) and codes.shape == (1, 16)
+        assert int(scales[0, 0]) == sb, x
+        assert int(codes[0, 0]) == code, x          # element 0 in the LOW nibble, element 1 = 0
+        assert not codes[0, 1:].any()
+        assert g[code] * 2.0 ** (sb - 127) == deq
+        assert o.e8m0_from_amax(abs(x)) == sb
+    # the maximum is taken over all 32 positions of the group, and over magnitudes
+    for pos in (0, 1, 15, 16, 30, 31):
+        for val in (7.0, -7.0):
+            gq = np.full((1, 32), 0.3, dtype=np.float32)
+            gq[0, pos] = val
+            cq, sq = o.mxfp4_quantize(gq)
+            assert int(sq[0, 0]) == 127
+            u = _unpack(cq)[0]
+            assert int(u[pos]) == (7 if val > 0 else 15) and (np.delete(u, pos) == 1).all()
+    # E8M0 byte b means 2^(b-127)
+    assert o.e8m0_value(127) == 1.0 and o.e8m0_value(0) == 2.0 ** -127 and o.e8m0_value(254) == 2.0 ** 127
+    # closed form on the fp32 exponent field: byte = max(field - 2, 0); never 0xFF
+    for bits in (0x00000000, 0x00000001, 0x007FFFFF, 0x00800000, 0x01000000, 0x01800000, 0x3F800000,
+                 0x3FFFFFFF, 0x40000000, 0x7F7FFFFF):
+        a = np.uint32(bits).view(np.float32)
+        assert o.e8m0_from_amax(a) == max((bits >> 23) - 2, 0), hex(bits)
+    # amax / 2^e lies in [4, 8) whenever the byte is not clamped; scale monotone in amax
+    rng = np.random.default_rng(7)
+    a = np.sort(np.abs(rng.standard_normal(200)).astype(np.float32) * np.float32(1e3) + np.float32(1e-3))
+    b = [o.e8m0_from_amax(v) for v in a]
+    assert all(b[i] <= b[i + 1] for i in range(len(b) - 1))
+    for v, sb in zip(a, b):
+        r = math.ldexp(float(v), 127 - sb)
+        assert 4.0 <= r < 8.0
+
+
+def pin_group_structure(o):
+    # groups are 32 consecutive elements of a row; nibble order; row-major scales
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((3, 96)).astype(np.float32)
+    codes, scales = o.mxfp4_quantize(x)
+    assert codes.shape == (3, 48) and scales.shape == (3, 3) and codes.dtype == np.uint8
+    x2 = x.copy()
+    x2[1, 40] = 1000.0   # group 1 of row 1 only
+    c2, s2 = o.mxfp4_quantize(x2)
+    diff_s = np.argwhere(s2 != scales)
+    assert diff_s.tolist() == [[1, 1]]
+    assert np.array_equal(np.unique(np.argwhere(c2 != codes)[:, 0]), [1])
+    assert set(np.argwhere(c2 != codes)[:, 1] // 16) == {1}
+    assert (c2[1, 20] & 0xF) == 6 or (c2[1, 20] & 0xF) == 7      # element 40 -> byte 20, low nibble
+    # scaling a whole group by 2^k shifts the byte by k and leaves the codes unchanged
+    c3, s3 = o.mxfp4_quantize(x * np.float32(2.0 ** 7))
+    assert np.array_equal(c3, codes) and np.array_equal(s3.astype(int), scales.astype(int) + 7)
+    # an all-zero group, and negative values too small to survive, give code 0 (no "-0")
+    z = np.zeros((1, 32), dtype=np.float32)
+    z[0, 5] = -0.0
+    cz, sz = o.mxfp4_quantize(z)
+    assert not cz.any() and int(sz[0, 0]) == 0
+    t = _group(4.0)
+    t[0, 1] = -0.2   # r = -0.2 -> magnitude code 0 -> nibble 0, not 8
+    ct, _ = o.mxfp4_quantize(t)
+    assert int(ct[0, 0]) == 0x06
+
+
+def pin_round_trip_of_representable_blocks(o):
+    g = golden_e2m1()
+    rng = np.random.default_rng(9)
+    for sb in (3, 100, 127, 140, 250):
+        code = rng.integers(0, 16, size=(8, 64)).astype(np.uint8)
+        code[code == 8] = 0
+        code[:, 0] = 7          # a 6 in group 0, a 4 in group 1: pins the shared exponent
+        code[:, 32] = 14
+        vals = np.vectorize(g.get)(code) * 2.0 ** (sb - 127)
+        x = vals.astype(np.float32)
+        assert np.array_equal(x.astype(np.float64), vals)
+        codes, scales = o.mxfp4_quantize(x)
+        assert (scales == sb).all()
+        assert np.array_equal(_unpack(codes), code)
+        assert np.array_equal(o.mxfp4_dequantize(codes, scales), vals)
+
+
+def pin_bf16_and_f32_inputs_agree(o):
+    rng = np.random.default_rng(10)
+    bits = rng.integers(0, 1 << 16, size=(4, 64)).astype(np.uint16)
+    bits[(bits & 0x7F80) == 0x7F80] = 0x3F80      # no Inf/NaN
+    wide = (bits.astype(np.uint32) << 16).view(np.float32)
+    cb, sb = o.mxfp4_quantize(bits)
+    cf, sf = o.mxfp4_quantize(wide)
+    assert np.array_equal(cb, cf) and np.array_equal(sb, sf)
+    assert np.array_equal(o.block_rotate(bits, 32), o.block_rotate(wide, 32))
+
+
+def pin_fused_is_the_composition(o):
+    rng = np.random.default_rng(11)
+    x = (rng.standard_t(4, size=(5, 256)) * 3).astype(np.float32)
+    for B in (32, 64, 256):
+        c1, s1 = o.rotate_quantize_fused(x, B)
+        c2, s2 = o.mxfp4_quantize(o.block_rotate(x, B))
+        assert np.array_equal(c1, c2) and np.array_equal(s1, s2)
+    # and it is NOT the quantizer alone: the rotation must have happened
+    c0, _ = o.mxfp4_quantize(x)
+    assert not np.array_equal(c0, o.rotate_quantize_fused(x, 32)[0])
+
+
+# --------------------------------------------------------------------------- product
+
+def pin_equivalent_transformation(o):
+    # Sec. 2 / Eq. (1): (X R)(W R)^T = X W^T for orthogonal R, before quantization
+    rng = np.random.default_rng(12)
+    X = rng.standard_normal((6, 128))
+    W = rng.standard_normal((5, 128))
+    ref = X @ W.T
+    for B in (32, 64, 128):
+        got = o.matmul_nt_f64(o.rotate_dense_f64(X, B), o.rotate_dense_f64(W, B))
+        assert np.allclose(got, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+    assert np.allclose(o.matmul_nt_f64(X, W), ref, rtol=0, atol=1e-12)
+
+
+def pin_gemm_against_brute_force(o):
+    g = golden_e2m1()
+    rng = np.random.default_rng(13)
+    M, N, K = 5, 7, 96
+    aq = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    wq = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    as_ = rng.integers(120, 135, size=(M, K // 32), dtype=np.uint8)
+    ws = rng.integers(120, 135, size=(N, K // 32), dtype=np.uint8)
+    lut = np.array([g[c] for c in range(16)])
+
+    def deq(q, s):
+        return lut[_unpack(q)] * np.repeat(2.0 ** (s.astype(np.float64) - 127), 32, axis=1)
+
+    A, W = deq(aq, as_), deq(wq, ws)
+    assert np.array_equal(o.mxfp4_dequantize(aq, as_), A)
+    y, bound = o.mxfp4_gemm(aq, as_, wq, ws)
+    want = np.zeros((M, N))
+    for m in range(M):
+        for n in range(N):
+            for k in range(K):
+                want[m, n] += A[m, k] * W[n, k]
+    assert np.allclose(y, want, rtol=1e-14, atol=0)
+    assert np.allclose(bound, np.abs(A) @ np.abs(W).T, rtol=1e-14)
+    # a row subset returns exactly those rows
+    ys, _ = o.mxfp4_gemm(aq, as_, wq, ws, rows=[3, 0])
+    assert np.array_equal(ys, y[[3, 0]])
+    # all ones (code 2, byte 127) -> Y = K exactly
+    ones_q = np.full((2, K // 2), 0x22, dtype=np.uint8)
+    ones_s = np.full((2, K // 32), 127, dtype=np.uint8)
+    y1, _ = o.mxfp4_gemm(ones_q, ones_s, ones_q, ones_s)
+    assert (y1 == K).all()
+    # bumping one scale byte doubles exactly that group's contribution
+    s2 = ones_s.copy()
+    s2[1, 2] += 1
+    y2, _ = o.mxfp4_gemm(ones_q, s2, ones_q, ones_s)
+    assert (y2[0] == K).all() and (y2[1] == K + 32).all()
+    # one-hot A (element 33 = 6, high nibble of byte 16) picks a single product
+    oh = np.zeros((1, K // 2), dtype=np.uint8)
+    oh[0, 16] = 0x70
+    yo, _ = o.mxfp4_gemm(oh, ones_s[:1], wq, ws)
+    assert np.array_equal(yo[0], 6.0 * W[:, 33])
+
+
+ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]

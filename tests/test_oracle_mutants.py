@@ -1,0 +1,66 @@
+"""Plant one mistake at a time in a COPY of the oracle's C source (on the CPU, in a temp
+directory) and check that the pins notice: a plausible slip anywhere in the oracle -- a
+wrong sign, a dropped term, a swapped index, a wrong constant -- must fail at least one
+pin.  The committed oracle itself is never modified."""
+import os
+import subprocess
+
+import pytest
+
+import oracle
+from oracle_pins import ALL_PINS
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "brq_oracle.c")
+
+# (name, text in brq_oracle.c, replacement)
+MUTANTS = [
+    ("butterfly_diff_sign", "v[i + h] = a - b;", "v[i + h] = b - a;"),
+    ("butterfly_descending", "for (int64_t h = 1; h < B; h *= 2)\n        for (int64_t i = 0; i < B; ++i)",
+     "for (int64_t h = B / 2; h >= 1; h /= 2)\n        for (int64_t i = 0; i < B; ++i)"),
+    ("butterfly_missing_last_stage", "for (int64_t h = 1; h < B; h *= 2)\n        for (int64_t i = 0; i < B; ++i)",
+     "for (int64_t h = 1; h < B / 2; h *= 2)\n        for (int64_t i = 0; i < B; ++i)"),
+    ("no_normalisation", "float out = v[i] * c;", "float out = v[i];"),
+    ("norm_is_1_over_B", "return (float)(1.0 / sqrt((double)B));", "return (float)(1.0 / (double)B);"),
+    ("hadamard_or_instead_of_and", "popcount_u32((uint32_t)i & (uint32_t)j)", "popcount_u32((uint32_t)i | (uint32_t)j)"),
+    ("sylvester_wrong_corner", "out[(i + n) * B + (j + n)] = -h;", "out[(i + n) * B + (j + n)] = h;"),
+    ("dense_transposed_block", "x[r * K + b * B + i] * (double)oracle_hadamard_entry((int)B, (int)i, (int)j)",
+     "x[r * K + b * B + j] * (double)oracle_hadamard_entry((int)B, (int)i, (int)j)"),
+    ("e2m1_bias_0", "ldexp(1.0 + 0.5 * m, E - 1)", "ldexp(1.0 + 0.5 * m, E)"),
+    ("e2m1_no_subnormal", ": 0.5 * m;", ": 0.0;"),
+    ("scale_emax_3", "e = (ex - 1) - 2;", "e = (ex - 1) - 3;"),
+    ("scale_ceil", "e = (ex - 1) - 2;", "e = ex - 2;"),
+    ("scale_bias_128", "return (uint8_t)(e + 127);", "return (uint8_t)(e + 128);"),
+    ("ties_to_odd", "(d == bestd && (c & 1) == 0)", "(d == bestd && (c & 1) == 1)"),
+    ("ties_down", "(d == bestd && (c & 1) == 0)", "0"),
+    ("negative_zero_kept", "if (best == 0) return 0;", ""),
+    ("sign_dropped", "(signbit(y) ? 8 : 0)", "0"),
+    ("nibbles_swapped", "(uint8_t)(lo | (hi << 4))", "(uint8_t)(hi | (lo << 4))"),
+    ("group_of_16", "for (int i = 0; i < 32; ++i) {\n        float a = fabsf(y[i]);", "for (int i = 0; i < 16; ++i) {\n        float a = fabsf(y[i]);"),
+    ("amax_without_abs", "float a = fabsf(y[i]);", "float a = y[i];"),
+    ("dequant_nibbles_swapped", "(k & 1) ? (byte >> 4) : (byte & 0xF)", "(k & 1) ? (byte & 0xF) : (byte >> 4)"),
+    ("dequant_scale_per_16", "scales[r * (K / 32) + k / 32]", "scales[r * (K / 32) + (k / 16) % (K / 32)]"),
+    ("gemm_w_row_pitch", "double p = ad[k] * wd[n * K + k];", "double p = ad[k] * wd[n * (K - 32) + k];"),
+    ("bf16_truncates", "u += 0x7FFFu + lsb;", ""),
+    ("bf16_half_up", "u += 0x7FFFu + lsb;", "u += 0x8000u;"),
+    ("fused_skips_rotation", "if (rc == ORACLE_OK) rc = oracle_mxfp4_quantize(y, ORACLE_F32, M, K, K, codes, scales);",
+     "rc = oracle_mxfp4_quantize(x, xdt, M, K, ldx, codes, scales);"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_mutant_is_caught(tmp_path, name, old, new):
+    src = open(SRC).read()
+    assert src.count(old) == 1, "mutation site for %s not found exactly once" % name
+    c = tmp_path / "mutant.c"
+    c.write_text(src.replace(old, new))
+    so = tmp_path / ("mutant_%s.so" % name)
+    subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-w",
+                           "-o", str(so), str(c), "-lm"])
+    mutant = oracle.Oracle(str(so))
+    failed = []
+    for pin in ALL_PINS:
+        try:
+            pin(mutant)
+        except Exception:  # a pin may also trip over a crash-free but malformed result
+            failed.append(pin.__name__)
+    assert failed, "no pin notices the planted mistake '%s'" % name
