@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-rotation MXFP4 hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic activations that are
+already resident in HBM: fused block rotation + MXFP4 quantization of X (B = 32), then the
+W4A4 product against weights that were rotated and quantized offline.  The default
+workload is the 8B-shaped MLP layer (X 8192x4096 bf16, W 14336x4096), the largest product
+shape, which the MFMA target is quoted on; the HBM target of the rotate+quantize kernel is
+quoted on X 16384x8192, measured in the same run and reported under "rotate_quant_16384x8192".
+
+Prints ONE JSON line.
+  value        whole-step throughput: 2*M*N*K useful flops of the layer per second of step
+               time (rotate+quantize included), TFLOP/s
+  kernels      per-kernel averages from HIP events recorded on the launch stream
+  roofline     the dominant kernel of the step against its roof
+  cpu_baseline the C oracle on a bounded sample of the same workload, on the host cores
+Buffers rotate through several sets so that no step finds its operands in the 256 MB
+last-level cache left behind by the previous one.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+MXFP4_PEAK_TFLOPS = 10100.0      # MI355X dense fp4 MFMA, published
+BYTES_PER_ELEM = 2 + 0.5 + 1.0 / 32     # bf16 in, 4-bit code out, one scale byte per 32
+
+
+def event_ms(pairs):
+    import numpy as np
+    return np.array([a.elapsed_time(b) for a, b in pairs])
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="mlp8b", help="llama1b_up | down_sweep | mlp8b | decode")
+    ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-aux", action="store_true", help="skip the 16384x8192 rotate+quantize measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (rows shard without "
+              "communication; nothing here uses a second GPU)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2511_04214_amd as brq
+    from paper_2511_04214_amd import inputs
+
+    brq.lib()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = inputs.CONFIGS[args.workload]
+    M, K, N, B = cfg["M"], cfg["K"], cfg["N"], 32
+    gemm_M = 16 if args.workload == "decode" else M
+    out_dtype = torch.bfloat16 if args.out_dtype == "bf16" else torch.float32
+    out_es = 2 if args.out_dtype == "bf16" else 4
+
+    def to_dev(a):
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+
+    x_np = inputs.make_x(cfg)
+    w_np = inputs.make_w(cfg)
+    wq0, ws0 = brq.rotate_quantize_fused(to_dev(w_np), B)          # offline weight preparation
+    del w_np
+    set_bytes = M * K * BYTES_PER_ELEM + N * K * 0.53125 + gemm_M * N * out_es
+    nsets = int(max(2, min(6, 600e6 // set_bytes + 1)))
+    xs = [to_dev(x_np)] + [None] * (nsets - 1)
+    for i in range(1, nsets):
+        xs[i] = xs[0].clone()
+    wqs = [wq0] + [wq0.clone() for _ in range(nsets - 1)]
+    wss = [ws0] + [ws0.clone() for _ in range(nsets - 1)]
+    codes = [torch.empty((M, K // 2), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    scales = [torch.empty((M, K // 32), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    ys = [torch.empty((gemm_M, N), dtype=out_dtype, device="cuda") for _ in range(nsets)]
+    stream = torch.cuda.Stream()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(i, evs=None):
+        j = i % nsets
+        if evs:
+            evs[0].record(stream)
+        brq.rotate_quantize_fused(xs[j], B, codes=codes[j], scales=scales[j], stream=stream)
+        if evs:
+            evs[1].record(stream)
+        brq.mxfp4_gemm(codes[j][:gemm_M], scales[j][:gemm_M], wqs[j], wss[j], out=ys[j], stream=stream)
+        if evs:
+            evs[2].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per = []
+    for i in range(args.steps):
+        e = [ev(), ev(), ev()]
+        step(i, e)
+        per.append(e)
+    stream.synchronize()
+    rq_ms = event_ms([(e[0], e[1]) for e in per])
+    gm_ms = event_ms([(e[1], e[2]) for e in per])
+
+    ms_per_step = wall * 1e3 / args.steps
+    rq_bytes = M * K * BYTES_PER_ELEM
+    gemm_flops = 2.0 * gemm_M * N * K
+    gemm_bytes = (gemm_M + N) * K * 0.53125 + gemm_M * N * out_es
+    rq_avg, gm_avg = float(rq_ms.mean()), float(gm_ms.mean())
+    kernels = {
+        "rotate_quantize_fused": {"avg_ms": rq_avg, "min_ms": float(rq_ms.min()), "alg_bytes": rq_bytes,
+                                  "GB/s": rq_bytes / rq_avg / 1e6,
+                                  "frac_hbm_peak": rq_bytes / rq_avg / 1e6 / HBM_PEAK_GBS},
+        "mxfp4_gemm": {"avg_ms": gm_avg, "min_ms": float(gm_ms.min()), "flops": gemm_flops, "alg_bytes": gemm_bytes,
+                       "TFLOP/s": gemm_flops / gm_avg / 1e9,
+                       "frac_mxfp4_peak": gemm_flops / gm_avg / 1e9 / MXFP4_PEAK_TFLOPS,
+                       "GB/s": gemm_bytes / gm_avg / 1e6, "frac_hbm_peak": gemm_bytes / gm_avg / 1e6 / HBM_PEAK_GBS},
+    }
+    if args.workload == "decode":     # M = 16 product: weight streaming, HBM bound
+        roofline = {"kernel": "mxfp4_gemm (M=16, weight streaming)", "bound": "hbm",
+                    "achieved": kernels["mxfp4_gemm"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": kernels["mxfp4_gemm"]["frac_hbm_peak"], "traffic": None}
+    else:
+        roofline = {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": kernels["mxfp4_gemm"]["TFLOP/s"],
+                    "peak": MXFP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": kernels["mxfp4_gemm"]["frac_mxfp4_peak"],
+                    "traffic": None}
+
+    # ---- the rotate+quantize kernel on the shape its HBM target is quoted on
+    aux = None
+    if not args.no_aux:
+        del xs, codes, scales, ys, wqs, wss
+        torch.cuda.empty_cache()
+        acfg = inputs.CONFIGS["decode"]
+        aM, aK = acfg["M"], acfg["K"]
+        ax_np = inputs.make_x(acfg) if args.workload != "decode" else x_np
+        axs = [to_dev(ax_np)]
+        axs.append(axs[0].clone())
+        axs.append(axs[0].clone())
+        ac = [torch.empty((aM, aK // 2), dtype=torch.uint8, device="cuda") for _ in range(3)]
+        asc = [torch.empty((aM, aK // 32), dtype=torch.uint8, device="cuda") for _ in range(3)]
+        for i in range(args.warmup):
+            brq.rotate_quantize_fused(axs[i % 3], B, codes=ac[i % 3], scales=asc[i % 3], stream=stream)
+        stream.synchronize()
+        pairs = []
+        for i in range(args.steps):
+            a, b = ev(), ev()
+            a.record(stream)
+            brq.rotate_quantize_fused(axs[i % 3], B, codes=ac[i % 3], scales=asc[i % 3], stream=stream)
+            b.record(stream)
+            pairs.append((a, b))
+        stream.synchronize()
+        ams = event_ms(pairs)
+        ab = aM * aK * BYTES_PER_ELEM
+        aux = {"kernel": "rotate_quantize_fused", "bound": "hbm", "avg_ms": float(ams.mean()),
+               "min_ms": float(ams.min()), "alg_bytes": ab, "achieved": ab / float(ams.mean()) / 1e6,
+               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ab / float(ams.mean()) / 1e6 / HBM_PEAK_GBS,
+               "traffic": None}
+        del axs, ac, asc
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        o = oracle.default()
+        threads = o.get_threads()
+        rows = int(min(M, max(64, 6e7 // K)))                 # a few seconds of oracle work
+        t0 = time.perf_counter()
+        rc, rs = o.rotate_quantize_fused(x_np[:rows], B)
+        t_rq = time.perf_counter() - t0
+        grows = int(min(gemm_M, rows, max(1, 6e9 // (N * K))))
+        wq_h, ws_h = wq0.cpu().numpy(), ws0.cpu().numpy()
+        t0 = time.perf_counter()
+        o.mxfp4_gemm(rc[:grows], rs[:grows], wq_h, ws_h, want_bound=False)
+        t_g = time.perf_counter() - t0
+        # the same unit as `value`: useful layer flops per second of (rotate+quantize + product) time,
+        # both legs scaled to the full M rows
+        t_full = t_rq * (M / rows) + t_g * (gemm_M / grows)
+        cpu_baseline = {
+            "value": gemm_flops / t_full / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "rotate+quantize of the first %d of %d rows in %.2f s (%.2f GB/s); product of %d rows "
+                      "x N=%d x K=%d in %.2f s incl. dequantizing W (%.4f TFLOP/s); both scaled linearly to M=%d"
+                      % (rows, M, t_rq, rows * K * BYTES_PER_ELEM / t_rq / 1e9, grows, N, K, t_g,
+                         2.0 * grows * N * K / t_g / 1e12, M)}
+
+    out = {
+        "metric": "rotate+quant GB/s (% HBM peak); MXFP4 GEMM TFLOPS (% MXFP4 MFMA peak)",
+        "value": gemm_flops / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "value_note": "whole step: 2*M*N*K of the layer / (rotate+quantize + product) wall time",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "mxfp4",
+        "data": "synthetic",
+        "config": {"workload": "%s: X %dx%d bf16 -> block Hadamard B=32 + MXFP4; product M=%d N=%d K=%d, %s out"
+                               % (args.workload, M, K, gemm_M, N, K, args.out_dtype), "buffer_sets": nsets},
+        "rotate_quant_GBps": kernels["rotate_quantize_fused"]["GB/s"],
+        "gemm_TFLOPs": kernels["mxfp4_gemm"]["TFLOP/s"],
+        "roofline": roofline,
+        "rotate_quant_16384x8192": aux,
+        "kernels": kernels,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

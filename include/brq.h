@@ -1,0 +1,108 @@
+/*
+ * brq.h -- C ABI of the block-rotation MXFP4 hot path for MI355X (gfx950).
+ *
+ * The library implements the online part of "Block Rotation is All You Need for MXFP4
+ * Quantization": a block-diagonal Hadamard rotation of activations along the reduction
+ * axis K (Sec. 4.3, Eq. 1), MXFP4 quantization (Sec. 4.1: E2M1 elements, one power-of-two
+ * E8M0 scale per 32 consecutive K elements) and the W4A4 product
+ * Y = Q(X R) Q(W R)^T that the rotation leaves invariant (Sec. 2, equivalent
+ * transformations).  Weights go through the same calls offline (rows of W are rows of
+ * "X" with M := N).
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers (HBM of the current HIP device).  The caller
+ *     owns every buffer; the library allocates nothing and keeps no state.
+ *   - Matrices are row-major with K contiguous.  X is [M][ldx] (ldx >= K, in elements),
+ *     codes are [M][K/2] bytes, scales are [M][K/32] bytes, Y is [M][ldy].
+ *   - codes: two E2M1 codes per byte, element 2j in the low nibble of byte j, element
+ *     2j+1 in the high nibble.  A code is s<<3 | e<<1 | m (magnitudes 0, .5, 1, 1.5, 2,
+ *     3, 4, 6).  A zero magnitude is always stored as code 0 (no negative zero).
+ *   - scales: E8M0, byte b means 2^(b-127).  For a group with maximum magnitude amax the
+ *     byte is max(exponent_field(amax) - 2, 0), i.e. floor(log2 amax) - 2 clamped.
+ *     0xFF is never produced.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work is
+ *     enqueued and the call returns; nothing synchronises with the host.
+ *   - Argument errors are found on the host before anything is launched: the call
+ *     returns the error code and touches no buffer.  BRQ_ERR_LAUNCH reports a failed
+ *     kernel launch.  Asynchronous device faults surface at the caller's next sync.
+ *   - Inputs must be finite and, for rotations, small enough that sums of B of them stay
+ *     finite in fp32.  fp32 subnormals are honoured, not flushed.
+ *   - M == 0 (or N == 0 for the product) is valid and does nothing; the data pointers of an
+ *     empty matrix may be NULL.
+ *   - Pointers must be 16-byte aligned and the row pitches of X and of the rotated output
+ *     multiples of 16 bytes.  The product's output pitch ldy is free (>= N).
+ */
+#ifndef BRQ_H
+#define BRQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BRQ_OK = 0,
+    BRQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    BRQ_ERR_SHAPE = 2,       /* negative size, K % 32 != 0, ld < K, size beyond 2^31 work items */
+    BRQ_ERR_BLOCK = 3,       /* B not a power of two, B < 32, B > 16384 or B does not divide K */
+    BRQ_ERR_ALIGN = 4,       /* pointer or pitch not 16-byte aligned */
+    BRQ_ERR_DTYPE = 5,       /* dtype is not one of brq_dtype */
+    BRQ_ERR_LAUNCH = 6       /* hipLaunchKernel failed (hipGetLastError) */
+} brq_status;
+
+typedef enum { BRQ_F32 = 0, BRQ_BF16 = 1 } brq_dtype;
+
+/*
+ * y = x * diag(H_B, ..., H_B) / sqrt(B)          (Sec. 4.3, Eq. 1 with R_i = Sylvester
+ * Hadamard of order B, normalised so that R_i^T R_i = I; B = K is the global rotation
+ * the paper compares with).
+ * Arithmetic: inputs widened exactly to fp32; stages h = 1, 2, ..., B/2 in ascending
+ * order, pair (i, i+h) -> (a+b, a-b), each one IEEE fp32 operation; one fp32 multiply by
+ * fl(1/sqrt(B)).  ydt = BRQ_F32 stores that value, BRQ_BF16 its round-to-nearest-even.
+ * x [M][ldx] of xdt, y [M][ldy] of ydt; x and y must not overlap.
+ * B: power of two, 32 <= B <= 16384, B divides K.
+ */
+brq_status brq_block_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx,
+                            int64_t B, void* y, brq_dtype ydt, int64_t ldy, void* stream);
+
+/*
+ * MXFP4 quantization of x along K (Sec. 4.1): per row and per group of 32 consecutive
+ * elements one E8M0 scale from the group's maximum magnitude, elements rounded to the
+ * nearest E2M1 value of x / 2^e (ties to the even code, saturation at +-6).
+ * x [M][ldx] of xdt -> codes [M][K/2], scales [M][K/32].  K % 32 == 0.
+ */
+brq_status brq_mxfp4_quantize(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx,
+                              uint8_t* codes, uint8_t* scales, void* stream);
+
+/*
+ * The online step of the method (Sec. 4.3, the rotation applied before a quantized
+ * linear layer): brq_mxfp4_quantize(brq_block_rotate(x, B) kept in fp32), in one pass
+ * over x, bit-identical to that composition.  The quantization group stays 32 whatever
+ * B is.  Same argument rules as the two calls above.
+ */
+brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K,
+                                     int64_t ldx, int64_t B, uint8_t* codes, uint8_t* scales,
+                                     void* stream);
+
+/*
+ * W4A4 product on MXFP4 operands (Sec. 2; Sec. 4.1 "scaling factor integrated into
+ * hardware"):   y[m][n] = sum_g 2^(as[m][g]-127 + ws[n][g]-127) *
+ *                          sum_{j<32} val(aq[m][32g+j]) * val(wq[n][32g+j]),  fp32 accumulate.
+ * aq [M][K/2], as [M][K/32], wq [N][K/2], ws [N][K/32] -> y [M][ldy] of ydt (fp32, or
+ * bf16 = round-to-nearest-even of the fp32 sum).  K % 32 == 0, ldy >= N.
+ */
+brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* wq,
+                          const uint8_t* ws, int64_t M, int64_t N, int64_t K, void* y,
+                          brq_dtype ydt, int64_t ldy, void* stream);
+
+/* Static, human-readable text for a status code. */
+const char* brq_strerror(brq_status s);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int brq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BRQ_H */

@@ -1,0 +1,108 @@
+// extern "C" boundary of the library: argument validation on the host, then a kernel launch
+// on the caller's stream.  No allocation, no state, no host synchronisation.
+#include "../../include/brq.h"
+#include "brq_launch.h"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+int dtype_size(brq_dtype d) { return d == BRQ_F32 ? 4 : (d == BRQ_BF16 ? 2 : 0); }
+
+// log2 of the rotation block, or -1 if B is not an accepted block size for this K
+int block_log2(int64_t B, int64_t K) {
+    if (B < 32 || B > 16384 || (B & (B - 1)) != 0 || K % B != 0) return -1;
+    int l = 0;
+    while ((int64_t(1) << l) < B) ++l;
+    return l;
+}
+
+// An empty matrix (M == 0) may come with a NULL pointer; everything else is still checked.
+brq_status check_rows(const void* x, brq_dtype dt, int64_t M, int64_t K, int64_t ld) {
+    int es = dtype_size(dt);
+    if (es == 0) return BRQ_ERR_DTYPE;
+    if (M < 0 || K <= 0 || K % 32 != 0 || ld < K) return BRQ_ERR_SHAPE;
+    if (K >= (int64_t(1) << 31) || M >= (int64_t(1) << 31) || M * (K / 8) >= (int64_t(1) << 31)) return BRQ_ERR_SHAPE;
+    if (M > 0 && !x) return BRQ_ERR_NULL;
+    if (!aligned16(x) || (ld * es) % 16 != 0) return BRQ_ERR_ALIGN;
+    return BRQ_OK;
+}
+
+brq_status check_out(const uint8_t* codes, const uint8_t* scales, int64_t M) {
+    if (M > 0 && (!codes || !scales)) return BRQ_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(scales)) return BRQ_ERR_ALIGN;
+    return BRQ_OK;
+}
+
+brq_status launched(hipError_t e) { return e == hipSuccess ? BRQ_OK : BRQ_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+brq_status brq_block_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
+                            void* y, brq_dtype ydt, int64_t ldy, void* stream) {
+    brq_status st = check_rows(x, xdt, M, K, ldx);
+    if (st != BRQ_OK) return st;
+    st = check_rows(y, ydt, M, K, ldy);
+    if (st != BRQ_OK) return st;
+    int l2 = block_log2(B, K);
+    if (l2 < 0) return BRQ_ERR_BLOCK;
+    if (M == 0) return BRQ_OK;
+    return launched(brq::launch_rowwise(0, l2, xdt == BRQ_BF16, ydt == BRQ_BF16, x, M, K, ldx, y, ldy, nullptr,
+                                        nullptr, static_cast<hipStream_t>(stream)));
+}
+
+brq_status brq_mxfp4_quantize(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, uint8_t* codes,
+                              uint8_t* scales, void* stream) {
+    brq_status st = check_rows(x, xdt, M, K, ldx);
+    if (st != BRQ_OK) return st;
+    st = check_out(codes, scales, M);
+    if (st != BRQ_OK) return st;
+    if (M == 0) return BRQ_OK;
+    return launched(brq::launch_rowwise(1, 0, xdt == BRQ_BF16, false, x, M, K, ldx, nullptr, 0, codes, scales,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
+                                     uint8_t* codes, uint8_t* scales, void* stream) {
+    brq_status st = check_rows(x, xdt, M, K, ldx);
+    if (st != BRQ_OK) return st;
+    st = check_out(codes, scales, M);
+    if (st != BRQ_OK) return st;
+    int l2 = block_log2(B, K);
+    if (l2 < 0) return BRQ_ERR_BLOCK;
+    if (M == 0) return BRQ_OK;
+    return launched(brq::launch_rowwise(2, l2, xdt == BRQ_BF16, false, x, M, K, ldx, nullptr, 0, codes, scales,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws, int64_t M,
+                          int64_t N, int64_t K, void* y, brq_dtype ydt, int64_t ldy, void* stream) {
+    int es = dtype_size(ydt);
+    if (es == 0) return BRQ_ERR_DTYPE;
+    if (M < 0 || N < 0 || K <= 0 || K % 32 != 0 || ldy < N) return BRQ_ERR_SHAPE;
+    if (M >= (int64_t(1) << 31) || N >= (int64_t(1) << 31) || K >= (int64_t(1) << 31)) return BRQ_ERR_SHAPE;
+    if (M > 0 && N > 0 && (!aq || !as || !wq || !ws || !y)) return BRQ_ERR_NULL;
+    if (!aligned16(aq) || !aligned16(as) || !aligned16(wq) || !aligned16(ws) || !aligned16(y))
+        return BRQ_ERR_ALIGN;
+    if (M == 0 || N == 0) return BRQ_OK;
+    return launched(brq::launch_mxfp4_gemm(aq, as, wq, ws, M, N, K, y, ydt == BRQ_BF16, ldy,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+const char* brq_strerror(brq_status s) {
+    switch (s) {
+        case BRQ_OK: return "ok";
+        case BRQ_ERR_NULL: return "a required pointer is NULL";
+        case BRQ_ERR_SHAPE: return "bad shape: negative size, K not a multiple of 32, pitch below row length, or too large";
+        case BRQ_ERR_BLOCK: return "bad rotation block: need a power of two, 32 <= B <= 16384, B dividing K";
+        case BRQ_ERR_ALIGN: return "pointer or row pitch not 16-byte aligned";
+        case BRQ_ERR_DTYPE: return "unknown dtype";
+        case BRQ_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+int brq_version(void) { return 100; }
+
+}  // extern "C"

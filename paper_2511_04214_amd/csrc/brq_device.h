@@ -1,0 +1,148 @@
+// Device-side building blocks shared by the gfx950 kernels of the block-rotation MXFP4
+// path: bf16 widening, wavefront lane exchange, the E8M0 scale rule and the packed E2M1
+// encoder.  CDNA4 only (64-wide wavefronts, DPP, the scaled fp4 convert instruction).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace brq {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// A dword holds two bf16 values; bf16 is the upper half of an fp32, so widening is a
+// shift (low element) or a mask (high element), both exact.
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return as_f32(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return as_f32(w & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (finite input), integer form.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = as_u32(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Value of `v` held by lane (lane ^ MASK).  MASK 1 and 2 stay inside a quad and fold
+// into the consuming VALU instruction as a DPP modifier; 4, 8, 16 use the swizzle
+// crossbar; 32 crosses the two halves of the wavefront.
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float v) {
+    int iv = __builtin_bit_cast(int, v);
+    if constexpr (MASK == 1) {
+        iv = __builtin_amdgcn_update_dpp(iv, iv, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
+    } else if constexpr (MASK == 2) {
+        iv = __builtin_amdgcn_update_dpp(iv, iv, 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, true);
+    } else if constexpr (MASK == 4 || MASK == 8 || MASK == 16) {
+        iv = __builtin_amdgcn_ds_swizzle(iv, 0x1F | (MASK << 10)); /* and 0x1f, or 0, xor MASK */
+    } else {
+        static_assert(MASK == 32, "lane_xor: mask must be a power of two below 64");
+        int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        iv = __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, iv);
+    }
+    return __builtin_bit_cast(float, iv);
+}
+
+// Radix-8 butterfly on 8 consecutive elements held by one lane: stages h = 1, 2, 4 of
+// the ascending-order Walsh-Hadamard transform, pair (i, i+h) -> (a+b, a-b).
+__device__ __forceinline__ void wht8(float (&v)[8]) {
+#pragma unroll
+    for (int h = 1; h < 8; h *= 2) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if ((i & h) == 0) {
+                float a = v[i], b = v[i + h];
+                v[i] = a + b;
+                v[i + h] = a - b;
+            }
+        }
+    }
+}
+
+// One cross-lane stage (partner lane = lane ^ MASK).  The lane whose MASK bit is clear
+// owns a and needs a+b; the other owns b and needs a-b.  Both evaluate
+// fma(partner, s, own) with s = +1 / -1: the lower lane gets a+b, the upper lane gets
+// b-a, i.e. the NEGATED result (one rounding, so exactly -fl(a-b)).  The caller tracks
+// the sign (it flips once per stage in which the lane is the upper one) and folds it into
+// the final normalisation multiply; only the sign of exact zeros can differ, and the
+// encoder stores every zero magnitude as code 0.
+template <int MASK>
+__device__ __forceinline__ void wht_cross(float (&v)[8], float s) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(lane_xor<MASK>(v[i]), s, v[i]);
+}
+
+// The two stages that stay inside a quad (partner lane ^ 1, then lane ^ 2), i.e. h = 8 and
+// h = 16 at 8 elements per lane.  The compiler folds a DPP lane permute into v_add/v_sub
+// but not into v_fmac, so the 16 fused multiply-adds are written out: v_fmac_f32_dpp
+// computes D = dpp(S0) * S1 + D.  A VGPR written by a VALU instruction may be read through
+// DPP only 2 wait states later: the leading s_nop covers the compiler's code in front, and
+// inside the block 7 instructions separate every write from its DPP read.
+#define BRQ_FMAC_DPP(r, s, perm) \
+    "v_fmac_f32_dpp " r ", " r ", " s " quad_perm:" perm " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+__device__ __forceinline__ void wht_cross_quad(float (&v)[8], float s1, float s2) {
+    asm volatile(
+        "s_nop 1\n\t"
+        BRQ_FMAC_DPP("%0", "%8", "[1,0,3,2]") BRQ_FMAC_DPP("%1", "%8", "[1,0,3,2]")
+        BRQ_FMAC_DPP("%2", "%8", "[1,0,3,2]") BRQ_FMAC_DPP("%3", "%8", "[1,0,3,2]")
+        BRQ_FMAC_DPP("%4", "%8", "[1,0,3,2]") BRQ_FMAC_DPP("%5", "%8", "[1,0,3,2]")
+        BRQ_FMAC_DPP("%6", "%8", "[1,0,3,2]") BRQ_FMAC_DPP("%7", "%8", "[1,0,3,2]")
+        BRQ_FMAC_DPP("%0", "%9", "[2,3,0,1]") BRQ_FMAC_DPP("%1", "%9", "[2,3,0,1]")
+        BRQ_FMAC_DPP("%2", "%9", "[2,3,0,1]") BRQ_FMAC_DPP("%3", "%9", "[2,3,0,1]")
+        BRQ_FMAC_DPP("%4", "%9", "[2,3,0,1]") BRQ_FMAC_DPP("%5", "%9", "[2,3,0,1]")
+        BRQ_FMAC_DPP("%6", "%9", "[2,3,0,1]") BRQ_FMAC_DPP("%7", "%9", "[2,3,0,1]")
+        : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7])
+        : "v"(s1), "v"(s2));
+}
+#undef BRQ_FMAC_DPP
+
+// Maximum magnitude of the lane's 8 values.
+__device__ __forceinline__ float absmax8(const float (&y)[8]) {
+    float m = fmaxf(fmaxf(fabsf(y[0]), fabsf(y[1])), fabsf(y[2]));
+    m = fmaxf(fmaxf(m, fabsf(y[3])), fabsf(y[4]));
+    m = fmaxf(fmaxf(m, fabsf(y[5])), fabsf(y[6]));
+    return fmaxf(m, fabsf(y[7]));
+}
+
+// Maximum over the 4 lanes of a quad (= one 32-element MXFP4 group at 8 per lane).  The
+// argument is non-negative, so comparing the bit patterns as unsigned integers orders
+// them like the floats.  Same DPP read-after-write spacing rule as above.
+__device__ __forceinline__ float quad_max(float m) {
+    uint32_t u = as_u32(m);
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_max_u32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "s_nop 1\n\t"
+        "v_max_u32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        : "+v"(u));
+    return as_f32(u);
+}
+
+// E8M0 byte of a group from its maximum magnitude: max(exponent field - 2, 0).
+// (2 = exponent of the largest E2M1 value, 6 = 1.5 * 2^2.)
+__device__ __forceinline__ uint32_t e8m0_from_amax(float amax) {
+    uint32_t e = (as_u32(amax) >> 23) & 0xffu;
+    return __builtin_elementwise_sub_sat(e, 2u);
+}
+
+// 8 fp32 values -> 8 packed E2M1 codes (element i in nibble i) under E8M0 byte `sb`.
+// v_cvt_scalef32_pk_fp4_f32 divides by 2^(sb-127) (it reads only the exponent field of
+// its scale operand, field 0 meaning 2^-127), rounds to nearest with ties to the even
+// code and saturates at 6.  It keeps the sign of results that round to zero; those
+// nibbles are cleared afterwards so that a zero magnitude is always code 0.
+__device__ __forceinline__ uint32_t encode8_e2m1(const float (&y)[8], uint32_t sb) {
+    float scale = as_f32(sb << 23);
+    uint32_t w = 0;
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, y[0], y[1], scale, 0);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, y[2], y[3], scale, 1);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, y[4], y[5], scale, 2);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, y[6], y[7], scale, 3);
+    uint32_t mag = w & 0x77777777u;
+    uint32_t nz = mag + 0x77777777u;            // bit 3 of a nibble set <=> magnitude != 0
+    return w & (nz | 0x77777777u);
+}
+
+}  // namespace brq

@@ -1,0 +1,121 @@
+// W4A4 product on MXFP4 operands for gfx950 (Sec. 2 and Sec. 4.1 of the paper: the product
+// the rotation leaves invariant, evaluated on E2M1 codes with E8M0 group scales).
+//
+// The contraction runs on CDNA4's block-scaled MFMA.  Operand layout of
+// v_mfma_scale_f32_32x32x64_f8f6f4 with fp4 inputs: lane l supplies, for row (l & 31), the
+// 32 consecutive K elements of group (l >> 5) as 16 packed bytes (low nibble first), and
+// one E8M0 byte for exactly that group; accumulator register i of lane l is element
+// (row 8*(i/4) + 4*(l>>5) + i%4, column l & 31).  The 16x16x128 form: row (l & 15), group
+// (l >> 4); accumulator i is (row 4*(l>>4) + i, column l & 15).
+#include "brq_device.h"
+#include "brq_launch.h"
+
+namespace brq {
+
+__device__ __forceinline__ void store_out(void* y, bool out_bf16, int64_t idx, float v) {
+    if (out_bf16) reinterpret_cast<uint16_t*>(y)[idx] = (uint16_t)f32_to_bf16_bits(v);
+    else reinterpret_cast<float*>(y)[idx] = v;
+}
+
+// ---- general shapes: one 32x32 output tile per wavefront, operands straight from global ----
+__global__ void __launch_bounds__(256) k_gemm_direct(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
+                                                     const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
+                                                     int M, int N, int K, void* __restrict__ y, int out_bf16,
+                                                     int64_t ldy) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m0 = blockIdx.y * 64 + (wave >> 1) * 32, n0 = blockIdx.x * 64 + (wave & 1) * 32;
+    if (m0 >= M || n0 >= N) return;   // whole wavefront leaves together
+    const int r = lane & 31, h = lane >> 5;
+    const int64_t ra = min(m0 + r, M - 1), rw = min(n0 + r, N - 1);   // clamp: rows past the edge are computed, not stored
+    const int groups = K / 32;
+    const uint8_t* pa = aq + ra * (K / 2);
+    const uint8_t* pw = wq + rw * (K / 2);
+    const uint8_t* sa = as + ra * groups;
+    const uint8_t* sw = ws + rw * groups;
+    v16f acc = {};
+    for (int g0 = 0; g0 < groups; g0 += 2) {
+        int g = g0 + h;
+        v8i a = {}, b = {};
+        int sca = 0, scb = 0;
+        if (g < groups) {   // odd group count: the last step's second half contributes zeros
+            v4i ta = *reinterpret_cast<const v4i*>(pa + g * 16);
+            v4i tb = *reinterpret_cast<const v4i*>(pw + g * 16);
+            a[0] = ta[0]; a[1] = ta[1]; a[2] = ta[2]; a[3] = ta[3];
+            b[0] = tb[0]; b[1] = tb[1]; b[2] = tb[2]; b[3] = tb[3];
+            sca = sa[g]; scb = sw[g];
+        }
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc, 4, 4, 0, sca, 0, scb);
+    }
+    const int col = n0 + r;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        int row = m0 + 8 * (i / 4) + 4 * h + (i % 4);
+        if (row < M && col < N) store_out(y, out_bf16, (int64_t)row * ldy + col, acc[i]);
+    }
+}
+
+// ---- M <= 16 (decode): weight streaming, 16 output columns per workgroup -------------------
+// Each of the 4 wavefronts takes every 4th 128-wide K step for the same 16 weight rows; the
+// partial 16x16 tiles are summed through LDS in a fixed order.
+__global__ void __launch_bounds__(256) k_gemm_skinny(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
+                                                     const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
+                                                     int M, int N, int K, void* __restrict__ y, int out_bf16,
+                                                     int64_t ldy) {
+    __shared__ float part[4][64][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 15, kq = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const int groups = K / 32;
+    const int64_t rw = min(n0 + r, N - 1);
+    const bool arow = r < M;
+    const uint8_t* pa = aq + (int64_t)(arow ? r : 0) * (K / 2);
+    const uint8_t* sa = as + (int64_t)(arow ? r : 0) * groups;
+    const uint8_t* pw = wq + rw * (K / 2);
+    const uint8_t* sw = ws + rw * groups;
+    v4f acc = {};
+    for (int g0 = wave * 4; g0 < groups; g0 += 16) {
+        int g = g0 + kq;
+        v8i a = {}, b = {};
+        int sca = 0, scb = 0;
+        if (g < groups) {
+            v4i tb = *reinterpret_cast<const v4i*>(pw + g * 16);
+            b[0] = tb[0]; b[1] = tb[1]; b[2] = tb[2]; b[3] = tb[3];
+            scb = sw[g];
+            if (arow) {
+                v4i ta = *reinterpret_cast<const v4i*>(pa + g * 16);
+                a[0] = ta[0]; a[1] = ta[1]; a[2] = ta[2]; a[3] = ta[3];
+                sca = sa[g];
+            }
+        }
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc, 4, 4, 0, sca, 0, scb);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) part[wave][lane][i] = acc[i];
+    __syncthreads();
+    if (wave == 0) {
+        const int col = n0 + r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float s = ((part[0][lane][i] + part[1][lane][i]) + part[2][lane][i]) + part[3][lane][i];
+            int row = 4 * kq + i;
+            if (row < M && col < N) store_out(y, out_bf16, (int64_t)row * ldy + col, s);
+        }
+    }
+}
+
+hipError_t launch_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws,
+                             int64_t M, int64_t N, int64_t K, void* y, bool out_bf16, int64_t ldy,
+                             hipStream_t s) {
+    if (M <= 16) {
+        dim3 grid((uint32_t)((N + 15) / 16));
+        hipLaunchKernelGGL(k_gemm_skinny, grid, dim3(256), 0, s, aq, as, wq, ws, (int)M, (int)N, (int)K, y,
+                           (int)out_bf16, ldy);
+    } else {
+        dim3 grid((uint32_t)((N + 63) / 64), (uint32_t)((M + 63) / 64));
+        hipLaunchKernelGGL(k_gemm_direct, grid, dim3(256), 0, s, aq, as, wq, ws, (int)M, (int)N, (int)K, y,
+                           (int)out_bf16, ldy);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace brq

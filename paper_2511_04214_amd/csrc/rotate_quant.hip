@@ -1,0 +1,292 @@
+// Row-wise kernels of the block-rotation MXFP4 path for gfx950: block Hadamard rotation
+// (Sec. 4.3, Eq. 1), MXFP4 quantization (Sec. 4.1) and their fusion, the online step
+// that precedes a quantized linear layer.  All of them stream X once from HBM.
+//
+// Work decomposition.  A "chunk" is 8 consecutive elements of a row (16 bytes of bf16,
+// 32 bytes of fp32), held by one lane; 4 consecutive lanes (a DPP quad) hold one
+// 32-element MXFP4 group, so the group maximum is two quad-permute steps and the group's
+// 8 packed codes per lane form one dword store.  Rotation stages h = 1, 2, 4 run inside
+// the lane, h = 8 ... 256 between lanes of the wavefront, larger h through LDS.
+#include "brq_device.h"
+#include "brq_launch.h"
+
+namespace brq {
+
+enum RowMode { MODE_ROTATE = 0, MODE_QUANT = 1, MODE_FUSED = 2 };
+
+struct RowArgs {
+    const void* x;      // [M][ldx]
+    void* y;            // rotate: [M][ldy]
+    uint32_t* codes;    // quant/fused: [M][K/8] dwords
+    uint8_t* scales;    // quant/fused: [M][K/32]
+    int64_t ldx, ldy;   // in elements
+    uint32_t cpr;       // chunks per row = K/8
+    uint32_t nchunks;   // M * K/8
+};
+
+// ---- chunk load / store ---------------------------------------------------------
+
+template <bool BF16>
+__device__ __forceinline__ void load_chunk(const void* p, float (&v)[8]) {
+    if constexpr (BF16) {
+        uint4 w = *reinterpret_cast<const uint4*>(p);
+        v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x); v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
+        v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z); v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
+    } else {
+        float4 a = reinterpret_cast<const float4*>(p)[0];
+        float4 b = reinterpret_cast<const float4*>(p)[1];
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void store_chunk(void* p, const float (&v)[8]) {
+    if constexpr (BF16) {
+        uint4 w;
+        w.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+        w.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+        w.z = f32_to_bf16_bits(v[4]) | (f32_to_bf16_bits(v[5]) << 16);
+        w.w = f32_to_bf16_bits(v[6]) | (f32_to_bf16_bits(v[7]) << 16);
+        *reinterpret_cast<uint4*>(p) = w;
+    } else {
+        reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
+        reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+    }
+}
+
+// Element offset of chunk c.  Contiguous rows (ld == K) need no division.
+template <bool CONTIG>
+__device__ __forceinline__ int64_t chunk_offset(uint32_t c, uint32_t cpr, int64_t ld) {
+    if constexpr (CONTIG) {
+        return (int64_t)c * 8;
+    } else {
+        uint32_t row = c / cpr;
+        return (int64_t)row * ld + (int64_t)(c - row * cpr) * 8;
+    }
+}
+
+// ---- in-wavefront rotation, 32 <= B <= 512 ------------------------------------------
+
+// Stages of the order-2^LOG2B transform for the chunk in `v`; returns the value through
+// sign-tracked cross-lane stages: afterwards v holds sigma * (x H), with sigma = -1 for
+// lanes with an odd number of set bits among the lane bits that took part.
+template <int LOG2B>
+__device__ __forceinline__ void wht_inwave(float (&v)[8], uint32_t lane) {
+    static_assert(LOG2B >= 5, "rotation blocks span at least one quad of lanes");
+    wht8(v);
+    wht_cross_quad(v, (lane & 1) ? -1.0f : 1.0f, (lane & 2) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 6) wht_cross<4>(v, (lane & 4) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 7) wht_cross<8>(v, (lane & 8) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 8) wht_cross<16>(v, (lane & 16) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 9) wht_cross<32>(v, (lane & 32) ? -1.0f : 1.0f);
+}
+
+// fl(1/sqrt(2^LOG2B)) as fp32 bits: sqrt(2)/2 = 0x3F3504F3 scaled by a power of two.
+__host__ __device__ constexpr uint32_t norm_bits(int log2b) {
+    return (log2b & 1) ? (0x3F3504F3u - ((uint32_t)((log2b - 1) / 2) << 23))
+                       : (0x3F800000u - ((uint32_t)(log2b / 2) << 23));
+}
+
+// Quantize the lane's 8 values (quad = one group) and store codes + scale.
+__device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t c, uint32_t lane,
+                                            uint32_t* codes, uint8_t* scales) {
+    uint32_t sb = e8m0_from_amax(quad_max(absmax8(y)));
+    codes[c] = encode8_e2m1(y, sb);
+    if ((lane & 3) == 0) scales[c >> 2] = (uint8_t)sb;
+}
+
+// One chunk per lane per step, U steps in flight.  LOG2B = 0 means "no rotation".
+template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool CONTIG, int U>
+__global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
+    const uint32_t lane = threadIdx.x & 63;
+    constexpr uint32_t inwave_bits = (LOG2B >= 3) ? ((1u << (LOG2B - 3)) - 1u) : 0u;
+    const float sigma = (__builtin_popcount(lane & inwave_bits) & 1) ? -1.0f : 1.0f;
+    const float cs = as_f32(norm_bits(LOG2B)) * sigma;
+    const uint32_t step = gridDim.x * 256u * U;
+    // `bb` is uniform over the workgroup and nothing below branches on the lane: chunks past
+    // the end re-read the last chunk (clamped index) and only their stores are masked, so
+    // every lane exchange sees a full wavefront.
+    for (uint32_t bb = blockIdx.x * 256u * U; bb < a.nchunks; bb += step) {
+        float v[U][8];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint32_t c = min(bb + u * 256u + threadIdx.x, a.nchunks - 1u);
+            const char* p = (const char*)a.x + chunk_offset<CONTIG>(c, a.cpr, a.ldx) * (IN_BF16 ? 2 : 4);
+            load_chunk<IN_BF16>(p, v[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t c = bb + u * 256u + threadIdx.x;
+            const bool live = c < a.nchunks;
+            if constexpr (MODE != MODE_QUANT) {
+                wht_inwave<LOG2B>(v[u], lane);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[u][i] *= cs;
+            }
+            if constexpr (MODE == MODE_ROTATE) {
+                if (live) {
+                    char* p = (char*)a.y + chunk_offset<CONTIG>(c, a.cpr, a.ldy) * (OUT_BF16 ? 2 : 4);
+                    store_chunk<OUT_BF16>(p, v[u]);
+                }
+            } else {
+                uint32_t sb = e8m0_from_amax(quad_max(absmax8(v[u])));
+                uint32_t w = encode8_e2m1(v[u], sb);
+                if (live) {
+                    a.codes[c] = w;
+                    if ((lane & 3) == 0) a.scales[c >> 2] = (uint8_t)sb;
+                }
+            }
+        }
+    }
+}
+
+// ---- LDS-staged rotation, 1024 <= B <= 16384 (includes the global, full-K rotation) ----
+//
+// One workgroup of NT = min(256, B/8) lanes transforms one B-block of one row.  Each
+// lane holds CH = B/(8*NT) chunks.  Stages h < 512 run as above; the remaining
+// R = log2(B) - 9 stages (h = 512 ... B/2, still ascending) run as one radix-2^R pass
+// over LDS: a lane gathers the 2^R elements {g + 512 j}, does the R stages in registers
+// and scatters them back.  Then every lane re-reads its own chunks and finishes.
+template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
+__global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_per_row) {
+    constexpr int B = 1 << LOG2B;
+    constexpr int NT = (B / 8 < 256) ? B / 8 : 256;
+    constexpr int CH = B / 8 / NT;
+    constexpr int R = LOG2B - 9;
+    constexpr int RADIX = 1 << R;
+    constexpr int GROUPS_PER_LANE = 512 / NT;
+    extern __shared__ float lds[];   // B floats
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint32_t row = blockIdx.x / blocks_per_row, blk = blockIdx.x - row * blocks_per_row;
+    const int64_t xoff = (int64_t)row * a.ldx + (int64_t)blk * B;
+    const float sigma = (__builtin_popcount(lane) & 1) ? -1.0f : 1.0f;
+
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        float v[8];
+        uint32_t q = c * NT + tid;   // chunk index inside the block
+        load_chunk<IN_BF16>((const char*)a.x + (xoff + (int64_t)q * 8) * (IN_BF16 ? 2 : 4), v);
+        wht_inwave<9>(v, lane);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] *= sigma;   // exact: back to the true sign
+        float4* dst = reinterpret_cast<float4*>(lds + q * 8);
+        dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+        dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int gi = 0; gi < GROUPS_PER_LANE; ++gi) {
+        uint32_t g = gi * NT + tid;   // 0 .. 511
+        float r[RADIX];
+#pragma unroll
+        for (int j = 0; j < RADIX; ++j) r[j] = lds[g + 512 * j];
+#pragma unroll
+        for (int h = 1; h < RADIX; h *= 2) {
+#pragma unroll
+            for (int j = 0; j < RADIX; ++j) {
+                if ((j & h) == 0) {
+                    float p = r[j], m = r[j + h];
+                    r[j] = p + m;
+                    r[j + h] = p - m;
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < RADIX; ++j) lds[g + 512 * j] = r[j];
+    }
+    __syncthreads();
+    const float cn = as_f32(norm_bits(LOG2B));
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        uint32_t q = c * NT + tid;
+        const float4* src = reinterpret_cast<const float4*>(lds + q * 8);
+        float4 lo = src[0], hi = src[1];
+        float y[8] = {lo.x * cn, lo.y * cn, lo.z * cn, lo.w * cn, hi.x * cn, hi.y * cn, hi.z * cn, hi.w * cn};
+        if constexpr (MODE == MODE_ROTATE) {
+            int64_t yoff = (int64_t)row * a.ldy + (int64_t)blk * B + (int64_t)q * 8;
+            store_chunk<OUT_BF16>((char*)a.y + yoff * (OUT_BF16 ? 2 : 4), y);
+        } else {
+            uint32_t cglob = row * a.cpr + blk * (B / 8) + q;
+            quant_store(y, cglob, lane, a.codes, a.scales);
+        }
+    }
+}
+
+// ---- host side ---------------------------------------------------------------------
+
+static int g_rowwise_grid = 0;   // workgroups for the streaming kernels (0 = not yet computed)
+
+static int rowwise_grid(uint32_t nchunks, int U) {
+    if (g_rowwise_grid == 0) {
+        int dev = 0, cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess) {
+            int v = 0;
+            if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+        }
+        g_rowwise_grid = cus * 8;
+    }
+    uint32_t need = (nchunks + 256u * U - 1) / (256u * U);
+    return (int)(need < (uint32_t)g_rowwise_grid ? need : (uint32_t)g_rowwise_grid);
+}
+
+template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
+static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
+    constexpr int U = 2;
+    int grid = rowwise_grid(a.nchunks, U);
+    if (contig)
+        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, true, U>), dim3(grid), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, false, U>), dim3(grid), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
+static hipError_t launch_lds(const RowArgs& a, int64_t M, int64_t K, hipStream_t s) {
+    constexpr int B = 1 << LOG2B;
+    constexpr int NT = (B / 8 < 256) ? B / 8 : 256;
+    uint32_t bpr = (uint32_t)(K / B);
+    hipLaunchKernelGGL((k_rowwise_lds<LOG2B, IN_BF16, MODE, OUT_BF16>), dim3((uint32_t)(M * bpr)), dim3(NT),
+                       B * sizeof(float), s, a, bpr);
+    return hipGetLastError();
+}
+
+template <bool IN_BF16, int MODE, bool OUT_BF16>
+static hipError_t dispatch_b(int log2b, const RowArgs& a, bool contig, int64_t M, int64_t K, hipStream_t s) {
+    switch (log2b) {
+        case 5: return launch_inwave<5, IN_BF16, MODE, OUT_BF16>(a, contig, s);
+        case 6: return launch_inwave<6, IN_BF16, MODE, OUT_BF16>(a, contig, s);
+        case 7: return launch_inwave<7, IN_BF16, MODE, OUT_BF16>(a, contig, s);
+        case 8: return launch_inwave<8, IN_BF16, MODE, OUT_BF16>(a, contig, s);
+        case 9: return launch_inwave<9, IN_BF16, MODE, OUT_BF16>(a, contig, s);
+        case 10: return launch_lds<10, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
+        case 11: return launch_lds<11, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
+        case 12: return launch_lds<12, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
+        case 13: return launch_lds<13, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
+        case 14: return launch_lds<14, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// mode: RowMode; log2b: 0 for MODE_QUANT, else 5..14.  Arguments are already validated.
+hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
+                          int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
+                          hipStream_t s) {
+    RowArgs a;
+    a.x = x; a.y = y; a.codes = reinterpret_cast<uint32_t*>(codes); a.scales = scales;
+    a.ldx = ldx; a.ldy = ldy; a.cpr = (uint32_t)(K / 8); a.nchunks = (uint32_t)(M * (K / 8));
+    bool contig = (ldx == K) && (mode != MODE_ROTATE || ldy == K);
+    if (mode == MODE_ROTATE) {
+        if (in_bf16) return out_bf16 ? dispatch_b<true, MODE_ROTATE, true>(log2b, a, contig, M, K, s)
+                                     : dispatch_b<true, MODE_ROTATE, false>(log2b, a, contig, M, K, s);
+        return out_bf16 ? dispatch_b<false, MODE_ROTATE, true>(log2b, a, contig, M, K, s)
+                        : dispatch_b<false, MODE_ROTATE, false>(log2b, a, contig, M, K, s);
+    }
+    if (mode == MODE_QUANT)
+        return in_bf16 ? launch_inwave<0, true, MODE_QUANT, false>(a, contig, s)
+                       : launch_inwave<0, false, MODE_QUANT, false>(a, contig, s);
+    return in_bf16 ? dispatch_b<true, MODE_FUSED, false>(log2b, a, contig, M, K, s)
+                   : dispatch_b<false, MODE_FUSED, false>(log2b, a, contig, M, K, s);
+}
+
+}  // namespace brq

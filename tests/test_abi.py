@@ -1,0 +1,102 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/brq.h declares, and
+its host-side argument validation returns error codes without launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "brq.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2511_04214_amd as brq
+    return brq.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(brq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(L):
+    syms = declared_symbols()
+    assert {"brq_block_rotate", "brq_mxfp4_quantize", "brq_rotate_quantize_fused", "brq_mxfp4_gemm",
+            "brq_strerror", "brq_version"} <= set(syms)
+    for s in syms:
+        assert hasattr(L, s), "%s declared in brq.h but not exported" % s
+
+
+def test_binding_names_match_header():
+    import paper_2511_04214_amd as brq
+    for s in declared_symbols():
+        if s in ("brq_strerror", "brq_version"):
+            continue
+        assert hasattr(brq, s[len("brq_"):]), s
+    assert set(brq.EXPORTS) == set(declared_symbols())
+
+
+def test_version_and_strerror(L):
+    assert L.brq_version() >= 100
+    texts = [L.brq_strerror(i).decode() for i in range(7)]
+    assert texts[0] == "ok" and len(set(texts)) == 7
+    assert "unknown" in L.brq_strerror(99).decode()
+
+
+def test_argument_errors_before_any_launch(L):
+    OK, NULL, SHAPE, BLOCK, ALIGN, DTYPE = 0, 1, 2, 3, 4, 5
+    p = 0x1000  # never dereferenced: every call below fails validation on the host
+    q = ctypes.c_void_p
+    # null pointers
+    assert L.brq_mxfp4_quantize(None, 1, 4, 64, 64, q(p), q(p), None) == NULL
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 64, None, q(p), None) == NULL
+    assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, q(p), None, None) == NULL
+    assert L.brq_block_rotate(q(p), 1, 4, 64, 64, 32, None, 0, 64, None) == NULL
+    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), None, 4, 4, 64, q(p), 0, 4, None) == NULL
+    # shapes
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 48, 48, q(p), q(p), None) == SHAPE      # K % 32
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 32, q(p), q(p), None) == SHAPE      # ldx < K
+    assert L.brq_mxfp4_quantize(q(p), 1, -1, 64, 64, q(p), q(p), None) == SHAPE
+    assert L.brq_mxfp4_quantize(q(p), 1, 1 << 40, 64, 64, q(p), q(p), None) == SHAPE
+    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 4, 8, 64, q(p), 0, 4, None) == SHAPE   # ldy < N
+    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 4, 8, 40, q(p), 0, 8, None) == SHAPE
+    # dtype
+    assert L.brq_mxfp4_quantize(q(p), 7, 4, 64, 64, q(p), q(p), None) == DTYPE
+    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 4, 8, 64, q(p), 3, 8, None) == DTYPE
+    # rotation block
+    for B in (0, 16, 48, 128, 32768):
+        assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, B, q(p), q(p), None) == BLOCK, B
+    assert L.brq_block_rotate(q(p), 1, 4, 96, 96, 64, q(p), 0, 96, None) == BLOCK   # B does not divide K
+    # alignment
+    assert L.brq_mxfp4_quantize(q(p + 2), 1, 4, 64, 64, q(p), q(p), None) == ALIGN
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 68, q(p), q(p), None) == ALIGN      # pitch 136 B
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 64, q(p + 4), q(p), None) == ALIGN
+    assert L.brq_mxfp4_gemm(q(p), q(p + 8), q(p), q(p), 4, 6, 64, q(p), 0, 6, None) == ALIGN
+    # empty problems are fine and launch nothing
+    assert L.brq_mxfp4_quantize(q(p), 1, 0, 64, 64, q(p), q(p), None) == OK
+    assert L.brq_rotate_quantize_fused(q(p), 1, 0, 64, 64, 32, q(p), q(p), None) == OK
+    assert L.brq_block_rotate(q(p), 1, 0, 64, 64, 64, q(p), 0, 64, None) == OK
+    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 0, 8, 64, q(p), 0, 8, None) == OK
+    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 8, 0, 64, q(p), 0, 0, None) == OK
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_2511_04214_amd as brq
+    x = torch.zeros(2, 64)
+    with pytest.raises(ValueError):
+        brq.mxfp4_quantize(x)
+    with pytest.raises(ValueError):
+        brq.rotate_quantize_fused(x, 32)
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2511_04214_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "brq_oracle" not in text, f
