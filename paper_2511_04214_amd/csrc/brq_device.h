@@ -26,6 +26,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Two fp32 -> one dword of two bf16 (lo in the low half), round to nearest even:
+// v_cvt_pk_bf16_f32.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+
 // Value of `v` held by lane (lane ^ MASK).  MASK 1 and 2 stay inside a quad and fold
 // into the consuming VALU instruction as a DPP modifier; 4, 8, 16 use the swizzle
 // crossbar; 32 crosses the two halves of the wavefront.

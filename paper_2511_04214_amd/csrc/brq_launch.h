@@ -14,4 +14,10 @@ hipError_t launch_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t
                              int64_t M, int64_t N, int64_t K, void* y, bool out_bf16, int64_t ldy,
                              hipStream_t s);
 
+// Persistent LDS-staged kernel for large shapes (M, N multiples of 256, K a multiple of 512).
+bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy);
+hipError_t launch_gemm_tiled(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws,
+                             int64_t M, int64_t N, int64_t K, void* y, bool out_bf16, int64_t ldy,
+                             hipStream_t s);
+
 }  // namespace brq

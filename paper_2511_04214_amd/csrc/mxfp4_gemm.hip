@@ -103,10 +103,13 @@ __global__ void __launch_bounds__(256) k_gemm_skinny(const uint8_t* __restrict__
     }
 }
 
+
 hipError_t launch_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws,
                              int64_t M, int64_t N, int64_t K, void* y, bool out_bf16, int64_t ldy,
                              hipStream_t s) {
-    if (M <= 16) {
+    if (tiled_gemm_supported(M, N, K, out_bf16, ldy)) {
+        return launch_gemm_tiled(aq, as, wq, ws, M, N, K, y, out_bf16, ldy, s);
+    } else if (M <= 16) {
         dim3 grid((uint32_t)((N + 15) / 16));
         hipLaunchKernelGGL(k_gemm_skinny, grid, dim3(256), 0, s, aq, as, wq, ws, (int)M, (int)N, (int)K, y,
                            (int)out_bf16, ldy);
