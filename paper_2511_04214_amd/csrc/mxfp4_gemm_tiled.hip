@@ -23,13 +23,15 @@
 //
 // A ring of 4 code stages and 2 scale buffers runs continuously across the tiles a
 // workgroup processes: the next tile's first stages are loading during the current tile's
-// epilogue.  Per stage: the step-1 fragments are read from LDS while the 16 step-0 MFMAs
-// run; then one s_barrier (next stage has landed everywhere, this stage's buffer is free);
-// then the step-0 fragments of the next stage are read and the 10 loads that refill the
-// freed buffer are issued, one between each pair of the 16 step-1 MFMAs.
+// epilogue.  With one wavefront per SIMD nothing hides a stall, and the SIMD issues one
+// instruction per 4 cycles while a 32x32x64 fp4 MFMA occupies the matrix core for 32: every
+// gap between two MFMAs takes at most ~4 other instructions.  The stage body is therefore
+// laid out by hand as 32 slots of (1 MFMA + a few LDS reads / LDS-DMA loads), pinned with
+// scheduling barriers, and the K loop is unrolled by 4 so that every LDS address is an
+// immediate offset.
 //
 // LDS map (bytes): [0, 128K) 4 stages x (W rows 16K | A rows 16K); [128K, 144K) 2 scale
-// buffers x (W 4K | A 4K); [144K, 160K) epilogue staging, 4K per wavefront.
+// buffers x (W 4K | A 4K).
 #include "brq_device.h"
 #include "brq_launch.h"
 
@@ -39,17 +41,19 @@ namespace tiled {
 constexpr int TM = 256, TN = 256, KS = 128;
 constexpr int STAGE_BYTES = 32768, OPER_BYTES = 16384;
 constexpr int SCALE_BASE = 4 * STAGE_BYTES, SCALE_BUF = 8192, SCALE_OPER = 4096;
-constexpr int EPI_BASE = SCALE_BASE + 2 * SCALE_BUF, EPI_WAVE = 4096;
-constexpr int LDS_BYTES = EPI_BASE + 4 * EPI_WAVE;   // 163840 = all of a CU's LDS
+constexpr int LDS_BYTES = SCALE_BASE + 2 * SCALE_BUF;   // 147456
 
-// One LDS-DMA load: 64 lanes x 16 bytes from base + voff(lane) to LDS lds_addr + 16 * lane.
-// lds_addr and base must be wavefront-uniform (they travel in scalar registers / M0).
-__device__ __forceinline__ void load_lds16(uint32_t lds_addr, const uint8_t* base, uint32_t voff) {
-    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-    uint64_t b = (uint64_t)base;
-    uint32_t blo = __builtin_amdgcn_readfirstlane((uint32_t)b), bhi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-    base = (const uint8_t*)(((uint64_t)bhi << 32) | blo);
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n\t" ::"s"(lds_addr), "v"(voff), "s"(base) : "memory");
+template <int V>
+struct IC { static constexpr int value = V; };
+
+// One LDS-DMA load: 64 lanes x 16 bytes from base + voff(lane) + G_OFF to LDS
+// lds_base + LDS_OFF + 16 * lane.  The instruction's immediate offset is added to the global
+// AND the LDS address, so M0 is biased by -G_OFF.  lds_base and base must be wavefront-uniform.
+template <int LDS_OFF, int G_OFF>
+__device__ __forceinline__ void dma16(uint32_t lds_base, const uint8_t* base, uint32_t voff) {
+    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2 offset:%4\n\t"
+                 :: "s"(lds_base), "v"(voff), "s"(base), "n"(LDS_OFF - G_OFF), "n"(G_OFF)
+                 : "memory", "scc");
 }
 
 // Wait until at most N of this wavefront's vector-memory operations are outstanding and all
@@ -57,6 +61,12 @@ __device__ __forceinline__ void load_lds16(uint32_t lds_addr, const uint8_t* bas
 template <int N>
 __device__ __forceinline__ void wait_vm_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier\n\t" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p) {
+    uint64_t b = (uint64_t)p;
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    return (const uint8_t*)(((uint64_t)hi << 32) | lo);
 }
 
 // Tiles of one workgroup.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its
@@ -74,10 +84,26 @@ struct TileWalk {
     }
 };
 
-#define BRQ_MFMA(ACC, WF, AF, SEL, SW, SA)                                                                  \
-    ACC = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(v8i{WF[0], WF[1], WF[2], WF[3], 0, 0, 0, 0},     \
-                                                          v8i{AF[0], AF[1], AF[2], AF[3], 0, 0, 0, 0}, ACC, \
-                                                          4, 4, SEL, SW, SEL, SA)
+// The MFMAs are issued through volatile inline assembly: the compiler treats pure intrinsic
+// calls as freely movable and sinks all of a stage's MFMAs behind its memory operations,
+// which is the opposite of the interleaving this kernel lives on.  Volatile asm statements
+// keep their source order relative to each other and to the LDS reads.  The accumulator is
+// an AGPR tuple ("a"), the fragments are 4-register VGPR tuples; SEL picks scale byte 0 / 1.
+__device__ __forceinline__ void mfma_fp4(v16f& acc, const v4i& wf, const v4i& af, IC<0>, int sw, int sa) {
+    asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %4 op_sel_hi:[0,0,0] cbsz:4 blgp:4"
+                 : "+a"(acc) : "v"(wf), "v"(af), "v"(sw), "v"(sa));
+}
+__device__ __forceinline__ void mfma_fp4(v16f& acc, const v4i& wf, const v4i& af, IC<1>, int sw, int sa) {
+    asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %4 op_sel:[1,1,0] op_sel_hi:[0,0,0] cbsz:4 blgp:4"
+                 : "+a"(acc) : "v"(wf), "v"(af), "v"(sw), "v"(sa));
+}
+#define BRQ_MFMA(ACC, WF, AF, SEL, SW, SA) mfma_fp4(ACC, WF, AF, IC<SEL>{}, SW, SA)
+#define BRQ_SLOT_END() __builtin_amdgcn_sched_barrier(0)
+// Refill load S/2 of the stage goes into slot S for the wavefront pair with parity S & 1: the
+// four wavefronts re-align at every barrier, and the CU's one texture-address unit takes 16
+// cycles per 64-lane load, so at most two wavefronts may issue a load in the same 32-cycle
+// MFMA slot without stalling their next MFMA.
+#define BRQ_DMA_SLOT(S) do { if (pw == ((S) & 1)) dma_step(Uc, IC<(S) / 2>{}); } while (0)
 
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
@@ -88,6 +114,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, h = lane >> 5;
     const int wn = wave >> 1, wm = wave & 1;   // this wavefront's 128 W rows / 128 A rows inside the tile
+    const int pw = wave >> 1;                  // wavefront pair, for the staggered refill slots
 
     TileWalk tw;
     tw.tiles_m = M / TM;
@@ -100,229 +127,248 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         tw.stride = G >> 3;
     }
     const int ntiles = tw.first < tw.end ? (tw.end - tw.first + tw.stride - 1) / tw.stride : 0;
-    const int KT = K / KS;                    // stages per tile, a multiple of 4
+    if (ntiles == 0) return;                  // uniform over the workgroup
+    const int KQ = K / (4 * KS);              // 512-element superstages (4 stages) per tile
     const int64_t cpitch = K / 2, spitch = K / 32;
 
-    // per-lane constant parts of the global offsets
-    const uint32_t code_voff = (uint32_t)((lane >> 2) * cpitch + (((lane & 3) ^ ((lane >> 4) & 3)) << 4));
-    const uint32_t scale_voff = (uint32_t)(lane * spitch);
-
-    // ---- producer: the stage whose loads are issued next, as (stream index, tile, stage in tile)
-    int ig = 0, iti = 0, ikt = 0;
-    const uint8_t *t_w = nullptr, *t_a = nullptr, *t_ws = nullptr, *t_as = nullptr;   // rows of the producer's tile
-    const uint8_t *p_w = nullptr, *p_a = nullptr, *p_ws = nullptr, *p_as = nullptr;   // ... at the producer's stage
-    uint32_t p_lds = 0, p_sc = 0;
-    bool p_scales = false;
-    // Past the end of the stream (iti >= ntiles) the last tile is loaded again: 4 throw-away
-    // stages that nobody reads keep the number of loads in flight the same in every iteration.
-    auto issue_begin = [&]() {
-        if (ikt == 0) {   // new tile: the only place with an integer division
-            int tm, tn;
-            tw.tile(min(iti, ntiles - 1), tm, tn);
-            t_w = wq + ((int64_t)tn * TN + wave * 64) * cpitch;
-            t_a = aq + ((int64_t)tm * TM + wave * 64) * cpitch;
-            t_ws = ws + ((int64_t)tn * TN + wave * 64) * spitch;
-            t_as = as + ((int64_t)tm * TM + wave * 64) * spitch;
-        }
-        p_lds = lds0 + (ig & 3) * STAGE_BYTES + wave * 4096;
-        p_w = t_w + ikt * 64;
-        p_a = t_a + ikt * 64;
-        p_scales = (ikt & 3) == 0;
-        p_sc = lds0 + SCALE_BASE + ((ig >> 2) & 1) * SCALE_BUF + wave * 1024;
-        p_ws = t_ws + (ikt >> 2) * 16;
-        p_as = t_as + (ikt >> 2) * 16;
-        ++ig;
-        if (++ikt == KT) { ikt = 0; ++iti; }
-    };
-    // step 0..7: 16 rows x 64 bytes of codes each (W, A alternating); 8, 9: the scale rows
-    auto issue_step = [&](int i) {
-        if (i < 8) {
-            const int q = i >> 1;
-            if (i & 1) load_lds16(p_lds + OPER_BYTES + q * 1024, p_a + q * 16 * cpitch, code_voff);
-            else load_lds16(p_lds + q * 1024, p_w + q * 16 * cpitch, code_voff);
-        } else if (i == 8) {
-            load_lds16(p_sc, p_ws, scale_voff);
-        } else {
-            load_lds16(p_sc + SCALE_OPER, p_as, scale_voff);
-        }
-    };
-    auto issue_all = [&]() {
-        issue_begin();
-        if (p_scales) {   // scales first: they are then older than the stage's code loads
-            issue_step(8);
-            issue_step(9);
-        }
+    // ---- producer state.  The producer runs one superstage (4 stages) ahead of the MFMAs.
+    // Per-lane offsets: rows (lane >> 2) + 16 q of a 64-row slab, swizzled 16-byte chunk.
+    uint32_t vq[4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) issue_step(i);
+    for (int q = 0; q < 4; ++q)
+        vq[q] = (uint32_t)(((lane >> 2) + 16 * q) * cpitch + (((lane & 3) ^ ((lane >> 4) & 3)) << 4));
+    const uint32_t vsc = (uint32_t)(lane * spitch);
+    const uint32_t dma_lds = lds0 + wave * 4096;             // this wavefront's 64-row slab in a stage
+    const uint32_t dma_sc = lds0 + SCALE_BASE + wave * 1024; // ... and in a scale buffer
+    int p_tile = 0, p_kq = 0;                                 // producer position: tile index, superstage in tile
+    uint32_t p_buf = 0;                                       // byte offset of the scale buffer the producer fills next
+    const uint8_t *p_w = nullptr, *p_a = nullptr, *p_ws = nullptr, *p_as = nullptr;
+    // Past the end of the stream (p_tile >= ntiles) the last tile is loaded again: one throw-away
+    // superstage that nobody reads keeps the number of loads in flight the same in every iteration.
+    auto producer_next = [&]() {   // pointers of the next superstage; once per 128 MFMAs
+        if (p_kq == 0) {
+            int tm, tn;
+            tw.tile(min(p_tile, ntiles - 1), tm, tn);
+            p_w = uniform_ptr(wq + ((int64_t)tn * TN + wave * 64) * cpitch);
+            p_a = uniform_ptr(aq + ((int64_t)tm * TM + wave * 64) * cpitch);
+            p_ws = uniform_ptr(ws + ((int64_t)tn * TN + wave * 64) * spitch);
+            p_as = uniform_ptr(as + ((int64_t)tm * TM + wave * 64) * spitch);
+        } else {
+            p_w += 256; p_a += 256; p_ws += 16; p_as += 16;
+        }
+        if (++p_kq == KQ) { p_kq = 0; ++p_tile; }
+    };
+    // loads of stage U of the producer's superstage: I = 0, 1 the scale rows (U == 0 only, and
+    // first, so that they are older than the stage's code loads), I = 2..9 the code slabs
+    // (W and A alternating, 16 rows x 64 bytes each)
+    auto dma_step = [&](auto Uc, auto Ic) {
+        constexpr int U = decltype(Uc)::value, I = decltype(Ic)::value;
+        if constexpr (I == 0) {
+            if constexpr (U == 0) dma16<0, 0>(dma_sc + p_buf, p_ws, vsc);
+        } else if constexpr (I == 1) {
+            if constexpr (U == 0) dma16<SCALE_OPER, 0>(dma_sc + p_buf, p_as, vsc);
+        } else {
+            constexpr int q = (I - 2) >> 1;
+            if constexpr (((I - 2) & 1) == 0) dma16<U * STAGE_BYTES + q * 1024, U * 64>(dma_lds, p_w, vq[q]);
+            else dma16<U * STAGE_BYTES + OPER_BYTES + q * 1024, U * 64>(dma_lds, p_a, vq[q]);
+        }
+    };
+    auto dma_stage = [&](auto Uc) {
+        dma_step(Uc, IC<0>{}); dma_step(Uc, IC<1>{}); dma_step(Uc, IC<2>{}); dma_step(Uc, IC<3>{});
+        dma_step(Uc, IC<4>{}); dma_step(Uc, IC<5>{}); dma_step(Uc, IC<6>{}); dma_step(Uc, IC<7>{});
+        dma_step(Uc, IC<8>{}); dma_step(Uc, IC<9>{});
     };
 
-    // ---- consumer: MFMA-side LDS offsets (bytes) inside a stage / scale buffer
+    // ---- consumer: per-lane LDS read pointers.  [0]: stages 0-1, [1]: stages 2-3 (the
+    // immediate offset of a ds_read reaches 64 KB).
     const int sw = (r >> 2) & 3;
-    uint32_t woff[2], aoff[2];   // chunk of step j, rows of MFMA tile 0; tile t adds 32 rows = 2048 bytes
+    const uint8_t *wp[2][2], *ap[2][2];     // [stage pair][step j]
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        woff[j] = (wn * 128 + r) * 64 + (((2 * h + j) ^ sw) << 4);
-        aoff[j] = OPER_BYTES + (wm * 128 + r) * 64 + (((2 * h + j) ^ sw) << 4);
+        const uint32_t c16 = ((2 * h + j) ^ sw) << 4;
+        wp[0][j] = lds + (wn * 128 + r) * 64 + c16;
+        ap[0][j] = lds + OPER_BYTES + (wm * 128 + r) * 64 + c16;
+        wp[1][j] = wp[0][j] + 2 * STAGE_BYTES;
+        ap[1][j] = ap[0][j] + 2 * STAGE_BYTES;
     }
-    const uint32_t wsoff = SCALE_BASE + (wn * 128 + r) * 16, asoff = SCALE_BASE + SCALE_OPER + (wm * 128 + r) * 16;
+    const uint8_t* wsp = lds + SCALE_BASE + (wn * 128 + r) * 16;                 // scale rows, buffer 0
+    const uint8_t* asp = lds + SCALE_BASE + SCALE_OPER + (wm * 128 + r) * 16;
+    uint32_t c_buf = 0;                  // byte offset of the consumer's scale buffer
     const int hshift = h * 16;
 
-    v4i w0[4], a0[4], w1[4], a1[4];     // step-0 / step-1 operand fragments
-    int sws[4], sas[4], nws[4], nas[4]; // scale registers of the current / next stage
-    auto read_frags = [&](int stage, int j, v4i (&wf)[4], v4i (&af)[4]) {
-        const uint8_t* st = lds + (stage & 3) * STAGE_BYTES;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            wf[t] = *reinterpret_cast<const v4i*>(st + woff[j] + t * 2048);
-            af[t] = *reinterpret_cast<const v4i*>(st + aoff[j] + t * 2048);
-        }
+    v4i w0[4], a0[4], w1[4], a1[4];      // step-0 / step-1 operand fragments
+    int scw[2][4], sca[2][4];            // scale registers, [stage parity][MFMA tile]
+    v16f acc[4][4];                      // [W tile][A tile]
+
+    auto ld_w = [&](auto Uc, auto Jc, auto Tc) -> v4i {
+        constexpr int U = decltype(Uc)::value, J = decltype(Jc)::value, T = decltype(Tc)::value;
+        return *reinterpret_cast<const v4i*>(wp[U >> 1][J] + (U & 1) * STAGE_BYTES + T * 2048);
     };
-    auto read_scales = [&](int stage, int (&sw_)[4], int (&sa_)[4]) {
-        const uint8_t* sc = lds + ((stage >> 2) & 1) * SCALE_BUF + (stage & 3) * 4;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            sw_[t] = (int)(*reinterpret_cast<const uint32_t*>(sc + wsoff + t * 512) >> hshift);
-            sa_[t] = (int)(*reinterpret_cast<const uint32_t*>(sc + asoff + t * 512) >> hshift);
-        }
+    auto ld_a = [&](auto Uc, auto Jc, auto Tc) -> v4i {
+        constexpr int U = decltype(Uc)::value, J = decltype(Jc)::value, T = decltype(Tc)::value;
+        return *reinterpret_cast<const v4i*>(ap[U >> 1][J] + (U & 1) * STAGE_BYTES + T * 2048);
     };
 
-    if (ntiles == 0) return;   // uniform over the workgroup
+    // One stage (U = stage & 3).  Slots m0..m31 = MFMAs in (W tile a, A tile b) order, step 0
+    // then step 1.  F1 = step-1 fragments of this stage, N0 = step-0 fragments of the next.
+    //   m0..m7    one F1 read each (this stage landed before the previous barrier)
+    //   m11|m12   wait (next stage landed) + barrier (everyone is done reading this stage)
+    //   m12..m15  N0 W-fragments 0..2 (registers last used by m3, m7, m11); raw scale dwords
+    //   m16..m20  N0 W-fragment 3 and the A-fragments (registers free after m15)
+    //   m12..m31  the loads that refill this stage's buffer with stage + 4, every other slot
+    //   m26..m29  next stage's scale registers
+    auto stage = [&](auto Uc) {
+        constexpr int U = decltype(Uc)::value, P = U & 1, NU = (U + 1) & 3;
+        using N_ = IC<NU>;
+        using J0 = IC<0>;
+        using J1 = IC<1>;
+        int (&csw)[4] = scw[P];
+        int (&csa)[4] = sca[P];
+        int (&nsw)[4] = scw[P ^ 1];
+        int (&nsa)[4] = sca[P ^ 1];
+        const uint32_t nbuf = (U == 3) ? (c_buf ^ SCALE_BUF) : c_buf;   // scale buffer of the next stage
+        uint32_t rw[4], ra[4];
 
-    // ---- prologue: 4 stages in flight, first fragments in registers
-    issue_all();
-    issue_all();
-    issue_all();
-    issue_all();
-    wait_vm_and_barrier<24>();        // the 3 younger stages: 8 code loads each
-    read_frags(0, 0, w0, a0);
-    read_scales(0, sws, sas);
+        BRQ_MFMA(acc[0][0], w0[0], a0[0], 0, csw[0], csa[0]); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+        BRQ_MFMA(acc[0][1], w0[0], a0[1], 0, csw[0], csa[1]); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+        BRQ_MFMA(acc[0][2], w0[0], a0[2], 0, csw[0], csa[2]); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+        BRQ_MFMA(acc[0][3], w0[0], a0[3], 0, csw[0], csa[3]); a1[2] = ld_a(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
+        BRQ_MFMA(acc[1][0], w0[1], a0[0], 0, csw[1], csa[0]); a1[3] = ld_a(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
+        BRQ_MFMA(acc[1][1], w0[1], a0[1], 0, csw[1], csa[1]); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+        BRQ_MFMA(acc[1][2], w0[1], a0[2], 0, csw[1], csa[2]); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
+        BRQ_MFMA(acc[1][3], w0[1], a0[3], 0, csw[1], csa[3]); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
+        BRQ_MFMA(acc[2][0], w0[2], a0[0], 0, csw[2], csa[0]); BRQ_SLOT_END();
+        BRQ_MFMA(acc[2][1], w0[2], a0[1], 0, csw[2], csa[1]); BRQ_SLOT_END();
+        BRQ_MFMA(acc[2][2], w0[2], a0[2], 0, csw[2], csa[2]); BRQ_SLOT_END();
+        BRQ_MFMA(acc[2][3], w0[2], a0[3], 0, csw[2], csa[3]); BRQ_SLOT_END();
+        // younger than the next stage's loads: the two stages after it, 8 code loads each
+        wait_vm_and_barrier<16>();
+        BRQ_MFMA(acc[3][0], w0[3], a0[0], 0, csw[3], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(0); BRQ_SLOT_END();
+        BRQ_MFMA(acc[3][1], w0[3], a0[1], 0, csw[3], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(1); BRQ_SLOT_END();
+        BRQ_MFMA(acc[3][2], w0[3], a0[2], 0, csw[3], csa[2]); w0[2] = ld_w(N_{}, J0{}, IC<2>{});
+#pragma unroll
+        for (int t = 0; t < 4; ++t) rw[t] = *reinterpret_cast<const uint32_t*>(wsp + nbuf + NU * 4 + t * 512);
+        BRQ_DMA_SLOT(2); BRQ_SLOT_END();
+        BRQ_MFMA(acc[3][3], w0[3], a0[3], 0, csw[3], csa[3]);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) ra[t] = *reinterpret_cast<const uint32_t*>(asp + nbuf + NU * 4 + t * 512);
+        BRQ_DMA_SLOT(3); BRQ_SLOT_END();
 
-    int g = 0;
+        BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(4); BRQ_SLOT_END();
+        BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(5); BRQ_SLOT_END();
+        BRQ_MFMA(acc[0][2], w1[0], a1[2], 1, csw[0], csa[2]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(6); BRQ_SLOT_END();
+        BRQ_MFMA(acc[0][3], w1[0], a1[3], 1, csw[0], csa[3]); a0[2] = ld_a(N_{}, J0{}, IC<2>{}); BRQ_DMA_SLOT(7); BRQ_SLOT_END();
+        BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[3] = ld_a(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(8); BRQ_SLOT_END();
+        BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); BRQ_DMA_SLOT(9); BRQ_SLOT_END();
+        BRQ_MFMA(acc[1][2], w1[1], a1[2], 1, csw[1], csa[2]); BRQ_DMA_SLOT(10); BRQ_SLOT_END();
+        BRQ_MFMA(acc[1][3], w1[1], a1[3], 1, csw[1], csa[3]); BRQ_DMA_SLOT(11); BRQ_SLOT_END();
+        BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); BRQ_DMA_SLOT(12); BRQ_SLOT_END();
+        BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); BRQ_DMA_SLOT(13); BRQ_SLOT_END();
+        BRQ_MFMA(acc[2][2], w1[2], a1[2], 1, csw[2], csa[2]); nsw[0] = (int)(rw[0] >> hshift); nsw[1] = (int)(rw[1] >> hshift); BRQ_DMA_SLOT(14); BRQ_SLOT_END();
+        BRQ_MFMA(acc[2][3], w1[2], a1[3], 1, csw[2], csa[3]); nsw[2] = (int)(rw[2] >> hshift); nsw[3] = (int)(rw[3] >> hshift); BRQ_DMA_SLOT(15); BRQ_SLOT_END();
+        BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsa[0] = (int)(ra[0] >> hshift); nsa[1] = (int)(ra[1] >> hshift); BRQ_DMA_SLOT(16); BRQ_SLOT_END();
+        BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsa[2] = (int)(ra[2] >> hshift); nsa[3] = (int)(ra[3] >> hshift); BRQ_DMA_SLOT(17); BRQ_SLOT_END();
+        BRQ_MFMA(acc[3][2], w1[3], a1[2], 1, csw[3], csa[2]); BRQ_DMA_SLOT(18); BRQ_SLOT_END();
+        BRQ_MFMA(acc[3][3], w1[3], a1[3], 1, csw[3], csa[3]); BRQ_DMA_SLOT(19); BRQ_SLOT_END();
+    };
+
+    // ---- prologue: superstage 0 in flight, its first fragments in registers
+    producer_next();
+    dma_stage(IC<0>{});
+    dma_stage(IC<1>{});
+    dma_stage(IC<2>{});
+    dma_stage(IC<3>{});
+    producer_next();
+    p_buf ^= SCALE_BUF;
+    wait_vm_and_barrier<24>();        // stage 0 and its scales landed; stages 1..3 (24 loads) may be in flight
+    w0[0] = ld_w(IC<0>{}, IC<0>{}, IC<0>{}); w0[1] = ld_w(IC<0>{}, IC<0>{}, IC<1>{});
+    w0[2] = ld_w(IC<0>{}, IC<0>{}, IC<2>{}); w0[3] = ld_w(IC<0>{}, IC<0>{}, IC<3>{});
+    a0[0] = ld_a(IC<0>{}, IC<0>{}, IC<0>{}); a0[1] = ld_a(IC<0>{}, IC<0>{}, IC<1>{});
+    a0[2] = ld_a(IC<0>{}, IC<0>{}, IC<2>{}); a0[3] = ld_a(IC<0>{}, IC<0>{}, IC<3>{});
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        scw[0][t] = (int)(*reinterpret_cast<const uint32_t*>(wsp + t * 512) >> hshift);
+        sca[0][t] = (int)(*reinterpret_cast<const uint32_t*>(asp + t * 512) >> hshift);
+    }
+
+    uint8_t* const ybytes = reinterpret_cast<uint8_t*>(y);
     for (int ti = 0; ti < ntiles; ++ti) {
-        v16f acc[4][4];   // [W tile][A tile]
 #pragma unroll
         for (int a = 0; a < 4; ++a)
 #pragma unroll
             for (int b = 0; b < 4; ++b) acc[a][b] = v16f{};
 
-        for (int kt = 0; kt < KT; ++kt, ++g) {
-            // first half: step-1 fragments of this stage stream in behind the step-0 MFMAs
-            read_frags(g, 1, w1, a1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) BRQ_MFMA(acc[a][b], w0[a], a0[b], 0, sws[a], sas[b]);
-            __builtin_amdgcn_sched_barrier(0);
-
-            // This wavefront has read stage g completely; the next stage must have landed.  The
-            // stream is padded with 4 throw-away stages at its end (see issue_begin), so exactly
-            // two younger stages (16 code loads) are in flight here, always.
-            wait_vm_and_barrier<16>();
-            read_frags(g + 1, 0, w0, a0);
-            read_scales(g + 1, nws, nas);
-            __builtin_amdgcn_sched_barrier(0);
-
-            // second half: step-1 MFMAs, the refill loads spread between them
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    BRQ_MFMA(acc[a][b], w1[a], a1[b], 1, sws[a], sas[b]);
-                    const int idx = a * 4 + b;
-                    if (idx == 0) {
-                        issue_begin();                            // stage g+4 goes into stage g's buffer
-                        if (p_scales) { issue_step(8); issue_step(9); }
-                        __builtin_amdgcn_sched_barrier(0);
-                    } else if (idx <= 8) {
-                        issue_step(idx - 1);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) { sws[t] = nws[t]; sas[t] = nas[t]; }
+        for (int kq = 0; kq < KQ; ++kq) {
+            // the four stages below also load the producer's superstage, the next one of the stream
+            stage(IC<0>{});
+            stage(IC<1>{});
+            stage(IC<2>{});
+            stage(IC<3>{});
+            producer_next();
+            p_buf ^= SCALE_BUF;
+            c_buf ^= SCALE_BUF;
         }
 
-        // ---- epilogue: lane (r, h) holds, for W tile a / A tile b, output row m = b*32 + r and
-        // columns n = a*32 + 8q + 4h + {0..3}, q = 0..3.  Each wavefront transposes through its
-        // own 4 KB of LDS into full 128-byte row segments.
+        // ---- epilogue, straight from the accumulators.  Lane (r, h) holds, for W tile a and A
+        // tile b, output row m = 32 b + r and columns n = 32 a + 8 q + 4 h + {0..3}, q = 0..3.
+        // The accumulators were last written by MFMAs hidden in inline assembly: the compiler does
+        // not know to keep the 18 wait states between a 16-pass MFMA and a read of its result.
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
         int ti_e = ti;
         asm volatile("" : "+s"(ti_e));    // keeps the address arithmetic below out of the K loop
         int tm, tn;
         tw.tile(ti_e, tm, tn);
-        uint8_t* ep = lds + EPI_BASE + wave * EPI_WAVE;
-        const int64_t row0 = (int64_t)tm * TM + wm * 128, col0 = (int64_t)tn * TN + wn * 128;
-        const int rr0 = lane >> 3, ck = lane & 7;     // read-back: 16-byte chunk ck of rows rr0 + 8p
+        const int64_t row0 = (int64_t)tm * TM + wm * 128 + r, col0 = (int64_t)tn * TN + wn * 128;
         if constexpr (OUT_BF16) {
-            // pass = 32 output rows x 64 columns (two W tiles) = 32 x 128 bytes
-            uint8_t* yb = reinterpret_cast<uint8_t*>(y) + ((row0 + rr0) * ldy + col0 + ck * 8) * 2;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-#pragma unroll
-                for (int ap = 0; ap < 2; ++ap) {
-#pragma unroll
-                    for (int a2 = 0; a2 < 2; ++a2) {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const v16f& c = acc[ap * 2 + a2][b];
-                            uint2 pk;
-                            pk.x = pack_bf16x2(c[4 * q + 0], c[4 * q + 1]);
-                            pk.y = pack_bf16x2(c[4 * q + 2], c[4 * q + 3]);
-                            const int c8 = a2 * 8 + 2 * q + h;           // 8-byte column index 0..15
-                            *reinterpret_cast<uint2*>(ep + r * 128 + ((c8 ^ ((r & 7) << 1)) << 3)) = pk;
-                        }
-                    }
-                    // staging is private to the wavefront: only its own writes are read back
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) {
-                        const int rr = p * 8 + rr0;
-                        uint4 v = *reinterpret_cast<const uint4*>(ep + rr * 128 + ((ck ^ (rr & 7)) << 4));
-                        *reinterpret_cast<uint4*>(yb + ((int64_t)(b * 32 + p * 8) * ldy + ap * 64) * 2) = v;
-                    }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_sched_barrier(0);    // one pass at a time: keeps register pressure flat
-                }
-            }
-        } else {
-            // pass = 32 output rows x 32 columns (one W tile) = 32 x 128 bytes
-            uint8_t* yb = reinterpret_cast<uint8_t*>(y) + ((row0 + rr0) * ldy + col0 + ck * 4) * 4;
+            // v_permlane32_swap pairs q with q+1 across the lane halves: afterwards a lane holds 8
+            // consecutive columns (16 bytes): 32 a + 16 p + 8 h + {0..7}, p = 0, 1
+            uint8_t* yb = ybytes + (row0 * ldy + col0 + 8 * h) * 2;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
+                    const v16f& c = acc[a][b];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const v16f& c = acc[a][b];
-                        const int c16 = 2 * q + h;
-                        *reinterpret_cast<float4*>(ep + r * 128 + ((c16 ^ (r & 7)) << 4)) =
-                            make_float4(c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]);
+                    for (int p = 0; p < 2; ++p) {
+                        uint32_t x0 = pack_bf16x2(c[8 * p + 0], c[8 * p + 1]), x1 = pack_bf16x2(c[8 * p + 2], c[8 * p + 3]);
+                        uint32_t y0 = pack_bf16x2(c[8 * p + 4], c[8 * p + 5]), y1 = pack_bf16x2(c[8 * p + 6], c[8 * p + 7]);
+                        auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+                        auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+                        uint4 v = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+                        *reinterpret_cast<uint4*>(yb + ((int64_t)(b * 32) * ldy + a * 32 + 16 * p) * 2) = v;
                     }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) {
-                        const int rr = p * 8 + rr0;
-                        float4 v = *reinterpret_cast<const float4*>(ep + rr * 128 + ((ck ^ (rr & 7)) << 4));
-                        *reinterpret_cast<float4*>(yb + ((int64_t)(b * 32 + p * 8) * ldy + a * 32) * 4) = v;
-                    }
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_sched_barrier(0);
                 }
+                BRQ_SLOT_END();    // one A tile at a time keeps the register pressure flat
+            }
+        } else {
+            uint8_t* yb = ybytes + (row0 * ldy + col0 + 4 * h) * 4;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const v16f& c = acc[a][b];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<float4*>(yb + ((int64_t)(b * 32) * ldy + a * 32 + 8 * q) * 4) =
+                            make_float4(c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]);
+                }
+                BRQ_SLOT_END();
             }
         }
     }
-    // the throw-away stages are still in flight: let them land before the LDS is released
+    // the throw-away superstage is still in flight: let it land before the LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 #undef BRQ_MFMA
+#undef BRQ_SLOT_END
+#undef BRQ_DMA_SLOT
 
 }  // namespace tiled
 
 bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy) {
     return M > 0 && N > 0 && M % tiled::TM == 0 && N % tiled::TN == 0 && K % 512 == 0 &&
-           (ldy * (out_bf16 ? 2 : 4)) % 16 == 0 && (K / 2) * 16 < (int64_t(1) << 31);
+           (ldy * (out_bf16 ? 2 : 4)) % 16 == 0 && (K / 2) * 64 < (int64_t(1) << 31);
 }
 
 hipError_t launch_gemm_tiled(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws,
