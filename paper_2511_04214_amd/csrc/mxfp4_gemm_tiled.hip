@@ -41,7 +41,8 @@ namespace tiled {
 constexpr int TM = 256, TN = 256, KS = 128;
 constexpr int STAGE_BYTES = 32768, OPER_BYTES = 16384;
 constexpr int SCALE_BASE = 4 * STAGE_BYTES, SCALE_BUF = 8192, SCALE_OPER = 4096;
-constexpr int LDS_BYTES = SCALE_BASE + 2 * SCALE_BUF;   // 147456
+constexpr int EPI_BASE = SCALE_BASE + 2 * SCALE_BUF;    // 147456: one 4 KB output block per wavefront
+constexpr int LDS_BYTES = EPI_BASE + 4 * 4096;          // 163840, all of the CU's 160 KB
 
 template <int V>
 struct IC { static constexpr int value = V; };
@@ -61,6 +62,15 @@ __device__ __forceinline__ void dma16(uint32_t lds_base, const uint8_t* base, ui
 template <int N>
 __device__ __forceinline__ void wait_vm_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier\n\t" ::"n"(N) : "memory");
+}
+// The same, but the wait for global memory is skipped when `skip_vm` (wave-uniform) is non-zero.
+template <int N>
+__device__ __forceinline__ void wait_vm_unless_and_barrier(int skip_vm) {
+    asm volatile("s_cmp_lg_u32 %1, 0\n\t"
+                 "s_cbranch_scc1 .Lbrq_novm%=\n\t"
+                 "s_waitcnt vmcnt(%0)\n"
+                 ".Lbrq_novm%=:\n\t"
+                 "s_waitcnt lgkmcnt(0)\n\ts_barrier\n\t" ::"n"(N), "s"(skip_vm) : "memory", "scc");
 }
 
 __device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p) {
@@ -217,6 +227,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     //   m16..m20  N0 W-fragment 3 and the A-fragments (registers free after m15)
     //   m12..m31  the loads that refill this stage's buffer with stage + 4, every other slot
     //   m26..m29  next stage's scale registers
+    int fresh = 1;    // 1 during the first superstage of a tile
     auto stage = [&](auto Uc) {
         constexpr int U = decltype(Uc)::value, P = U & 1, NU = (U + 1) & 3;
         using N_ = IC<NU>;
@@ -241,8 +252,13 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         BRQ_MFMA(acc[2][1], w0[2], a0[1], 0, csw[2], csa[1]); BRQ_SLOT_END();
         BRQ_MFMA(acc[2][2], w0[2], a0[2], 0, csw[2], csa[2]); BRQ_SLOT_END();
         BRQ_MFMA(acc[2][3], w0[2], a0[3], 0, csw[2], csa[3]); BRQ_SLOT_END();
-        // younger than the next stage's loads: the two stages after it, 8 code loads each
-        wait_vm_and_barrier<16>();
+        // Younger than the next stage's loads: the two stages after it, 8 code loads each.  The
+        // first three stages of a tile find their data landed (everything in flight was waited
+        // for before the previous epilogue) and must not wait: the counter still holds that
+        // epilogue's stores, which drain behind these stages.  From the fourth stage on the stores
+        // are older than every load that is waited for, so counting stays safe.
+        if constexpr (U == 3) wait_vm_and_barrier<16>();
+        else wait_vm_unless_and_barrier<16>(fresh);
         BRQ_MFMA(acc[3][0], w0[3], a0[0], 0, csw[3], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(0); BRQ_SLOT_END();
         BRQ_MFMA(acc[3][1], w0[3], a0[1], 0, csw[3], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(1); BRQ_SLOT_END();
         BRQ_MFMA(acc[3][2], w0[3], a0[2], 0, csw[3], csa[2]); w0[2] = ld_w(N_{}, J0{}, IC<2>{});
@@ -280,7 +296,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     dma_stage(IC<3>{});
     producer_next();
     p_buf ^= SCALE_BUF;
-    wait_vm_and_barrier<24>();        // stage 0 and its scales landed; stages 1..3 (24 loads) may be in flight
+    wait_vm_and_barrier<0>();         // superstage 0 landed: the state every later tile starts from
     w0[0] = ld_w(IC<0>{}, IC<0>{}, IC<0>{}); w0[1] = ld_w(IC<0>{}, IC<0>{}, IC<1>{});
     w0[2] = ld_w(IC<0>{}, IC<0>{}, IC<2>{}); w0[3] = ld_w(IC<0>{}, IC<0>{}, IC<3>{});
     a0[0] = ld_a(IC<0>{}, IC<0>{}, IC<0>{}); a0[1] = ld_a(IC<0>{}, IC<0>{}, IC<1>{});
@@ -292,6 +308,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     }
 
     uint8_t* const ybytes = reinterpret_cast<uint8_t*>(y);
+    uint8_t* const ebuf = lds + EPI_BASE + wave * 4096;
     for (int ti = 0; ti < ntiles; ++ti) {
 #pragma unroll
         for (int a = 0; a < 4; ++a)
@@ -307,10 +324,24 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             producer_next();
             p_buf ^= SCALE_BUF;
             c_buf ^= SCALE_BUF;
+            fresh = 0;
         }
+        fresh = 1;
+        // Let the four stages in flight land now.  The epilogue's stores count in the same vmcnt
+        // as the loads and complete out of order with them, so no load that is older than a
+        // store may be waited for by count.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-        // ---- epilogue, straight from the accumulators.  Lane (r, h) holds, for W tile a and A
-        // tile b, output row m = 32 b + r and columns n = 32 a + 8 q + 4 h + {0..3}, q = 0..3.
+        // ---- epilogue.  Lane (r, h) holds, for W tile a and A tile b, output row m = 32 b + r and
+        // columns n = 32 a + 8 q + 4 h + {0..3}, q = 0..3: neighbouring lanes hold different rows.
+        // The store path merges the 16-byte accesses of neighbouring lanes only, so storing from
+        // this layout costs one cycle per lane (64 per instruction, 8K per tile).  Each wavefront
+        // therefore turns its output round in a private 4 KB LDS block, 32 rows x 128 bytes at a
+        // time: written as 16-byte chunks from the accumulator layout, read back with 8
+        // consecutive lanes per row, stored as 8 rows x 128 contiguous bytes per instruction.
+        // Chunk c of row i sits at i * 128 + ((c ^ (i & 7)) << 4): 8 lanes that write (8 rows, one
+        // chunk) or read (one row, 8 chunks) then cover all 32 banks.  LDS operations of one
+        // wavefront execute in order, so write -> read -> next write need no waits.
         // The accumulators were last written by MFMAs hidden in inline assembly: the compiler does
         // not know to keep the 18 wait states between a 16-pass MFMA and a read of its result.
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
@@ -318,42 +349,72 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         asm volatile("" : "+s"(ti_e));    // keeps the address arithmetic below out of the K loop
         int tm, tn;
         tw.tile(ti_e, tm, tn);
-        const int64_t row0 = (int64_t)tm * TM + wm * 128 + r, col0 = (int64_t)tn * TN + wn * 128;
+        constexpr int ES = OUT_BF16 ? 2 : 4;
+        const int64_t pitch = ldy * ES;
+        uint8_t* const ytile = ybytes + ((int64_t)tm * TM + wm * 128) * pitch + ((int64_t)tn * TN + wn * 128) * ES;
+        const uint32_t st_off = (uint32_t)(lane >> 3) * (uint32_t)pitch + (lane & 7) * 16;
+        uint8_t* const ewr = ebuf + r * 128;                     // this lane's row for writing
+        const uint32_t wsw = (uint32_t)((r & 7) ^ h) << 4;        // its chunk swizzle, h folded in
+        const uint8_t* const erd = ebuf + (lane >> 3) * 128 + (((lane & 7) ^ ((lane >> 3) & 7)) << 4);
+        uint4 o0, o1, o2, o3;    // the block read back: rows (lane >> 3) + 8 j, j = 0..3
+        auto read_block = [&]() {
+            o0 = *reinterpret_cast<const uint4*>(erd);
+            o1 = *reinterpret_cast<const uint4*>(erd + 1024);
+            o2 = *reinterpret_cast<const uint4*>(erd + 2048);
+            o3 = *reinterpret_cast<const uint4*>(erd + 3072);
+        };
+        auto store_block = [&](int row, int colbytes) {
+            uint8_t* dst = ytile + row * pitch + colbytes;
+            *reinterpret_cast<uint4*>(dst + st_off) = o0;
+            *reinterpret_cast<uint4*>(dst + st_off + 8 * pitch) = o1;
+            *reinterpret_cast<uint4*>(dst + st_off + 16 * pitch) = o2;
+            *reinterpret_cast<uint4*>(dst + st_off + 24 * pitch) = o3;
+        };
         if constexpr (OUT_BF16) {
-            // v_permlane32_swap pairs q with q+1 across the lane halves: afterwards a lane holds 8
-            // consecutive columns (16 bytes): 32 a + 16 p + 8 h + {0..7}, p = 0, 1
-            uint8_t* yb = ybytes + (row0 * ldy + col0 + 8 * h) * 2;
+            // block = (b, pair of W tiles): 32 rows x 64 columns.  v_permlane32_swap trades q
+            // between the lane halves: a lane then holds columns 32 a + 16 p + 8 h + {0..7},
+            // p = 0, 1, as one chunk, index (a & 1) * 4 + 2 p + h within the block's row
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
+            for (int blk = 0; blk < 8; ++blk) {
+                const int b = blk >> 1, ap = blk & 1;
+                uint4 ch[2][2];
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const v16f& c = acc[a][b];
+                for (int a1 = 0; a1 < 2; ++a1) {
+                    const v16f& c = acc[2 * ap + a1][b];
 #pragma unroll
                     for (int p = 0; p < 2; ++p) {
                         uint32_t x0 = pack_bf16x2(c[8 * p + 0], c[8 * p + 1]), x1 = pack_bf16x2(c[8 * p + 2], c[8 * p + 3]);
                         uint32_t y0 = pack_bf16x2(c[8 * p + 4], c[8 * p + 5]), y1 = pack_bf16x2(c[8 * p + 6], c[8 * p + 7]);
                         auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
                         auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
-                        uint4 v = make_uint4(s0[0], s1[0], s0[1], s1[1]);
-                        *reinterpret_cast<uint4*>(yb + ((int64_t)(b * 32) * ldy + a * 32 + 16 * p) * 2) = v;
+                        ch[a1][p] = make_uint4(s0[0], s1[0], s0[1], s1[1]);
                     }
                 }
-                BRQ_SLOT_END();    // one A tile at a time keeps the register pressure flat
+                BRQ_SLOT_END();
+#pragma unroll
+                for (int a1 = 0; a1 < 2; ++a1)
+#pragma unroll
+                    for (int p = 0; p < 2; ++p)
+                        *reinterpret_cast<uint4*>(ewr + (wsw ^ (uint32_t)((a1 * 4 + 2 * p) << 4))) = ch[a1][p];
+                if (blk > 0) store_block(((blk - 1) >> 1) * 32, ((blk - 1) & 1) * 128);   // the block read before
+                read_block();
+                BRQ_SLOT_END();    // one block at a time keeps the register pressure flat
             }
+            store_block(3 * 32, 128);
         } else {
-            uint8_t* yb = ybytes + (row0 * ldy + col0 + 4 * h) * 4;
+            // block = one accumulator: 32 rows x 32 columns; chunk index 2 q + h
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
+            for (int blk = 0; blk < 16; ++blk) {
+                const int b = blk >> 2, a = blk & 3;
+                const v16f& c = acc[a][b];
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const v16f& c = acc[a][b];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        *reinterpret_cast<float4*>(yb + ((int64_t)(b * 32) * ldy + a * 32 + 8 * q) * 4) =
-                            make_float4(c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]);
-                }
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<float4*>(ewr + (wsw ^ (uint32_t)(q << 5))) = make_float4(c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]);
+                if (blk > 0) store_block(((blk - 1) >> 2) * 32, ((blk - 1) & 3) * 128);
+                read_block();
                 BRQ_SLOT_END();
             }
+            store_block(3 * 32, 3 * 128);
         }
     }
     // the throw-away superstage is still in flight: let it land before the LDS is released
@@ -368,7 +429,8 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 
 bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy) {
     return M > 0 && N > 0 && M % tiled::TM == 0 && N % tiled::TN == 0 && K % 512 == 0 &&
-           (ldy * (out_bf16 ? 2 : 4)) % 16 == 0 && (K / 2) * 64 < (int64_t(1) << 31);
+           (ldy * (out_bf16 ? 2 : 4)) % 16 == 0 && ldy * (out_bf16 ? 2 : 4) < (int64_t(1) << 28) &&
+           (K / 2) * 64 < (int64_t(1) << 31);
 }
 
 hipError_t launch_gemm_tiled(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws,
