@@ -26,15 +26,18 @@ struct RowArgs {
 
 // ---- chunk load / store ---------------------------------------------------------
 
+// X is read exactly once and the outputs are next touched by another kernel: loads and stores
+// carry the non-temporal hint, so the stream does not displace what the caches hold (on a
+// 16 B in / 4 B out stream this alone is worth about 10% of HBM throughput).
 template <bool BF16>
 __device__ __forceinline__ void load_chunk(const void* p, float (&v)[8]) {
     if constexpr (BF16) {
-        uint4 w = *reinterpret_cast<const uint4*>(p);
-        v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x); v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
-        v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z); v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
+        v4i w = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
+        v[0] = bf16_lo((uint32_t)w.x); v[1] = bf16_hi((uint32_t)w.x); v[2] = bf16_lo((uint32_t)w.y); v[3] = bf16_hi((uint32_t)w.y);
+        v[4] = bf16_lo((uint32_t)w.z); v[5] = bf16_hi((uint32_t)w.z); v[6] = bf16_lo((uint32_t)w.w); v[7] = bf16_hi((uint32_t)w.w);
     } else {
-        float4 a = reinterpret_cast<const float4*>(p)[0];
-        float4 b = reinterpret_cast<const float4*>(p)[1];
+        v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+        v4f b = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p) + 1);
         v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
     }
 }
@@ -42,15 +45,15 @@ __device__ __forceinline__ void load_chunk(const void* p, float (&v)[8]) {
 template <bool BF16>
 __device__ __forceinline__ void store_chunk(void* p, const float (&v)[8]) {
     if constexpr (BF16) {
-        uint4 w;
-        w.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
-        w.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
-        w.z = f32_to_bf16_bits(v[4]) | (f32_to_bf16_bits(v[5]) << 16);
-        w.w = f32_to_bf16_bits(v[6]) | (f32_to_bf16_bits(v[7]) << 16);
-        *reinterpret_cast<uint4*>(p) = w;
+        v4i w;
+        w.x = (int)(f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16));
+        w.y = (int)(f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16));
+        w.z = (int)(f32_to_bf16_bits(v[4]) | (f32_to_bf16_bits(v[5]) << 16));
+        w.w = (int)(f32_to_bf16_bits(v[6]) | (f32_to_bf16_bits(v[7]) << 16));
+        __builtin_nontemporal_store(w, reinterpret_cast<v4i*>(p));
     } else {
-        reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
-        reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+        __builtin_nontemporal_store(v4f{v[0], v[1], v[2], v[3]}, reinterpret_cast<v4f*>(p));
+        __builtin_nontemporal_store(v4f{v[4], v[5], v[6], v[7]}, reinterpret_cast<v4f*>(p) + 1);
     }
 }
 
@@ -91,8 +94,8 @@ __host__ __device__ constexpr uint32_t norm_bits(int log2b) {
 __device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t c, uint32_t lane,
                                             uint32_t* codes, uint8_t* scales) {
     uint32_t sb = e8m0_from_amax(quad_max(absmax8(y)));
-    codes[c] = encode8_e2m1(y, sb);
-    if ((lane & 3) == 0) scales[c >> 2] = (uint8_t)sb;
+    __builtin_nontemporal_store(encode8_e2m1(y, sb), &codes[c]);
+    if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, &scales[c >> 2]);
 }
 
 // One chunk per lane per step, U steps in flight.  LOG2B = 0 means "no rotation".
@@ -132,8 +135,8 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
                 uint32_t sb = e8m0_from_amax(quad_max(absmax8(v[u])));
                 uint32_t w = encode8_e2m1(v[u], sb);
                 if (live) {
-                    a.codes[c] = w;
-                    if ((lane & 3) == 0) a.scales[c >> 2] = (uint8_t)sb;
+                    __builtin_nontemporal_store(w, &a.codes[c]);
+                    if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, &a.scales[c >> 2]);
                 }
             }
         }
@@ -215,24 +218,34 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
 
 // ---- host side ---------------------------------------------------------------------
 
-static int g_rowwise_grid = 0;   // workgroups for the streaming kernels (0 = not yet computed)
+static int g_rowwise_cus = 0;   // compute units of the device (0 = not yet asked)
 
+// Workgroups of a streaming launch.  Measured on X 16384 x 8192 (bf16, B = 32): one chunk in
+// flight per lane and many short-lived workgroups beat a persistent grid (8 per CU, two
+// chunks in flight: 63 us; 64 per CU, one chunk: 55 us): the dispatcher keeps every CU topped up
+// and the loads of a finished workgroup's successor overlap the arithmetic of its neighbours.
+// Each workgroup still makes about 4 passes so that small inputs do not pay for launching
+// thousands of workgroups.
 static int rowwise_grid(uint32_t nchunks, int U) {
-    if (g_rowwise_grid == 0) {
+    if (g_rowwise_cus == 0) {
         int dev = 0, cus = 256;
         if (hipGetDevice(&dev) == hipSuccess) {
             int v = 0;
             if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
         }
-        g_rowwise_grid = cus * 8;
+        g_rowwise_cus = cus;
     }
-    uint32_t need = (nchunks + 256u * U - 1) / (256u * U);
-    return (int)(need < (uint32_t)g_rowwise_grid ? need : (uint32_t)g_rowwise_grid);
+    const uint32_t need = (nchunks + 256u * U - 1) / (256u * U);
+    uint32_t grid = need / 4;
+    const uint32_t lo = (uint32_t)g_rowwise_cus * 8, hi = (uint32_t)g_rowwise_cus * 64;
+    if (grid < lo) grid = lo;
+    if (grid > hi) grid = hi;
+    return (int)(need < grid ? need : grid);
 }
 
 template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
 static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
-    constexpr int U = 2;
+    constexpr int U = 1;
     int grid = rowwise_grid(a.nchunks, U);
     if (contig)
         hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, true, U>), dim3(grid), dim3(256), 0, s, a);
