@@ -11,7 +11,7 @@ quoted on X 16384x8192, measured in the same run and reported under "rotate_quan
 Prints ONE JSON line.
   value        whole-step throughput: 2*M*N*K useful flops of the layer per second of step
                time (rotate+quantize included), TFLOP/s
-  kernels      per-kernel averages from HIP events recorded on the launch stream
+  kernels      per-kernel averages: back-to-back launch trains between HIP events on the launch stream
   roofline     the dominant kernel of the step against its roof
   cpu_baseline the C oracle on a bounded sample of the same workload, on the host cores
 Buffers rotate through several sets so that no step finds its operands in the 256 MB
@@ -29,11 +29,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MXFP4_PEAK_TFLOPS = 10100.0      # MI355X dense fp4 MFMA, published
 BYTES_PER_ELEM = 2 + 0.5 + 1.0 / 32     # bf16 in, 4-bit code out, one scale byte per 32
-
-
-def event_ms(pairs):
-    import numpy as np
-    return np.array([a.elapsed_time(b) for a, b in pairs])
+# Bytes per launch that leave the L2s (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, scaled by a plain copy
+# of known size), from the committed counter summary under profiles/; a counter run is not part of a
+# bench run, so other workloads report null.
+PROFILED_TRAFFIC = {"mxfp4_gemm_mlp8b_bf16": 619.9e6, "rotate_quant_16384x8192": 341.3e6}
 
 
 def main():
@@ -45,6 +44,9 @@ def main():
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-aux", action="store_true", help="skip the 16384x8192 rotate+quantize measurement")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy 4 times (reference for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (rows shard without "
@@ -89,16 +91,10 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    def step(i, evs=None):
+    def step(i):
         j = i % nsets
-        if evs:
-            evs[0].record(stream)
         brq.rotate_quantize_fused(xs[j], B, codes=codes[j], scales=scales[j], stream=stream)
-        if evs:
-            evs[1].record(stream)
         brq.mxfp4_gemm(codes[j][:gemm_M], scales[j][:gemm_M], wqs[j], wss[j], out=ys[j], stream=stream)
-        if evs:
-            evs[2].record(stream)
 
     for i in range(args.warmup):
         step(i)
@@ -110,14 +106,23 @@ def main():
     stream.synchronize()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per = []
-    for i in range(args.steps):
-        e = [ev(), ev(), ev()]
-        step(i, e)
-        per.append(e)
-    stream.synchronize()
-    rq_ms = event_ms([(e[0], e[1]) for e in per])
-    gm_ms = event_ms([(e[1], e[2]) for e in per])
+    # Per-kernel time: a train of back-to-back launches of that kernel alone between two events on the
+    # launch stream, repeated 5 times (a pair of events around every single launch would add the
+    # launch gap, 5-6 us, to the short row-wise kernel).
+    def train(launch, reps=5):
+        out = []
+        for _ in range(reps):
+            a, b = ev(), ev()
+            a.record(stream)
+            for i in range(args.steps):
+                launch(i % nsets)
+            b.record(stream)
+            stream.synchronize()
+            out.append(a.elapsed_time(b) / args.steps)
+        return np.array(out)
+
+    rq_ms = train(lambda j: brq.rotate_quantize_fused(xs[j], B, codes=codes[j], scales=scales[j], stream=stream))
+    gm_ms = train(lambda j: brq.mxfp4_gemm(codes[j][:gemm_M], scales[j][:gemm_M], wqs[j], wss[j], out=ys[j], stream=stream))
 
     ms_per_step = wall * 1e3 / args.steps
     rq_bytes = M * K * BYTES_PER_ELEM
@@ -140,7 +145,7 @@ def main():
     else:
         roofline = {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": kernels["mxfp4_gemm"]["TFLOP/s"],
                     "peak": MXFP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": kernels["mxfp4_gemm"]["frac_mxfp4_peak"],
-                    "traffic": None}
+                    "traffic": PROFILED_TRAFFIC.get("mxfp4_gemm_%s_%s" % (args.workload, args.out_dtype))}
 
     # ---- the rotate+quantize kernel on the shape its HBM target is quoted on
     aux = None
@@ -158,32 +163,41 @@ def main():
         for i in range(args.warmup):
             brq.rotate_quantize_fused(axs[i % 3], B, codes=ac[i % 3], scales=asc[i % 3], stream=stream)
         stream.synchronize()
-        pairs = []
-        for i in range(args.steps):
+        ams = []
+        for _ in range(5):
             a, b = ev(), ev()
             a.record(stream)
-            brq.rotate_quantize_fused(axs[i % 3], B, codes=ac[i % 3], scales=asc[i % 3], stream=stream)
+            for i in range(args.steps):
+                brq.rotate_quantize_fused(axs[i % 3], B, codes=ac[i % 3], scales=asc[i % 3], stream=stream)
             b.record(stream)
-            pairs.append((a, b))
-        stream.synchronize()
-        ams = event_ms(pairs)
+            stream.synchronize()
+            ams.append(a.elapsed_time(b) / args.steps)
+        ams = np.array(ams)
         ab = aM * aK * BYTES_PER_ELEM
         aux = {"kernel": "rotate_quantize_fused", "bound": "hbm", "avg_ms": float(ams.mean()),
                "min_ms": float(ams.min()), "alg_bytes": ab, "achieved": ab / float(ams.mean()) / 1e6,
                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ab / float(ams.mean()) / 1e6 / HBM_PEAK_GBS,
-               "traffic": None}
+               "traffic": PROFILED_TRAFFIC["rotate_quant_16384x8192"]}
         del axs, ac, asc
+
+    if args.calibrate_copy:
+        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
         o = oracle.default()
         threads = o.get_threads()
-        rows = int(min(M, max(64, 6e7 // K)))                 # a few seconds of oracle work
+        rows = int(min(M, max(64, 6e7 // K)))
         t0 = time.perf_counter()
         rc, rs = o.rotate_quantize_fused(x_np[:rows], B)
         t_rq = time.perf_counter() - t0
-        grows = int(min(gemm_M, rows, max(1, 6e9 // (N * K))))
+        grows = int(min(gemm_M, rows, max(1, 2e11 // (N * K))))       # some 10 s of oracle work
         wq_h, ws_h = wq0.cpu().numpy(), ws0.cpu().numpy()
         t0 = time.perf_counter()
         o.mxfp4_gemm(rc[:grows], rs[:grows], wq_h, ws_h, want_bound=False)
