@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mlp8b", help="llama1b_up | down_sweep | mlp8b | decode")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--layout", default="tiled", choices=["tiled", "rowmajor"],
+                    help="layout of the quantized operands between the two kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-aux", action="store_true", help="skip the 16384x8192 rotate+quantize measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -74,7 +76,8 @@ def main():
 
     x_np = inputs.make_x(cfg)
     w_np = inputs.make_w(cfg)
-    wq0, ws0 = brq.rotate_quantize_fused(to_dev(w_np), B)          # offline weight preparation
+    LAY = args.layout
+    wq0, ws0 = brq.rotate_quantize_fused(to_dev(w_np), B, layout=LAY)          # offline weight preparation
     del w_np
     set_bytes = M * K * BYTES_PER_ELEM + N * K * 0.53125 + gemm_M * N * out_es
     nsets = int(max(2, min(6, 600e6 // set_bytes + 1)))
@@ -83,8 +86,19 @@ def main():
         xs[i] = xs[0].clone()
     wqs = [wq0] + [wq0.clone() for _ in range(nsets - 1)]
     wss = [ws0] + [ws0.clone() for _ in range(nsets - 1)]
-    codes = [torch.empty((M, K // 2), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
-    scales = [torch.empty((M, K // 32), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    cbytes, sbytes = brq.operand_bytes(M, K, LAY)
+    cshape, sshape = ((M, K // 2), (M, K // 32)) if LAY == "rowmajor" else ((cbytes,), (sbytes,))
+    codes = [torch.empty(cshape, dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    scales = [torch.empty(sshape, dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+
+    def rq(j):
+        brq.rotate_quantize_fused(xs[j], B, codes=codes[j], scales=scales[j], stream=stream, layout=LAY)
+
+    def gemm(j):
+        # the product reads the first gemm_M rows of the quantized activations (all of them but for "decode")
+        a_c, a_s = (codes[j][:gemm_M], scales[j][:gemm_M]) if LAY == "rowmajor" else (codes[j], scales[j])
+        brq.mxfp4_gemm(a_c, a_s, wqs[j], wss[j], out=ys[j], stream=stream, a_layout=LAY, w_layout=LAY,
+                       M=gemm_M, N=N, K=K)
     ys = [torch.empty((gemm_M, N), dtype=out_dtype, device="cuda") for _ in range(nsets)]
     stream = torch.cuda.Stream()
 
@@ -93,8 +107,8 @@ def main():
 
     def step(i):
         j = i % nsets
-        brq.rotate_quantize_fused(xs[j], B, codes=codes[j], scales=scales[j], stream=stream)
-        brq.mxfp4_gemm(codes[j][:gemm_M], scales[j][:gemm_M], wqs[j], wss[j], out=ys[j], stream=stream)
+        rq(j)
+        gemm(j)
 
     for i in range(args.warmup):
         step(i)
@@ -121,8 +135,8 @@ def main():
             out.append(a.elapsed_time(b) / args.steps)
         return np.array(out)
 
-    rq_ms = train(lambda j: brq.rotate_quantize_fused(xs[j], B, codes=codes[j], scales=scales[j], stream=stream))
-    gm_ms = train(lambda j: brq.mxfp4_gemm(codes[j][:gemm_M], scales[j][:gemm_M], wqs[j], wss[j], out=ys[j], stream=stream))
+    rq_ms = train(rq)
+    gm_ms = train(gemm)
 
     ms_per_step = wall * 1e3 / args.steps
     rq_bytes = M * K * BYTES_PER_ELEM
@@ -158,17 +172,18 @@ def main():
         axs = [to_dev(ax_np)]
         axs.append(axs[0].clone())
         axs.append(axs[0].clone())
-        ac = [torch.empty((aM, aK // 2), dtype=torch.uint8, device="cuda") for _ in range(3)]
-        asc = [torch.empty((aM, aK // 32), dtype=torch.uint8, device="cuda") for _ in range(3)]
+        acb, asb = brq.operand_bytes(aM, aK, LAY)
+        ac = [torch.empty((aM, aK // 2) if LAY == "rowmajor" else (acb,), dtype=torch.uint8, device="cuda") for _ in range(3)]
+        asc = [torch.empty((aM, aK // 32) if LAY == "rowmajor" else (asb,), dtype=torch.uint8, device="cuda") for _ in range(3)]
         for i in range(args.warmup):
-            brq.rotate_quantize_fused(axs[i % 3], B, codes=ac[i % 3], scales=asc[i % 3], stream=stream)
+            brq.rotate_quantize_fused(axs[i % 3], B, codes=ac[i % 3], scales=asc[i % 3], stream=stream, layout=LAY)
         stream.synchronize()
         ams = []
         for _ in range(5):
             a, b = ev(), ev()
             a.record(stream)
             for i in range(args.steps):
-                brq.rotate_quantize_fused(axs[i % 3], B, codes=ac[i % 3], scales=asc[i % 3], stream=stream)
+                brq.rotate_quantize_fused(axs[i % 3], B, codes=ac[i % 3], scales=asc[i % 3], stream=stream, layout=LAY)
             b.record(stream)
             stream.synchronize()
             ams.append(a.elapsed_time(b) / args.steps)
@@ -198,7 +213,8 @@ def main():
         rc, rs = o.rotate_quantize_fused(x_np[:rows], B)
         t_rq = time.perf_counter() - t0
         grows = int(min(gemm_M, rows, max(1, 2e11 // (N * K))))       # some 10 s of oracle work
-        wq_h, ws_h = wq0.cpu().numpy(), ws0.cpu().numpy()
+        wq_r, ws_r = (wq0, ws0) if LAY == "rowmajor" else brq.to_rowmajor(wq0, ws0, N, K)
+        wq_h, ws_h = wq_r.cpu().numpy(), ws_r.cpu().numpy()
         t0 = time.perf_counter()
         o.mxfp4_gemm(rc[:grows], rs[:grows], wq_h, ws_h, want_bound=False)
         t_g = time.perf_counter() - t0
@@ -221,7 +237,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "mxfp4",
         "data": "synthetic",
         "config": {"workload": "%s: X %dx%d bf16 -> block Hadamard B=32 + MXFP4; product M=%d N=%d K=%d, %s out"
-                               % (args.workload, M, K, gemm_M, N, K, args.out_dtype), "buffer_sets": nsets},
+                               % (args.workload, M, K, gemm_M, N, K, args.out_dtype), "buffer_sets": nsets,
+                   "operand_layout": LAY},
         "rotate_quant_GBps": kernels["rotate_quantize_fused"]["GB/s"],
         "gemm_TFLOPs": kernels["mxfp4_gemm"]["TFLOP/s"],
         "roofline": roofline,

@@ -13,7 +13,18 @@
  *   - All data pointers are DEVICE pointers (HBM of the current HIP device).  The caller
  *     owns every buffer; the library allocates nothing and keeps no state.
  *   - Matrices are row-major with K contiguous.  X is [M][ldx] (ldx >= K, in elements),
- *     codes are [M][K/2] bytes, scales are [M][K/32] bytes, Y is [M][ldy].
+ *     Y is [M][ldy].  Quantized operands come in one of two layouts (brq_layout):
+ *       BRQ_LAYOUT_ROWMAJOR  codes [M][K/2] bytes, scales [M][K/32] bytes.
+ *       BRQ_LAYOUT_TILED     what the product kernels stream fastest: rows in slabs of 64, K in
+ *                            stages of 128 elements (64 code bytes) and superstages of 512
+ *                            elements (16 scale bytes), every (slab, stage) block of codes
+ *                            (4096 bytes) and every (slab, superstage) block of scales (1024
+ *                            bytes) contiguous.  With Kp = K rounded up to a multiple of 512:
+ *                              code byte j of row m   at ((m/64)*(Kp/128) + j/64)*4096 + (m%64)*64 + j%64
+ *                              scale of group g, row m at ((m/64)*(Kp/512) + g/16)*1024 + (m%64)*16 + g%16
+ *                            Buffer sizes (brq_operand_bytes): ceil64(M)*Kp/2 and ceil64(M)*Kp/32
+ *                            bytes.  Padding rows and padding K are never read and never written.
+ *                            brq_to_rowmajor converts back.
  *   - codes: two E2M1 codes per byte, element 2j in the low nibble of byte j, element
  *     2j+1 in the high nibble.  A code is s<<3 | e<<1 | m (magnitudes 0, .5, 1, 1.5, 2,
  *     3, 4, 6).  A zero magnitude is always stored as code 0 (no negative zero).
@@ -48,10 +59,21 @@ typedef enum {
     BRQ_ERR_BLOCK = 3,       /* B not a power of two, B < 32, B > 16384 or B does not divide K */
     BRQ_ERR_ALIGN = 4,       /* pointer or pitch not 16-byte aligned */
     BRQ_ERR_DTYPE = 5,       /* dtype is not one of brq_dtype */
-    BRQ_ERR_LAUNCH = 6       /* hipLaunchKernel failed (hipGetLastError) */
+    BRQ_ERR_LAUNCH = 6,      /* hipLaunchKernel failed (hipGetLastError) */
+    BRQ_ERR_LAYOUT = 7       /* layout is not one of brq_layout */
 } brq_status;
 
 typedef enum { BRQ_F32 = 0, BRQ_BF16 = 1 } brq_dtype;
+
+typedef enum { BRQ_LAYOUT_ROWMAJOR = 0, BRQ_LAYOUT_TILED = 1 } brq_layout;
+
+/*
+ * Sizes in bytes of the codes and scales buffers of a quantized [rows][K] operand in `layout`
+ * (the "GEMM-consumable layout" of the quantizer's output; the definition is above).  Host
+ * arithmetic only.  Either output pointer may be NULL.
+ */
+brq_status brq_operand_bytes(int64_t rows, int64_t K, brq_layout layout, int64_t* codes_bytes,
+                             int64_t* scales_bytes);
 
 /*
  * y = x * diag(H_B, ..., H_B) / sqrt(B)          (Sec. 4.3, Eq. 1 with R_i = Sylvester
@@ -70,10 +92,10 @@ brq_status brq_block_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, 
  * MXFP4 quantization of x along K (Sec. 4.1): per row and per group of 32 consecutive
  * elements one E8M0 scale from the group's maximum magnitude, elements rounded to the
  * nearest E2M1 value of x / 2^e (ties to the even code, saturation at +-6).
- * x [M][ldx] of xdt -> codes [M][K/2], scales [M][K/32].  K % 32 == 0.
+ * x [M][ldx] of xdt -> codes, scales in `layout`.  K % 32 == 0.
  */
 brq_status brq_mxfp4_quantize(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx,
-                              uint8_t* codes, uint8_t* scales, void* stream);
+                              uint8_t* codes, uint8_t* scales, brq_layout layout, void* stream);
 
 /*
  * The online step of the method (Sec. 4.3, the rotation applied before a quantized
@@ -83,18 +105,26 @@ brq_status brq_mxfp4_quantize(const void* x, brq_dtype xdt, int64_t M, int64_t K
  */
 brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K,
                                      int64_t ldx, int64_t B, uint8_t* codes, uint8_t* scales,
-                                     void* stream);
+                                     brq_layout layout, void* stream);
 
 /*
  * W4A4 product on MXFP4 operands (Sec. 2; Sec. 4.1 "scaling factor integrated into
  * hardware"):   y[m][n] = sum_g 2^(as[m][g]-127 + ws[n][g]-127) *
  *                          sum_{j<32} val(aq[m][32g+j]) * val(wq[n][32g+j]),  fp32 accumulate.
- * aq [M][K/2], as [M][K/32], wq [N][K/2], ws [N][K/32] -> y [M][ldy] of ydt (fp32, or
- * bf16 = round-to-nearest-even of the fp32 sum).  K % 32 == 0, ldy >= N.
+ * (aq, as) the quantized [M][K] operand in a_layout, (wq, ws) the quantized [N][K] operand in
+ * w_layout -> y [M][ldy] of ydt (fp32, or bf16 = round-to-nearest-even of the fp32 sum).
+ * K % 32 == 0, ldy >= N.  The result does not depend on the layouts.
  */
-brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* wq,
-                          const uint8_t* ws, int64_t M, int64_t N, int64_t K, void* y,
-                          brq_dtype ydt, int64_t ldy, void* stream);
+brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout,
+                          const uint8_t* wq, const uint8_t* ws, brq_layout w_layout, int64_t M,
+                          int64_t N, int64_t K, void* y, brq_dtype ydt, int64_t ldy, void* stream);
+
+/*
+ * Tiled -> row-major copy of a quantized [rows][K] operand (for inspection and parity checks;
+ * nothing on the product path needs it): codes_out [rows][K/2], scales_out [rows][K/32].
+ */
+brq_status brq_to_rowmajor(const uint8_t* codes_tiled, const uint8_t* scales_tiled, int64_t rows,
+                           int64_t K, uint8_t* codes_out, uint8_t* scales_out, void* stream);
 
 /* Static, human-readable text for a status code. */
 const char* brq_strerror(brq_status s);

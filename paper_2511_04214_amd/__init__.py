@@ -15,8 +15,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbrq.so")
 
 BRQ_F32, BRQ_BF16 = 0, 1
-EXPORTS = ["brq_block_rotate", "brq_mxfp4_quantize", "brq_rotate_quantize_fused", "brq_mxfp4_gemm",
-           "brq_strerror", "brq_version"]
+LAYOUTS = {"rowmajor": 0, "tiled": 1}
+EXPORTS = ["brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
+           "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_strerror", "brq_version"]
 
 _lib = None
 
@@ -38,12 +39,16 @@ def lib():
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.brq_block_rotate.argtypes = [vp, i32, i64, i64, i64, i64, vp, i32, i64, vp]
         L.brq_block_rotate.restype = i32
-        L.brq_mxfp4_quantize.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp]
+        L.brq_operand_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.brq_operand_bytes.restype = i32
+        L.brq_mxfp4_quantize.argtypes = [vp, i32, i64, i64, i64, vp, vp, i32, vp]
         L.brq_mxfp4_quantize.restype = i32
-        L.brq_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
+        L.brq_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i32, vp]
         L.brq_rotate_quantize_fused.restype = i32
-        L.brq_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i32, i64, vp]
+        L.brq_mxfp4_gemm.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp]
         L.brq_mxfp4_gemm.restype = i32
+        L.brq_to_rowmajor.argtypes = [vp, vp, i64, i64, vp, vp, vp]
+        L.brq_to_rowmajor.restype = i32
         L.brq_strerror.argtypes = [i32]
         L.brq_strerror.restype = ctypes.c_char_p
         L.brq_version.restype = i32
@@ -87,45 +92,102 @@ def block_rotate(x, B, out_dtype=torch.float32, out=None, stream=None):
     return y
 
 
-def _alloc_q(x, M, K, codes, scales):
+def _layout_code(layout):
+    if layout not in LAYOUTS:
+        raise ValueError("layout must be one of %s" % sorted(LAYOUTS))
+    return LAYOUTS[layout]
+
+
+def operand_bytes(rows, K, layout="rowmajor"):
+    """(codes_bytes, scales_bytes) of a quantized [rows][K] operand (brq_operand_bytes)."""
+    c, s_ = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().brq_operand_bytes(rows, K, _layout_code(layout), ctypes.byref(c), ctypes.byref(s_)))
+    return c.value, s_.value
+
+
+def _alloc_q(x, M, K, codes, scales, layout):
+    """Row-major operands are [M, K/2] and [M, K/32] tensors, tiled operands flat byte buffers."""
+    if layout == "rowmajor":
+        cshape, sshape = (M, K // 2), (M, K // 32)
+    else:
+        cb, sb = operand_bytes(M, K, layout)
+        cshape, sshape = (cb,), (sb,)
     if codes is None:
-        codes = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
+        codes = torch.empty(cshape, dtype=torch.uint8, device=x.device)
     if scales is None:
-        scales = torch.empty((M, K // 32), dtype=torch.uint8, device=x.device)
+        scales = torch.empty(sshape, dtype=torch.uint8, device=x.device)
     if not (codes.is_contiguous() and scales.is_contiguous()):
         raise ValueError("codes and scales must be contiguous")
+    if codes.dtype != torch.uint8 or scales.dtype != torch.uint8 or not (codes.is_cuda and scales.is_cuda):
+        raise ValueError("codes and scales must be uint8 GPU tensors")
+    if codes.numel() < cshape[0] * (cshape[1] if len(cshape) > 1 else 1) or \
+            scales.numel() < sshape[0] * (sshape[1] if len(sshape) > 1 else 1):
+        raise ValueError("codes or scales buffer too small for this operand and layout")
     return codes, scales
 
 
-def mxfp4_quantize(x, codes=None, scales=None, stream=None):
-    """x -> (codes [M, K/2] u8, scales [M, K/32] u8) (brq_mxfp4_quantize)."""
+def mxfp4_quantize(x, codes=None, scales=None, stream=None, layout="rowmajor"):
+    """x -> (codes, scales) in `layout` (brq_mxfp4_quantize)."""
     M, K, ldx = _rows(x, "x")
-    codes, scales = _alloc_q(x, M, K, codes, scales)
+    lc = _layout_code(layout)
+    codes, scales = _alloc_q(x, M, K, codes, scales, layout)
     _check(lib().brq_mxfp4_quantize(x.data_ptr(), _dtype_code(x), M, K, ldx, codes.data_ptr(), scales.data_ptr(),
-                                    _stream(stream)))
+                                    lc, _stream(stream)))
     return codes, scales
 
 
-def rotate_quantize_fused(x, B, codes=None, scales=None, stream=None):
+def rotate_quantize_fused(x, B, codes=None, scales=None, stream=None, layout="rowmajor"):
     """Block rotation fused with MXFP4 quantization (brq_rotate_quantize_fused)."""
     M, K, ldx = _rows(x, "x")
-    codes, scales = _alloc_q(x, M, K, codes, scales)
+    lc = _layout_code(layout)
+    codes, scales = _alloc_q(x, M, K, codes, scales, layout)
     _check(lib().brq_rotate_quantize_fused(x.data_ptr(), _dtype_code(x), M, K, ldx, B, codes.data_ptr(),
-                                           scales.data_ptr(), _stream(stream)))
+                                           scales.data_ptr(), lc, _stream(stream)))
     return codes, scales
 
 
-def mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.float32, out=None, stream=None):
-    """Y[M, N] = deq(aq, as) @ deq(wq, ws)^T on the block-scaled MFMA (brq_mxfp4_gemm)."""
+def to_rowmajor(codes_tiled, scales_tiled, rows, K, stream=None):
+    """Tiled operand -> (codes [rows, K/2], scales [rows, K/32]) (brq_to_rowmajor)."""
+    cb, sb = operand_bytes(rows, K, "tiled")
+    for t, n, need in ((codes_tiled, "codes_tiled", cb), (scales_tiled, "scales_tiled", sb)):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.uint8 and t.numel() >= need):
+            raise ValueError("%s must be a contiguous uint8 GPU tensor of at least %d bytes" % (n, need))
+    codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=codes_tiled.device)
+    scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=codes_tiled.device)
+    _check(lib().brq_to_rowmajor(codes_tiled.data_ptr(), scales_tiled.data_ptr(), rows, K, codes.data_ptr(),
+                                 scales.data_ptr(), _stream(stream)))
+    return codes, scales
+
+
+def mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.float32, out=None, stream=None, a_layout="rowmajor",
+               w_layout="rowmajor", M=None, N=None, K=None):
+    """Y[M, N] = deq(aq, as) @ deq(wq, ws)^T on the block-scaled MFMA (brq_mxfp4_gemm).
+
+    Row-major operands are 2-D tensors that carry their shape; a tiled operand is a flat byte
+    buffer, so its rows (M or N) and K must be given.
+    """
     for t, n in ((aq, "aq"), (as_, "as"), (wq, "wq"), (ws, "ws")):
-        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.uint8 and t.dim() == 2):
-            raise ValueError("%s must be a contiguous 2-D uint8 GPU tensor" % n)
-    M, K = aq.shape[0], aq.shape[1] * 2
-    N = wq.shape[0]
-    if wq.shape[1] * 2 != K or tuple(as_.shape) != (M, K // 32) or tuple(ws.shape) != (N, K // 32):
-        raise ValueError("operand shapes disagree")
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.uint8):
+            raise ValueError("%s must be a contiguous uint8 GPU tensor" % n)
+    la, lw = _layout_code(a_layout), _layout_code(w_layout)
+    if a_layout == "rowmajor":
+        if aq.dim() != 2 or (M is not None and M != aq.shape[0]) or (K is not None and K != aq.shape[1] * 2):
+            raise ValueError("row-major aq must be [M, K/2]")
+        M, K = aq.shape[0], aq.shape[1] * 2
+    if w_layout == "rowmajor":
+        if wq.dim() != 2 or (N is not None and N != wq.shape[0]) or (K is not None and K != wq.shape[1] * 2):
+            raise ValueError("row-major wq must be [N, K/2] with the K of the other operand")
+        N, K = wq.shape[0], wq.shape[1] * 2
+    if M is None or N is None or K is None:
+        raise ValueError("M, N and K must be given for tiled operands")
+    for (c, s_, rows, lay, n) in ((aq, as_, M, a_layout, "a"), (wq, ws, N, w_layout, "w")):
+        cb, sb = operand_bytes(rows, K, lay)
+        if c.numel() < cb or s_.numel() < sb or (lay == "rowmajor" and tuple(s_.shape) != (rows, K // 32)):
+            raise ValueError("operand %s: buffers do not match its shape and layout" % n)
     y = torch.empty((M, N), dtype=out_dtype, device=aq.device) if out is None else out
     _, _, ldy = _rows(y, "out")
-    _check(lib().brq_mxfp4_gemm(aq.data_ptr(), as_.data_ptr(), wq.data_ptr(), ws.data_ptr(), M, N, K, y.data_ptr(),
-                                _dtype_code(y), ldy, _stream(stream)))
+    if y.shape[0] != M or y.shape[1] != N:
+        raise ValueError("out must be [M, N]")
+    _check(lib().brq_mxfp4_gemm(aq.data_ptr(), as_.data_ptr(), la, wq.data_ptr(), ws.data_ptr(), lw, M, N, K,
+                                y.data_ptr(), _dtype_code(y), ldy, _stream(stream)))
     return y

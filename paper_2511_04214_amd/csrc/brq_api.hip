@@ -33,6 +33,8 @@ brq_status check_out(const uint8_t* codes, const uint8_t* scales, int64_t M) {
     return BRQ_OK;
 }
 
+bool layout_ok(brq_layout l) { return l == BRQ_LAYOUT_ROWMAJOR || l == BRQ_LAYOUT_TILED; }
+
 brq_status launched(hipError_t e) { return e == hipSuccess ? BRQ_OK : BRQ_ERR_LAUNCH; }
 
 }  // namespace
@@ -49,45 +51,75 @@ brq_status brq_block_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, 
     if (l2 < 0) return BRQ_ERR_BLOCK;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_rowwise(0, l2, xdt == BRQ_BF16, ydt == BRQ_BF16, x, M, K, ldx, y, ldy, nullptr,
-                                        nullptr, static_cast<hipStream_t>(stream)));
+                                        nullptr, false, static_cast<hipStream_t>(stream)));
+}
+
+brq_status brq_operand_bytes(int64_t rows, int64_t K, brq_layout layout, int64_t* codes_bytes,
+                             int64_t* scales_bytes) {
+    if (rows < 0 || K <= 0 || K % 32 != 0) return BRQ_ERR_SHAPE;
+    if (!layout_ok(layout)) return BRQ_ERR_LAYOUT;
+    int64_t r = rows, k = K;
+    if (layout == BRQ_LAYOUT_TILED) {
+        r = (rows + 63) / 64 * 64;
+        k = (K + 511) / 512 * 512;
+    }
+    if (codes_bytes) *codes_bytes = r * (k / 2);
+    if (scales_bytes) *scales_bytes = r * (k / 32);
+    return BRQ_OK;
 }
 
 brq_status brq_mxfp4_quantize(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, uint8_t* codes,
-                              uint8_t* scales, void* stream) {
+                              uint8_t* scales, brq_layout layout, void* stream) {
     brq_status st = check_rows(x, xdt, M, K, ldx);
     if (st != BRQ_OK) return st;
+    if (!layout_ok(layout)) return BRQ_ERR_LAYOUT;
     st = check_out(codes, scales, M);
     if (st != BRQ_OK) return st;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_rowwise(1, 0, xdt == BRQ_BF16, false, x, M, K, ldx, nullptr, 0, codes, scales,
-                                        static_cast<hipStream_t>(stream)));
+                                        layout == BRQ_LAYOUT_TILED, static_cast<hipStream_t>(stream)));
 }
 
 brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
-                                     uint8_t* codes, uint8_t* scales, void* stream) {
+                                     uint8_t* codes, uint8_t* scales, brq_layout layout, void* stream) {
     brq_status st = check_rows(x, xdt, M, K, ldx);
     if (st != BRQ_OK) return st;
+    if (!layout_ok(layout)) return BRQ_ERR_LAYOUT;
     st = check_out(codes, scales, M);
     if (st != BRQ_OK) return st;
     int l2 = block_log2(B, K);
     if (l2 < 0) return BRQ_ERR_BLOCK;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_rowwise(2, l2, xdt == BRQ_BF16, false, x, M, K, ldx, nullptr, 0, codes, scales,
-                                        static_cast<hipStream_t>(stream)));
+                                        layout == BRQ_LAYOUT_TILED, static_cast<hipStream_t>(stream)));
 }
 
-brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws, int64_t M,
-                          int64_t N, int64_t K, void* y, brq_dtype ydt, int64_t ldy, void* stream) {
+brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
+                          const uint8_t* ws, brq_layout w_layout, int64_t M, int64_t N, int64_t K, void* y,
+                          brq_dtype ydt, int64_t ldy, void* stream) {
     int es = dtype_size(ydt);
     if (es == 0) return BRQ_ERR_DTYPE;
+    if (!layout_ok(a_layout) || !layout_ok(w_layout)) return BRQ_ERR_LAYOUT;
     if (M < 0 || N < 0 || K <= 0 || K % 32 != 0 || ldy < N) return BRQ_ERR_SHAPE;
     if (M >= (int64_t(1) << 31) || N >= (int64_t(1) << 31) || K >= (int64_t(1) << 31)) return BRQ_ERR_SHAPE;
     if (M > 0 && N > 0 && (!aq || !as || !wq || !ws || !y)) return BRQ_ERR_NULL;
     if (!aligned16(aq) || !aligned16(as) || !aligned16(wq) || !aligned16(ws) || !aligned16(y))
         return BRQ_ERR_ALIGN;
     if (M == 0 || N == 0) return BRQ_OK;
-    return launched(brq::launch_mxfp4_gemm(aq, as, wq, ws, M, N, K, y, ydt == BRQ_BF16, ldy,
-                                           static_cast<hipStream_t>(stream)));
+    const brq::Operand a{aq, as, a_layout == BRQ_LAYOUT_TILED}, w{wq, ws, w_layout == BRQ_LAYOUT_TILED};
+    return launched(brq::launch_mxfp4_gemm(a, w, M, N, K, y, ydt == BRQ_BF16, ldy, static_cast<hipStream_t>(stream)));
+}
+
+brq_status brq_to_rowmajor(const uint8_t* codes_tiled, const uint8_t* scales_tiled, int64_t rows, int64_t K,
+                           uint8_t* codes_out, uint8_t* scales_out, void* stream) {
+    if (rows < 0 || K <= 0 || K % 32 != 0) return BRQ_ERR_SHAPE;
+    if (rows >= (int64_t(1) << 31) || K >= (int64_t(1) << 31)) return BRQ_ERR_SHAPE;
+    if (rows > 0 && (!codes_tiled || !scales_tiled || !codes_out || !scales_out)) return BRQ_ERR_NULL;
+    if (!aligned16(codes_tiled) || !aligned16(scales_tiled) || !aligned16(codes_out) || !aligned16(scales_out))
+        return BRQ_ERR_ALIGN;
+    if (rows == 0) return BRQ_OK;
+    return launched(brq::launch_to_rowmajor(codes_tiled, scales_tiled, rows, K, codes_out, scales_out,
+                                            static_cast<hipStream_t>(stream)));
 }
 
 const char* brq_strerror(brq_status s) {
@@ -99,10 +131,11 @@ const char* brq_strerror(brq_status s) {
         case BRQ_ERR_ALIGN: return "pointer or row pitch not 16-byte aligned";
         case BRQ_ERR_DTYPE: return "unknown dtype";
         case BRQ_ERR_LAUNCH: return "kernel launch failed";
+        case BRQ_ERR_LAYOUT: return "unknown operand layout";
     }
     return "unknown status";
 }
 
-int brq_version(void) { return 100; }
+int brq_version(void) { return 200; }
 
 }  // extern "C"

@@ -6,18 +6,28 @@
 namespace brq {
 
 // mode: 0 rotate, 1 quantize, 2 fused rotate+quantize.  log2b: 0 for quantize, else 5..14.
+// tiled: codes and scales go out in the tiled operand layout instead of row-major.
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
-                          hipStream_t s);
+                          bool tiled, hipStream_t s);
 
-hipError_t launch_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws,
-                             int64_t M, int64_t N, int64_t K, void* y, bool out_bf16, int64_t ldy,
-                             hipStream_t s);
+// A quantized [rows][K] operand as the product kernels see it.
+struct Operand {
+    const uint8_t* codes;
+    const uint8_t* scales;
+    bool tiled;
+};
+
+hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
+                             bool out_bf16, int64_t ldy, hipStream_t s);
 
 // Persistent LDS-staged kernel for large shapes (M, N multiples of 256, K a multiple of 512).
 bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy);
-hipError_t launch_gemm_tiled(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws,
-                             int64_t M, int64_t N, int64_t K, void* y, bool out_bf16, int64_t ldy,
-                             hipStream_t s);
+hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
+                             bool out_bf16, int64_t ldy, hipStream_t s);
+
+// Tiled -> row-major copy of a quantized operand.
+hipError_t launch_to_rowmajor(const uint8_t* codes_t, const uint8_t* scales_t, int64_t rows, int64_t K,
+                              uint8_t* codes, uint8_t* scales, hipStream_t s);
 
 }  // namespace brq

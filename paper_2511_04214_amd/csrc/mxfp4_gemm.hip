@@ -12,6 +12,32 @@
 
 namespace brq {
 
+// Addressing of one row of a quantized operand, valid for both layouts: the 16 code bytes of
+// group g sit at codes + (g >> 2) * cstep + (g & 3) * 16 and its scale at scales + (g >> 4) * sstep
+// + (g & 15), with (cstep, sstep) = (64, 16) for row-major rows and (4096, 1024) for the tiled
+// layout (64-row slabs; 64 code bytes per row and stage, 16 scale bytes per row and superstage).
+struct RowView {
+    const uint8_t* codes;
+    const uint8_t* scales;
+    uint32_t cstep, sstep;
+    __device__ __forceinline__ RowView(const uint8_t* c, const uint8_t* s, bool tiled, int64_t row, int K) {
+        if (tiled) {
+            const int64_t Kp = ((int64_t)K + 511) / 512 * 512;
+            codes = c + (row >> 6) * (Kp / 128) * 4096 + (row & 63) * 64;
+            scales = s + (row >> 6) * (Kp / 512) * 1024 + (row & 63) * 16;
+            cstep = 4096; sstep = 1024;
+        } else {
+            codes = c + row * (K / 2);
+            scales = s + row * (K / 32);
+            cstep = 64; sstep = 16;
+        }
+    }
+    __device__ __forceinline__ v4i group(int g) const {
+        return *reinterpret_cast<const v4i*>(codes + (int64_t)(g >> 2) * cstep + (g & 3) * 16);
+    }
+    __device__ __forceinline__ int scale(int g) const { return scales[(int64_t)(g >> 4) * sstep + (g & 15)]; }
+};
+
 __device__ __forceinline__ void store_out(void* y, bool out_bf16, int64_t idx, float v) {
     if (out_bf16) reinterpret_cast<uint16_t*>(y)[idx] = (uint16_t)f32_to_bf16_bits(v);
     else reinterpret_cast<float*>(y)[idx] = v;
@@ -19,30 +45,27 @@ __device__ __forceinline__ void store_out(void* y, bool out_bf16, int64_t idx, f
 
 // ---- general shapes: one 32x32 output tile per wavefront, operands straight from global ----
 __global__ void __launch_bounds__(256) k_gemm_direct(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
-                                                     const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
-                                                     int M, int N, int K, void* __restrict__ y, int out_bf16,
-                                                     int64_t ldy) {
+                                                     int a_tiled, const uint8_t* __restrict__ wq,
+                                                     const uint8_t* __restrict__ ws, int w_tiled, int M, int N, int K,
+                                                     void* __restrict__ y, int out_bf16, int64_t ldy) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m0 = blockIdx.y * 64 + (wave >> 1) * 32, n0 = blockIdx.x * 64 + (wave & 1) * 32;
     if (m0 >= M || n0 >= N) return;   // whole wavefront leaves together
     const int r = lane & 31, h = lane >> 5;
     const int64_t ra = min(m0 + r, M - 1), rw = min(n0 + r, N - 1);   // clamp: rows past the edge are computed, not stored
     const int groups = K / 32;
-    const uint8_t* pa = aq + ra * (K / 2);
-    const uint8_t* pw = wq + rw * (K / 2);
-    const uint8_t* sa = as + ra * groups;
-    const uint8_t* sw = ws + rw * groups;
+    const RowView va(aq, as, a_tiled != 0, ra, K), vw(wq, ws, w_tiled != 0, rw, K);
     v16f acc = {};
     for (int g0 = 0; g0 < groups; g0 += 2) {
         int g = g0 + h;
         v8i a = {}, b = {};
         int sca = 0, scb = 0;
         if (g < groups) {   // odd group count: the last step's second half contributes zeros
-            v4i ta = *reinterpret_cast<const v4i*>(pa + g * 16);
-            v4i tb = *reinterpret_cast<const v4i*>(pw + g * 16);
+            v4i ta = va.group(g);
+            v4i tb = vw.group(g);
             a[0] = ta[0]; a[1] = ta[1]; a[2] = ta[2]; a[3] = ta[3];
             b[0] = tb[0]; b[1] = tb[1]; b[2] = tb[2]; b[3] = tb[3];
-            sca = sa[g]; scb = sw[g];
+            sca = va.scale(g); scb = vw.scale(g);
         }
         acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc, 4, 4, 0, sca, 0, scb);
     }
@@ -58,9 +81,9 @@ __global__ void __launch_bounds__(256) k_gemm_direct(const uint8_t* __restrict__
 // Each of the 4 wavefronts takes every 4th 128-wide K step for the same 16 weight rows; the
 // partial 16x16 tiles are summed through LDS in a fixed order.
 __global__ void __launch_bounds__(256) k_gemm_skinny(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
-                                                     const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
-                                                     int M, int N, int K, void* __restrict__ y, int out_bf16,
-                                                     int64_t ldy) {
+                                                     int a_tiled, const uint8_t* __restrict__ wq,
+                                                     const uint8_t* __restrict__ ws, int w_tiled, int M, int N, int K,
+                                                     void* __restrict__ y, int out_bf16, int64_t ldy) {
     __shared__ float part[4][64][4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, kq = lane >> 4;
@@ -68,23 +91,20 @@ __global__ void __launch_bounds__(256) k_gemm_skinny(const uint8_t* __restrict__
     const int groups = K / 32;
     const int64_t rw = min(n0 + r, N - 1);
     const bool arow = r < M;
-    const uint8_t* pa = aq + (int64_t)(arow ? r : 0) * (K / 2);
-    const uint8_t* sa = as + (int64_t)(arow ? r : 0) * groups;
-    const uint8_t* pw = wq + rw * (K / 2);
-    const uint8_t* sw = ws + rw * groups;
+    const RowView va(aq, as, a_tiled != 0, arow ? r : 0, K), vw(wq, ws, w_tiled != 0, rw, K);
     v4f acc = {};
     for (int g0 = wave * 4; g0 < groups; g0 += 16) {
         int g = g0 + kq;
         v8i a = {}, b = {};
         int sca = 0, scb = 0;
         if (g < groups) {
-            v4i tb = *reinterpret_cast<const v4i*>(pw + g * 16);
+            v4i tb = vw.group(g);
             b[0] = tb[0]; b[1] = tb[1]; b[2] = tb[2]; b[3] = tb[3];
-            scb = sw[g];
+            scb = vw.scale(g);
             if (arow) {
-                v4i ta = *reinterpret_cast<const v4i*>(pa + g * 16);
+                v4i ta = va.group(g);
                 a[0] = ta[0]; a[1] = ta[1]; a[2] = ta[2]; a[3] = ta[3];
-                sca = sa[g];
+                sca = va.scale(g);
             }
         }
         acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc, 4, 4, 0, sca, 0, scb);
@@ -104,19 +124,18 @@ __global__ void __launch_bounds__(256) k_gemm_skinny(const uint8_t* __restrict__
 }
 
 
-hipError_t launch_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws,
-                             int64_t M, int64_t N, int64_t K, void* y, bool out_bf16, int64_t ldy,
-                             hipStream_t s) {
+hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
+                             bool out_bf16, int64_t ldy, hipStream_t s) {
     if (tiled_gemm_supported(M, N, K, out_bf16, ldy)) {
-        return launch_gemm_tiled(aq, as, wq, ws, M, N, K, y, out_bf16, ldy, s);
+        return launch_gemm_tiled(a, w, M, N, K, y, out_bf16, ldy, s);
     } else if (M <= 16) {
         dim3 grid((uint32_t)((N + 15) / 16));
-        hipLaunchKernelGGL(k_gemm_skinny, grid, dim3(256), 0, s, aq, as, wq, ws, (int)M, (int)N, (int)K, y,
-                           (int)out_bf16, ldy);
+        hipLaunchKernelGGL(k_gemm_skinny, grid, dim3(256), 0, s, a.codes, a.scales, (int)a.tiled, w.codes, w.scales,
+                           (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
     } else {
         dim3 grid((uint32_t)((N + 63) / 64), (uint32_t)((M + 63) / 64));
-        hipLaunchKernelGGL(k_gemm_direct, grid, dim3(256), 0, s, aq, as, wq, ws, (int)M, (int)N, (int)K, y,
-                           (int)out_bf16, ldy);
+        hipLaunchKernelGGL(k_gemm_direct, grid, dim3(256), 0, s, a.codes, a.scales, (int)a.tiled, w.codes, w.scales,
+                           (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
     }
     return hipGetLastError();
 }

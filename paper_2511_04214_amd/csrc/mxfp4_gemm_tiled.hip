@@ -47,13 +47,12 @@ constexpr int LDS_BYTES = EPI_BASE + 4 * 4096;          // 163840, all of the CU
 template <int V>
 struct IC { static constexpr int value = V; };
 
-// One LDS-DMA load: 64 lanes x 16 bytes from base + voff(lane) + G_OFF to LDS
-// lds_base + LDS_OFF + 16 * lane.  The instruction's immediate offset is added to the global
-// AND the LDS address, so M0 is biased by -G_OFF.  lds_base and base must be wavefront-uniform.
-template <int LDS_OFF, int G_OFF>
+// One LDS-DMA load: 64 lanes x 16 bytes from base + voff(lane) to LDS lds_base + LDS_OFF +
+// 16 * lane (M0 carries the LDS address).  lds_base and base must be wavefront-uniform.
+template <int LDS_OFF>
 __device__ __forceinline__ void dma16(uint32_t lds_base, const uint8_t* base, uint32_t voff) {
-    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2 offset:%4\n\t"
-                 :: "s"(lds_base), "v"(voff), "s"(base), "n"(LDS_OFF - G_OFF), "n"(G_OFF)
+    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2\n\t"
+                 :: "s"(lds_base), "v"(voff), "s"(base), "n"(LDS_OFF)
                  : "memory", "scc");
 }
 
@@ -118,7 +117,7 @@ __device__ __forceinline__ void mfma_fp4(v16f& acc, const v4i& wf, const v4i& af
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
                                                        const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
-                                                       int M, int N, int K, void* __restrict__ y, int64_t ldy) {
+                                                       int M, int N, int K, void* __restrict__ y, int64_t ldy, int a_tiled, int w_tiled) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -142,29 +141,51 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     const int64_t cpitch = K / 2, spitch = K / 32;
 
     // ---- producer state.  The producer runs one superstage (4 stages) ahead of the MFMAs.
-    // Per-lane offsets: rows (lane >> 2) + 16 q of a 64-row slab, swizzled 16-byte chunk.
-    uint32_t vq[4];
+    // A wavefront loads its own 64-row slab of each operand: per stage 4 loads of 16 rows x 64
+    // bytes, which land in LDS as rows of 64 bytes with the 16-byte chunks of row i XOR-swizzled by
+    // (i >> 2) & 3.  Row-major operand: lane offset ((lane >> 2) + 16 q) rows, a stage is 64
+    // bytes further along K.  Tiled operand: the slab's stage is one contiguous 4096-byte block
+    // (16 rows per KB), the next stage the next block: a load then touches 8 cache lines
+    // instead of 16, which is what the texture-address unit charges for.
+    const uint32_t swz16 = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+    uint32_t vqw[4], vqa[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-        vq[q] = (uint32_t)(((lane >> 2) + 16 * q) * cpitch + (((lane & 3) ^ ((lane >> 4) & 3)) << 4));
-    const uint32_t vsc = (uint32_t)(lane * spitch);
+    for (int q = 0; q < 4; ++q) {
+        vqw[q] = w_tiled ? (uint32_t)(q * 1024 + (lane >> 2) * 64) + swz16
+                         : (uint32_t)(((lane >> 2) + 16 * q) * cpitch) + swz16;
+        vqa[q] = a_tiled ? (uint32_t)(q * 1024 + (lane >> 2) * 64) + swz16
+                         : (uint32_t)(((lane >> 2) + 16 * q) * cpitch) + swz16;
+    }
+    const uint32_t vscw = w_tiled ? (uint32_t)(lane * 16) : (uint32_t)(lane * spitch);
+    const uint32_t vsca = a_tiled ? (uint32_t)(lane * 16) : (uint32_t)(lane * spitch);
+    // byte steps: stage to stage, superstage to superstage (codes), superstage to superstage (scales)
+    const int w_stage = w_tiled ? 4096 : 64, w_super = w_tiled ? 16384 : 256, w_ssuper = w_tiled ? 1024 : 16;
+    const int a_stage = a_tiled ? 4096 : 64, a_super = a_tiled ? 16384 : 256, a_ssuper = a_tiled ? 1024 : 16;
     const uint32_t dma_lds = lds0 + wave * 4096;             // this wavefront's 64-row slab in a stage
     const uint32_t dma_sc = lds0 + SCALE_BASE + wave * 1024; // ... and in a scale buffer
     int p_tile = 0, p_kq = 0;                                 // producer position: tile index, superstage in tile
     uint32_t p_buf = 0;                                       // byte offset of the scale buffer the producer fills next
-    const uint8_t *p_w = nullptr, *p_a = nullptr, *p_ws = nullptr, *p_as = nullptr;
+    const uint8_t *p_w[4] = {}, *p_a[4] = {}, *p_ws = nullptr, *p_as = nullptr;   // [stage of the superstage]
     // Past the end of the stream (p_tile >= ntiles) the last tile is loaded again: one throw-away
     // superstage that nobody reads keeps the number of loads in flight the same in every iteration.
     auto producer_next = [&]() {   // pointers of the next superstage; once per 128 MFMAs
         if (p_kq == 0) {
             int tm, tn;
             tw.tile(min(p_tile, ntiles - 1), tm, tn);
-            p_w = uniform_ptr(wq + ((int64_t)tn * TN + wave * 64) * cpitch);
-            p_a = uniform_ptr(aq + ((int64_t)tm * TM + wave * 64) * cpitch);
-            p_ws = uniform_ptr(ws + ((int64_t)tn * TN + wave * 64) * spitch);
-            p_as = uniform_ptr(as + ((int64_t)tm * TM + wave * 64) * spitch);
+            const int64_t wrow = (int64_t)tn * TN + wave * 64, arow = (int64_t)tm * TM + wave * 64;   // slab rows
+            const uint8_t* bw = w_tiled ? wq + (wrow >> 6) * (cpitch / 64) * 4096 : wq + wrow * cpitch;
+            const uint8_t* ba = a_tiled ? aq + (arow >> 6) * (cpitch / 64) * 4096 : aq + arow * cpitch;
+            p_ws = uniform_ptr(w_tiled ? ws + (wrow >> 6) * (spitch / 16) * 1024 : ws + wrow * spitch);
+            p_as = uniform_ptr(a_tiled ? as + (arow >> 6) * (spitch / 16) * 1024 : as + arow * spitch);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                p_w[u] = uniform_ptr(bw + u * w_stage);
+                p_a[u] = uniform_ptr(ba + u * a_stage);
+            }
         } else {
-            p_w += 256; p_a += 256; p_ws += 16; p_as += 16;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { p_w[u] += w_super; p_a[u] += a_super; }
+            p_ws += w_ssuper; p_as += a_ssuper;
         }
         if (++p_kq == KQ) { p_kq = 0; ++p_tile; }
     };
@@ -174,13 +195,13 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     auto dma_step = [&](auto Uc, auto Ic) {
         constexpr int U = decltype(Uc)::value, I = decltype(Ic)::value;
         if constexpr (I == 0) {
-            if constexpr (U == 0) dma16<0, 0>(dma_sc + p_buf, p_ws, vsc);
+            if constexpr (U == 0) dma16<0>(dma_sc + p_buf, p_ws, vscw);
         } else if constexpr (I == 1) {
-            if constexpr (U == 0) dma16<SCALE_OPER, 0>(dma_sc + p_buf, p_as, vsc);
+            if constexpr (U == 0) dma16<SCALE_OPER>(dma_sc + p_buf, p_as, vsca);
         } else {
             constexpr int q = (I - 2) >> 1;
-            if constexpr (((I - 2) & 1) == 0) dma16<U * STAGE_BYTES + q * 1024, U * 64>(dma_lds, p_w, vq[q]);
-            else dma16<U * STAGE_BYTES + OPER_BYTES + q * 1024, U * 64>(dma_lds, p_a, vq[q]);
+            if constexpr (((I - 2) & 1) == 0) dma16<U * STAGE_BYTES + q * 1024>(dma_lds, p_w[U], vqw[q]);
+            else dma16<U * STAGE_BYTES + OPER_BYTES + q * 1024>(dma_lds, p_a[U], vqa[q]);
         }
     };
     auto dma_stage = [&](auto Uc) {
@@ -433,9 +454,8 @@ bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_
            (K / 2) * 64 < (int64_t(1) << 31);
 }
 
-hipError_t launch_gemm_tiled(const uint8_t* aq, const uint8_t* as, const uint8_t* wq, const uint8_t* ws,
-                             int64_t M, int64_t N, int64_t K, void* y, bool out_bf16, int64_t ldy,
-                             hipStream_t s) {
+hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
+                             bool out_bf16, int64_t ldy, hipStream_t s) {
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, v = 0;
@@ -454,11 +474,11 @@ hipError_t launch_gemm_tiled(const uint8_t* aq, const uint8_t* as, const uint8_t
     const int T = (int)((M / tiled::TM) * (N / tiled::TN));
     const int grid = T < cus ? ((T + 7) & ~7) : cus;
     if (out_bf16)
-        hipLaunchKernelGGL(tiled::k_gemm_tiled<true>, dim3(grid), dim3(256), tiled::LDS_BYTES, s, aq, as, wq, ws,
-                           (int)M, (int)N, (int)K, y, ldy);
+        hipLaunchKernelGGL(tiled::k_gemm_tiled<true>, dim3(grid), dim3(256), tiled::LDS_BYTES, s, a.codes, a.scales,
+                           w.codes, w.scales, (int)M, (int)N, (int)K, y, ldy, (int)a.tiled, (int)w.tiled);
     else
-        hipLaunchKernelGGL(tiled::k_gemm_tiled<false>, dim3(grid), dim3(256), tiled::LDS_BYTES, s, aq, as, wq, ws,
-                           (int)M, (int)N, (int)K, y, ldy);
+        hipLaunchKernelGGL(tiled::k_gemm_tiled<false>, dim3(grid), dim3(256), tiled::LDS_BYTES, s, a.codes, a.scales,
+                           w.codes, w.scales, (int)M, (int)N, (int)K, y, ldy, (int)a.tiled, (int)w.tiled);
     return hipGetLastError();
 }
 

@@ -22,7 +22,19 @@ struct RowArgs {
     int64_t ldx, ldy;   // in elements
     uint32_t cpr;       // chunks per row = K/8
     uint32_t nchunks;   // M * K/8
+    // Tiled output (codes: 64 rows x 64 bytes per (slab, stage) block; scales: 64 rows x 16
+    // bytes per (slab, superstage) block): blocks per slab, 0 = row-major output.
+    uint32_t stages;    // Kp/128, Kp = K rounded up to a multiple of 512
+    uint32_t sstages;   // Kp/512
 };
+
+// Byte offsets of chunk kc (8 elements = 4 code bytes) of row `row` in the tiled layout.
+__device__ __forceinline__ uint64_t tiled_code_offset(uint32_t row, uint32_t kc, uint32_t stages) {
+    return ((uint64_t)(row >> 6) * stages + (kc >> 4)) * 4096u + (row & 63u) * 64u + (kc & 15u) * 4u;
+}
+__device__ __forceinline__ uint64_t tiled_scale_offset(uint32_t row, uint32_t kc, uint32_t sstages) {
+    return ((uint64_t)(row >> 6) * sstages + (kc >> 6)) * 1024u + (row & 63u) * 16u + ((kc >> 2) & 15u);
+}
 
 // ---- chunk load / store ---------------------------------------------------------
 
@@ -91,11 +103,20 @@ __host__ __device__ constexpr uint32_t norm_bits(int log2b) {
 }
 
 // Quantize the lane's 8 values (quad = one group) and store codes + scale.
-__device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t c, uint32_t lane,
-                                            uint32_t* codes, uint8_t* scales) {
+// Chunk kc of row `row`.
+__device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t row, uint32_t kc, uint32_t lane,
+                                            const RowArgs& a) {
     uint32_t sb = e8m0_from_amax(quad_max(absmax8(y)));
-    __builtin_nontemporal_store(encode8_e2m1(y, sb), &codes[c]);
-    if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, &scales[c >> 2]);
+    uint32_t w = encode8_e2m1(y, sb);
+    if (a.stages == 0) {
+        uint32_t c = row * a.cpr + kc;
+        __builtin_nontemporal_store(w, &a.codes[c]);
+        if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, &a.scales[c >> 2]);
+    } else {
+        __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.codes) +
+                                                                   tiled_code_offset(row, kc, a.stages)));
+        if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, a.scales + tiled_scale_offset(row, kc, a.sstages));
+    }
 }
 
 // One chunk per lane per step, U steps in flight.  LOG2B = 0 means "no rotation".
@@ -134,9 +155,27 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
             } else {
                 uint32_t sb = e8m0_from_amax(quad_max(absmax8(v[u])));
                 uint32_t w = encode8_e2m1(v[u], sb);
-                if (live) {
-                    __builtin_nontemporal_store(w, &a.codes[c]);
-                    if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, &a.scales[c >> 2]);
+                if (a.stages == 0) {
+                    if (live) {
+                        __builtin_nontemporal_store(w, &a.codes[c]);
+                        if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, &a.scales[c >> 2]);
+                    }
+                } else if ((a.cpr & 63u) == 0) {
+                    // K % 512 == 0: the 64 chunks of a wavefront lie in one row and one scale
+                    // superstage, so the row arithmetic is scalar and a lane adds a constant
+                    const uint32_t cb = __builtin_amdgcn_readfirstlane(c);       // lane 0's chunk
+                    const uint32_t row = cb / a.cpr, kc0 = cb - row * a.cpr;     // kc0 % 64 == 0
+                    uint8_t* cbase = reinterpret_cast<uint8_t*>(a.codes) + tiled_code_offset(row, kc0, a.stages);
+                    uint8_t* sbase = a.scales + tiled_scale_offset(row, kc0, a.sstages);
+                    if (live) {
+                        __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(cbase + (lane >> 4) * 4096u + (lane & 15u) * 4u));
+                        if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, sbase + (lane >> 2));
+                    }
+                } else if (live) {
+                    const uint32_t row = c / a.cpr, kc = c - row * a.cpr;
+                    __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.codes) +
+                                                                               tiled_code_offset(row, kc, a.stages)));
+                    if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, a.scales + tiled_scale_offset(row, kc, a.sstages));
                 }
             }
         }
@@ -210,8 +249,7 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
             int64_t yoff = (int64_t)row * a.ldy + (int64_t)blk * B + (int64_t)q * 8;
             store_chunk<OUT_BF16>((char*)a.y + yoff * (OUT_BF16 ? 2 : 4), y);
         } else {
-            uint32_t cglob = row * a.cpr + blk * (B / 8) + q;
-            quant_store(y, cglob, lane, a.codes, a.scales);
+            quant_store(y, row, blk * (B / 8) + q, lane, a);
         }
     }
 }
@@ -284,10 +322,13 @@ static hipError_t dispatch_b(int log2b, const RowArgs& a, bool contig, int64_t M
 // mode: RowMode; log2b: 0 for MODE_QUANT, else 5..14.  Arguments are already validated.
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
-                          hipStream_t s) {
+                          bool tiled, hipStream_t s) {
     RowArgs a;
     a.x = x; a.y = y; a.codes = reinterpret_cast<uint32_t*>(codes); a.scales = scales;
     a.ldx = ldx; a.ldy = ldy; a.cpr = (uint32_t)(K / 8); a.nchunks = (uint32_t)(M * (K / 8));
+    const int64_t Kp = (K + 511) / 512 * 512;
+    a.stages = tiled ? (uint32_t)(Kp / 128) : 0u;
+    a.sstages = tiled ? (uint32_t)(Kp / 512) : 0u;
     bool contig = (ldx == K) && (mode != MODE_ROTATE || ldy == K);
     if (mode == MODE_ROTATE) {
         if (in_bf16) return out_bf16 ? dispatch_b<true, MODE_ROTATE, true>(log2b, a, contig, M, K, s)
@@ -300,6 +341,32 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
                        : launch_inwave<0, false, MODE_QUANT, false>(a, contig, s);
     return in_bf16 ? dispatch_b<true, MODE_FUSED, false>(log2b, a, contig, M, K, s)
                    : dispatch_b<false, MODE_FUSED, false>(log2b, a, contig, M, K, s);
+}
+
+// ---- tiled -> row-major copy of a quantized operand (inspection and parity checks) ----
+// One lane per 32-element group: its 16 code bytes and its scale byte.
+__global__ void __launch_bounds__(256) k_to_rowmajor(const uint8_t* __restrict__ ct, const uint8_t* __restrict__ st,
+                                                     uint32_t rows, uint32_t K, uint32_t stages, uint32_t sstages,
+                                                     uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+    const uint32_t gpr = K / 32;                       // groups (16 code bytes, 1 scale byte) per row
+    const uint64_t n = (uint64_t)rows * gpr;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256) {
+        const uint32_t row = (uint32_t)(i / gpr), g = (uint32_t)(i - (uint64_t)row * gpr);
+        const v4i c = *reinterpret_cast<const v4i*>(ct + tiled_code_offset(row, g * 4, stages));
+        *reinterpret_cast<v4i*>(codes + i * 16) = c;
+        scales[i] = st[tiled_scale_offset(row, g * 4, sstages)];
+    }
+}
+
+hipError_t launch_to_rowmajor(const uint8_t* codes_t, const uint8_t* scales_t, int64_t rows, int64_t K,
+                              uint8_t* codes, uint8_t* scales, hipStream_t s) {
+    const int64_t Kp = (K + 511) / 512 * 512;
+    const int64_t n = rows * (K / 32);
+    const int64_t want = (n + 255) / 256;
+    const int grid = (int)(want < 16384 ? want : 16384);
+    hipLaunchKernelGGL(k_to_rowmajor, dim3(grid), dim3(256), 0, s, codes_t, scales_t, (uint32_t)rows, (uint32_t)K,
+                       (uint32_t)(Kp / 128), (uint32_t)(Kp / 512), codes, scales);
+    return hipGetLastError();
 }
 
 }  // namespace brq

@@ -24,8 +24,8 @@ def declared_symbols():
 
 def test_header_symbols_are_exported(L):
     syms = declared_symbols()
-    assert {"brq_block_rotate", "brq_mxfp4_quantize", "brq_rotate_quantize_fused", "brq_mxfp4_gemm",
-            "brq_strerror", "brq_version"} <= set(syms)
+    assert {"brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
+            "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_strerror", "brq_version"} <= set(syms)
     for s in syms:
         assert hasattr(L, s), "%s declared in brq.h but not exported" % s
 
@@ -41,46 +41,68 @@ def test_binding_names_match_header():
 
 def test_version_and_strerror(L):
     assert L.brq_version() >= 100
-    texts = [L.brq_strerror(i).decode() for i in range(7)]
-    assert texts[0] == "ok" and len(set(texts)) == 7
+    texts = [L.brq_strerror(i).decode() for i in range(8)]
+    assert texts[0] == "ok" and len(set(texts)) == 8
     assert "unknown" in L.brq_strerror(99).decode()
 
 
 def test_argument_errors_before_any_launch(L):
-    OK, NULL, SHAPE, BLOCK, ALIGN, DTYPE = 0, 1, 2, 3, 4, 5
+    OK, NULL, SHAPE, BLOCK, ALIGN, DTYPE, LAYOUT = 0, 1, 2, 3, 4, 5, 7
     p = 0x1000  # never dereferenced: every call below fails validation on the host
     q = ctypes.c_void_p
     # null pointers
-    assert L.brq_mxfp4_quantize(None, 1, 4, 64, 64, q(p), q(p), None) == NULL
-    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 64, None, q(p), None) == NULL
-    assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, q(p), None, None) == NULL
+    assert L.brq_mxfp4_quantize(None, 1, 4, 64, 64, q(p), q(p), 0, None) == NULL
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 64, None, q(p), 0, None) == NULL
+    assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, q(p), None, 0, None) == NULL
     assert L.brq_block_rotate(q(p), 1, 4, 64, 64, 32, None, 0, 64, None) == NULL
-    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), None, 4, 4, 64, q(p), 0, 4, None) == NULL
+    assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), None, 0, 4, 4, 64, q(p), 0, 4, None) == NULL
     # shapes
-    assert L.brq_mxfp4_quantize(q(p), 1, 4, 48, 48, q(p), q(p), None) == SHAPE      # K % 32
-    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 32, q(p), q(p), None) == SHAPE      # ldx < K
-    assert L.brq_mxfp4_quantize(q(p), 1, -1, 64, 64, q(p), q(p), None) == SHAPE
-    assert L.brq_mxfp4_quantize(q(p), 1, 1 << 40, 64, 64, q(p), q(p), None) == SHAPE
-    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 4, 8, 64, q(p), 0, 4, None) == SHAPE   # ldy < N
-    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 4, 8, 40, q(p), 0, 8, None) == SHAPE
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 48, 48, q(p), q(p), 0, None) == SHAPE      # K % 32
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 32, q(p), q(p), 0, None) == SHAPE      # ldx < K
+    assert L.brq_mxfp4_quantize(q(p), 1, -1, 64, 64, q(p), q(p), 0, None) == SHAPE
+    assert L.brq_mxfp4_quantize(q(p), 1, 1 << 40, 64, 64, q(p), q(p), 0, None) == SHAPE
+    assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 4, 8, 64, q(p), 0, 4, None) == SHAPE   # ldy < N
+    assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 4, 8, 40, q(p), 0, 8, None) == SHAPE
     # dtype
-    assert L.brq_mxfp4_quantize(q(p), 7, 4, 64, 64, q(p), q(p), None) == DTYPE
-    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 4, 8, 64, q(p), 3, 8, None) == DTYPE
+    assert L.brq_mxfp4_quantize(q(p), 7, 4, 64, 64, q(p), q(p), 0, None) == DTYPE
+    assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 4, 8, 64, q(p), 3, 8, None) == DTYPE
+    # layout
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 64, q(p), q(p), 2, None) == LAYOUT
+    assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, q(p), q(p), -1, None) == LAYOUT
+    assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 5, 4, 8, 64, q(p), 0, 8, None) == LAYOUT
+    assert L.brq_to_rowmajor(q(p), q(p), 4, 48, q(p), q(p), None) == SHAPE
+    assert L.brq_to_rowmajor(q(p), None, 4, 64, q(p), q(p), None) == NULL
+    assert L.brq_to_rowmajor(q(p), q(p), 0, 64, q(p), q(p), None) == OK
     # rotation block
     for B in (0, 16, 48, 128, 32768):
-        assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, B, q(p), q(p), None) == BLOCK, B
+        assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, B, q(p), q(p), 0, None) == BLOCK, B
     assert L.brq_block_rotate(q(p), 1, 4, 96, 96, 64, q(p), 0, 96, None) == BLOCK   # B does not divide K
     # alignment
-    assert L.brq_mxfp4_quantize(q(p + 2), 1, 4, 64, 64, q(p), q(p), None) == ALIGN
-    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 68, q(p), q(p), None) == ALIGN      # pitch 136 B
-    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 64, q(p + 4), q(p), None) == ALIGN
-    assert L.brq_mxfp4_gemm(q(p), q(p + 8), q(p), q(p), 4, 6, 64, q(p), 0, 6, None) == ALIGN
+    assert L.brq_mxfp4_quantize(q(p + 2), 1, 4, 64, 64, q(p), q(p), 0, None) == ALIGN
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 68, q(p), q(p), 0, None) == ALIGN      # pitch 136 B
+    assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 64, q(p + 4), q(p), 0, None) == ALIGN
+    assert L.brq_mxfp4_gemm(q(p), q(p + 8), 0, q(p), q(p), 0, 4, 6, 64, q(p), 0, 6, None) == ALIGN
     # empty problems are fine and launch nothing
-    assert L.brq_mxfp4_quantize(q(p), 1, 0, 64, 64, q(p), q(p), None) == OK
-    assert L.brq_rotate_quantize_fused(q(p), 1, 0, 64, 64, 32, q(p), q(p), None) == OK
+    assert L.brq_mxfp4_quantize(q(p), 1, 0, 64, 64, q(p), q(p), 0, None) == OK
+    assert L.brq_rotate_quantize_fused(q(p), 1, 0, 64, 64, 32, q(p), q(p), 0, None) == OK
     assert L.brq_block_rotate(q(p), 1, 0, 64, 64, 64, q(p), 0, 64, None) == OK
-    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 0, 8, 64, q(p), 0, 8, None) == OK
-    assert L.brq_mxfp4_gemm(q(p), q(p), q(p), q(p), 8, 0, 64, q(p), 0, 0, None) == OK
+    assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 0, 8, 64, q(p), 0, 8, None) == OK
+    assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 8, 0, 64, q(p), 0, 0, None) == OK
+
+
+def test_operand_bytes(L):
+    import paper_2511_04214_amd as brq
+    assert brq.operand_bytes(8192, 4096, "rowmajor") == (8192 * 2048, 8192 * 128)
+    assert brq.operand_bytes(8192, 4096, "tiled") == (8192 * 2048, 8192 * 128)      # already whole blocks
+    assert brq.operand_bytes(16, 256, "tiled") == (64 * 256, 64 * 16)                # 64 rows x 512 elements
+    assert brq.operand_bytes(65, 544, "tiled") == (128 * 512, 128 * 32)
+    assert brq.operand_bytes(0, 64, "tiled") == (0, 0)
+    c = ctypes.c_int64()
+    assert L.brq_operand_bytes(4, 48, 0, ctypes.byref(c), None) == 2     # shape
+    assert L.brq_operand_bytes(4, 64, 9, ctypes.byref(c), None) == 7     # layout
+    assert L.brq_operand_bytes(4, 64, 1, None, None) == 0
+    with pytest.raises(ValueError):
+        brq.operand_bytes(4, 64, "columns")
 
 
 def test_binding_refuses_cpu_tensors():

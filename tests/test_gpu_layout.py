@@ -1,0 +1,135 @@
+"""GPU tests of the tiled operand layout.
+
+The layout is bookkeeping, not arithmetic: a tiled output must hold exactly the bytes of the
+row-major output (which the other GPU tests compare with the oracle) at the addresses that
+include/brq.h states, and the product must not depend on the layout of its operands.  The
+address formulas are written out here in numpy, independently of the kernels.
+"""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def brq():
+    import paper_2511_04214_amd as b
+    b.lib()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return b
+
+
+def tiled_indices(rows, K):
+    """Byte index in the tiled buffers of every (row, code byte) and (row, group)."""
+    Kp = (K + 511) // 512 * 512
+    m = np.arange(rows, dtype=np.int64)[:, None]
+    j = np.arange(K // 2, dtype=np.int64)[None, :]
+    g = np.arange(K // 32, dtype=np.int64)[None, :]
+    ci = ((m // 64) * (Kp // 128) + j // 64) * 4096 + (m % 64) * 64 + j % 64
+    si = ((m // 64) * (Kp // 512) + g // 16) * 1024 + (m % 64) * 16 + g % 16
+    return ci, si
+
+
+def to_tiled(codes, scales, fill=0xEE):
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    Kp = (K + 511) // 512 * 512
+    R = (rows + 63) // 64 * 64
+    ci, si = tiled_indices(rows, K)
+    ct = np.full(R * Kp // 2, fill, dtype=np.uint8)
+    st = np.full(R * Kp // 32, fill, dtype=np.uint8)
+    ct[ci] = codes
+    st[si] = scales
+    return ct, st
+
+
+def make_x(M, K, seed, dtype):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_t(4, size=(M, K)).astype(np.float32)
+    x[:, rng.choice(K, size=max(1, K // 100), replace=False)] *= 20.0
+    if dtype == "bf16":
+        from paper_2511_04214_amd.inputs import f32_to_bf16_bits
+        return f32_to_bf16_bits(x)
+    return x
+
+
+@pytest.mark.parametrize("M,K,B,dtype", [(16, 256, 32, "f32"), (100, 544, 32, "bf16"), (300, 1024, 64, "bf16"),
+                                         (65, 96, 32, "f32"), (2048, 2048, 32, "bf16"), (130, 2048, 1024, "bf16"),
+                                         (64, 512, 512, "bf16"), (1, 32, 32, "f32")])
+def test_fused_tiled_holds_the_rowmajor_bytes(brq, M, K, B, dtype):
+    x = to_dev(make_x(M, K, 11, dtype))
+    c0, s0 = brq.rotate_quantize_fused(x, B)
+    cb, sb = brq.operand_bytes(M, K, "tiled")
+    ct = torch.full((cb,), 0xEE, dtype=torch.uint8, device="cuda")
+    st = torch.full((sb,), 0xEE, dtype=torch.uint8, device="cuda")
+    brq.rotate_quantize_fused(x, B, codes=ct, scales=st, layout="tiled")
+    want_c, want_s = to_tiled(to_host(c0), to_host(s0))
+    assert np.array_equal(to_host(ct), want_c), "codes: wrong bytes or padding touched"
+    assert np.array_equal(to_host(st), want_s), "scales: wrong bytes or padding touched"
+    c1, s1 = brq.to_rowmajor(ct, st, M, K)
+    assert torch.equal(c1, c0) and torch.equal(s1, s0)
+
+
+@pytest.mark.parametrize("M,K", [(48, 128), (257, 1536)])
+def test_quantize_tiled(brq, M, K):
+    x = to_dev(make_x(M, K, 12, "bf16"))
+    c0, s0 = brq.mxfp4_quantize(x)
+    ct, st = brq.mxfp4_quantize(x, layout="tiled")
+    c1, s1 = brq.to_rowmajor(ct, st, M, K)
+    assert torch.equal(c1, c0) and torch.equal(s1, s0)
+
+
+def test_fused_tiled_against_the_oracle(brq, orc):
+    M, K = 70, 1024
+    xh = make_x(M, K, 13, "bf16")
+    ct, st = brq.rotate_quantize_fused(to_dev(xh), 32, layout="tiled")
+    oc, os_ = orc.rotate_quantize_fused(xh, 32)
+    ci, si = tiled_indices(M, K)
+    assert np.array_equal(to_host(ct)[ci], oc)
+    assert np.array_equal(to_host(st)[si], os_)
+
+
+# tiled persistent kernel, general 32x32-tile kernel, M <= 16 kernel
+@pytest.mark.parametrize("M,N,K", [(512, 768, 2048), (256, 256, 512), (100, 200, 544), (300, 64, 1024),
+                                   (8, 300, 1024), (16, 48, 96)])
+def test_product_does_not_depend_on_the_layout(brq, M, N, K):
+    from paper_2511_04214_amd import inputs
+    aq, as_ = inputs.random_mxfp4(M, K, seed=21)
+    wq, ws = inputs.random_mxfp4(N, K, seed=22)
+    at = [to_dev(t) for t in to_tiled(aq, as_)]
+    wt = [to_dev(t) for t in to_tiled(wq, ws)]
+    ar = [to_dev(aq), to_dev(as_)]
+    wr = [to_dev(wq), to_dev(ws)]
+    for dt in (torch.float32, torch.bfloat16):
+        y0 = brq.mxfp4_gemm(ar[0], ar[1], wr[0], wr[1], out_dtype=dt)
+        y1 = brq.mxfp4_gemm(at[0], at[1], wt[0], wt[1], out_dtype=dt, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)
+        y2 = brq.mxfp4_gemm(at[0], at[1], wr[0], wr[1], out_dtype=dt, a_layout="tiled", M=M, K=K)
+        y3 = brq.mxfp4_gemm(ar[0], ar[1], wt[0], wt[1], out_dtype=dt, w_layout="tiled", N=N, K=K)
+        assert torch.equal(y0, y1) and torch.equal(y0, y2) and torch.equal(y0, y3)
+
+
+def test_end_to_end_tiled_against_the_oracle(brq, orc):
+    """Fused rotate+quantize of X and W straight into the tiled layout, then the product."""
+    M, N, K = 256, 512, 1024
+    xh, wh = make_x(M, K, 31, "bf16"), make_x(N, K, 32, "bf16")
+    act, ast = brq.rotate_quantize_fused(to_dev(xh), 32, layout="tiled")
+    wct, wst = brq.rotate_quantize_fused(to_dev(wh), 32, layout="tiled")
+    y = to_host(brq.mxfp4_gemm(act, ast, wct, wst, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)).astype(np.float64)
+    oa, oas = orc.rotate_quantize_fused(xh, 32)
+    ow, ows = orc.rotate_quantize_fused(wh, 32)
+    ref, bound = orc.mxfp4_gemm(oa, oas, ow, ows)
+    assert (np.abs(y - ref) <= 1e-5 * bound + 2.0 ** -126).all()
+
+
+def test_binding_checks_tiled_buffers(brq):
+    x = torch.zeros((64, 512), dtype=torch.bfloat16, device="cuda")
+    small = torch.empty((100,), dtype=torch.uint8, device="cuda")
+    with pytest.raises(ValueError):
+        brq.rotate_quantize_fused(x, 32, codes=small, layout="tiled")
+    ct, st = brq.rotate_quantize_fused(x, 32, layout="tiled")
+    with pytest.raises(ValueError):
+        brq.mxfp4_gemm(ct, st, ct, st, a_layout="tiled", w_layout="tiled")      # no shape given
+    with pytest.raises(ValueError):
+        brq.mxfp4_gemm(ct, st, ct, st, a_layout="tiled", w_layout="tiled", M=128, N=64, K=512)   # too small
