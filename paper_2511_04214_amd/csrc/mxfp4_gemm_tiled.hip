@@ -108,11 +108,10 @@ __device__ __forceinline__ void mfma_fp4(v16f& acc, const v4i& wf, const v4i& af
 }
 #define BRQ_MFMA(ACC, WF, AF, SEL, SW, SA) mfma_fp4(ACC, WF, AF, IC<SEL>{}, SW, SA)
 #define BRQ_SLOT_END() __builtin_amdgcn_sched_barrier(0)
-// Refill load S/2 of the stage goes into slot S for the wavefront pair with parity S & 1: the
-// four wavefronts re-align at every barrier, and the CU's one texture-address unit takes 16
-// cycles per 64-lane load, so at most two wavefronts may issue a load in the same 32-cycle
-// MFMA slot without stalling their next MFMA.
-#define BRQ_DMA_SLOT(S) do { if (pw == ((S) & 1)) dma_step(Uc, IC<(S) / 2>{}); } while (0)
+// Refill load S/2 of the stage goes into the even slot S, for all four wavefronts alike.
+// Staggering the wavefronts over the slots needs a branch per slot, and the taken branches cost
+// more (5% of the kernel) than the short queue of four loads at the texture-address unit does.
+#define BRQ_DMA_SLOT(S) do { if constexpr (((S) & 1) == 0) dma_step(Uc, IC<(S) / 2>{}); } while (0)
 
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
@@ -123,7 +122,6 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, h = lane >> 5;
     const int wn = wave >> 1, wm = wave & 1;   // this wavefront's 128 W rows / 128 A rows inside the tile
-    const int pw = wave >> 1;                  // wavefront pair, for the staggered refill slots
 
     TileWalk tw;
     tw.tiles_m = M / TM;

@@ -38,9 +38,11 @@ __device__ __forceinline__ uint64_t tiled_scale_offset(uint32_t row, uint32_t kc
 
 // ---- chunk load / store ---------------------------------------------------------
 
-// X is read exactly once and the outputs are next touched by another kernel: loads and stores
-// carry the non-temporal hint, so the stream does not displace what the caches hold (on a
-// 16 B in / 4 B out stream this alone is worth about 10% of HBM throughput).
+// X is read exactly once and the outputs are next touched by another kernel: loads and the
+// stores of rotated values and codes carry the non-temporal hint, so the stream does not
+// displace what the caches hold (on a 16 B in / 4 B out stream this alone is worth about 10% of
+// HBM throughput).  The scale bytes are stored plainly: a cache line of scales is completed by
+// several wavefronts, and the L2 merges their pieces before the line goes to memory.
 template <bool BF16>
 __device__ __forceinline__ void load_chunk(const void* p, float (&v)[8]) {
     if constexpr (BF16) {
@@ -111,11 +113,11 @@ __device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t row, u
     if (a.stages == 0) {
         uint32_t c = row * a.cpr + kc;
         __builtin_nontemporal_store(w, &a.codes[c]);
-        if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, &a.scales[c >> 2]);
+        if ((lane & 3) == 0) *(&a.scales[c >> 2]) = (uint8_t)sb;
     } else {
         __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.codes) +
                                                                    tiled_code_offset(row, kc, a.stages)));
-        if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, a.scales + tiled_scale_offset(row, kc, a.sstages));
+        if ((lane & 3) == 0) *(a.scales + tiled_scale_offset(row, kc, a.sstages)) = (uint8_t)sb;
     }
 }
 
@@ -158,7 +160,7 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
                 if (a.stages == 0) {
                     if (live) {
                         __builtin_nontemporal_store(w, &a.codes[c]);
-                        if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, &a.scales[c >> 2]);
+                        if ((lane & 3) == 0) *(&a.scales[c >> 2]) = (uint8_t)sb;
                     }
                 } else if ((a.cpr & 63u) == 0) {
                     // K % 512 == 0: the 64 chunks of a wavefront lie in one row and one scale
@@ -169,15 +171,55 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
                     uint8_t* sbase = a.scales + tiled_scale_offset(row, kc0, a.sstages);
                     if (live) {
                         __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(cbase + (lane >> 4) * 4096u + (lane & 15u) * 4u));
-                        if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, sbase + (lane >> 2));
+                        if ((lane & 3) == 0) *(sbase + (lane >> 2)) = (uint8_t)sb;
                     }
                 } else if (live) {
                     const uint32_t row = c / a.cpr, kc = c - row * a.cpr;
                     __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.codes) +
                                                                                tiled_code_offset(row, kc, a.stages)));
-                    if ((lane & 3) == 0) __builtin_nontemporal_store((uint8_t)sb, a.scales + tiled_scale_offset(row, kc, a.sstages));
+                    if ((lane & 3) == 0) *(a.scales + tiled_scale_offset(row, kc, a.sstages)) = (uint8_t)sb;
                 }
             }
+        }
+    }
+}
+
+// Quantize / fused rotate+quantize into the tiled layout, B <= 128 and K % 128 == 0.  In that
+// layout 128 contiguous bytes of codes are one stage (128 elements) of TWO rows, so the
+// row-wise mapping above would write half cache lines.  Here a wavefront takes 4 rows x one
+// stage: lane l holds chunk (l & 15) of row 4 rq + (l >> 4), reads 4 x 256 contiguous bytes and
+// writes 256 contiguous bytes of codes (two whole lines).  Every address is a wavefront-uniform
+// base plus a per-lane constant.  Rotation blocks of up to 16 chunks stay inside one row's lanes.
+template <int LOG2B, bool IN_BF16, int MODE>
+__global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, uint32_t nitems) {
+    static_assert(LOG2B == 0 || (LOG2B >= 5 && LOG2B <= 7), "a rotation block must fit 16 lanes");
+    constexpr int ES = IN_BF16 ? 2 : 4;
+    const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr uint32_t inwave_bits = (LOG2B >= 3) ? ((1u << (LOG2B - 3)) - 1u) : 0u;
+    const float sigma = (__builtin_popcount(lane & inwave_bits) & 1) ? -1.0f : 1.0f;
+    const float cs = as_f32(norm_bits(LOG2B)) * sigma;
+    const uint32_t spr = a.cpr >> 4;                                   // stages per row
+    const uint32_t lrow = lane >> 4;
+    for (uint32_t it = blockIdx.x * 4u + wave; it < nitems; it += gridDim.x * 4u) {
+        const uint32_t rq = it / spr, st = it - rq * spr;              // scalar
+        const uint32_t row0 = rq * 4u;
+        // rows past the end (M % 4 != 0) re-read the last row; their stores are masked
+        const uint32_t rrow = min(row0 + lrow, rows - 1u);
+        const char* p = (const char*)a.x + ((uint64_t)rrow * (uint64_t)a.ldx + (uint64_t)st * 128u + (lane & 15u) * 8u) * ES;
+        float v[8];
+        load_chunk<IN_BF16>(p, v);
+        if constexpr (MODE != MODE_QUANT) {
+            wht_inwave<LOG2B>(v, lane);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] *= cs;
+        }
+        const uint32_t sb = e8m0_from_amax(quad_max(absmax8(v)));
+        const uint32_t w = encode8_e2m1(v, sb);
+        uint8_t* cbase = reinterpret_cast<uint8_t*>(a.codes) + ((uint64_t)(row0 >> 6) * a.stages + st) * 4096u + (row0 & 63u) * 64u;
+        uint8_t* sbase = a.scales + ((uint64_t)(row0 >> 6) * a.sstages + (st >> 2)) * 1024u + (row0 & 63u) * 16u + (st & 3u) * 4u;
+        if (row0 + lrow < rows) {
+            __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(cbase + lane * 4u));
+            if ((lane & 3) == 0) *(sbase + lrow * 16u + ((lane >> 2) & 3u)) = (uint8_t)sb;
         }
     }
 }
@@ -283,6 +325,14 @@ static int rowwise_grid(uint32_t nchunks, int U) {
 
 template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
 static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
+    if constexpr (MODE != MODE_ROTATE && LOG2B <= 7) {
+        if (a.stages != 0 && (a.cpr & 15u) == 0) {
+            const uint32_t rows = a.nchunks / a.cpr, nitems = ((rows + 3u) / 4u) * (a.cpr >> 4);
+            int grid = rowwise_grid(nitems * 64u, 1);
+            hipLaunchKernelGGL((k_rowwise_t4<LOG2B, IN_BF16, MODE>), dim3(grid), dim3(256), 0, s, a, rows, nitems);
+            return hipGetLastError();
+        }
+    }
     constexpr int U = 1;
     int grid = rowwise_grid(a.nchunks, U);
     if (contig)

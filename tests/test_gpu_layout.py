@@ -57,7 +57,8 @@ def make_x(M, K, seed, dtype):
 
 @pytest.mark.parametrize("M,K,B,dtype", [(16, 256, 32, "f32"), (100, 544, 32, "bf16"), (300, 1024, 64, "bf16"),
                                          (65, 96, 32, "f32"), (2048, 2048, 32, "bf16"), (130, 2048, 1024, "bf16"),
-                                         (64, 512, 512, "bf16"), (1, 32, 32, "f32")])
+                                         (64, 512, 512, "bf16"), (1, 32, 32, "f32"), (66, 384, 128, "bf16"),
+                                         (7, 128, 32, "f32"), (1027, 4096, 32, "bf16")])
 def test_fused_tiled_holds_the_rowmajor_bytes(brq, M, K, B, dtype):
     x = to_dev(make_x(M, K, 11, dtype))
     c0, s0 = brq.rotate_quantize_fused(x, B)
