@@ -161,6 +161,28 @@ def main():
                     "peak": MXFP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": kernels["mxfp4_gemm"]["frac_mxfp4_peak"],
                     "traffic": PROFILED_TRAFFIC.get("mxfp4_gemm_%s_%s" % (args.workload, args.out_dtype))}
 
+    # ---- what the chip sustains on the block-scaled MFMA alone, fed from registers with bit patterns
+    # of this workload (the first 2 KB of quantized activations): the ceiling of any product kernel
+    ncu = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty((ncu * 256,), dtype=torch.float32, device="cuda")
+    with torch.cuda.stream(stream):
+        ops = codes[0].flatten()[:2048].clone()
+    c_iters = 2000
+    c_flops = brq.diag_mfma_ceiling(ops, 50, ncu, sink=sink, stream=stream)
+    c_ms = []
+    for _ in range(3):
+        a, b = ev(), ev()
+        a.record(stream)
+        for _ in range(3):
+            c_flops = brq.diag_mfma_ceiling(ops, c_iters, ncu, sink=sink, stream=stream)
+        b.record(stream)
+        stream.synchronize()
+        c_ms.append(a.elapsed_time(b) / 3)
+    ceiling = {"TFLOP/s": c_flops / (sum(c_ms) / len(c_ms)) / 1e9,
+               "frac_mxfp4_peak": c_flops / (sum(c_ms) / len(c_ms)) / 1e9 / MXFP4_PEAK_TFLOPS,
+               "note": "v_mfma_scale_f32_32x32x64 fp4 back to back from registers on every CU, operand "
+                       "bit patterns from this workload's quantized activations"}
+
     # ---- the rotate+quantize kernel on the shape its HBM target is quoted on
     aux = None
     if not args.no_aux:
@@ -242,6 +264,7 @@ def main():
         "rotate_quant_GBps": kernels["rotate_quantize_fused"]["GB/s"],
         "gemm_TFLOPs": kernels["mxfp4_gemm"]["TFLOP/s"],
         "roofline": roofline,
+        "mfma_loop_ceiling": ceiling,
         "rotate_quant_16384x8192": aux,
         "kernels": kernels,
         "cpu_baseline": cpu_baseline,

@@ -126,6 +126,19 @@ brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_lay
 brq_status brq_to_rowmajor(const uint8_t* codes_tiled, const uint8_t* scales_tiled, int64_t rows,
                            int64_t K, uint8_t* codes_out, uint8_t* scales_out, void* stream);
 
+/*
+ * Measurement aid, not part of the method: `workgroups` workgroups of 4 wavefronts each issue
+ * iters x 16 block-scaled fp4 MFMAs (v_mfma_scale_f32_32x32x64, the instruction of the product
+ * kernels) back to back from registers, 2 * 32*32*64 flops apiece, i.e. a launch does
+ * workgroups * 4 * iters * 16 * 131072 flops.  Operand fragments are read once from
+ * `operands` (2048 bytes: 16 bytes per lane for each of the two operands, e.g. the first bytes
+ * of a quantized matrix, so that the arithmetic sees realistic bit patterns); `sink` receives
+ * workgroups * 256 floats.  Timing a launch gives the rate the chip sustains on this
+ * instruction alone, the ceiling against which a product kernel's own losses can be read.
+ */
+brq_status brq_diag_mfma_ceiling(const uint8_t* operands, int64_t iters, int64_t workgroups,
+                                 float* sink, void* stream);
+
 /* Static, human-readable text for a status code. */
 const char* brq_strerror(brq_status s);
 

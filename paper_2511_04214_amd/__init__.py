@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbrq.so")
 BRQ_F32, BRQ_BF16 = 0, 1
 LAYOUTS = {"rowmajor": 0, "tiled": 1}
 EXPORTS = ["brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
-           "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_strerror", "brq_version"]
+           "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_strerror", "brq_version"]
 
 _lib = None
 
@@ -49,6 +49,8 @@ def lib():
         L.brq_mxfp4_gemm.restype = i32
         L.brq_to_rowmajor.argtypes = [vp, vp, i64, i64, vp, vp, vp]
         L.brq_to_rowmajor.restype = i32
+        L.brq_diag_mfma_ceiling.argtypes = [vp, i64, i64, vp, vp]
+        L.brq_diag_mfma_ceiling.restype = i32
         L.brq_strerror.argtypes = [i32]
         L.brq_strerror.restype = ctypes.c_char_p
         L.brq_version.restype = i32
@@ -191,3 +193,15 @@ def mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.float32, out=None, stream=None, 
     _check(lib().brq_mxfp4_gemm(aq.data_ptr(), as_.data_ptr(), la, wq.data_ptr(), ws.data_ptr(), lw, M, N, K,
                                 y.data_ptr(), _dtype_code(y), ldy, _stream(stream)))
     return y
+
+
+def diag_mfma_ceiling(operands, iters, workgroups, sink=None, stream=None):
+    """Launch the MFMA-only measurement loop (brq_diag_mfma_ceiling); returns the flops it does."""
+    if not (operands.is_cuda and operands.is_contiguous() and operands.dtype == torch.uint8 and operands.numel() >= 2048):
+        raise ValueError("operands must be a contiguous uint8 GPU tensor of at least 2048 bytes")
+    if sink is None:
+        sink = torch.empty((workgroups * 256,), dtype=torch.float32, device=operands.device)
+    if not (sink.is_cuda and sink.is_contiguous() and sink.dtype == torch.float32 and sink.numel() >= workgroups * 256):
+        raise ValueError("sink must be a contiguous float32 GPU tensor of workgroups * 256 elements")
+    _check(lib().brq_diag_mfma_ceiling(operands.data_ptr(), iters, workgroups, sink.data_ptr(), _stream(stream)))
+    return workgroups * 4 * iters * 16 * 131072

@@ -122,6 +122,16 @@ brq_status brq_to_rowmajor(const uint8_t* codes_tiled, const uint8_t* scales_til
                                             static_cast<hipStream_t>(stream)));
 }
 
+brq_status brq_diag_mfma_ceiling(const uint8_t* operands, int64_t iters, int64_t workgroups, float* sink,
+                                 void* stream) {
+    if (iters < 0 || iters >= (int64_t(1) << 31) || workgroups < 0 || workgroups > 65536) return BRQ_ERR_SHAPE;
+    if (!operands || !sink) return BRQ_ERR_NULL;
+    if (!aligned16(operands) || !aligned16(sink)) return BRQ_ERR_ALIGN;
+    if (workgroups == 0) return BRQ_OK;
+    return launched(brq::launch_mfma_ceiling(operands, (int)iters, (int)workgroups, sink,
+                                             static_cast<hipStream_t>(stream)));
+}
+
 const char* brq_strerror(brq_status s) {
     switch (s) {
         case BRQ_OK: return "ok";

@@ -30,4 +30,7 @@ hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int6
 hipError_t launch_to_rowmajor(const uint8_t* codes_t, const uint8_t* scales_t, int64_t rows, int64_t K,
                               uint8_t* codes, uint8_t* scales, hipStream_t s);
 
+// Measurement aid: `workgroups` x 4 wavefronts, each iters x 16 block-scaled fp4 MFMAs (32x32x64).
+hipError_t launch_mfma_ceiling(const uint8_t* operands, int iters, int workgroups, float* sink, hipStream_t s);
+
 }  // namespace brq

@@ -189,6 +189,41 @@ __global__ void __launch_bounds__(64) k_gemm_skinny_stream(const uint8_t* __rest
     }
 }
 
+// ---- measurement aid: the block-scaled fp4 MFMA back to back from registers ------------------
+// 4 wavefronts per workgroup, one per SIMD, 16 independent 32x32 accumulators each; operands are
+// 16 bytes per lane from `operands` (W fragment from bytes [0, 1024), A fragment from [1024, 2048)),
+// scale bytes 127.  What a launch of this sustains is the ceiling of any product kernel on the
+// same operand bit patterns: it includes the instruction's own issue overhead and whatever clock
+// the chip holds under that load, and nothing else.
+__global__ void __launch_bounds__(256, 1) k_mfma_ceiling(const uint8_t* __restrict__ operands, int iters,
+                                                         float* __restrict__ sink) {
+    const int lane = threadIdx.x & 63;
+    const v4i w = *reinterpret_cast<const v4i*>(operands + lane * 16);
+    const v4i a = *reinterpret_cast<const v4i*>(operands + 1024 + lane * 16);
+    v8i w8 = {}, a8 = {};
+    w8[0] = w[0]; w8[1] = w[1]; w8[2] = w[2]; w8[3] = w[3];
+    a8[0] = a[0]; a8[1] = a[1]; a8[2] = a[2]; a8[3] = a[3];
+    v16f acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = v16f{};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(w8, a8, acc[i], 4, 4, 0, 127, 0, 127);
+    }
+    float t = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) t += acc[i][j];
+    sink[blockIdx.x * 256 + threadIdx.x] = t;
+}
+
+hipError_t launch_mfma_ceiling(const uint8_t* operands, int iters, int workgroups, float* sink, hipStream_t s) {
+    hipLaunchKernelGGL(k_mfma_ceiling, dim3(workgroups), dim3(256), 0, s, operands, iters, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
                              bool out_bf16, int64_t ldy, hipStream_t s) {
     if (tiled_gemm_supported(M, N, K, out_bf16, ldy)) {
