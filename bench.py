@@ -32,7 +32,7 @@ BYTES_PER_ELEM = 2 + 0.5 + 1.0 / 32     # bf16 in, 4-bit code out, one scale byt
 # Bytes per launch that leave the L2s (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, scaled by a plain copy
 # of known size), from the committed counter summary under profiles/; a counter run is not part of a
 # bench run, so other workloads report null.
-PROFILED_TRAFFIC = {"mxfp4_gemm_mlp8b_bf16": 619.9e6, "rotate_quant_16384x8192": 341.3e6}
+PROFILED_TRAFFIC = {"mxfp4_gemm_mlp8b_bf16": 616.2e6, "rotate_quant_16384x8192": 339.7e6}
 
 
 def main():
