@@ -31,7 +31,7 @@ MXFP4_PEAK_TFLOPS = 10100.0      # MI355X dense fp4 MFMA, published
 BYTES_PER_ELEM = 2 + 0.5 + 1.0 / 32     # bf16 in, 4-bit code out, one scale byte per 32
 # Bytes per launch that leave the L2s (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, scaled by a plain copy
 # of known size), from the committed counter summary under profiles/; a counter run is not part of a
-# bench run, so other workloads report null.
+# bench run, so other workloads (and the row-major layout) report null.
 PROFILED_TRAFFIC = {"mxfp4_gemm_mlp8b_bf16": 616.2e6, "rotate_quant_16384x8192": 339.7e6}
 
 
@@ -159,7 +159,8 @@ def main():
     else:
         roofline = {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": kernels["mxfp4_gemm"]["TFLOP/s"],
                     "peak": MXFP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": kernels["mxfp4_gemm"]["frac_mxfp4_peak"],
-                    "traffic": PROFILED_TRAFFIC.get("mxfp4_gemm_%s_%s" % (args.workload, args.out_dtype))}
+                    "traffic": PROFILED_TRAFFIC.get("mxfp4_gemm_%s_%s" % (args.workload, args.out_dtype))
+                    if LAY == "tiled" else None}
 
     # ---- what the chip sustains on the block-scaled MFMA alone, fed from registers with bit patterns
     # of this workload (the first 2 KB of quantized activations): the ceiling of any product kernel
@@ -214,7 +215,7 @@ def main():
         aux = {"kernel": "rotate_quantize_fused", "bound": "hbm", "avg_ms": float(ams.mean()),
                "min_ms": float(ams.min()), "alg_bytes": ab, "achieved": ab / float(ams.mean()) / 1e6,
                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ab / float(ams.mean()) / 1e6 / HBM_PEAK_GBS,
-               "traffic": PROFILED_TRAFFIC["rotate_quant_16384x8192"]}
+               "traffic": PROFILED_TRAFFIC["rotate_quant_16384x8192"] if LAY == "tiled" else None}
         del axs, ac, asc
 
     if args.calibrate_copy:
