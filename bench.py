@@ -137,6 +137,8 @@ def main():
 
     rq_ms = train(rq)
     gm_ms = train(gemm)
+    # the same product on ONE buffer set: operands stay in the 256 MB memory-side cache ("warm")
+    gm_warm_ms = train(lambda j: gemm(0), reps=3)
 
     ms_per_step = wall * 1e3 / args.steps
     rq_bytes = M * K * BYTES_PER_ELEM
@@ -144,10 +146,12 @@ def main():
     gemm_bytes = (gemm_M + N) * K * 0.53125 + gemm_M * N * out_es
     rq_avg, gm_avg = float(rq_ms.mean()), float(gm_ms.mean())
     kernels = {
-        "rotate_quantize_fused": {"avg_ms": rq_avg, "min_ms": float(rq_ms.min()), "alg_bytes": rq_bytes,
+        "rotate_quantize_fused": {"avg_ms": rq_avg, "median_ms": float(np.median(rq_ms)), "min_ms": float(rq_ms.min()),
+                                  "alg_bytes": rq_bytes,
                                   "GB/s": rq_bytes / rq_avg / 1e6,
                                   "frac_hbm_peak": rq_bytes / rq_avg / 1e6 / HBM_PEAK_GBS},
-        "mxfp4_gemm": {"avg_ms": gm_avg, "min_ms": float(gm_ms.min()), "flops": gemm_flops, "alg_bytes": gemm_bytes,
+        "mxfp4_gemm": {"avg_ms": gm_avg, "median_ms": float(np.median(gm_ms)), "min_ms": float(gm_ms.min()),
+                       "warm_cache_avg_ms": float(gm_warm_ms.mean()), "flops": gemm_flops, "alg_bytes": gemm_bytes,
                        "TFLOP/s": gemm_flops / gm_avg / 1e9,
                        "frac_mxfp4_peak": gemm_flops / gm_avg / 1e9 / MXFP4_PEAK_TFLOPS,
                        "GB/s": gemm_bytes / gm_avg / 1e6, "frac_hbm_peak": gemm_bytes / gm_avg / 1e6 / HBM_PEAK_GBS},
@@ -244,8 +248,20 @@ def main():
         # the same unit as `value`: useful layer flops per second of (rotate+quantize + product) time,
         # both legs scaled to the full M rows
         t_full = t_rq * (M / rows) + t_g * (gemm_M / grows)
+        # the same two legs on one thread, on smaller samples (1/8 and 1/32)
+        o.set_threads(1)
+        r1, g1 = max(1, rows // 8), max(1, grows // 32)
+        t0 = time.perf_counter()
+        o.rotate_quantize_fused(x_np[:r1], B)
+        t_rq1 = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        o.mxfp4_gemm(rc[:g1], rs[:g1], wq_h, ws_h, want_bound=False)
+        t_g1 = time.perf_counter() - t0
+        o.set_threads(threads)
+        t_full1 = t_rq1 * (M / r1) + t_g1 * (gemm_M / g1)
         cpu_baseline = {
             "value": gemm_flops / t_full / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "value_one_thread": gemm_flops / t_full1 / 1e12,
             "sample": "rotate+quantize of the first %d of %d rows in %.2f s (%.2f GB/s); product of %d rows "
                       "x N=%d x K=%d in %.2f s incl. dequantizing W (%.4f TFLOP/s); both scaled linearly to M=%d"
                       % (rows, M, t_rq, rows * K * BYTES_PER_ELEM / t_rq / 1e9, grows, N, K, t_g,
