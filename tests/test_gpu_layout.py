@@ -134,3 +134,62 @@ def test_binding_checks_tiled_buffers(brq):
         brq.mxfp4_gemm(ct, st, ct, st, a_layout="tiled", w_layout="tiled")      # no shape given
     with pytest.raises(ValueError):
         brq.mxfp4_gemm(ct, st, ct, st, a_layout="tiled", w_layout="tiled", M=128, N=64, K=512)   # too small
+
+
+# ------------------------------------------------------------------ full-size workloads, as bench.py runs them
+
+@pytest.mark.parametrize("name", ["mlp8b", "decode"])
+def test_fused_tiled_full_size_against_the_oracle(brq, orc, name):
+    """The benchmark's launch (tiled output) at the benchmark's sizes: every code and every scale
+    byte against the oracle, through the address formulas above."""
+    from paper_2511_04214_amd import inputs
+    cfg = inputs.CONFIGS[name]
+    x = inputs.make_x(cfg)
+    M, K = x.shape
+    ct, st = brq.rotate_quantize_fused(to_dev(x), 32, layout="tiled")
+    oc, os_ = orc.rotate_quantize_fused(x, 32)
+    ci, si = tiled_indices(M, K)
+    assert np.array_equal(to_host(ct)[ci], oc)
+    assert np.array_equal(to_host(st)[si], os_)
+
+
+@pytest.mark.parametrize("name", ["mlp8b", "down_sweep"])
+def test_product_tiled_full_size_sampled_rows(brq, orc, name):
+    """bench.py's step on its own inputs (tiled operands, bf16 and fp32 out); the oracle computes
+    a sample of full output rows from its own quantization of the same inputs."""
+    from paper_2511_04214_amd import inputs
+    cfg = inputs.CONFIGS[name]
+    M, N, K = cfg["M"], cfg["N"], cfg["K"]
+    x, w = inputs.make_x(cfg), inputs.make_w(cfg)
+    act, ast = brq.rotate_quantize_fused(to_dev(x), 32, layout="tiled")
+    wct, wst = brq.rotate_quantize_fused(to_dev(w), 32, layout="tiled")
+    y32 = brq.mxfp4_gemm(act, ast, wct, wst, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)
+    y16 = brq.mxfp4_gemm(act, ast, wct, wst, out_dtype=torch.bfloat16, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)
+    rng = np.random.default_rng(78)
+    rows = sorted(set([0, 63, 64, 255, 256, M - 256, M - 1] + rng.integers(0, M, 5).tolist()))
+    oa, oas = orc.rotate_quantize_fused(x[rows], 32)
+    ow, ows = orc.rotate_quantize_fused(w, 32)
+    ref, bound = orc.mxfp4_gemm(oa, oas, ow, ows)
+    got = to_host(y32).astype(np.float64)[rows]
+    assert (np.abs(got - ref) <= 1e-5 * bound + 2.0 ** -126).all()
+    assert np.linalg.norm(got - ref) <= 1e-5 * np.linalg.norm(ref)
+    # bf16 output = round-to-nearest-even of the fp32 output, everywhere
+    u = to_host(y32).view(np.uint32)
+    rne = ((u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) >> np.uint32(16)).astype(np.uint16)
+    assert np.array_equal(to_host(y16), rne)
+
+
+@pytest.mark.parametrize("M", [1, 16])
+def test_product_decode_tiled_full_size(brq, orc, M):
+    from paper_2511_04214_amd import inputs
+    cfg = inputs.CONFIGS["decode"]
+    N, K = cfg["N"], cfg["K"]
+    x = inputs.make_x(cfg, M=16)[:M]
+    w = inputs.make_w(cfg)
+    act, ast = brq.rotate_quantize_fused(to_dev(x), 32, layout="tiled")
+    wct, wst = brq.rotate_quantize_fused(to_dev(w), 32, layout="tiled")
+    y = to_host(brq.mxfp4_gemm(act, ast, wct, wst, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)).astype(np.float64)
+    oa, oas = orc.rotate_quantize_fused(x, 32)
+    ow, ows = orc.rotate_quantize_fused(w, 32)
+    ref, bound = orc.mxfp4_gemm(oa, oas, ow, ows)
+    assert (np.abs(y - ref) <= 1e-5 * bound + 2.0 ** -126).all()
