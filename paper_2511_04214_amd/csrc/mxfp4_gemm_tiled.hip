@@ -124,7 +124,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     const int wn = wave >> 1, wm = wave & 1;   // this wavefront's 128 W rows / 128 A rows inside the tile
 
     TileWalk tw;
-    tw.tiles_m = M / TM;
+    tw.tiles_m = (M + TM - 1) / TM;            // the last tile row may be ragged: loads clamp, stores mask
     tw.tiles_n = N / TN;
     {
         const int T = tw.tiles_m * tw.tiles_n, G = gridDim.x;   // G is a multiple of 8
@@ -155,7 +155,8 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
                          : (uint32_t)(((lane >> 2) + 16 * q) * cpitch) + swz16;
     }
     const uint32_t vscw = w_tiled ? (uint32_t)(lane * 16) : (uint32_t)(lane * spitch);
-    const uint32_t vsca = a_tiled ? (uint32_t)(lane * 16) : (uint32_t)(lane * spitch);
+    uint32_t vsca = a_tiled ? (uint32_t)(lane * 16) : (uint32_t)(lane * spitch);
+    bool a_clamped = false;   // row-major A: the per-lane offsets currently hold clamped rows
     // byte steps: stage to stage, superstage to superstage (codes), superstage to superstage (scales)
     const int w_stage = w_tiled ? 4096 : 64, w_super = w_tiled ? 16384 : 256, w_ssuper = w_tiled ? 1024 : 16;
     const int a_stage = a_tiled ? 4096 : 64, a_super = a_tiled ? 16384 : 256, a_ssuper = a_tiled ? 1024 : 16;
@@ -172,9 +173,29 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             tw.tile(min(p_tile, ntiles - 1), tm, tn);
             const int64_t wrow = (int64_t)tn * TN + wave * 64, arow = (int64_t)tm * TM + wave * 64;   // slab rows
             const uint8_t* bw = w_tiled ? wq + (wrow >> 6) * (cpitch / 64) * 4096 : wq + wrow * cpitch;
-            const uint8_t* ba = a_tiled ? aq + (arow >> 6) * (cpitch / 64) * 4096 : aq + arow * cpitch;
             p_ws = uniform_ptr(w_tiled ? ws + (wrow >> 6) * (spitch / 16) * 1024 : ws + wrow * spitch);
-            p_as = uniform_ptr(a_tiled ? as + (arow >> 6) * (spitch / 16) * 1024 : as + arow * spitch);
+            // A slab of the ragged last tile row: rows past M - 1 are never stored, but their loads
+            // must stay inside the operand.  Tiled: the buffer has whole 64-row slabs, so a slab
+            // index past the last one is clamped.  Row-major: the slab base moves back to at most
+            // M - 64 and every lane clamps its row to M - 1.
+            const uint8_t *ba, *bas;
+            if (a_tiled) {
+                const int64_t slab = min(arow >> 6, (int64_t)(M + 63) / 64 - 1);
+                ba = aq + slab * (cpitch / 64) * 4096;
+                bas = as + slab * (spitch / 16) * 1024;
+            } else {
+                const int64_t abase = min(arow, max((int64_t)M - 64, (int64_t)0));
+                ba = aq + abase * cpitch;
+                bas = as + abase * spitch;
+                if (arow + 64 > M || a_clamped) {        // uniform; also restores the plain offsets afterwards
+                    a_clamped = arow + 64 > M;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        vqa[q] = (uint32_t)((min(arow + (lane >> 2) + 16 * q, (int64_t)M - 1) - abase) * cpitch) + swz16;
+                    vsca = (uint32_t)((min(arow + lane, (int64_t)M - 1) - abase) * spitch);
+                }
+            }
+            p_as = uniform_ptr(bas);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 p_w[u] = uniform_ptr(bw + u * w_stage);
@@ -382,12 +403,13 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             o2 = *reinterpret_cast<const uint4*>(erd + 2048);
             o3 = *reinterpret_cast<const uint4*>(erd + 3072);
         };
+        const int mrem = M - (tm * TM + wm * 128) - (lane >> 3);   // this lane stores rows row + 8 j < mrem
         auto store_block = [&](int row, int colbytes) {
             uint8_t* dst = ytile + row * pitch + colbytes;
-            *reinterpret_cast<uint4*>(dst + st_off) = o0;
-            *reinterpret_cast<uint4*>(dst + st_off + 8 * pitch) = o1;
-            *reinterpret_cast<uint4*>(dst + st_off + 16 * pitch) = o2;
-            *reinterpret_cast<uint4*>(dst + st_off + 24 * pitch) = o3;
+            if (row < mrem) *reinterpret_cast<uint4*>(dst + st_off) = o0;
+            if (row + 8 < mrem) *reinterpret_cast<uint4*>(dst + st_off + 8 * pitch) = o1;
+            if (row + 16 < mrem) *reinterpret_cast<uint4*>(dst + st_off + 16 * pitch) = o2;
+            if (row + 24 < mrem) *reinterpret_cast<uint4*>(dst + st_off + 24 * pitch) = o3;
         };
         if constexpr (OUT_BF16) {
             // block = (b, pair of W tiles): 32 rows x 64 columns.  v_permlane32_swap trades q
@@ -447,7 +469,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 }  // namespace tiled
 
 bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy) {
-    return M > 0 && N > 0 && M % tiled::TM == 0 && N % tiled::TN == 0 && K % 512 == 0 &&
+    return M > 0 && N > 0 && N % tiled::TN == 0 && K % 512 == 0 &&
            (ldy * (out_bf16 ? 2 : 4)) % 16 == 0 && ldy * (out_bf16 ? 2 : 4) < (int64_t(1) << 28) &&
            (K / 2) * 64 < (int64_t(1) << 31);
 }
@@ -469,7 +491,7 @@ hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int6
         if (e != hipSuccess) return e;
         cus = n;
     }
-    const int T = (int)((M / tiled::TM) * (N / tiled::TN));
+    const int T = (int)(((M + tiled::TM - 1) / tiled::TM) * (N / tiled::TN));
     const int grid = T < cus ? ((T + 7) & ~7) : cus;
     if (out_bf16)
         hipLaunchKernelGGL(tiled::k_gemm_tiled<true>, dim3(grid), dim3(256), tiled::LDS_BYTES, s, a.codes, a.scales,

@@ -57,7 +57,10 @@ def check_gemm(brq, orc, aq, as_, wq, ws, rows=None, ldy=None):
 
 @pytest.mark.parametrize("M,N,K", [(64, 64, 64), (33, 70, 96), (128, 256, 512), (1, 16, 32), (100, 36, 2080),
                                    (256, 256, 1024), (300, 520, 768), (17, 1000, 256),
-                                   (256, 256, 512), (512, 768, 2048), (768, 256, 1536), (2304, 512, 512)])
+                                   (256, 256, 512), (512, 768, 2048), (768, 256, 1536), (2304, 512, 512),
+                                   # ragged M in the persistent tiled kernel (N % 256 == 0, K % 512 == 0)
+                                   (300, 256, 512), (257, 512, 1024), (17, 256, 512), (1000, 768, 2048),
+                                   (255, 256, 512), (64, 256, 512), (513, 256, 512)])
 def test_gemm_random_codes(brq, orc, M, N, K):
     from paper_2511_04214_amd import inputs
     aq, as_ = inputs.random_mxfp4(M, K, seed=M * 7 + K)

@@ -94,7 +94,7 @@ def test_fused_tiled_against_the_oracle(brq, orc):
 
 # tiled persistent kernel, general 32x32-tile kernel, M <= 16 kernel
 @pytest.mark.parametrize("M,N,K", [(512, 768, 2048), (256, 256, 512), (100, 200, 544), (300, 64, 1024),
-                                   (8, 300, 1024), (16, 48, 96)])
+                                   (8, 300, 1024), (16, 48, 96), (300, 256, 1024), (65, 512, 512), (700, 256, 512)])
 def test_product_does_not_depend_on_the_layout(brq, M, N, K):
     from paper_2511_04214_amd import inputs
     aq, as_ = inputs.random_mxfp4(M, K, seed=21)
