@@ -19,7 +19,9 @@
 // read one contiguous 64-byte row segment, and the XOR spreads rows over the LDS banks for
 // the MFMA-side ds_read_b128 (16 consecutive rows of one chunk -> 16 distinct 16-byte bank
 // groups).  Scales travel the same way, 16 bytes (the 16 groups of 512 K elements) of one
-// row per lane.
+// row per lane.  Both operands may come row-major or in the tiled layout of brq.h (64-row
+// slabs, one contiguous 4 KB block per slab and stage): only the per-lane global offsets and
+// the stage-to-stage pointer steps differ, the LDS image is the same.
 //
 // A ring of 4 code stages and 2 scale buffers runs continuously across the tiles a
 // workgroup processes: the next tile's first stages are loading during the current tile's
@@ -30,8 +32,12 @@
 // scheduling barriers, and the K loop is unrolled by 4 so that every LDS address is an
 // immediate offset.
 //
+// The output leaves through a 4 KB LDS block per wavefront that turns the accumulator layout
+// (neighbouring lanes = different rows) into whole 128-byte row segments per 8 lanes.  M may be
+// ragged: the last tile row clamps its A loads and masks its stores.
+//
 // LDS map (bytes): [0, 128K) 4 stages x (W rows 16K | A rows 16K); [128K, 144K) 2 scale
-// buffers x (W 4K | A 4K).
+// buffers x (W 4K | A 4K); [144K, 160K) 4 epilogue blocks.
 #include "brq_device.h"
 #include "brq_launch.h"
 
