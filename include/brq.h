@@ -56,7 +56,7 @@ typedef enum {
     BRQ_OK = 0,
     BRQ_ERR_NULL = 1,        /* a required pointer is NULL */
     BRQ_ERR_SHAPE = 2,       /* negative size, K % 32 != 0, ld < K, size beyond 2^31 work items */
-    BRQ_ERR_BLOCK = 3,       /* B not a power of two, B < 32, B > 16384 or B does not divide K */
+    BRQ_ERR_BLOCK = 3,       /* B not a power of two, B < 8, B > 16384 or B does not divide K */
     BRQ_ERR_ALIGN = 4,       /* pointer or pitch not 16-byte aligned */
     BRQ_ERR_DTYPE = 5,       /* dtype is not one of brq_dtype */
     BRQ_ERR_LAUNCH = 6,      /* hipLaunchKernel failed (hipGetLastError) */
@@ -76,17 +76,22 @@ brq_status brq_operand_bytes(int64_t rows, int64_t K, brq_layout layout, int64_t
                              int64_t* scales_bytes);
 
 /*
- * y = x * diag(H_B, ..., H_B) / sqrt(B)          (Sec. 4.3, Eq. 1 with R_i = Sylvester
+ * y = x * diag(s) * diag(H_B, ..., H_B) / sqrt(B)   (Sec. 4.3, Eq. 1 with R_i = Sylvester
  * Hadamard of order B, normalised so that R_i^T R_i = I; B = K is the global rotation
- * the paper compares with).
+ * the paper compares with; B = 8 ... 128 is the rotation-dimension sweep of Sec. 5.3).
+ * signs: NULL, or K sign bytes s_k (device memory, 16-byte aligned): element k of every row is
+ * negated before the butterfly where signs[k] < 0 -- the random sign diagonal of the
+ * "randomized Hadamard" rotations of Sec. 5.1; diag(s) H_B / sqrt(B) is still orthogonal, and
+ * weights and activations must use the same signs.
  * Arithmetic: inputs widened exactly to fp32; stages h = 1, 2, ..., B/2 in ascending
  * order, pair (i, i+h) -> (a+b, a-b), each one IEEE fp32 operation; one fp32 multiply by
  * fl(1/sqrt(B)).  ydt = BRQ_F32 stores that value, BRQ_BF16 its round-to-nearest-even.
  * x [M][ldx] of xdt, y [M][ldy] of ydt; x and y must not overlap.
- * B: power of two, 32 <= B <= 16384, B divides K.
+ * B: power of two, 8 <= B <= 16384, B divides K.
  */
 brq_status brq_block_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx,
-                            int64_t B, void* y, brq_dtype ydt, int64_t ldy, void* stream);
+                            int64_t B, const int8_t* signs, void* y, brq_dtype ydt, int64_t ldy,
+                            void* stream);
 
 /*
  * MXFP4 quantization of x along K (Sec. 4.1): per row and per group of 32 consecutive
@@ -99,13 +104,13 @@ brq_status brq_mxfp4_quantize(const void* x, brq_dtype xdt, int64_t M, int64_t K
 
 /*
  * The online step of the method (Sec. 4.3, the rotation applied before a quantized
- * linear layer): brq_mxfp4_quantize(brq_block_rotate(x, B) kept in fp32), in one pass
+ * linear layer): brq_mxfp4_quantize(brq_block_rotate(x, B, signs) kept in fp32), in one pass
  * over x, bit-identical to that composition.  The quantization group stays 32 whatever
  * B is.  Same argument rules as the two calls above.
  */
 brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K,
-                                     int64_t ldx, int64_t B, uint8_t* codes, uint8_t* scales,
-                                     brq_layout layout, void* stream);
+                                     int64_t ldx, int64_t B, const int8_t* signs, uint8_t* codes,
+                                     uint8_t* scales, brq_layout layout, void* stream);
 
 /*
  * W4A4 product on MXFP4 operands (Sec. 2; Sec. 4.1 "scaling factor integrated into

@@ -46,6 +46,7 @@ def _bind(path):
     L.oracle_rotation_norm.argtypes = [i64]
     L.oracle_rotation_norm.restype = ctypes.c_float
     L.oracle_block_rotate.argtypes = [vp, i32, i64, i64, i64, i64, vp, i32, i64]
+    L.oracle_block_rotate_signed.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i32, i64]
     L.oracle_e2m1_value.argtypes = [i32]
     L.oracle_e2m1_value.restype = ctypes.c_double
     L.oracle_e8m0_from_amax.argtypes = [ctypes.c_float]
@@ -56,6 +57,7 @@ def _bind(path):
     L.oracle_e2m1_encode.restype = ctypes.c_uint8
     L.oracle_mxfp4_quantize.argtypes = [vp, i32, i64, i64, i64, vp, vp]
     L.oracle_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp]
+    L.oracle_rotate_quantize_fused_signed.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
     L.oracle_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, vp]
     L.oracle_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_matmul_nt_f64.argtypes = [vp, vp, i64, i64, i64, vp]
@@ -77,6 +79,13 @@ def _dt(a):
     if a.dtype == np.uint16:
         return BF16
     raise TypeError("oracle takes float32, or uint16 holding bf16 bits; got %s" % a.dtype)
+
+
+def _signs(signs, K):
+    sg = np.ascontiguousarray(signs, dtype=np.int8)
+    if sg.shape != (K,):
+        raise ValueError("signs must have K elements")
+    return sg
 
 
 def _rows(a):
@@ -126,11 +135,16 @@ class Oracle:
     def rotation_norm(self, B):
         return np.float32(self.L.oracle_rotation_norm(B))
 
-    def block_rotate(self, x, B, out_bf16=False):
+    def block_rotate(self, x, B, out_bf16=False, signs=None):
         x, M, K, ldx = _rows(x)
         y = np.empty((M, K), dtype=np.uint16 if out_bf16 else np.float32)
-        _check(self.L.oracle_block_rotate(_p(x), _dt(x), M, K, ldx, B, _p(y), BF16 if out_bf16 else F32, K),
-               "block_rotate")
+        if signs is None:
+            _check(self.L.oracle_block_rotate(_p(x), _dt(x), M, K, ldx, B, _p(y), BF16 if out_bf16 else F32, K),
+                   "block_rotate")
+        else:
+            sg = _signs(signs, K)
+            _check(self.L.oracle_block_rotate_signed(_p(x), _dt(x), M, K, ldx, B, _p(sg), _p(y),
+                                                     BF16 if out_bf16 else F32, K), "block_rotate_signed")
         return y
 
     def e2m1_value(self, code):
@@ -152,12 +166,17 @@ class Oracle:
         _check(self.L.oracle_mxfp4_quantize(_p(x), _dt(x), M, K, ldx, _p(codes), _p(scales)), "mxfp4_quantize")
         return codes, scales
 
-    def rotate_quantize_fused(self, x, B):
+    def rotate_quantize_fused(self, x, B, signs=None):
         x, M, K, ldx = _rows(x)
         codes = np.empty((M, K // 2), dtype=np.uint8)
         scales = np.empty((M, K // 32), dtype=np.uint8)
-        _check(self.L.oracle_rotate_quantize_fused(_p(x), _dt(x), M, K, ldx, B, _p(codes), _p(scales)),
-               "rotate_quantize_fused")
+        if signs is None:
+            _check(self.L.oracle_rotate_quantize_fused(_p(x), _dt(x), M, K, ldx, B, _p(codes), _p(scales)),
+                   "rotate_quantize_fused")
+        else:
+            sg = _signs(signs, K)
+            _check(self.L.oracle_rotate_quantize_fused_signed(_p(x), _dt(x), M, K, ldx, B, _p(sg), _p(codes),
+                                                              _p(scales)), "rotate_quantize_fused_signed")
         return codes, scales
 
     def mxfp4_dequantize(self, codes, scales):

@@ -158,8 +158,8 @@ static void butterfly_f32(float *v, int64_t B) {
 float oracle_rotation_norm(int64_t B) { return (float)(1.0 / sqrt((double)B)); }
 
 /* x: [M][ldx] of xdt, y: [M][ldy] of ydt (fp32, or bf16 = RNE of the fp32 value). */
-int oracle_block_rotate(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
-                        void *y, int ydt, int64_t ldy) {
+int oracle_block_rotate_signed(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
+                               const int8_t *signs, void *y, int ydt, int64_t ldy) {
     if (!x || !y || !is_pow2(B) || B < 2 || K % B || ldx < K || ldy < K) return ORACLE_ERR_ARG;
     const float c = oracle_rotation_norm(B);
     int rc = ORACLE_OK;
@@ -170,7 +170,13 @@ int oracle_block_rotate(const void *x, int xdt, int64_t M, int64_t K, int64_t ld
         for (int64_t r = 0; r < M; ++r) {
             if (!v) { rc = ORACLE_ERR_ARG; continue; }
             for (int64_t b = 0; b < K / B; ++b) {
-                for (int64_t i = 0; i < B; ++i) v[i] = load_elem(x, xdt, r * ldx + b * B + i);
+                for (int64_t i = 0; i < B; ++i) {
+                    float e = load_elem(x, xdt, r * ldx + b * B + i);
+                    /* randomized Hadamard (Sec. 5.1): x D H with D = diag(s), s_k = +-1; the
+                       flip is exact and comes before the butterfly */
+                    if (signs && signs[b * B + i] < 0) e = -e;
+                    v[i] = e;
+                }
                 butterfly_f32(v, B);
                 for (int64_t i = 0; i < B; ++i) {
                     float out = v[i] * c;
@@ -184,6 +190,11 @@ int oracle_block_rotate(const void *x, int xdt, int64_t M, int64_t K, int64_t ld
         free(v);
     }
     return rc;
+}
+
+int oracle_block_rotate(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
+                        void *y, int ydt, int64_t ldy) {
+    return oracle_block_rotate_signed(x, xdt, M, K, ldx, B, NULL, y, ydt, ldy);
 }
 
 /* ------------------------------------------------------------------------------------
@@ -269,15 +280,22 @@ int oracle_mxfp4_quantize(const void *x, int xdt, int64_t M, int64_t K, int64_t 
 }
 
 /* Fused call = quantize(block_rotate(x) kept in fp32): the composition, nothing else. */
-int oracle_rotate_quantize_fused(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx,
-                                 int64_t B, uint8_t *codes, uint8_t *scales) {
-    if (!x || !codes || !scales || K % 32 || B < 32) return ORACLE_ERR_ARG;
+int oracle_rotate_quantize_fused_signed(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx,
+                                        int64_t B, const int8_t *signs, uint8_t *codes, uint8_t *scales) {
+    /* B may be smaller than the quantization group (rotation-dimension sweep, Sec. 5.3): the
+       rotation block and the 32-element group are independent */
+    if (!x || !codes || !scales || K % 32 || B < 2) return ORACLE_ERR_ARG;
     float *y = (float *)malloc((size_t)M * (size_t)K * sizeof(float));
     if (!y) return ORACLE_ERR_ARG;
-    int rc = oracle_block_rotate(x, xdt, M, K, ldx, B, y, ORACLE_F32, K);
+    int rc = oracle_block_rotate_signed(x, xdt, M, K, ldx, B, signs, y, ORACLE_F32, K);
     if (rc == ORACLE_OK) rc = oracle_mxfp4_quantize(y, ORACLE_F32, M, K, K, codes, scales);
     free(y);
     return rc;
+}
+
+int oracle_rotate_quantize_fused(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx,
+                                 int64_t B, uint8_t *codes, uint8_t *scales) {
+    return oracle_rotate_quantize_fused_signed(x, xdt, M, K, ldx, B, NULL, codes, scales);
 }
 
 /* deq[r][k] = value(code) * 2^(scale - 127), fp64 (exact). */

@@ -37,13 +37,13 @@ def lib():
                               "(python paper_2511_04214_amd/build.py) first")
         L = ctypes.CDLL(LIB_PATH)
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
-        L.brq_block_rotate.argtypes = [vp, i32, i64, i64, i64, i64, vp, i32, i64, vp]
+        L.brq_block_rotate.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i32, i64, vp]
         L.brq_block_rotate.restype = i32
         L.brq_operand_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.brq_operand_bytes.restype = i32
         L.brq_mxfp4_quantize.argtypes = [vp, i32, i64, i64, i64, vp, vp, i32, vp]
         L.brq_mxfp4_quantize.restype = i32
-        L.brq_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i32, vp]
+        L.brq_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp, i32, vp]
         L.brq_rotate_quantize_fused.restype = i32
         L.brq_mxfp4_gemm.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp]
         L.brq_mxfp4_gemm.restype = i32
@@ -84,13 +84,22 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def block_rotate(x, B, out_dtype=torch.float32, out=None, stream=None):
-    """y = x * diag(H_B..H_B)/sqrt(B) along the last axis (brq_block_rotate)."""
+def _signs_ptr(signs, K):
+    """signs: None, or an int8 GPU tensor of K sign values (negative = flip)."""
+    if signs is None:
+        return None
+    if not (signs.is_cuda and signs.is_contiguous() and signs.dtype == torch.int8 and signs.numel() == K):
+        raise ValueError("signs must be a contiguous int8 GPU tensor with K elements")
+    return signs.data_ptr()
+
+
+def block_rotate(x, B, out_dtype=torch.float32, out=None, stream=None, signs=None):
+    """y = x * diag(signs) * diag(H_B..H_B)/sqrt(B) along the last axis (brq_block_rotate)."""
     M, K, ldx = _rows(x, "x")
     y = torch.empty((M, K), dtype=out_dtype, device=x.device) if out is None else out
     _, _, ldy = _rows(y, "out")
-    _check(lib().brq_block_rotate(x.data_ptr(), _dtype_code(x), M, K, ldx, B, y.data_ptr(), _dtype_code(y), ldy,
-                                  _stream(stream)))
+    _check(lib().brq_block_rotate(x.data_ptr(), _dtype_code(x), M, K, ldx, B, _signs_ptr(signs, K), y.data_ptr(),
+                                  _dtype_code(y), ldy, _stream(stream)))
     return y
 
 
@@ -138,13 +147,13 @@ def mxfp4_quantize(x, codes=None, scales=None, stream=None, layout="rowmajor"):
     return codes, scales
 
 
-def rotate_quantize_fused(x, B, codes=None, scales=None, stream=None, layout="rowmajor"):
+def rotate_quantize_fused(x, B, codes=None, scales=None, stream=None, layout="rowmajor", signs=None):
     """Block rotation fused with MXFP4 quantization (brq_rotate_quantize_fused)."""
     M, K, ldx = _rows(x, "x")
     lc = _layout_code(layout)
     codes, scales = _alloc_q(x, M, K, codes, scales, layout)
-    _check(lib().brq_rotate_quantize_fused(x.data_ptr(), _dtype_code(x), M, K, ldx, B, codes.data_ptr(),
-                                           scales.data_ptr(), lc, _stream(stream)))
+    _check(lib().brq_rotate_quantize_fused(x.data_ptr(), _dtype_code(x), M, K, ldx, B, _signs_ptr(signs, K),
+                                           codes.data_ptr(), scales.data_ptr(), lc, _stream(stream)))
     return codes, scales
 
 

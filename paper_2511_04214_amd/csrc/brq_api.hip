@@ -10,7 +10,7 @@ int dtype_size(brq_dtype d) { return d == BRQ_F32 ? 4 : (d == BRQ_BF16 ? 2 : 0);
 
 // log2 of the rotation block, or -1 if B is not an accepted block size for this K
 int block_log2(int64_t B, int64_t K) {
-    if (B < 32 || B > 16384 || (B & (B - 1)) != 0 || K % B != 0) return -1;
+    if (B < 8 || B > 16384 || (B & (B - 1)) != 0 || K % B != 0) return -1;
     int l = 0;
     while ((int64_t(1) << l) < B) ++l;
     return l;
@@ -42,16 +42,17 @@ brq_status launched(hipError_t e) { return e == hipSuccess ? BRQ_OK : BRQ_ERR_LA
 extern "C" {
 
 brq_status brq_block_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
-                            void* y, brq_dtype ydt, int64_t ldy, void* stream) {
+                            const int8_t* signs, void* y, brq_dtype ydt, int64_t ldy, void* stream) {
     brq_status st = check_rows(x, xdt, M, K, ldx);
     if (st != BRQ_OK) return st;
     st = check_rows(y, ydt, M, K, ldy);
     if (st != BRQ_OK) return st;
+    if (!aligned16(signs)) return BRQ_ERR_ALIGN;
     int l2 = block_log2(B, K);
     if (l2 < 0) return BRQ_ERR_BLOCK;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_rowwise(0, l2, xdt == BRQ_BF16, ydt == BRQ_BF16, x, M, K, ldx, y, ldy, nullptr,
-                                        nullptr, false, static_cast<hipStream_t>(stream)));
+                                        nullptr, false, signs, static_cast<hipStream_t>(stream)));
 }
 
 brq_status brq_operand_bytes(int64_t rows, int64_t K, brq_layout layout, int64_t* codes_bytes,
@@ -77,21 +78,23 @@ brq_status brq_mxfp4_quantize(const void* x, brq_dtype xdt, int64_t M, int64_t K
     if (st != BRQ_OK) return st;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_rowwise(1, 0, xdt == BRQ_BF16, false, x, M, K, ldx, nullptr, 0, codes, scales,
-                                        layout == BRQ_LAYOUT_TILED, static_cast<hipStream_t>(stream)));
+                                        layout == BRQ_LAYOUT_TILED, nullptr, static_cast<hipStream_t>(stream)));
 }
 
 brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
-                                     uint8_t* codes, uint8_t* scales, brq_layout layout, void* stream) {
+                                     const int8_t* signs, uint8_t* codes, uint8_t* scales, brq_layout layout,
+                                     void* stream) {
     brq_status st = check_rows(x, xdt, M, K, ldx);
     if (st != BRQ_OK) return st;
     if (!layout_ok(layout)) return BRQ_ERR_LAYOUT;
+    if (!aligned16(signs)) return BRQ_ERR_ALIGN;
     st = check_out(codes, scales, M);
     if (st != BRQ_OK) return st;
     int l2 = block_log2(B, K);
     if (l2 < 0) return BRQ_ERR_BLOCK;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_rowwise(2, l2, xdt == BRQ_BF16, false, x, M, K, ldx, nullptr, 0, codes, scales,
-                                        layout == BRQ_LAYOUT_TILED, static_cast<hipStream_t>(stream)));
+                                        layout == BRQ_LAYOUT_TILED, signs, static_cast<hipStream_t>(stream)));
 }
 
 brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
@@ -137,7 +140,7 @@ const char* brq_strerror(brq_status s) {
         case BRQ_OK: return "ok";
         case BRQ_ERR_NULL: return "a required pointer is NULL";
         case BRQ_ERR_SHAPE: return "bad shape: negative size, K not a multiple of 32, pitch below row length, or too large";
-        case BRQ_ERR_BLOCK: return "bad rotation block: need a power of two, 32 <= B <= 16384, B dividing K";
+        case BRQ_ERR_BLOCK: return "bad rotation block: need a power of two, 8 <= B <= 16384, B dividing K";
         case BRQ_ERR_ALIGN: return "pointer or row pitch not 16-byte aligned";
         case BRQ_ERR_DTYPE: return "unknown dtype";
         case BRQ_ERR_LAUNCH: return "kernel launch failed";
@@ -146,6 +149,6 @@ const char* brq_strerror(brq_status s) {
     return "unknown status";
 }
 
-int brq_version(void) { return 200; }
+int brq_version(void) { return 300; }
 
 }  // extern "C"

@@ -5,11 +5,12 @@
 
 namespace brq {
 
-// mode: 0 rotate, 1 quantize, 2 fused rotate+quantize.  log2b: 0 for quantize, else 5..14.
+// mode: 0 rotate, 1 quantize, 2 fused rotate+quantize.  log2b: 0 for quantize, else 3..14.
 // tiled: codes and scales go out in the tiled operand layout instead of row-major.
+// signs: [K] sign bytes of a randomized rotation (element k negated where signs[k] < 0) or null.
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
-                          bool tiled, hipStream_t s);
+                          bool tiled, const int8_t* signs, hipStream_t s);
 
 // A quantized [rows][K] operand as the product kernels see it.
 struct Operand {

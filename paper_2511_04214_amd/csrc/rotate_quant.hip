@@ -26,7 +26,20 @@ struct RowArgs {
     // bytes per (slab, superstage) block): blocks per slab, 0 = row-major output.
     uint32_t stages;    // Kp/128, Kp = K rounded up to a multiple of 512
     uint32_t sstages;   // Kp/512
+    const int8_t* signs;   // [K] or null: element k is negated on load where signs[k] < 0
 };
+
+// The random sign diagonal of a randomized Hadamard rotation (Sec. 5.1 and the Appendix use
+// "randomized"/"stochastic" Hadamard matrices): x_k -> s_k x_k before the butterfly, an exact
+// flip of the fp32 sign bit.  `signs` points at the 8 sign bytes of this chunk (8-byte aligned).
+__device__ __forceinline__ void apply_signs(float (&v)[8], const int8_t* signs) {
+    const uint2 sg = *reinterpret_cast<const uint2*>(signs);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t word = (i < 4) ? sg.x : sg.y;
+        v[i] = as_f32(as_u32(v[i]) ^ ((word << (24 - 8 * (i & 3))) & 0x80000000u));
+    }
+}
 
 // Byte offsets of chunk kc (8 elements = 4 code bytes) of row `row` in the tiled layout.
 __device__ __forceinline__ uint64_t tiled_code_offset(uint32_t row, uint32_t kc, uint32_t stages) {
@@ -89,9 +102,10 @@ __device__ __forceinline__ int64_t chunk_offset(uint32_t c, uint32_t cpr, int64_
 // lanes with an odd number of set bits among the lane bits that took part.
 template <int LOG2B>
 __device__ __forceinline__ void wht_inwave(float (&v)[8], uint32_t lane) {
-    static_assert(LOG2B >= 5, "rotation blocks span at least one quad of lanes");
+    static_assert(LOG2B >= 3, "a lane holds 8 elements");
     wht8(v);
-    wht_cross_quad(v, (lane & 1) ? -1.0f : 1.0f, (lane & 2) ? -1.0f : 1.0f);
+    if constexpr (LOG2B == 4) wht_cross<1>(v, (lane & 1) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 5) wht_cross_quad(v, (lane & 1) ? -1.0f : 1.0f, (lane & 2) ? -1.0f : 1.0f);
     if constexpr (LOG2B >= 6) wht_cross<4>(v, (lane & 4) ? -1.0f : 1.0f);
     if constexpr (LOG2B >= 7) wht_cross<8>(v, (lane & 8) ? -1.0f : 1.0f);
     if constexpr (LOG2B >= 8) wht_cross<16>(v, (lane & 16) ? -1.0f : 1.0f);
@@ -139,6 +153,18 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
             uint32_t c = min(bb + u * 256u + threadIdx.x, a.nchunks - 1u);
             const char* p = (const char*)a.x + chunk_offset<CONTIG>(c, a.cpr, a.ldx) * (IN_BF16 ? 2 : 4);
             load_chunk<IN_BF16>(p, v[u]);
+            if constexpr (MODE != MODE_QUANT) {
+                if (a.signs) {   // uniform
+                    uint32_t kc;
+                    if ((a.cpr & 63u) == 0) {   // a wavefront's 64 chunks lie in one row: scalar modulo
+                        const uint32_t cb = __builtin_amdgcn_readfirstlane(c);
+                        kc = cb % a.cpr + (c - cb);
+                    } else {
+                        kc = c % a.cpr;
+                    }
+                    apply_signs(v[u], a.signs + (size_t)kc * 8);
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -192,7 +218,7 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
 // base plus a per-lane constant.  Rotation blocks of up to 16 chunks stay inside one row's lanes.
 template <int LOG2B, bool IN_BF16, int MODE>
 __global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, uint32_t nitems) {
-    static_assert(LOG2B == 0 || (LOG2B >= 5 && LOG2B <= 7), "a rotation block must fit 16 lanes");
+    static_assert(LOG2B == 0 || (LOG2B >= 3 && LOG2B <= 7), "a rotation block must fit 16 lanes");
     constexpr int ES = IN_BF16 ? 2 : 4;
     const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     constexpr uint32_t inwave_bits = (LOG2B >= 3) ? ((1u << (LOG2B - 3)) - 1u) : 0u;
@@ -209,6 +235,7 @@ __global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, ui
         float v[8];
         load_chunk<IN_BF16>(p, v);
         if constexpr (MODE != MODE_QUANT) {
+            if (a.signs) apply_signs(v, a.signs + ((size_t)st * 16u + (lane & 15u)) * 8);
             wht_inwave<LOG2B>(v, lane);
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] *= cs;
@@ -251,6 +278,7 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
         float v[8];
         uint32_t q = c * NT + tid;   // chunk index inside the block
         load_chunk<IN_BF16>((const char*)a.x + (xoff + (int64_t)q * 8) * (IN_BF16 ? 2 : 4), v);
+        if (a.signs) apply_signs(v, a.signs + ((size_t)blk * B + (size_t)q * 8));
         wht_inwave<9>(v, lane);
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] *= sigma;   // exact: back to the true sign
@@ -355,6 +383,8 @@ static hipError_t launch_lds(const RowArgs& a, int64_t M, int64_t K, hipStream_t
 template <bool IN_BF16, int MODE, bool OUT_BF16>
 static hipError_t dispatch_b(int log2b, const RowArgs& a, bool contig, int64_t M, int64_t K, hipStream_t s) {
     switch (log2b) {
+        case 3: return launch_inwave<3, IN_BF16, MODE, OUT_BF16>(a, contig, s);
+        case 4: return launch_inwave<4, IN_BF16, MODE, OUT_BF16>(a, contig, s);
         case 5: return launch_inwave<5, IN_BF16, MODE, OUT_BF16>(a, contig, s);
         case 6: return launch_inwave<6, IN_BF16, MODE, OUT_BF16>(a, contig, s);
         case 7: return launch_inwave<7, IN_BF16, MODE, OUT_BF16>(a, contig, s);
@@ -372,8 +402,9 @@ static hipError_t dispatch_b(int log2b, const RowArgs& a, bool contig, int64_t M
 // mode: RowMode; log2b: 0 for MODE_QUANT, else 5..14.  Arguments are already validated.
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
-                          bool tiled, hipStream_t s) {
+                          bool tiled, const int8_t* signs, hipStream_t s) {
     RowArgs a;
+    a.signs = signs;
     a.x = x; a.y = y; a.codes = reinterpret_cast<uint32_t*>(codes); a.scales = scales;
     a.ldx = ldx; a.ldy = ldy; a.cpr = (uint32_t)(K / 8); a.nchunks = (uint32_t)(M * (K / 8));
     const int64_t Kp = (K + 511) / 512 * 512;

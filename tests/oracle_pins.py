@@ -292,6 +292,73 @@ def pin_fused_is_the_composition(o):
     assert not np.array_equal(c0, o.rotate_quantize_fused(x, 32)[0])
 
 
+def pin_signed_rotation(o):
+    # Randomized Hadamard (Sec. 5.1): R = diag(s) H_B / sqrt(B).  Closed form of its entries from
+    # the one-hot rows; orthogonality; and the sign acts on the INPUT side, element by element:
+    # rotating x with signs equals rotating the pre-flipped x (flips are exact), which is not the
+    # same as flipping the output.
+    rng = np.random.default_rng(21)
+    for B in (8, 16, 32, 64):
+        K = 2 * B
+        s = rng.choice([-1, 1], size=K).astype(np.int8)
+        s[1] = -1
+        s[B] = -1
+        s[0] = 1
+        R = o.block_rotate(np.eye(K, dtype=np.float32), B, signs=s).astype(np.float64)
+        H = scipy.linalg.hadamard(B).astype(np.float64)
+        want = np.zeros((K, K))
+        for b in range(2):
+            want[b * B:(b + 1) * B, b * B:(b + 1) * B] = (s[b * B:(b + 1) * B, None] * H) / np.sqrt(B)
+        assert np.allclose(R, want, rtol=0, atol=1e-7), B
+        assert np.allclose(R @ R.T, np.eye(K), rtol=0, atol=1e-6)
+        x = (rng.standard_t(4, size=(4, K)) * 3).astype(np.float32)
+        a = o.block_rotate(x, B, signs=s)
+        assert np.array_equal(a.view(np.uint32), o.block_rotate(x * s.astype(np.float32), B).view(np.uint32))
+        assert not np.array_equal(a, o.block_rotate(x, B) * s.astype(np.float32))
+        # all-plus signs change nothing
+        assert np.array_equal(o.block_rotate(x, B, signs=np.ones(K, np.int8)), o.block_rotate(x, B))
+    # the product is still invariant when both operands use the same signs (fp64 route through the
+    # fp32 rotation: tolerance of fp32 rounding)
+    X = rng.standard_normal((5, 64)).astype(np.float32)
+    W = rng.standard_normal((4, 64)).astype(np.float32)
+    s = rng.choice([-1, 1], size=64).astype(np.int8)
+    got = o.block_rotate(X, 32, signs=s).astype(np.float64) @ o.block_rotate(W, 32, signs=s).astype(np.float64).T
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    assert np.allclose(got, ref, rtol=0, atol=1e-5 * np.abs(ref).max())
+    # ... and broken when they do not
+    bad = o.block_rotate(X, 32, signs=s).astype(np.float64) @ o.block_rotate(W, 32).astype(np.float64).T
+    assert not np.allclose(bad, ref, rtol=0, atol=1e-3 * np.abs(ref).max())
+
+
+def pin_fused_small_blocks_and_signs(o):
+    # Rotation blocks smaller than the 32-element quantization group (Sec. 5.3 sweeps the
+    # rotation dimension) and signed rotations: still the composition, group stays 32.
+    rng = np.random.default_rng(22)
+    x = (rng.standard_t(4, size=(5, 128)) * 3).astype(np.float32)
+    s = rng.choice([-1, 1], size=128).astype(np.int8)
+    for B in (8, 16, 32, 128):
+        for sg in (None, s):
+            c1, s1 = o.rotate_quantize_fused(x, B, signs=sg)
+            c2, s2 = o.mxfp4_quantize(o.block_rotate(x, B, signs=sg))
+            assert np.array_equal(c1, c2) and np.array_equal(s1, s2)
+            assert s1.shape == (5, 4)
+    # B = 16 (norm 1/4, exact): a one-hot of 32 spreads as +-8 over its 16-block only; the
+    # group's scale comes from amax 8 = 1.0 * 2^3 (exponent 3 - 2 = 1, byte 128) and the 16 other
+    # codes of the group are 0
+    x1 = np.zeros((1, 32), dtype=np.float32)
+    x1[0, 20] = 32.0
+    c, sc = o.rotate_quantize_fused(x1, 16)
+    vals = o.mxfp4_dequantize(c, sc)[0]
+    assert sc[0, 0] == 128
+    assert np.count_nonzero(vals) == 16 and np.all(vals[:16] == 0)
+    assert np.array_equal(np.abs(vals[16:]), np.full(16, 8.0))
+    # the same with a flipped sign on the hot element: every output changes sign, magnitudes stay
+    sg = np.ones(32, np.int8)
+    sg[20] = -1
+    c2, sc2 = o.rotate_quantize_fused(x1, 16, signs=sg)
+    assert np.array_equal(o.mxfp4_dequantize(c2, sc2)[0], -vals) and sc2[0, 0] == 128
+
+
 # --------------------------------------------------------------------------- product
 
 def pin_equivalent_transformation(o):

@@ -53,8 +53,8 @@ def test_argument_errors_before_any_launch(L):
     # null pointers
     assert L.brq_mxfp4_quantize(None, 1, 4, 64, 64, q(p), q(p), 0, None) == NULL
     assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 64, None, q(p), 0, None) == NULL
-    assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, q(p), None, 0, None) == NULL
-    assert L.brq_block_rotate(q(p), 1, 4, 64, 64, 32, None, 0, 64, None) == NULL
+    assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, None, q(p), None, 0, None) == NULL
+    assert L.brq_block_rotate(q(p), 1, 4, 64, 64, 32, None, None, 0, 64, None) == NULL
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), None, 0, 4, 4, 64, q(p), 0, 4, None) == NULL
     # shapes
     assert L.brq_mxfp4_quantize(q(p), 1, 4, 48, 48, q(p), q(p), 0, None) == SHAPE      # K % 32
@@ -68,15 +68,18 @@ def test_argument_errors_before_any_launch(L):
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 4, 8, 64, q(p), 3, 8, None) == DTYPE
     # layout
     assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 64, q(p), q(p), 2, None) == LAYOUT
-    assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, q(p), q(p), -1, None) == LAYOUT
+    assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, None, q(p), q(p), -1, None) == LAYOUT
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 5, 4, 8, 64, q(p), 0, 8, None) == LAYOUT
     assert L.brq_to_rowmajor(q(p), q(p), 4, 48, q(p), q(p), None) == SHAPE
     assert L.brq_to_rowmajor(q(p), None, 4, 64, q(p), q(p), None) == NULL
     assert L.brq_to_rowmajor(q(p), q(p), 0, 64, q(p), q(p), None) == OK
+    # sign vector alignment
+    assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, q(p + 8), q(p), q(p), 0, None) == ALIGN
+    assert L.brq_block_rotate(q(p), 1, 4, 64, 64, 32, q(p + 1), q(p), 0, 64, None) == ALIGN
     # rotation block
-    for B in (0, 16, 48, 128, 32768):
-        assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, B, q(p), q(p), 0, None) == BLOCK, B
-    assert L.brq_block_rotate(q(p), 1, 4, 96, 96, 64, q(p), 0, 96, None) == BLOCK   # B does not divide K
+    for B in (0, 4, 48, 128, 32768):
+        assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, B, None, q(p), q(p), 0, None) == BLOCK, B
+    assert L.brq_block_rotate(q(p), 1, 4, 96, 96, 64, None, q(p), 0, 96, None) == BLOCK   # B does not divide K
     # alignment
     assert L.brq_mxfp4_quantize(q(p + 2), 1, 4, 64, 64, q(p), q(p), 0, None) == ALIGN
     assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 68, q(p), q(p), 0, None) == ALIGN      # pitch 136 B
@@ -84,8 +87,8 @@ def test_argument_errors_before_any_launch(L):
     assert L.brq_mxfp4_gemm(q(p), q(p + 8), 0, q(p), q(p), 0, 4, 6, 64, q(p), 0, 6, None) == ALIGN
     # empty problems are fine and launch nothing
     assert L.brq_mxfp4_quantize(q(p), 1, 0, 64, 64, q(p), q(p), 0, None) == OK
-    assert L.brq_rotate_quantize_fused(q(p), 1, 0, 64, 64, 32, q(p), q(p), 0, None) == OK
-    assert L.brq_block_rotate(q(p), 1, 0, 64, 64, 64, q(p), 0, 64, None) == OK
+    assert L.brq_rotate_quantize_fused(q(p), 1, 0, 64, 64, 32, None, q(p), q(p), 0, None) == OK
+    assert L.brq_block_rotate(q(p), 1, 0, 64, 64, 64, None, q(p), 0, 64, None) == OK
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 0, 8, 64, q(p), 0, 8, None) == OK
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 8, 0, 64, q(p), 0, 0, None) == OK
 

@@ -42,6 +42,11 @@ MUTANTS = [
     ("gemm_w_row_pitch", "double p = ad[k] * wd[n * K + k];", "double p = ad[k] * wd[n * (K - 32) + k];"),
     ("bf16_truncates", "u += 0x7FFFu + lsb;", ""),
     ("bf16_half_up", "u += 0x7FFFu + lsb;", "u += 0x8000u;"),
+    ("sign_test_inverted", "if (signs && signs[b * B + i] < 0) e = -e;", "if (signs && signs[b * B + i] > 0) e = -e;"),
+    ("sign_index_within_block_only", "if (signs && signs[b * B + i] < 0) e = -e;", "if (signs && signs[i] < 0) e = -e;"),
+    ("signs_ignored", "if (signs && signs[b * B + i] < 0) e = -e;", ""),
+    ("fused_drops_signs", "int rc = oracle_block_rotate_signed(x, xdt, M, K, ldx, B, signs, y, ORACLE_F32, K);",
+     "int rc = oracle_block_rotate_signed(x, xdt, M, K, ldx, B, NULL, y, ORACLE_F32, K);"),
     ("fused_skips_rotation", "if (rc == ORACLE_OK) rc = oracle_mxfp4_quantize(y, ORACLE_F32, M, K, K, codes, scales);",
      "rc = oracle_mxfp4_quantize(x, xdt, M, K, ldx, codes, scales);"),
 ]
