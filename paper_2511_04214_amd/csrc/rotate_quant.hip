@@ -27,11 +27,24 @@ struct RowArgs {
     uint32_t stages;    // Kp/128, Kp = K rounded up to a multiple of 512
     uint32_t sstages;   // Kp/512
     const int8_t* signs;   // [K] or null: element k is negated on load where signs[k] < 0
+    uint32_t sign_fixed;   // the grid was sized so that a lane's column is the same in every pass
 };
 
 // The random sign diagonal of a randomized Hadamard rotation (Sec. 5.1 and the Appendix use
 // "randomized"/"stochastic" Hadamard matrices): x_k -> s_k x_k before the butterfly, an exact
 // flip of the fp32 sign bit.  `signs` points at the 8 sign bytes of this chunk (8-byte aligned).
+// The same flip as 8 ready-made sign-bit masks: kernels whose lanes keep their column from one
+// grid-stride pass to the next (the host sizes the grid for that: sign_fixed) expand the sign
+// bytes once, and a chunk then costs 8 XORs.
+__device__ __forceinline__ void sign_masks(uint32_t (&m)[8], const int8_t* signs) {
+    const uint2 sg = *reinterpret_cast<const uint2*>(signs);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m[i] = (((i < 4) ? sg.x : sg.y) << (24 - 8 * (i & 3))) & 0x80000000u;
+}
+__device__ __forceinline__ void flip(float (&v)[8], const uint32_t (&m)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = as_f32(as_u32(v[i]) ^ m[i]);
+}
 __device__ __forceinline__ void apply_signs(float (&v)[8], const int8_t* signs) {
     const uint2 sg = *reinterpret_cast<const uint2*>(signs);
 #pragma unroll
@@ -143,6 +156,13 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
     const float sigma = (__builtin_popcount(lane & inwave_bits) & 1) ? -1.0f : 1.0f;
     const float cs = as_f32(norm_bits(LOG2B)) * sigma;
     const uint32_t step = gridDim.x * 256u * U;
+    uint32_t sm[U][8];
+    const bool presigned = MODE != MODE_QUANT && a.signs && a.sign_fixed;   // uniform
+    if (presigned) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            sign_masks(sm[u], a.signs + (size_t)((blockIdx.x * 256u * U + u * 256u + threadIdx.x) % a.cpr) * 8);
+    }
     // `bb` is uniform over the workgroup and nothing below branches on the lane: chunks past
     // the end re-read the last chunk (clamped index) and only their stores are masked, so
     // every lane exchange sees a full wavefront.
@@ -154,7 +174,9 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
             const char* p = (const char*)a.x + chunk_offset<CONTIG>(c, a.cpr, a.ldx) * (IN_BF16 ? 2 : 4);
             load_chunk<IN_BF16>(p, v[u]);
             if constexpr (MODE != MODE_QUANT) {
-                if (a.signs) {   // uniform
+                if (presigned) {
+                    flip(v[u], sm[u]);
+                } else if (a.signs) {   // uniform
                     uint32_t kc;
                     if ((a.cpr & 63u) == 0) {   // a wavefront's 64 chunks lie in one row: scalar modulo
                         const uint32_t cb = __builtin_amdgcn_readfirstlane(c);
@@ -226,6 +248,9 @@ __global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, ui
     const float cs = as_f32(norm_bits(LOG2B)) * sigma;
     const uint32_t spr = a.cpr >> 4;                                   // stages per row
     const uint32_t lrow = lane >> 4;
+    uint32_t sm[8];
+    const bool presigned = MODE != MODE_QUANT && a.signs && a.sign_fixed;   // uniform
+    if (presigned) sign_masks(sm, a.signs + ((size_t)((blockIdx.x * 4u + wave) % spr) * 16u + (lane & 15u)) * 8);
     for (uint32_t it = blockIdx.x * 4u + wave; it < nitems; it += gridDim.x * 4u) {
         const uint32_t rq = it / spr, st = it - rq * spr;              // scalar
         const uint32_t row0 = rq * 4u;
@@ -235,7 +260,8 @@ __global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, ui
         float v[8];
         load_chunk<IN_BF16>(p, v);
         if constexpr (MODE != MODE_QUANT) {
-            if (a.signs) apply_signs(v, a.signs + ((size_t)st * 16u + (lane & 15u)) * 8);
+            if (presigned) flip(v, sm);
+            else if (a.signs) apply_signs(v, a.signs + ((size_t)st * 16u + (lane & 15u)) * 8);
             wht_inwave<LOG2B>(v, lane);
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] *= cs;
@@ -351,22 +377,41 @@ static int rowwise_grid(uint32_t nchunks, int U) {
     return (int)(need < grid ? need : grid);
 }
 
+// Signed rotations: round `grid` down to a multiple of period / gcd(period, per_wg), so that one
+// grid-stride pass (grid * per_wg work items) is a whole number of rows' worth of columns and
+// every lane meets the same column, hence the same signs, in every pass.  Returns 1 if the grid
+// could be sized that way (it is left alone, and 0 returned, when that would shrink it by more
+// than half).
+static uint32_t fix_columns(int& grid, uint32_t period, uint32_t per_wg) {
+    uint32_t x = period, y = per_wg;
+    while (y) { uint32_t t = x % y; x = y; y = t; }
+    const uint32_t unit = period / x;
+    const uint32_t g = (uint32_t)grid / unit * unit;
+    if (g == 0 || g * 2 < (uint32_t)grid) return 0;
+    grid = (int)g;
+    return 1;
+}
+
 template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
 static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
     if constexpr (MODE != MODE_ROTATE && LOG2B <= 7) {
         if (a.stages != 0 && (a.cpr & 15u) == 0) {
             const uint32_t rows = a.nchunks / a.cpr, nitems = ((rows + 3u) / 4u) * (a.cpr >> 4);
             int grid = rowwise_grid(nitems * 64u, 1);
-            hipLaunchKernelGGL((k_rowwise_t4<LOG2B, IN_BF16, MODE>), dim3(grid), dim3(256), 0, s, a, rows, nitems);
+            RowArgs b = a;
+            b.sign_fixed = a.signs ? fix_columns(grid, a.cpr >> 4, 4) : 0;
+            hipLaunchKernelGGL((k_rowwise_t4<LOG2B, IN_BF16, MODE>), dim3(grid), dim3(256), 0, s, b, rows, nitems);
             return hipGetLastError();
         }
     }
     constexpr int U = 1;
     int grid = rowwise_grid(a.nchunks, U);
+    RowArgs b = a;
+    b.sign_fixed = (a.signs && MODE != MODE_QUANT) ? fix_columns(grid, a.cpr, 256 * U) : 0;
     if (contig)
-        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, true, U>), dim3(grid), dim3(256), 0, s, a);
+        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, true, U>), dim3(grid), dim3(256), 0, s, b);
     else
-        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, false, U>), dim3(grid), dim3(256), 0, s, a);
+        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, false, U>), dim3(grid), dim3(256), 0, s, b);
     return hipGetLastError();
 }
 
@@ -405,6 +450,7 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
                           bool tiled, const int8_t* signs, hipStream_t s) {
     RowArgs a;
     a.signs = signs;
+    a.sign_fixed = 0;
     a.x = x; a.y = y; a.codes = reinterpret_cast<uint32_t*>(codes); a.scales = scales;
     a.ldx = ldx; a.ldy = ldy; a.cpr = (uint32_t)(K / 8); a.nchunks = (uint32_t)(M * (K / 8));
     const int64_t Kp = (K + 511) / 512 * 512;

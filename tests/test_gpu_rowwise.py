@@ -119,7 +119,7 @@ def test_quantize_strided_rows(brq, orc):
 
 # ------------------------------------------------------------------ rotation
 
-@pytest.mark.parametrize("B", [32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384])
+@pytest.mark.parametrize("B", [8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384])
 @pytest.mark.parametrize("dt", ["bf16", "f32"])
 def test_block_rotate_matches_oracle(brq, orc, B, dt):
     rng = np.random.default_rng(200 + B)
@@ -148,9 +148,72 @@ def test_block_rotate_integers_exact(brq, orc):
         assert np.array_equal(to_host(brq.block_rotate(to_dev(x), B)), orc.block_rotate(x, B))
 
 
+# ------------------------------------------------------------------ randomized (signed) rotation
+
+def same_up_to_zero_sign_f32(a, b):
+    ua, ub = a.view(np.uint32), b.view(np.uint32)
+    return ((ua == ub) | (((ua | ub) & np.uint32(0x7FFFFFFF)) == 0)).all()
+
+
+@pytest.mark.parametrize("B", [8, 16, 32, 128, 512, 1024, 4096])
+@pytest.mark.parametrize("K,M", [(4096, 37), (4096 + 8 * 32, 21)])      # chunks per row: multiple of 64, and not
+def test_signed_rotation_matches_oracle(brq, orc, B, K, M):
+    if K % B:
+        pytest.skip("B does not divide this K")
+    rng = np.random.default_rng(300 + B)
+    x = windowed_bf16(rng, M, K, lo=100, hi=135, width=10)
+    s = rng.choice([-1, 1], size=K).astype(np.int8)
+    sd = torch.from_numpy(s).cuda()
+    y = to_host(brq.block_rotate(to_dev(x), B, signs=sd))
+    assert same_up_to_zero_sign_f32(y, orc.block_rotate(x, B, signs=s))
+    oc, os_ = orc.rotate_quantize_fused(x, B, signs=s)
+    for layout in ("rowmajor", "tiled"):
+        c, sc = brq.rotate_quantize_fused(to_dev(x), B, signs=sd, layout=layout)
+        if layout == "tiled":
+            c, sc = brq.to_rowmajor(c, sc, M, K)
+        assert np.array_equal(to_host(c), oc) and np.array_equal(to_host(sc), os_), layout
+    # the signs matter, and all-plus signs are the plain rotation
+    c0, s0 = brq.rotate_quantize_fused(to_dev(x), B)
+    assert not np.array_equal(to_host(c0), oc)
+    c1, s1 = brq.rotate_quantize_fused(to_dev(x), B, signs=torch.ones(K, dtype=torch.int8, device="cuda"))
+    assert torch.equal(c0, c1) and torch.equal(s0, s1)
+
+
+def test_signed_rotation_fp32_input_and_strided_rows(brq, orc):
+    rng = np.random.default_rng(311)
+    M, K, ld = 13, 1024, 1024 + 64
+    buf = (rng.standard_t(4, size=(M, ld)) * 2).astype(np.float32)
+    s = rng.choice([-1, 1], size=K).astype(np.int8)
+    xd = to_dev(buf)[:, :K]
+    c, sc = brq.rotate_quantize_fused(xd, 32, signs=torch.from_numpy(s).cuda())
+    oc, os_ = orc.rotate_quantize_fused(np.ascontiguousarray(buf[:, :K]), 32, signs=s)
+    assert np.array_equal(to_host(c), oc) and np.array_equal(to_host(sc), os_)
+
+
+def test_signed_product_is_invariant(brq, orc):
+    """Same signs on activations and weights: the quantized product still approximates X W^T
+    (Sec. 2: R = diag(s) H / sqrt(B) is orthogonal), and matches the oracle's."""
+    rng = np.random.default_rng(312)
+    M, N, K = 64, 256, 512
+    from paper_2511_04214_amd.inputs import f32_to_bf16_bits, bf16_bits_to_f32
+    x = f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    w = f32_to_bf16_bits((rng.standard_normal((N, K)) * 0.05).astype(np.float32))
+    s = rng.choice([-1, 1], size=K).astype(np.int8)
+    sd = torch.from_numpy(s).cuda()
+    aq, as_ = brq.rotate_quantize_fused(to_dev(x), 32, signs=sd)
+    wq, ws = brq.rotate_quantize_fused(to_dev(w), 32, signs=sd)
+    y = to_host(brq.mxfp4_gemm(aq, as_, wq, ws)).astype(np.float64)
+    oa, oas = orc.rotate_quantize_fused(x, 32, signs=s)
+    ow, ows = orc.rotate_quantize_fused(w, 32, signs=s)
+    ref, bound = orc.mxfp4_gemm(oa, oas, ow, ows)
+    assert (np.abs(y - ref) <= 1e-5 * bound + 2.0 ** -126).all()
+    exact = bf16_bits_to_f32(x).astype(np.float64) @ bf16_bits_to_f32(w).astype(np.float64).T
+    assert np.linalg.norm(y - exact) / np.linalg.norm(exact) < 0.25
+
+
 # ------------------------------------------------------------------ fused
 
-@pytest.mark.parametrize("B", [32, 64, 128, 256, 512, 1024, 2048, 8192])
+@pytest.mark.parametrize("B", [8, 16, 32, 64, 128, 256, 512, 1024, 2048, 8192])
 def test_fused_matches_oracle_and_composition(brq, orc, B):
     from paper_2511_04214_amd import inputs
     cfg = inputs.CONFIGS["down_sweep"]
