@@ -119,7 +119,9 @@ __device__ __forceinline__ void mfma_fp4(v16f& acc, const v4i& wf, const v4i& af
 // more (5% of the kernel) than the short queue of four loads at the texture-address unit does.
 #define BRQ_DMA_SLOT(S) do { if constexpr (((S) & 1) == 0) dma_step(Uc, IC<(S) / 2>{}); } while (0)
 
-template <bool OUT_BF16>
+// MB = A tiles (32 rows) per wavefront: 4 -> 256 x 256 output tile, 2 -> 128 x 256 (for shapes
+// with too few 256 x 256 tiles to fill the chip; the stage is then 16 MFMA slots long).
+template <bool OUT_BF16, int MB>
 __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
                                                        const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
                                                        int M, int N, int K, void* __restrict__ y, int64_t ldy, int a_tiled, int w_tiled) {
@@ -127,10 +129,12 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, h = lane >> 5;
-    const int wn = wave >> 1, wm = wave & 1;   // this wavefront's 128 W rows / 128 A rows inside the tile
+    const int wn = wave >> 1, wm = wave & 1;   // this wavefront's 128 W rows / 32 MB A rows inside the tile
+    constexpr int TMv = 64 * MB;               // output rows per tile
+    constexpr int ARW = 16 * MB;               // A rows each wavefront loads per stage (its share of the tile's)
 
     TileWalk tw;
-    tw.tiles_m = (M + TM - 1) / TM;            // the last tile row may be ragged: loads clamp, stores mask
+    tw.tiles_m = (M + TMv - 1) / TMv;            // the last tile row may be ragged: loads clamp, stores mask
     tw.tiles_n = N / TN;
     {
         const int T = tw.tiles_m * tw.tiles_n, G = gridDim.x;   // G is a multiple of 8
@@ -160,13 +164,15 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         vqa[q] = a_tiled ? (uint32_t)(q * 1024 + (lane >> 2) * 64) + swz16
                          : (uint32_t)(((lane >> 2) + 16 * q) * cpitch) + swz16;
     }
+    const int alane = lane & (ARW - 1);       // MB = 2: lanes 32..63 of the A scale load repeat rows 0..31
     const uint32_t vscw = w_tiled ? (uint32_t)(lane * 16) : (uint32_t)(lane * spitch);
-    uint32_t vsca = a_tiled ? (uint32_t)(lane * 16) : (uint32_t)(lane * spitch);
+    uint32_t vsca = a_tiled ? (uint32_t)(alane * 16) : (uint32_t)(alane * spitch);
     bool a_clamped = false;   // row-major A: the per-lane offsets currently hold clamped rows
     // byte steps: stage to stage, superstage to superstage (codes), superstage to superstage (scales)
     const int w_stage = w_tiled ? 4096 : 64, w_super = w_tiled ? 16384 : 256, w_ssuper = w_tiled ? 1024 : 16;
     const int a_stage = a_tiled ? 4096 : 64, a_super = a_tiled ? 16384 : 256, a_ssuper = a_tiled ? 1024 : 16;
-    const uint32_t dma_lds = lds0 + wave * 4096;             // this wavefront's 64-row slab in a stage
+    const uint32_t dma_lds = lds0 + wave * 4096;             // this wavefront's 64-row W slab in a stage
+    const uint32_t dma_lds_a = lds0 + wave * (ARW * 64);      // ... and its 16 MB-row A slab
     const uint32_t dma_sc = lds0 + SCALE_BASE + wave * 1024; // ... and in a scale buffer
     int p_tile = 0, p_kq = 0;                                 // producer position: tile index, superstage in tile
     uint32_t p_buf = 0;                                       // byte offset of the scale buffer the producer fills next
@@ -177,7 +183,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         if (p_kq == 0) {
             int tm, tn;
             tw.tile(min(p_tile, ntiles - 1), tm, tn);
-            const int64_t wrow = (int64_t)tn * TN + wave * 64, arow = (int64_t)tm * TM + wave * 64;   // slab rows
+            const int64_t wrow = (int64_t)tn * TN + wave * 64, arow = (int64_t)tm * TMv + wave * ARW;   // slab rows
             const uint8_t* bw = w_tiled ? wq + (wrow >> 6) * (cpitch / 64) * 4096 : wq + wrow * cpitch;
             p_ws = uniform_ptr(w_tiled ? ws + (wrow >> 6) * (spitch / 16) * 1024 : ws + wrow * spitch);
             // A slab of the ragged last tile row: rows past M - 1 are never stored, but their loads
@@ -186,19 +192,20 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             // M - 64 and every lane clamps its row to M - 1.
             const uint8_t *ba, *bas;
             if (a_tiled) {
+                // (for MB = 2 a wavefront's 32 rows are one half of a 64-row slab)
                 const int64_t slab = min(arow >> 6, (int64_t)(M + 63) / 64 - 1);
-                ba = aq + slab * (cpitch / 64) * 4096;
-                bas = as + slab * (spitch / 16) * 1024;
+                ba = aq + slab * (cpitch / 64) * 4096 + (arow & 63) * 64;
+                bas = as + slab * (spitch / 16) * 1024 + (arow & 63) * 16;
             } else {
-                const int64_t abase = min(arow, max((int64_t)M - 64, (int64_t)0));
+                const int64_t abase = min(arow, max((int64_t)M - ARW, (int64_t)0));
                 ba = aq + abase * cpitch;
                 bas = as + abase * spitch;
-                if (arow + 64 > M || a_clamped) {        // uniform; also restores the plain offsets afterwards
-                    a_clamped = arow + 64 > M;
+                if (arow + ARW > M || a_clamped) {        // uniform; also restores the plain offsets afterwards
+                    a_clamped = arow + ARW > M;
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         vqa[q] = (uint32_t)((min(arow + (lane >> 2) + 16 * q, (int64_t)M - 1) - abase) * cpitch) + swz16;
-                    vsca = (uint32_t)((min(arow + lane, (int64_t)M - 1) - abase) * spitch);
+                    vsca = (uint32_t)((min(arow + alane, (int64_t)M - 1) - abase) * spitch);
                 }
             }
             p_as = uniform_ptr(bas);
@@ -216,7 +223,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     };
     // loads of stage U of the producer's superstage: I = 0, 1 the scale rows (U == 0 only, and
     // first, so that they are older than the stage's code loads), I = 2..9 the code slabs
-    // (W and A alternating, 16 rows x 64 bytes each)
+    // (W and A alternating, 16 rows x 64 bytes each; with MB = 2 the A slab has 2 loads, not 4)
     auto dma_step = [&](auto Uc, auto Ic) {
         constexpr int U = decltype(Uc)::value, I = decltype(Ic)::value;
         if constexpr (I == 0) {
@@ -226,7 +233,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         } else {
             constexpr int q = (I - 2) >> 1;
             if constexpr (((I - 2) & 1) == 0) dma16<U * STAGE_BYTES + q * 1024>(dma_lds, p_w[U], vqw[q]);
-            else dma16<U * STAGE_BYTES + OPER_BYTES + q * 1024>(dma_lds, p_a[U], vqa[q]);
+            else if constexpr (q < MB) dma16<U * STAGE_BYTES + OPER_BYTES + q * 1024>(dma_lds_a, p_a[U], vqa[q]);
         }
     };
     auto dma_stage = [&](auto Uc) {
@@ -243,18 +250,20 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     for (int j = 0; j < 2; ++j) {
         const uint32_t c16 = ((2 * h + j) ^ sw) << 4;
         wp[0][j] = lds + (wn * 128 + r) * 64 + c16;
-        ap[0][j] = lds + OPER_BYTES + (wm * 128 + r) * 64 + c16;
+        ap[0][j] = lds + OPER_BYTES + (wm * 32 * MB + r) * 64 + c16;
         wp[1][j] = wp[0][j] + 2 * STAGE_BYTES;
         ap[1][j] = ap[0][j] + 2 * STAGE_BYTES;
     }
     const uint8_t* wsp = lds + SCALE_BASE + (wn * 128 + r) * 16;                 // scale rows, buffer 0
-    const uint8_t* asp = lds + SCALE_BASE + SCALE_OPER + (wm * 128 + r) * 16;
+    // A scale rows sit at 1 KB per loading wavefront: row i of the tile at (i / ARW) * 1024 + (i % ARW) * 16
+    constexpr int ASC_TILE = (MB == 4) ? 512 : 1024;     // from one 32-row A tile of a wavefront to the next
+    const uint8_t* asp = lds + SCALE_BASE + SCALE_OPER + (MB == 4 ? (wm * 128 + r) * 16 : wm * 2048 + r * 16);
     uint32_t c_buf = 0;                  // byte offset of the consumer's scale buffer
     const int hshift = h * 16;
 
-    v4i w0[4], a0[4], w1[4], a1[4];      // step-0 / step-1 operand fragments
-    int scw[2][4], sca[2][4];            // scale registers, [stage parity][MFMA tile]
-    v16f acc[4][4];                      // [W tile][A tile]
+    v4i w0[4], a0[MB], w1[4], a1[MB];    // step-0 / step-1 operand fragments
+    int scw[2][4], sca[2][MB];           // scale registers, [stage parity][MFMA tile]
+    v16f acc[4][MB];                     // [W tile][A tile]
 
     auto ld_w = [&](auto Uc, auto Jc, auto Tc) -> v4i {
         constexpr int U = decltype(Uc)::value, J = decltype(Jc)::value, T = decltype(Tc)::value;
@@ -280,58 +289,89 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         using J0 = IC<0>;
         using J1 = IC<1>;
         int (&csw)[4] = scw[P];
-        int (&csa)[4] = sca[P];
+        int (&csa)[MB] = sca[P];
         int (&nsw)[4] = scw[P ^ 1];
-        int (&nsa)[4] = sca[P ^ 1];
+        int (&nsa)[MB] = sca[P ^ 1];
         const uint32_t nbuf = (U == 3) ? (c_buf ^ SCALE_BUF) : c_buf;   // scale buffer of the next stage
-        uint32_t rw[4], ra[4];
+        uint32_t rw[4], ra[MB];
 
-        BRQ_MFMA(acc[0][0], w0[0], a0[0], 0, csw[0], csa[0]); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
-        BRQ_MFMA(acc[0][1], w0[0], a0[1], 0, csw[0], csa[1]); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
-        BRQ_MFMA(acc[0][2], w0[0], a0[2], 0, csw[0], csa[2]); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
-        BRQ_MFMA(acc[0][3], w0[0], a0[3], 0, csw[0], csa[3]); a1[2] = ld_a(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
-        BRQ_MFMA(acc[1][0], w0[1], a0[0], 0, csw[1], csa[0]); a1[3] = ld_a(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
-        BRQ_MFMA(acc[1][1], w0[1], a0[1], 0, csw[1], csa[1]); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
-        BRQ_MFMA(acc[1][2], w0[1], a0[2], 0, csw[1], csa[2]); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
-        BRQ_MFMA(acc[1][3], w0[1], a0[3], 0, csw[1], csa[3]); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
-        BRQ_MFMA(acc[2][0], w0[2], a0[0], 0, csw[2], csa[0]); BRQ_SLOT_END();
-        BRQ_MFMA(acc[2][1], w0[2], a0[1], 0, csw[2], csa[1]); BRQ_SLOT_END();
-        BRQ_MFMA(acc[2][2], w0[2], a0[2], 0, csw[2], csa[2]); BRQ_SLOT_END();
-        BRQ_MFMA(acc[2][3], w0[2], a0[3], 0, csw[2], csa[3]); BRQ_SLOT_END();
-        // Younger than the next stage's loads: the two stages after it, 8 code loads each.  The
-        // first three stages of a tile find their data landed (everything in flight was waited
-        // for before the previous epilogue) and must not wait: the counter still holds that
-        // epilogue's stores, which drain behind these stages.  From the fourth stage on the stores
-        // are older than every load that is waited for, so counting stays safe.
-        if constexpr (U == 3) wait_vm_and_barrier<16>();
-        else wait_vm_unless_and_barrier<16>(fresh);
-        BRQ_MFMA(acc[3][0], w0[3], a0[0], 0, csw[3], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(0); BRQ_SLOT_END();
-        BRQ_MFMA(acc[3][1], w0[3], a0[1], 0, csw[3], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(1); BRQ_SLOT_END();
-        BRQ_MFMA(acc[3][2], w0[3], a0[2], 0, csw[3], csa[2]); w0[2] = ld_w(N_{}, J0{}, IC<2>{});
-#pragma unroll
-        for (int t = 0; t < 4; ++t) rw[t] = *reinterpret_cast<const uint32_t*>(wsp + nbuf + NU * 4 + t * 512);
-        BRQ_DMA_SLOT(2); BRQ_SLOT_END();
-        BRQ_MFMA(acc[3][3], w0[3], a0[3], 0, csw[3], csa[3]);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) ra[t] = *reinterpret_cast<const uint32_t*>(asp + nbuf + NU * 4 + t * 512);
-        BRQ_DMA_SLOT(3); BRQ_SLOT_END();
+        if constexpr (MB == 4) {
+            BRQ_MFMA(acc[0][0], w0[0], a0[0], 0, csw[0], csa[0]); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][1], w0[0], a0[1], 0, csw[0], csa[1]); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][2], w0[0], a0[2], 0, csw[0], csa[2]); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][3], w0[0], a0[3], 0, csw[0], csa[3]); a1[2] = ld_a(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][0], w0[1], a0[0], 0, csw[1], csa[0]); a1[3] = ld_a(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][1], w0[1], a0[1], 0, csw[1], csa[1]); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][2], w0[1], a0[2], 0, csw[1], csa[2]); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][3], w0[1], a0[3], 0, csw[1], csa[3]); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][0], w0[2], a0[0], 0, csw[2], csa[0]); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][1], w0[2], a0[1], 0, csw[2], csa[1]); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][2], w0[2], a0[2], 0, csw[2], csa[2]); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][3], w0[2], a0[3], 0, csw[2], csa[3]); BRQ_SLOT_END();
+            // Younger than the next stage's loads: the two stages after it, 8 code loads each.  The
+            // first three stages of a tile find their data landed (everything in flight was waited
+            // for before the previous epilogue) and must not wait: the counter still holds that
+            // epilogue's stores, which drain behind these stages.  From the fourth stage on the stores
+            // are older than every load that is waited for, so counting stays safe.
+            if constexpr (U == 3) wait_vm_and_barrier<16>();
+            else wait_vm_unless_and_barrier<16>(fresh);
+            BRQ_MFMA(acc[3][0], w0[3], a0[0], 0, csw[3], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(0); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][1], w0[3], a0[1], 0, csw[3], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(1); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][2], w0[3], a0[2], 0, csw[3], csa[2]); w0[2] = ld_w(N_{}, J0{}, IC<2>{});
+    #pragma unroll
+            for (int t = 0; t < 4; ++t) rw[t] = *reinterpret_cast<const uint32_t*>(wsp + nbuf + NU * 4 + t * 512);
+            BRQ_DMA_SLOT(2); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][3], w0[3], a0[3], 0, csw[3], csa[3]);
+    #pragma unroll
+            for (int t = 0; t < 4; ++t) ra[t] = *reinterpret_cast<const uint32_t*>(asp + nbuf + NU * 4 + t * 512);
+            BRQ_DMA_SLOT(3); BRQ_SLOT_END();
 
-        BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(4); BRQ_SLOT_END();
-        BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(5); BRQ_SLOT_END();
-        BRQ_MFMA(acc[0][2], w1[0], a1[2], 1, csw[0], csa[2]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(6); BRQ_SLOT_END();
-        BRQ_MFMA(acc[0][3], w1[0], a1[3], 1, csw[0], csa[3]); a0[2] = ld_a(N_{}, J0{}, IC<2>{}); BRQ_DMA_SLOT(7); BRQ_SLOT_END();
-        BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[3] = ld_a(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(8); BRQ_SLOT_END();
-        BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); BRQ_DMA_SLOT(9); BRQ_SLOT_END();
-        BRQ_MFMA(acc[1][2], w1[1], a1[2], 1, csw[1], csa[2]); BRQ_DMA_SLOT(10); BRQ_SLOT_END();
-        BRQ_MFMA(acc[1][3], w1[1], a1[3], 1, csw[1], csa[3]); BRQ_DMA_SLOT(11); BRQ_SLOT_END();
-        BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); BRQ_DMA_SLOT(12); BRQ_SLOT_END();
-        BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); BRQ_DMA_SLOT(13); BRQ_SLOT_END();
-        BRQ_MFMA(acc[2][2], w1[2], a1[2], 1, csw[2], csa[2]); nsw[0] = (int)(rw[0] >> hshift); nsw[1] = (int)(rw[1] >> hshift); BRQ_DMA_SLOT(14); BRQ_SLOT_END();
-        BRQ_MFMA(acc[2][3], w1[2], a1[3], 1, csw[2], csa[3]); nsw[2] = (int)(rw[2] >> hshift); nsw[3] = (int)(rw[3] >> hshift); BRQ_DMA_SLOT(15); BRQ_SLOT_END();
-        BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsa[0] = (int)(ra[0] >> hshift); nsa[1] = (int)(ra[1] >> hshift); BRQ_DMA_SLOT(16); BRQ_SLOT_END();
-        BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsa[2] = (int)(ra[2] >> hshift); nsa[3] = (int)(ra[3] >> hshift); BRQ_DMA_SLOT(17); BRQ_SLOT_END();
-        BRQ_MFMA(acc[3][2], w1[3], a1[2], 1, csw[3], csa[2]); BRQ_DMA_SLOT(18); BRQ_SLOT_END();
-        BRQ_MFMA(acc[3][3], w1[3], a1[3], 1, csw[3], csa[3]); BRQ_DMA_SLOT(19); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(4); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(5); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][2], w1[0], a1[2], 1, csw[0], csa[2]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(6); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][3], w1[0], a1[3], 1, csw[0], csa[3]); a0[2] = ld_a(N_{}, J0{}, IC<2>{}); BRQ_DMA_SLOT(7); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[3] = ld_a(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(8); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); BRQ_DMA_SLOT(9); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][2], w1[1], a1[2], 1, csw[1], csa[2]); BRQ_DMA_SLOT(10); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][3], w1[1], a1[3], 1, csw[1], csa[3]); BRQ_DMA_SLOT(11); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); BRQ_DMA_SLOT(12); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); BRQ_DMA_SLOT(13); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][2], w1[2], a1[2], 1, csw[2], csa[2]); nsw[0] = (int)(rw[0] >> hshift); nsw[1] = (int)(rw[1] >> hshift); BRQ_DMA_SLOT(14); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][3], w1[2], a1[3], 1, csw[2], csa[3]); nsw[2] = (int)(rw[2] >> hshift); nsw[3] = (int)(rw[3] >> hshift); BRQ_DMA_SLOT(15); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsa[0] = (int)(ra[0] >> hshift); nsa[1] = (int)(ra[1] >> hshift); BRQ_DMA_SLOT(16); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsa[2] = (int)(ra[2] >> hshift); nsa[3] = (int)(ra[3] >> hshift); BRQ_DMA_SLOT(17); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][2], w1[3], a1[2], 1, csw[3], csa[2]); BRQ_DMA_SLOT(18); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][3], w1[3], a1[3], 1, csw[3], csa[3]); BRQ_DMA_SLOT(19); BRQ_SLOT_END();
+        } else {
+            // 128 x 256 tile: 16 slots.  m0..m5 F1 reads, m7|m8 wait + barrier, m8..m13 N0 reads,
+            // m8..m15 refill loads (6 code loads, and the 2 scale loads in stage 0), m13..m15 scales.
+            // Two windows of 6 code loads may stay in flight.
+            BRQ_MFMA(acc[0][0], w0[0], a0[0], 0, csw[0], csa[0]); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][1], w0[0], a0[1], 0, csw[0], csa[1]); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][0], w0[1], a0[0], 0, csw[1], csa[0]); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][1], w0[1], a0[1], 0, csw[1], csa[1]); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][0], w0[2], a0[0], 0, csw[2], csa[0]); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][1], w0[2], a0[1], 0, csw[2], csa[1]); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][0], w0[3], a0[0], 0, csw[3], csa[0]); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][1], w0[3], a0[1], 0, csw[3], csa[1]); BRQ_SLOT_END();
+            if constexpr (U == 3) wait_vm_and_barrier<12>();
+            else wait_vm_unless_and_barrier<12>(fresh);
+            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); dma_step(Uc, IC<0>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); dma_step(Uc, IC<1>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); dma_step(Uc, IC<2>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{});
+#pragma unroll
+            for (int t = 0; t < 4; ++t) rw[t] = *reinterpret_cast<const uint32_t*>(wsp + nbuf + NU * 4 + t * 512);
+            dma_step(Uc, IC<3>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); w0[2] = ld_w(N_{}, J0{}, IC<2>{});
+#pragma unroll
+            for (int t = 0; t < MB; ++t) ra[t] = *reinterpret_cast<const uint32_t*>(asp + nbuf + NU * 4 + t * ASC_TILE);
+            dma_step(Uc, IC<4>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); dma_step(Uc, IC<5>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsw[0] = (int)(rw[0] >> hshift); nsw[1] = (int)(rw[1] >> hshift); dma_step(Uc, IC<6>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsw[2] = (int)(rw[2] >> hshift); nsw[3] = (int)(rw[3] >> hshift);
+            nsa[0] = (int)(ra[0] >> hshift); nsa[1] = (int)(ra[1] >> hshift); dma_step(Uc, IC<8>{}); BRQ_SLOT_END();
+        }
     };
 
     // ---- prologue: superstage 0 in flight, its first fragments in registers
@@ -346,12 +386,11 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     w0[0] = ld_w(IC<0>{}, IC<0>{}, IC<0>{}); w0[1] = ld_w(IC<0>{}, IC<0>{}, IC<1>{});
     w0[2] = ld_w(IC<0>{}, IC<0>{}, IC<2>{}); w0[3] = ld_w(IC<0>{}, IC<0>{}, IC<3>{});
     a0[0] = ld_a(IC<0>{}, IC<0>{}, IC<0>{}); a0[1] = ld_a(IC<0>{}, IC<0>{}, IC<1>{});
-    a0[2] = ld_a(IC<0>{}, IC<0>{}, IC<2>{}); a0[3] = ld_a(IC<0>{}, IC<0>{}, IC<3>{});
+    if constexpr (MB == 4) { a0[2] = ld_a(IC<0>{}, IC<0>{}, IC<2>{}); a0[3] = ld_a(IC<0>{}, IC<0>{}, IC<3>{}); }
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        scw[0][t] = (int)(*reinterpret_cast<const uint32_t*>(wsp + t * 512) >> hshift);
-        sca[0][t] = (int)(*reinterpret_cast<const uint32_t*>(asp + t * 512) >> hshift);
-    }
+    for (int t = 0; t < 4; ++t) scw[0][t] = (int)(*reinterpret_cast<const uint32_t*>(wsp + t * 512) >> hshift);
+#pragma unroll
+    for (int t = 0; t < MB; ++t) sca[0][t] = (int)(*reinterpret_cast<const uint32_t*>(asp + t * ASC_TILE) >> hshift);
 
     uint8_t* const ybytes = reinterpret_cast<uint8_t*>(y);
     uint8_t* const ebuf = lds + EPI_BASE + wave * 4096;
@@ -359,7 +398,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 #pragma unroll
         for (int a = 0; a < 4; ++a)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) acc[a][b] = v16f{};
+            for (int b = 0; b < MB; ++b) acc[a][b] = v16f{};
 
         for (int kq = 0; kq < KQ; ++kq) {
             // the four stages below also load the producer's superstage, the next one of the stream
@@ -397,7 +436,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         tw.tile(ti_e, tm, tn);
         constexpr int ES = OUT_BF16 ? 2 : 4;
         const int64_t pitch = ldy * ES;
-        uint8_t* const ytile = ybytes + ((int64_t)tm * TM + wm * 128) * pitch + ((int64_t)tn * TN + wn * 128) * ES;
+        uint8_t* const ytile = ybytes + ((int64_t)tm * TMv + wm * 32 * MB) * pitch + ((int64_t)tn * TN + wn * 128) * ES;
         const uint32_t st_off = (uint32_t)(lane >> 3) * (uint32_t)pitch + (lane & 7) * 16;
         uint8_t* const ewr = ebuf + r * 128;                     // this lane's row for writing
         const uint32_t wsw = (uint32_t)((r & 7) ^ h) << 4;        // its chunk swizzle, h folded in
@@ -409,7 +448,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             o2 = *reinterpret_cast<const uint4*>(erd + 2048);
             o3 = *reinterpret_cast<const uint4*>(erd + 3072);
         };
-        const int mrem = M - (tm * TM + wm * 128) - (lane >> 3);   // this lane stores rows row + 8 j < mrem
+        const int mrem = M - (tm * TMv + wm * 32 * MB) - (lane >> 3);   // this lane stores rows row + 8 j < mrem
         auto store_block = [&](int row, int colbytes) {
             uint8_t* dst = ytile + row * pitch + colbytes;
             if (row < mrem) *reinterpret_cast<uint4*>(dst + st_off) = o0;
@@ -422,7 +461,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             // between the lane halves: a lane then holds columns 32 a + 16 p + 8 h + {0..7},
             // p = 0, 1, as one chunk, index (a & 1) * 4 + 2 p + h within the block's row
 #pragma unroll
-            for (int blk = 0; blk < 8; ++blk) {
+            for (int blk = 0; blk < 2 * MB; ++blk) {
                 const int b = blk >> 1, ap = blk & 1;
                 uint4 ch[2][2];
 #pragma unroll
@@ -447,11 +486,11 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
                 read_block();
                 BRQ_SLOT_END();    // one block at a time keeps the register pressure flat
             }
-            store_block(3 * 32, 128);
+            store_block((MB - 1) * 32, 128);
         } else {
             // block = one accumulator: 32 rows x 32 columns; chunk index 2 q + h
 #pragma unroll
-            for (int blk = 0; blk < 16; ++blk) {
+            for (int blk = 0; blk < 4 * MB; ++blk) {
                 const int b = blk >> 2, a = blk & 3;
                 const v16f& c = acc[a][b];
 #pragma unroll
@@ -461,7 +500,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
                 read_block();
                 BRQ_SLOT_END();
             }
-            store_block(3 * 32, 3 * 128);
+            store_block((MB - 1) * 32, 3 * 128);
         }
     }
     // the throw-away superstage is still in flight: let it land before the LDS is released
@@ -489,22 +528,37 @@ hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int6
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v >= 8)
             n = v & ~7;
-        hipError_t e = hipFuncSetAttribute((const void*)tiled::k_gemm_tiled<true>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, tiled::LDS_BYTES);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)tiled::k_gemm_tiled<false>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, tiled::LDS_BYTES);
-        if (e != hipSuccess) return e;
+        const void* kernels[4] = {(const void*)tiled::k_gemm_tiled<true, 4>, (const void*)tiled::k_gemm_tiled<false, 4>,
+                                  (const void*)tiled::k_gemm_tiled<true, 2>, (const void*)tiled::k_gemm_tiled<false, 2>};
+        for (const void* k : kernels) {
+            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, tiled::LDS_BYTES);
+            if (e != hipSuccess) return e;
+        }
         cus = n;
     }
-    const int T = (int)(((M + tiled::TM - 1) / tiled::TM) * (N / tiled::TN));
+    // 256 x 256 tiles unless there are too few of them to give every CU one: then 128 x 256
+    const int64_t tn = N / tiled::TN;
+    const int64_t T4 = ((M + 255) / 256) * tn, T2 = ((M + 127) / 128) * tn;
+    const bool half = T4 < cus && T2 > T4;
+    const int T = (int)(half ? T2 : T4);
     const int grid = T < cus ? ((T + 7) & ~7) : cus;
-    if (out_bf16)
-        hipLaunchKernelGGL(tiled::k_gemm_tiled<true>, dim3(grid), dim3(256), tiled::LDS_BYTES, s, a.codes, a.scales,
-                           w.codes, w.scales, (int)M, (int)N, (int)K, y, ldy, (int)a.tiled, (int)w.tiled);
-    else
-        hipLaunchKernelGGL(tiled::k_gemm_tiled<false>, dim3(grid), dim3(256), tiled::LDS_BYTES, s, a.codes, a.scales,
-                           w.codes, w.scales, (int)M, (int)N, (int)K, y, ldy, (int)a.tiled, (int)w.tiled);
+    const dim3 g(grid), b(256);
+    const int ai = (int)a.tiled, wi = (int)w.tiled;
+    if (half) {
+        if (out_bf16)
+            hipLaunchKernelGGL((tiled::k_gemm_tiled<true, 2>), g, b, tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
+                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi);
+        else
+            hipLaunchKernelGGL((tiled::k_gemm_tiled<false, 2>), g, b, tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
+                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi);
+    } else {
+        if (out_bf16)
+            hipLaunchKernelGGL((tiled::k_gemm_tiled<true, 4>), g, b, tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
+                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi);
+        else
+            hipLaunchKernelGGL((tiled::k_gemm_tiled<false, 4>), g, b, tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
+                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi);
+    }
     return hipGetLastError();
 }
 

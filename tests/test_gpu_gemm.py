@@ -151,6 +151,20 @@ def test_gemm_full_size_sampled_rows(brq, orc, name):
     check_gemm(brq, orc, to_host(aq), to_host(as_), to_host(wq), to_host(ws), rows=rows)
 
 
+def test_gemm_half_tiles_several_per_workgroup(brq, orc):
+    """4096 x 2560: 160 tiles of 256 x 256 would leave CUs idle, so the kernel runs 320 tiles of
+    128 x 256 and some workgroups take two of them (ring running across a tile boundary); ragged
+    variant: M = 4000."""
+    from paper_2511_04214_amd import inputs
+    for M in (4096, 4000):
+        N, K = 2560, 1024
+        aq, as_ = inputs.random_mxfp4(M, K, seed=41)
+        wq, ws = inputs.random_mxfp4(N, K, seed=42)
+        rng = np.random.default_rng(43)
+        rows = sorted(set([0, 63, 64, 127, 128, 255, 256, M - 129, M - 128, M - 1] + rng.integers(0, M, 12).tolist()))
+        check_gemm(brq, orc, aq, as_, wq, ws, rows=rows)
+
+
 @pytest.mark.parametrize("M", [1, 4, 16])
 def test_gemm_decode_full_size(brq, orc, M):
     from paper_2511_04214_amd import inputs
