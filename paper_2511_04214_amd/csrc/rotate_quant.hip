@@ -148,7 +148,7 @@ __device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t row, u
     }
 }
 
-// One chunk per lane per step, U steps in flight.  LOG2B = 0 means "no rotation".
+// One chunk per lane per step, U steps in flight (the launcher uses U = 1).  LOG2B = 0 means "no rotation".
 template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool CONTIG, int U>
 __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
     const uint32_t lane = threadIdx.x & 63;
