@@ -23,7 +23,9 @@
  *                              code byte j of row m   at ((m/64)*(Kp/128) + j/64)*4096 + (m%64)*64 + j%64
  *                              scale of group g, row m at ((m/64)*(Kp/512) + g/16)*1024 + (m%64)*16 + g%16
  *                            Buffer sizes (brq_operand_bytes): ceil64(M)*Kp/2 and ceil64(M)*Kp/32
- *                            bytes.  Padding rows and padding K are never read and never written.
+ *                            bytes.  The quantizers write the K padding (elements K..Kp-1 of every
+ *                            row) as zeros: code 0, scale byte 0; the product relies on that.
+ *                            Padding rows are never read into a result and never written.
  *                            brq_to_rowmajor converts back.
  *   - codes: two E2M1 codes per byte, element 2j in the low nibble of byte j, element
  *     2j+1 in the high nibble.  A code is s<<3 | e<<1 | m (magnitudes 0, .5, 1, 1.5, 2,
@@ -118,7 +120,8 @@ brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, in
  *                          sum_{j<32} val(aq[m][32g+j]) * val(wq[n][32g+j]),  fp32 accumulate.
  * (aq, as) the quantized [M][K] operand in a_layout, (wq, ws) the quantized [N][K] operand in
  * w_layout -> y [M][ldy] of ydt (fp32, or bf16 = round-to-nearest-even of the fp32 sum).
- * K % 32 == 0, ldy >= N.  The result does not depend on the layouts.
+ * K % 32 == 0, ldy >= N.  The layouts do not change what is summed, only (through the choice
+ * of kernel) the order of the fp32 additions.
  */
 brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout,
                           const uint8_t* wq, const uint8_t* ws, brq_layout w_layout, int64_t M,

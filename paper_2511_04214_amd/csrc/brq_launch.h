@@ -22,8 +22,9 @@ struct Operand {
 hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
                              bool out_bf16, int64_t ldy, hipStream_t s);
 
-// Persistent LDS-staged kernel for large shapes (N a multiple of 256, K a multiple of 512, any M).
-bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy);
+// Persistent LDS-staged kernel for large shapes (N a multiple of 256, any M; K a multiple of 512,
+// or any K when both operands are tiled, whose K padding is zero).
+bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy, bool both_tiled);
 hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
                              bool out_bf16, int64_t ldy, hipStream_t s);
 

@@ -226,7 +226,7 @@ hipError_t launch_mfma_ceiling(const uint8_t* operands, int iters, int workgroup
 
 hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
                              bool out_bf16, int64_t ldy, hipStream_t s) {
-    if (M > 16 && tiled_gemm_supported(M, N, K, out_bf16, ldy)) {
+    if (M > 16 && tiled_gemm_supported(M, N, K, out_bf16, ldy, a.tiled && w.tiled)) {
         return launch_gemm_tiled(a, w, M, N, K, y, out_bf16, ldy, s);
     } else if (M <= 16) {
         dim3 grid((uint32_t)((N + 15) / 16));

@@ -513,10 +513,13 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 
 }  // namespace tiled
 
-bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy) {
-    return M > 0 && N > 0 && N % tiled::TN == 0 && K % 512 == 0 &&
+// K must be whole 512-element superstages; tiled operands are zero-padded to that by the
+// quantizers, so with both operands tiled any K will do.
+bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy, bool both_tiled) {
+    const int64_t Kp = (K + 511) / 512 * 512;
+    return M > 0 && N > 0 && N % tiled::TN == 0 && (K == Kp || both_tiled) &&
            (ldy * (out_bf16 ? 2 : 4)) % 16 == 0 && ldy * (out_bf16 ? 2 : 4) < (int64_t(1) << 28) &&
-           (K / 2) * 64 < (int64_t(1) << 31);
+           (Kp / 2) * 64 < (int64_t(1) << 31);
 }
 
 hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
@@ -536,6 +539,7 @@ hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int6
         }
         cus = n;
     }
+    K = (K + 511) / 512 * 512;   // padded K of tiled operands (a no-op otherwise)
     // 256 x 256 tiles unless there are too few of them to give every CU one: then 128 x 256
     const int64_t tn = N / tiled::TN;
     const int64_t T4 = ((M + 255) / 256) * tn, T2 = ((M + 127) / 128) * tn;

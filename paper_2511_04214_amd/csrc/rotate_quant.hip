@@ -444,7 +444,22 @@ static hipError_t dispatch_b(int log2b, const RowArgs& a, bool contig, int64_t M
     }
 }
 
-// mode: RowMode; log2b: 0 for MODE_QUANT, else 5..14.  Arguments are already validated.
+// Tiled layout, K not a multiple of 512: the groups between K and the next multiple of 512 are
+// written as zeros (16 zero code bytes, scale byte 0) for every row, so that the persistent
+// product kernel can run whole 512-element superstages over tiled operands.  One lane per
+// padding group.
+__global__ void __launch_bounds__(256) k_zero_kpad(uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                                                   uint32_t rows, uint32_t g0, uint32_t gpad, uint32_t stages,
+                                                   uint32_t sstages) {
+    const uint64_t n = (uint64_t)rows * gpad;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256) {
+        const uint32_t row = (uint32_t)(i / gpad), g = g0 + (uint32_t)(i - (uint64_t)row * gpad);
+        *reinterpret_cast<v4i*>(codes + tiled_code_offset(row, g * 4, stages)) = v4i{0, 0, 0, 0};
+        scales[tiled_scale_offset(row, g * 4, sstages)] = 0;
+    }
+}
+
+// mode: RowMode; log2b: 0 for MODE_QUANT, else 3..14.  Arguments are already validated.
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
                           bool tiled, const int8_t* signs, hipStream_t s) {
@@ -457,6 +472,14 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
     a.stages = tiled ? (uint32_t)(Kp / 128) : 0u;
     a.sstages = tiled ? (uint32_t)(Kp / 512) : 0u;
     bool contig = (ldx == K) && (mode != MODE_ROTATE || ldy == K);
+    if (tiled && Kp != K && mode != MODE_ROTATE) {
+        const uint32_t gpad = (uint32_t)((Kp - K) / 32);
+        const int64_t want = (M * gpad + 255) / 256;
+        hipLaunchKernelGGL(k_zero_kpad, dim3((uint32_t)(want < 4096 ? want : 4096)), dim3(256), 0, s, codes, scales,
+                           (uint32_t)M, (uint32_t)(K / 32), gpad, a.stages, a.sstages);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     if (mode == MODE_ROTATE) {
         if (in_bf16) return out_bf16 ? dispatch_b<true, MODE_ROTATE, true>(log2b, a, contig, M, K, s)
                                      : dispatch_b<true, MODE_ROTATE, false>(log2b, a, contig, M, K, s);
