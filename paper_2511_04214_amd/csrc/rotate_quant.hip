@@ -251,12 +251,20 @@ __global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, ui
     uint32_t sm[8];
     const bool presigned = MODE != MODE_QUANT && a.signs && a.sign_fixed;   // uniform
     if (presigned) sign_masks(sm, a.signs + ((size_t)((blockIdx.x * 4u + wave) % spr) * 16u + (lane & 15u)) * 8);
-    for (uint32_t it = blockIdx.x * 4u + wave; it < nitems; it += gridDim.x * 4u) {
+    // Every address is a wavefront-uniform base plus a per-lane constant (the host checked that
+    // 4 rows of pitch fit 32 bits): the loop body spends no vector instruction on addresses.
+    const uint32_t in_lane = lrow * (uint32_t)a.ldx * ES + (lane & 15u) * (8u * ES);
+    const uint32_t step = gridDim.x * 4u;
+    for (uint32_t it = blockIdx.x * 4u + wave; it < nitems; it += step) {
         const uint32_t rq = it / spr, st = it - rq * spr;              // scalar
         const uint32_t row0 = rq * 4u;
-        // rows past the end (M % 4 != 0) re-read the last row; their stores are masked
-        const uint32_t rrow = min(row0 + lrow, rows - 1u);
-        const char* p = (const char*)a.x + ((uint64_t)rrow * (uint64_t)a.ldx + (uint64_t)st * 128u + (lane & 15u) * 8u) * ES;
+        const char* rowbase = (const char*)a.x + ((uint64_t)row0 * (uint64_t)a.ldx + (uint64_t)st * 128u) * ES;   // scalar
+        const char* p = rowbase + in_lane;
+        if (row0 + 4u > rows) {   // uniform: M % 4 != 0, last item of a column; rows past the end
+                                  // re-read the last row, their stores are masked below
+            const uint32_t rrow = min(row0 + lrow, rows - 1u);
+            p = (const char*)a.x + ((uint64_t)rrow * (uint64_t)a.ldx + (uint64_t)st * 128u + (lane & 15u) * 8u) * ES;
+        }
         float v[8];
         load_chunk<IN_BF16>(p, v);
         if constexpr (MODE != MODE_QUANT) {
@@ -395,7 +403,7 @@ static uint32_t fix_columns(int& grid, uint32_t period, uint32_t per_wg) {
 template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
 static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
     if constexpr (MODE != MODE_ROTATE && LOG2B <= 7) {
-        if (a.stages != 0 && (a.cpr & 15u) == 0) {
+        if (a.stages != 0 && (a.cpr & 15u) == 0 && a.ldx * (IN_BF16 ? 2 : 4) * 4 < (int64_t(1) << 32)) {
             const uint32_t rows = a.nchunks / a.cpr, nitems = ((rows + 3u) / 4u) * (a.cpr >> 4);
             int grid = rowwise_grid(nitems * 64u, 1);
             RowArgs b = a;
