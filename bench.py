@@ -46,6 +46,7 @@ def main():
                     help="layout of the quantized operands between the two kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-aux", action="store_true", help="skip the 16384x8192 rotate+quantize measurement")
+    ap.add_argument("--no-library", action="store_true", help="skip the torch._scaled_mm comparison")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy 4 times (reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -192,6 +193,38 @@ def main():
                "note": "v_mfma_scale_f32_32x32x64 fp4 back to back from registers on every CU, operand "
                        "bit patterns from this workload's quantized activations"}
 
+    # ---- context: the same product through the vendor library as PyTorch exposes it
+    # (torch._scaled_mm on float4_e2m1fn_x2 operands with e8m0 group scales = hipBLASLt), on
+    # row-major copies of this workload's operands
+    library = None
+    if not args.no_library and gemm_M >= 32:
+        try:
+            a_c, a_s = (codes[0], scales[0]) if LAY == "rowmajor" else brq.to_rowmajor(codes[0], scales[0], M, K, stream=stream)
+            w_c, w_s = (wq0, ws0) if LAY == "rowmajor" else brq.to_rowmajor(wq0, ws0, N, K, stream=stream)
+            stream.synchronize()
+            f4, e8 = torch.float4_e2m1fn_x2, torch.float8_e8m0fnu
+            ta, tb = a_c[:gemm_M].view(f4), w_c.view(f4).t()
+            tsa, tsb = a_s[:gemm_M].contiguous().view(e8), w_s.view(e8)
+            with torch.cuda.stream(stream):
+                for _ in range(20):
+                    torch._scaled_mm(ta, tb, scale_a=tsa, scale_b=tsb, out_dtype=out_dtype)
+                l_ms = []
+                for _ in range(3):
+                    a, b = ev(), ev()
+                    a.record(stream)
+                    for _ in range(args.steps):
+                        torch._scaled_mm(ta, tb, scale_a=tsa, scale_b=tsb, out_dtype=out_dtype)
+                    b.record(stream)
+                    stream.synchronize()
+                    l_ms.append(a.elapsed_time(b) / args.steps)
+            l_avg = sum(l_ms) / len(l_ms)
+            library = {"what": "torch._scaled_mm (hipBLASLt MXFP4) on the same operands, warm cache",
+                       "avg_ms": l_avg, "TFLOP/s": gemm_flops / l_avg / 1e9,
+                       "this_kernel_warm_cache_avg_ms": float(gm_warm_ms.mean())}
+            del a_c, a_s, w_c, w_s, ta, tb, tsa, tsb
+        except Exception as e:      # the comparison is context, never a reason to fail the bench
+            library = {"what": "torch._scaled_mm unavailable: %s" % str(e)[:200]}
+
     # ---- the rotate+quantize kernel on the shape its HBM target is quoted on
     aux = None
     if not args.no_aux:
@@ -286,6 +319,7 @@ def main():
         "gemm_TFLOPs": kernels["mxfp4_gemm"]["TFLOP/s"],
         "roofline": roofline,
         "mfma_loop_ceiling": ceiling,
+        "library_baseline": library,
         "rotate_quant_16384x8192": aux,
         "kernels": kernels,
         "cpu_baseline": cpu_baseline,
