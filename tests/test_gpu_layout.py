@@ -225,3 +225,38 @@ def test_product_decode_tiled_full_size(brq, orc, M):
     ow, ows = orc.rotate_quantize_fused(w, 32)
     ref, bound = orc.mxfp4_gemm(oa, oas, ow, ows)
     assert (np.abs(y - ref) <= 1e-5 * bound + 2.0 ** -126).all()
+
+
+def test_calls_run_on_the_given_stream(brq, orc):
+    """Work goes to the caller's stream: results are complete after synchronising that stream
+    alone, and two streams can run the path side by side on their own buffers."""
+    rng = np.random.default_rng(61)
+    from paper_2511_04214_amd.inputs import f32_to_bf16_bits
+    M, N, K = 256, 512, 1024
+    xs = [f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32)) for _ in range(2)]
+    w = f32_to_bf16_bits((rng.standard_normal((N, K)) * 0.05).astype(np.float32))
+    wct, wst = brq.rotate_quantize_fused(to_dev(w), 32, layout="tiled")
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    xd = [to_dev(x) for x in xs]
+    torch.cuda.synchronize()
+    outs = []
+    for x, st in zip(xd, streams):
+        c, s_ = brq.rotate_quantize_fused(x, 32, layout="tiled", stream=st)
+        outs.append(brq.mxfp4_gemm(c, s_, wct, wst, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K, stream=st))
+    ow, ows = orc.rotate_quantize_fused(w, 32)
+    for x, st, y in zip(xs, streams, outs):
+        st.synchronize()
+        oa, oas = orc.rotate_quantize_fused(x, 32)
+        ref, bound = orc.mxfp4_gemm(oa, oas, ow, ows)
+        assert (np.abs(to_host(y).astype(np.float64) - ref) <= 1e-5 * bound + 2.0 ** -126).all()
+
+
+def test_empty_operands_in_the_tiled_layout(brq):
+    x = torch.zeros((0, 512), dtype=torch.bfloat16, device="cuda")
+    c, s_ = brq.rotate_quantize_fused(x, 32, layout="tiled")
+    assert c.numel() == 0 and s_.numel() == 0
+    w = torch.zeros((256, 512), dtype=torch.bfloat16, device="cuda")
+    wc, ws = brq.rotate_quantize_fused(w, 32, layout="tiled")
+    y = brq.mxfp4_gemm(c, s_, wc, ws, a_layout="tiled", w_layout="tiled", M=0, N=256, K=512)
+    assert tuple(y.shape) == (0, 256)
