@@ -260,3 +260,46 @@ def test_empty_operands_in_the_tiled_layout(brq):
     wc, ws = brq.rotate_quantize_fused(w, 32, layout="tiled")
     y = brq.mxfp4_gemm(c, s_, wc, ws, a_layout="tiled", w_layout="tiled", M=0, N=256, K=512)
     assert tuple(y.shape) == (0, 256)
+
+
+def test_step_in_a_hip_graph(brq):
+    """The two-kernel step (fused rotate+quantize, product) captured in a HIP graph: every replay
+    gives the eager result, with eager launches and synchronisations between the replays."""
+    from paper_2511_04214_amd.inputs import f32_to_bf16_bits
+    rng = np.random.default_rng(71)
+    for M, N, K in ((16, 1024, 2048), (300, 512, 1024)):
+        w = to_dev(f32_to_bf16_bits((rng.standard_normal((N, K)) * 0.05).astype(np.float32)))
+        wct, wst = brq.rotate_quantize_fused(w, 32, layout="tiled")
+        xs = [to_dev(f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))) for _ in range(3)]
+        x = xs[0].clone()
+        cb, sb = brq.operand_bytes(M, K, "tiled")
+        c = torch.empty((cb,), dtype=torch.uint8, device="cuda")
+        s_ = torch.empty((sb,), dtype=torch.uint8, device="cuda")
+        y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        st = torch.cuda.Stream()
+
+        def step():
+            brq.rotate_quantize_fused(x, 32, codes=c, scales=s_, layout="tiled", stream=st)
+            brq.mxfp4_gemm(c, s_, wct, wst, out=y, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K, stream=st)
+
+        eager = []
+        for xi in xs:                      # eager results for three different inputs (also warms the library up)
+            x.copy_(xi)
+            torch.cuda.synchronize()
+            step()
+            st.synchronize()
+            eager.append(y.clone())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            step()
+        for rep in range(2):
+            for xi, want in zip(xs, eager):
+                x.copy_(xi)
+                y.zero_()
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(y, want), (M, rep)
+                step()                     # eager work between the replays
+                st.synchronize()
+                assert torch.equal(y, want)
