@@ -58,6 +58,10 @@ def _bind(path):
     L.oracle_mxfp4_quantize.argtypes = [vp, i32, i64, i64, i64, vp, vp]
     L.oracle_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp]
     L.oracle_rotate_quantize_fused_signed.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
+    L.oracle_swiglu_elem.argtypes = [ctypes.c_float, ctypes.c_float]
+    L.oracle_swiglu_elem.restype = ctypes.c_float
+    L.oracle_swiglu.argtypes = [vp, vp, i32, i64, i64, i64, i64, vp, i32, i64]
+    L.oracle_swiglu_rotate_quantize_fused.argtypes = [vp, vp, i32, i64, i64, i64, i64, i32, i64, vp, vp, vp]
     L.oracle_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, vp]
     L.oracle_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_matmul_nt_f64.argtypes = [vp, vp, i64, i64, i64, vp]
@@ -92,7 +96,8 @@ def _rows(a):
     """2-D array with contiguous rows -> (array, M, K, row pitch in elements)."""
     if a.ndim != 2 or a.strides[1] != a.itemsize or a.strides[0] % a.itemsize:
         raise ValueError("need a 2-D array with contiguous rows")
-    return a, a.shape[0], a.shape[1], a.strides[0] // a.itemsize
+    ld = a.strides[0] // a.itemsize if a.shape[0] > 1 else a.shape[1]   # a single row has no pitch
+    return a, a.shape[0], a.shape[1], ld
 
 
 class Oracle:
@@ -177,6 +182,34 @@ class Oracle:
             sg = _signs(signs, K)
             _check(self.L.oracle_rotate_quantize_fused_signed(_p(x), _dt(x), M, K, ldx, B, _p(sg), _p(codes),
                                                               _p(scales)), "rotate_quantize_fused_signed")
+        return codes, scales
+
+    def swiglu_elem(self, g, u):
+        return np.float32(self.L.oracle_swiglu_elem(float(np.float32(g)), float(np.float32(u))))
+
+    def swiglu(self, gate, up, out_bf16=False):
+        """h = silu(gate) * up in the oracle's fixed fp32 sequence; fp32, or bf16 bits."""
+        gate, M, K, ldg = _rows(gate)
+        up, M2, K2, ldu = _rows(up)
+        if (M, K) != (M2, K2) or gate.dtype != up.dtype:
+            raise ValueError("gate and up must agree in shape and type")
+        h = np.empty((M, K), dtype=np.uint16 if out_bf16 else np.float32)
+        _check(self.L.oracle_swiglu(_p(gate), _p(up), _dt(gate), M, K, ldg, ldu, _p(h), BF16 if out_bf16 else F32, K),
+               "swiglu")
+        return h
+
+    def swiglu_rotate_quantize_fused(self, gate, up, B, h_bf16=False, signs=None):
+        gate, M, K, ldg = _rows(gate)
+        up, M2, K2, ldu = _rows(up)
+        if (M, K) != (M2, K2) or gate.dtype != up.dtype:
+            raise ValueError("gate and up must agree in shape and type")
+        codes = np.empty((M, K // 2), dtype=np.uint8)
+        scales = np.empty((M, K // 32), dtype=np.uint8)
+        sg = None if signs is None else _signs(signs, K)
+        _check(self.L.oracle_swiglu_rotate_quantize_fused(_p(gate), _p(up), _dt(gate), M, K, ldg, ldu,
+                                                          BF16 if h_bf16 else F32, B,
+                                                          None if sg is None else _p(sg), _p(codes), _p(scales)),
+               "swiglu_rotate_quantize_fused")
         return codes, scales
 
     def mxfp4_dequantize(self, codes, scales):

@@ -17,6 +17,9 @@
  *     normalised Sylvester Hadamard H_g / sqrt(g) (Sec. 5.1 / Appendix: block-wise
  *     Hadamard, no learned rotation).  This file follows the benchmark's naming and
  *     calls the block SIZE "B" (the paper's g).
+ *   - Sec. 4.3 ("reduced online computing"): the online rotation sits in front of down_proj,
+ *     whose input in the evaluated LLaMA models is silu(gate) * up; oracle_swiglu* produce
+ *     that input and feed it to the same rotation and quantizer.
  *   - Sec. 2 ("equivalent transformations"): Y = (X R)(W R)^T = X W^T, evaluated on the
  *     quantized operands: Y[m][n] = sum_k deq(A)[m][k] * deq(W)[n][k].
  *
@@ -27,7 +30,9 @@
  * Pins (tests/test_oracle_pins.py): H H^T = B I; popcount closed form; exact integer
  * products; one-hot rows; norm preservation; involution; block independence; the E2M1
  * value table from the 1/2/1 bit split; hand-worked rounding / tie / saturation /
- * scale cases; round trip of representable blocks; (XH)(WH)^T = XW^T; brute-force GEMM.
+ * scale cases; round trip of representable blocks; (XH)(WH)^T = XW^T; brute-force GEMM;
+ * the SwiGLU producer against g / (1 + exp(-g)) * u in fp64 within its stated error, its
+ * exact special values, and the fused call against the composition of the pinned parts.
  * parity unpinned: the paper prints no quantized block, code, scale or kernel output,
  * so the whole pipeline has no paper-printed value to be compared with.
  *
@@ -296,6 +301,95 @@ int oracle_rotate_quantize_fused_signed(const void *x, int xdt, int64_t M, int64
 int oracle_rotate_quantize_fused(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx,
                                  int64_t B, uint8_t *codes, uint8_t *scales) {
     return oracle_rotate_quantize_fused_signed(x, xdt, M, K, ldx, B, NULL, codes, scales);
+}
+
+/* ------------------------------------------------------------------------------------
+ * The producer of the rotated layer's input (Sec. 4.3, "reduced online computing": the
+ * online rotation R_4 sits in front of down_proj).  In the LLaMA models the paper evaluates,
+ * down_proj reads h = silu(gate) * up, silu(g) = g / (1 + exp(-g)).  The paper does not say
+ * how h is computed; because h feeds a quantizer whose codes are compared bit for bit, the
+ * fp32 operation sequence is fixed here (every step one IEEE round-to-nearest-even fp32
+ * operation; fma = fused multiply-add with a single rounding):
+ *
+ *   gn = max(g, -86)                 silu below -86 is taken as silu(-86) ~ -4e-36
+ *   ge = min(gn, 86)                 keeps 2^n inside the normal range
+ *   z  = ge * (-log2(e))             -log2(e) as fp32 = -0x3FB8AA3B
+ *   n  = z rounded to the nearest integer, ties to even;  r = z - n   (exact, |r| <= 1/2)
+ *   p  = 1 + r (c1 + r (c2 + r (c3 + r (c4 + r c5))))     five fma, innermost first
+ *   e  = p * 2^n                     exact: p in [0.70, 1.42], |n| <= 125
+ *   d  = 1 + e
+ *   s  = gn / d                      IEEE division
+ *   h  = s * u
+ *   h  = bf16(h), round to nearest even, when the intermediate type is bf16 (what a
+ *        separate bf16 activation kernel would have stored); else h stays fp32
+ *
+ * c1..c5 approximate 2^r on [-1/2, 1/2] to 1.7e-7 relative (own minimax fit).
+ * ---------------------------------------------------------------------------------- */
+static float f32_from_bits(uint32_t u) {
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+float oracle_swiglu_elem(float g, float u) {
+    const float c1 = f32_from_bits(0x3F317215u), c2 = f32_from_bits(0x3E75FCDEu), c3 = f32_from_bits(0x3D635BA9u),
+                c4 = f32_from_bits(0x3C1E753Du), c5 = f32_from_bits(0x3AADDCFAu);
+    const float neg_log2e = -f32_from_bits(0x3FB8AA3Bu);
+    float gn = g > -86.0f ? g : -86.0f;
+    float ge = gn < 86.0f ? gn : 86.0f;
+    float z = ge * neg_log2e;
+    float n = rintf(z); /* default rounding mode: to nearest, ties to even */
+    float r = z - n;
+    float p = c5;
+    p = fmaf(p, r, c4);
+    p = fmaf(p, r, c3);
+    p = fmaf(p, r, c2);
+    p = fmaf(p, r, c1);
+    p = fmaf(p, r, 1.0f);
+    float e = ldexpf(p, (int)n);
+    float d = 1.0f + e;
+    float s = gn / d;
+    return s * u;
+}
+
+/* h[r][k] = swiglu(gate[r][k], up[r][k]); gate, up: [M][ldg], [M][ldu] of dt; h: [M][ldh] of
+ * hdt (bf16 = RNE of the fp32 value). */
+int oracle_swiglu(const void *gate, const void *up, int dt, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                  void *h, int hdt, int64_t ldh) {
+    if (!gate || !up || !h || ldg < K || ldu < K || ldh < K) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; ++r) {
+        for (int64_t k = 0; k < K; ++k) {
+            float v = oracle_swiglu_elem(load_elem(gate, dt, r * ldg + k), load_elem(up, dt, r * ldu + k));
+            if (hdt == ORACLE_BF16)
+                ((uint16_t *)h)[r * ldh + k] = oracle_f32_to_bf16(v);
+            else
+                ((float *)h)[r * ldh + k] = v;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* Producer fused with the online step: quantize(block_rotate(h)) with h as above, the
+ * composition and nothing else.  hdt says whether h passes through bf16 on the way (the
+ * value is then widened again, exactly).  B = 1 means no rotation (H_1 = [1]). */
+int oracle_swiglu_rotate_quantize_fused(const void *gate, const void *up, int dt, int64_t M, int64_t K,
+                                        int64_t ldg, int64_t ldu, int hdt, int64_t B, const int8_t *signs,
+                                        uint8_t *codes, uint8_t *scales) {
+    if (!codes || !scales || K % 32 || B < 1) return ORACLE_ERR_ARG;
+    float *h = (float *)malloc((size_t)(M > 0 ? M : 1) * (size_t)K * sizeof(float));
+    if (!h) return ORACLE_ERR_ARG;
+    int rc = oracle_swiglu(gate, up, dt, M, K, ldg, ldu, h, ORACLE_F32, K);
+    if (rc == ORACLE_OK && hdt == ORACLE_BF16)
+        for (int64_t i = 0; i < M * K; ++i) h[i] = oracle_bf16_to_f32(oracle_f32_to_bf16(h[i]));
+    if (rc == ORACLE_OK) {
+        if (B == 1)
+            rc = signs ? ORACLE_ERR_ARG : oracle_mxfp4_quantize(h, ORACLE_F32, M, K, K, codes, scales);
+        else
+            rc = oracle_rotate_quantize_fused_signed(h, ORACLE_F32, M, K, K, B, signs, codes, scales);
+    }
+    free(h);
+    return rc;
 }
 
 /* deq[r][k] = value(code) * 2^(scale - 127), fp64 (exact). */

@@ -359,6 +359,83 @@ def pin_fused_small_blocks_and_signs(o):
     assert np.array_equal(o.mxfp4_dequantize(c2, sc2)[0], -vals) and sc2[0, 0] == 128
 
 
+# --------------------------------------------------------------------------- producer (SwiGLU)
+
+def _bf16_bits_torch(x32):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def pin_swiglu_against_closed_form(o):
+    # h = g / (1 + exp(-g)) * u, the definition, in fp64 (numpy's exp, which the oracle does not
+    # call).  The oracle's fp32 sequence promises |h - exact| <= (5 + 1.25 |g|) 2^-24 |exact| on
+    # |g| <= 86: 1.7e-7 from the polynomial; z = g log2(e) carries half an ulp of its own size
+    # plus the rounding of log2(e) (1.22 |z| 2^-24 together), which exp turns into a relative
+    # error of ln(2) times that = 1.22 |g| 2^-24; the rest are single roundings.
+    rng = np.random.default_rng(31)
+    g = np.concatenate([np.linspace(-86, 86, 400001), rng.standard_normal(200000) * 4]).astype(np.float32)
+    u = (rng.standard_normal(g.size) * 2).astype(np.float32)
+    h = o.swiglu(g[None, :], u[None, :])[0]
+    exact = np.float64(g) / (1.0 + np.exp(-np.float64(g))) * np.float64(u)
+    assert np.all(np.abs(h - exact) <= (5 + 1.25 * np.abs(np.float64(g))) * 2.0 ** -24 * np.abs(exact))
+    # not symmetric in its arguments: silu acts on the first one
+    assert abs(float(o.swiglu_elem(1.0, 3.0)) - 3.0 / (1 + math.exp(-1.0))) < 1e-6
+    assert abs(float(o.swiglu_elem(3.0, 1.0)) - 3.0 / (1 + math.exp(-3.0))) < 1e-6
+    # exact cases: silu(0) = 0; exp(-g) < 2^-24 makes the denominator 1, so silu(g) = g for
+    # g >= 17; a power-of-two u scales exactly; far below zero the value is pinned at silu(-86)
+    assert float(o.swiglu_elem(0.0, 7.0)) == 0.0
+    for gv in (17.0, 20.5, 86.0, 100.0, 3.0e38):
+        assert float(o.swiglu_elem(gv, 1.0)) == float(np.float32(gv))
+        assert float(o.swiglu_elem(gv, -0.5)) == -0.5 * float(np.float32(gv))
+    for gv in (-3.0, 0.7, 5.0):
+        assert float(o.swiglu_elem(gv, 4.0)) == 4.0 * float(o.swiglu_elem(gv, 1.0))
+    tail = float(o.swiglu_elem(-86.0, 1.0))
+    assert -5e-36 < tail < -3e-36
+    for gv in (-86.5, -100.0, -1.0e30, -3.0e38):
+        assert float(o.swiglu_elem(gv, 1.0)) == tail
+    # bf16 inputs are widened exactly: the same values given as bf16 bits or as fp32 agree
+    gb, ub = _bf16_bits_torch(g[:4096]), _bf16_bits_torch(u[:4096])
+    gw, uw = o.bf16_to_f32(gb), o.bf16_to_f32(ub)
+    assert np.array_equal(o.swiglu(gb[None, :], ub[None, :]), o.swiglu(gw[None, :], uw[None, :]))
+    # bf16 output is the round-to-nearest-even of the fp32 output (torch's conversion)
+    h32 = o.swiglu(gw[None, :], uw[None, :])
+    assert np.array_equal(o.swiglu(gw[None, :], uw[None, :], out_bf16=True), _bf16_bits_torch(h32))
+
+
+def pin_swiglu_fused_is_the_composition(o):
+    rng = np.random.default_rng(32)
+    M, K = 5, 256
+    # gate and up as the two halves of one [M, 2K + 8] buffer: different pitches from K, and the
+    # up half starts elsewhere than the gate half
+    buf = (rng.standard_normal((M, 2 * K + 8)) * 3).astype(np.float32)
+    gate, up = buf[:, :K], buf[:, K + 8:]
+    wide = (rng.standard_normal((M, K + 32)) * 3).astype(np.float32)
+    up2 = wide[:, :K]                      # a third pitch
+    s = rng.choice([-1, 1], size=K).astype(np.int8)
+    for g_, u_ in ((gate, up), (gate, up2)):
+        h32 = o.swiglu(np.ascontiguousarray(g_), np.ascontiguousarray(u_))
+        hb = o.swiglu(np.ascontiguousarray(g_), np.ascontiguousarray(u_), out_bf16=True)
+        for B in (8, 32, 128):
+            for sg in (None, s):
+                c1, s1 = o.swiglu_rotate_quantize_fused(g_, u_, B, h_bf16=False, signs=sg)
+                c2, s2 = o.rotate_quantize_fused(h32, B, signs=sg)
+                assert np.array_equal(c1, c2) and np.array_equal(s1, s2)
+                c3, s3 = o.swiglu_rotate_quantize_fused(g_, u_, B, h_bf16=True, signs=sg)
+                c4, s4 = o.rotate_quantize_fused(hb, B, signs=sg)       # hb: bf16 bits, widened exactly
+                assert np.array_equal(c3, c4) and np.array_equal(s3, s4)
+        # B = 1: no rotation, the quantizer alone
+        c5, s5 = o.swiglu_rotate_quantize_fused(g_, u_, 1)
+        c6, s6 = o.mxfp4_quantize(h32)
+        assert np.array_equal(c5, c6) and np.array_equal(s5, s6)
+        assert not np.array_equal(c5, o.swiglu_rotate_quantize_fused(g_, u_, 32)[0])
+    # passing through bf16 is visible in the codes of a long enough row (a value near a rounding
+    # boundary of the encoder moves across it)
+    big_g = (rng.standard_normal((8, 4096)) * 3).astype(np.float32)
+    big_u = (rng.standard_normal((8, 4096)) * 3).astype(np.float32)
+    assert not np.array_equal(o.swiglu_rotate_quantize_fused(big_g, big_u, 32, h_bf16=False)[0],
+                              o.swiglu_rotate_quantize_fused(big_g, big_u, 32, h_bf16=True)[0])
+
+
 # --------------------------------------------------------------------------- product
 
 def pin_equivalent_transformation(o):

@@ -47,6 +47,18 @@ MUTANTS = [
     ("signs_ignored", "if (signs && signs[b * B + i] < 0) e = -e;", ""),
     ("fused_drops_signs", "int rc = oracle_block_rotate_signed(x, xdt, M, K, ldx, B, signs, y, ORACLE_F32, K);",
      "int rc = oracle_block_rotate_signed(x, xdt, M, K, ldx, B, NULL, y, ORACLE_F32, K);"),
+    ("swiglu_exp_sign", "const float neg_log2e = -f32_from_bits(0x3FB8AA3Bu);", "const float neg_log2e = f32_from_bits(0x3FB8AA3Bu);"),
+    ("swiglu_forgets_up", "return s * u;", "return s;"),
+    ("swiglu_numerator_clamped_above", "float s = gn / d;", "float s = ge / d;"),
+    ("swiglu_no_lower_clamp", "float gn = g > -86.0f ? g : -86.0f;", "float gn = g;"),
+    ("swiglu_poly_drops_top_term", "float p = c5;", "float p = 0.0f;"),
+    ("swiglu_poly_wrong_linear_term", "p = fmaf(p, r, c1);", "p = fmaf(p, r, 1.0f);"),
+    ("swiglu_denominator_without_one", "float d = 1.0f + e;", "float d = e;"),
+    ("swiglu_up_read_with_gate_pitch", "load_elem(up, dt, r * ldu + k)", "load_elem(up, dt, r * ldg + k)"),
+    ("swiglu_fused_skips_bf16", "if (rc == ORACLE_OK && hdt == ORACLE_BF16)", "if (0)"),
+    ("swiglu_fused_never_rotates", "        if (B == 1)\n            rc = signs ?", "        if (B >= 1)\n            rc = signs ?"),
+    ("swiglu_fused_drops_signs", "rc = oracle_rotate_quantize_fused_signed(h, ORACLE_F32, M, K, K, B, signs, codes, scales);",
+     "rc = oracle_rotate_quantize_fused_signed(h, ORACLE_F32, M, K, K, B, NULL, codes, scales);"),
     ("fused_skips_rotation", "if (rc == ORACLE_OK) rc = oracle_mxfp4_quantize(y, ORACLE_F32, M, K, K, codes, scales);",
      "rc = oracle_mxfp4_quantize(x, xdt, M, K, ldx, codes, scales);"),
 ]
