@@ -115,6 +115,40 @@ brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, in
                                      uint8_t* scales, brq_layout layout, void* stream);
 
 /*
+ * The online step with its producer in front (Sec. 4.3: the online rotation R_4 sits before
+ * down_proj; in the LLaMA models the paper evaluates, down_proj reads h = silu(gate) * up):
+ *     brq_rotate_quantize_fused(h, B, signs)  with  h[m][k] = silu(gate[m][k]) * up[m][k]
+ * in one pass over gate and up; h never visits memory.  Bit-identical to that composition
+ * with h computed as follows (the paper does not say how; since h feeds a quantizer, the
+ * fp32 operation sequence is part of this interface; every step is one IEEE
+ * round-to-nearest-even fp32 operation, fma = fused multiply-add):
+ *     gn = max(g, -86);  ge = min(gn, 86);  z = ge * -log2(e)      (-log2(e) = -0x3FB8AA3B)
+ *     n = z rounded to the nearest integer, ties to even;  r = z - n
+ *     p = fma(fma(fma(fma(fma(c5, r, c4), r, c3), r, c2), r, c1), r, 1)
+ *         c1..c5 = 0x3F317215, 0x3E75FCDE, 0x3D635BA9, 0x3C1E753D, 0x3AADDCFA   (2^r on [-1/2, 1/2])
+ *     e = p * 2^n (exact);  d = 1 + e;  s = gn / d;  h = s * u
+ * |h - silu(g) u| <= (5 + 1.25 |g|) 2^-24 |silu(g) u| for |g| <= 86; below -86 silu is held at
+ * silu(-86) ~ -4e-36.  hdt = BRQ_BF16 rounds h to bf16 (nearest even) before the rotation, which
+ * reproduces a separate activation kernel that stores bf16; BRQ_F32 keeps the fp32 value.
+ * gate [M][ldg], up [M][ldu], both of xdt (they may be two halves of one buffer).
+ * B as in brq_rotate_quantize_fused, or 1 for no rotation (quantization alone; signs must
+ * then be NULL).
+ */
+/*
+ * The activation alone: h = silu(gate) * up in the sequence above, stored as fp32 or as its
+ * bf16 rounding.  Not on the fused path (that is its point); it is the unfused first half that
+ * the fused call is measured and checked against.  h [M][ldh] of hdt may overlap neither input.
+ */
+brq_status brq_swiglu(const void* gate, const void* up, brq_dtype xdt, int64_t M, int64_t K,
+                      int64_t ldg, int64_t ldu, void* h, brq_dtype hdt, int64_t ldh, void* stream);
+
+brq_status brq_swiglu_rotate_quantize_fused(const void* gate, const void* up, brq_dtype xdt,
+                                            int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                                            brq_dtype hdt, int64_t B, const int8_t* signs,
+                                            uint8_t* codes, uint8_t* scales, brq_layout layout,
+                                            void* stream);
+
+/*
  * W4A4 product on MXFP4 operands (Sec. 2; Sec. 4.1 "scaling factor integrated into
  * hardware"):   y[m][n] = sum_g 2^(as[m][g]-127 + ws[n][g]-127) *
  *                          sum_{j<32} val(aq[m][32g+j]) * val(wq[n][32g+j]),  fp32 accumulate.

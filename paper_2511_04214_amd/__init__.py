@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbrq.so")
 BRQ_F32, BRQ_BF16 = 0, 1
 LAYOUTS = {"rowmajor": 0, "tiled": 1}
 EXPORTS = ["brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
-           "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_strerror", "brq_version"]
+           "brq_swiglu", "brq_swiglu_rotate_quantize_fused", "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_strerror", "brq_version"]
 
 _lib = None
 
@@ -45,6 +45,10 @@ def lib():
         L.brq_mxfp4_quantize.restype = i32
         L.brq_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp, i32, vp]
         L.brq_rotate_quantize_fused.restype = i32
+        L.brq_swiglu.argtypes = [vp, vp, i32, i64, i64, i64, i64, vp, i32, i64, vp]
+        L.brq_swiglu.restype = i32
+        L.brq_swiglu_rotate_quantize_fused.argtypes = [vp, vp, i32, i64, i64, i64, i64, i32, i64, vp, vp, vp, i32, vp]
+        L.brq_swiglu_rotate_quantize_fused.restype = i32
         L.brq_mxfp4_gemm.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp]
         L.brq_mxfp4_gemm.restype = i32
         L.brq_to_rowmajor.argtypes = [vp, vp, i64, i64, vp, vp, vp]
@@ -154,6 +158,41 @@ def rotate_quantize_fused(x, B, codes=None, scales=None, stream=None, layout="ro
     codes, scales = _alloc_q(x, M, K, codes, scales, layout)
     _check(lib().brq_rotate_quantize_fused(x.data_ptr(), _dtype_code(x), M, K, ldx, B, _signs_ptr(signs, K),
                                            codes.data_ptr(), scales.data_ptr(), lc, _stream(stream)))
+    return codes, scales
+
+
+def swiglu(gate, up, out_dtype=torch.float32, out=None, stream=None):
+    """h = silu(gate) * up in the library's fixed fp32 sequence (brq_swiglu)."""
+    M, K, ldg = _rows(gate, "gate")
+    M2, K2, ldu = _rows(up, "up")
+    if (M, K) != (M2, K2) or gate.dtype != up.dtype:
+        raise ValueError("gate and up must agree in shape and dtype")
+    h = torch.empty((M, K), dtype=out_dtype, device=gate.device) if out is None else out
+    _, _, ldh = _rows(h, "out")
+    _check(lib().brq_swiglu(gate.data_ptr(), up.data_ptr(), _dtype_code(gate), M, K, ldg, ldu, h.data_ptr(),
+                            _dtype_code(h), ldh, _stream(stream)))
+    return h
+
+
+def swiglu_rotate_quantize_fused(gate, up, B, h_dtype=torch.float32, codes=None, scales=None, stream=None,
+                                 layout="rowmajor", signs=None):
+    """silu(gate) * up -> block rotation -> MXFP4, in one pass (brq_swiglu_rotate_quantize_fused).
+
+    h_dtype: torch.bfloat16 rounds the activation to bf16 before the rotation, torch.float32
+    keeps it.  B = 1 quantizes without rotating.
+    """
+    M, K, ldg = _rows(gate, "gate")
+    M2, K2, ldu = _rows(up, "up")
+    if (M, K) != (M2, K2) or gate.dtype != up.dtype:
+        raise ValueError("gate and up must agree in shape and dtype")
+    if h_dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("h_dtype must be torch.float32 or torch.bfloat16")
+    lc = _layout_code(layout)
+    codes, scales = _alloc_q(gate, M, K, codes, scales, layout)
+    _check(lib().brq_swiglu_rotate_quantize_fused(gate.data_ptr(), up.data_ptr(), _dtype_code(gate), M, K, ldg, ldu,
+                                                  BRQ_BF16 if h_dtype == torch.bfloat16 else BRQ_F32, B,
+                                                  _signs_ptr(signs, K), codes.data_ptr(), scales.data_ptr(), lc,
+                                                  _stream(stream)))
     return codes, scales
 
 

@@ -52,7 +52,7 @@ brq_status brq_block_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, 
     if (l2 < 0) return BRQ_ERR_BLOCK;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_rowwise(0, l2, xdt == BRQ_BF16, ydt == BRQ_BF16, x, M, K, ldx, y, ldy, nullptr,
-                                        nullptr, false, signs, static_cast<hipStream_t>(stream)));
+                                        nullptr, false, signs, nullptr, static_cast<hipStream_t>(stream)));
 }
 
 brq_status brq_operand_bytes(int64_t rows, int64_t K, brq_layout layout, int64_t* codes_bytes,
@@ -78,7 +78,7 @@ brq_status brq_mxfp4_quantize(const void* x, brq_dtype xdt, int64_t M, int64_t K
     if (st != BRQ_OK) return st;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_rowwise(1, 0, xdt == BRQ_BF16, false, x, M, K, ldx, nullptr, 0, codes, scales,
-                                        layout == BRQ_LAYOUT_TILED, nullptr, static_cast<hipStream_t>(stream)));
+                                        layout == BRQ_LAYOUT_TILED, nullptr, nullptr, static_cast<hipStream_t>(stream)));
 }
 
 brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
@@ -94,7 +94,42 @@ brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, in
     if (l2 < 0) return BRQ_ERR_BLOCK;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_rowwise(2, l2, xdt == BRQ_BF16, false, x, M, K, ldx, nullptr, 0, codes, scales,
-                                        layout == BRQ_LAYOUT_TILED, signs, static_cast<hipStream_t>(stream)));
+                                        layout == BRQ_LAYOUT_TILED, signs, nullptr, static_cast<hipStream_t>(stream)));
+}
+
+brq_status brq_swiglu(const void* gate, const void* up, brq_dtype xdt, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                      void* h, brq_dtype hdt, int64_t ldh, void* stream) {
+    brq_status st = check_rows(gate, xdt, M, K, ldg);
+    if (st != BRQ_OK) return st;
+    st = check_rows(up, xdt, M, K, ldu);
+    if (st != BRQ_OK) return st;
+    st = check_rows(h, hdt, M, K, ldh);
+    if (st != BRQ_OK) return st;
+    if (M == 0) return BRQ_OK;
+    const brq::Producer prod{up, ldu, false};
+    return launched(brq::launch_rowwise(0, 0, xdt == BRQ_BF16, hdt == BRQ_BF16, gate, M, K, ldg, h, ldh, nullptr, nullptr,
+                                        false, nullptr, &prod, static_cast<hipStream_t>(stream)));
+}
+
+brq_status brq_swiglu_rotate_quantize_fused(const void* gate, const void* up, brq_dtype xdt, int64_t M, int64_t K,
+                                            int64_t ldg, int64_t ldu, brq_dtype hdt, int64_t B, const int8_t* signs,
+                                            uint8_t* codes, uint8_t* scales, brq_layout layout, void* stream) {
+    brq_status st = check_rows(gate, xdt, M, K, ldg);
+    if (st != BRQ_OK) return st;
+    st = check_rows(up, xdt, M, K, ldu);
+    if (st != BRQ_OK) return st;
+    if (dtype_size(hdt) == 0) return BRQ_ERR_DTYPE;
+    if (!layout_ok(layout)) return BRQ_ERR_LAYOUT;
+    if (!aligned16(signs)) return BRQ_ERR_ALIGN;
+    st = check_out(codes, scales, M);
+    if (st != BRQ_OK) return st;
+    const int l2 = (B == 1) ? 0 : block_log2(B, K);   // B = 1: H_1 = [1], the quantizer alone
+    if (l2 < 0 || (B == 1 && signs)) return BRQ_ERR_BLOCK;
+    if (M == 0) return BRQ_OK;
+    const brq::Producer prod{up, ldu, hdt == BRQ_BF16};
+    return launched(brq::launch_rowwise(B == 1 ? 1 : 2, l2, xdt == BRQ_BF16, false, gate, M, K, ldg, nullptr, 0, codes,
+                                        scales, layout == BRQ_LAYOUT_TILED, signs, &prod,
+                                        static_cast<hipStream_t>(stream)));
 }
 
 brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
@@ -149,6 +184,6 @@ const char* brq_strerror(brq_status s) {
     return "unknown status";
 }
 
-int brq_version(void) { return 300; }
+int brq_version(void) { return 310; }
 
 }  // extern "C"

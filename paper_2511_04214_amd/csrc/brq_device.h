@@ -107,6 +107,49 @@ __device__ __forceinline__ void wht_cross_quad(float (&v)[8], float s1, float s2
 }
 #undef BRQ_FMAC_DPP
 
+// silu(g) * u, the gated activation that produces the input of the rotated layer (Sec. 4.3: the
+// online rotation sits in front of down_proj).  The result feeds a quantizer whose codes are
+// compared bit for bit, so this is the fixed fp32 operation sequence that brq.h defines for
+// brq_swiglu_rotate_quantize_fused, one IEEE operation per step: clamp, z = g * -log2(e),
+// n = rint(z), r = z - n, a degree-5 polynomial of 2^r by fused multiply-adds, e = p * 2^n,
+// d = 1 + e, s = g / d (correctly rounded division), h = s * u.  No hardware approximation
+// (v_exp_f32, v_rcp_f32) takes part: their last bits are not reproducible elsewhere.
+// The clamps are written as instructions: the compiler would put a canonicalising
+// v_max_f32 x, x, x in front of fmaxf/fminf on values it cannot prove to be quiet.
+__device__ __forceinline__ float swiglu_f32(float g, float u) {
+    float gn, ge;
+    asm("v_max_f32 %0, %1, %2" : "=v"(gn) : "v"(g), "v"(-86.0f));
+    asm("v_min_f32 %0, %1, %2" : "=v"(ge) : "v"(gn), "v"(86.0f));
+    const float z = ge * -as_f32(0x3FB8AA3Bu);
+    const float n = __builtin_rintf(z);
+    const float r = z - n;
+    float p = as_f32(0x3AADDCFAu);
+    p = __builtin_fmaf(p, r, as_f32(0x3C1E753Du));
+    p = __builtin_fmaf(p, r, as_f32(0x3D635BA9u));
+    p = __builtin_fmaf(p, r, as_f32(0x3E75FCDEu));
+    p = __builtin_fmaf(p, r, as_f32(0x3F317215u));
+    p = __builtin_fmaf(p, r, 1.0f);
+    const float e = __builtin_ldexpf(p, (int)n);   // exact: p in [0.70, 1.42], |n| <= 125
+    const float d = 1.0f + e;
+    const float s = gn / d;
+    return s * u;
+}
+
+// The lane's 8 gate values in v become h = swiglu(v, w); with `to_bf16` (uniform) h passes
+// through bf16 (round to nearest even) as if a separate activation kernel had stored it.
+__device__ __forceinline__ void swiglu8(float (&v)[8], const float (&w)[8], bool to_bf16) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = swiglu_f32(v[i], w[i]);
+    if (to_bf16) {
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) {
+            const uint32_t pk = pack_bf16x2(v[i], v[i + 1]);
+            v[i] = bf16_lo(pk);
+            v[i + 1] = bf16_hi(pk);
+        }
+    }
+}
+
 // Maximum magnitude of the lane's 8 values.
 __device__ __forceinline__ float absmax8(const float (&y)[8]) {
     float m = fmaxf(fmaxf(fabsf(y[0]), fabsf(y[1])), fabsf(y[2]));

@@ -8,9 +8,16 @@ namespace brq {
 // mode: 0 rotate, 1 quantize, 2 fused rotate+quantize.  log2b: 0 for quantize, else 3..14.
 // tiled: codes and scales go out in the tiled operand layout instead of row-major.
 // signs: [K] sign bytes of a randomized rotation (element k negated where signs[k] < 0) or null.
+// prod: null, or the gated-activation producer in front of a quantize / fused launch: x is then
+// `gate`, prod->up the second matrix, and the kernel works on silu(gate) * up.
+struct Producer {
+    const void* up;      // [M][ldu], same element type as x
+    int64_t ldu;
+    bool through_bf16;   // the activation is rounded to bf16 before the rotation
+};
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
-                          bool tiled, const int8_t* signs, hipStream_t s);
+                          bool tiled, const int8_t* signs, const Producer* prod, hipStream_t s);
 
 // A quantized [rows][K] operand as the product kernels see it.
 struct Operand {

@@ -27,6 +27,9 @@ struct RowArgs {
     uint32_t stages;    // Kp/128, Kp = K rounded up to a multiple of 512
     uint32_t sstages;   // Kp/512
     const int8_t* signs;   // [K] or null: element k is negated on load where signs[k] < 0
+    const void* x2;        // producer kernels: the `up` matrix [M][ldx2] (x is then `gate`)
+    int64_t ldx2;
+    uint32_t hround;       // producer kernels: the activation passes through bf16
     uint32_t sign_fixed;   // the grid was sized so that a lane's column is the same in every pass
 };
 
@@ -97,6 +100,18 @@ __device__ __forceinline__ void store_chunk(void* p, const float (&v)[8]) {
     }
 }
 
+// The lane's 8 input values: the chunk at p, or (PROD) the gated activation of the chunks at p
+// (gate) and p2 (up), computed here so that it never visits HBM.
+template <bool BF16, bool PROD>
+__device__ __forceinline__ void load_input(const void* p, const void* p2, bool hround, float (&v)[8]) {
+    load_chunk<BF16>(p, v);
+    if constexpr (PROD) {
+        float w[8];
+        load_chunk<BF16>(p2, w);
+        swiglu8(v, w, hround);
+    }
+}
+
 // Element offset of chunk c.  Contiguous rows (ld == K) need no division.
 template <bool CONTIG>
 __device__ __forceinline__ int64_t chunk_offset(uint32_t c, uint32_t cpr, int64_t ld) {
@@ -148,16 +163,18 @@ __device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t row, u
     }
 }
 
-// One chunk per lane per step, U steps in flight (the launcher uses U = 1).  LOG2B = 0 means "no rotation".
-template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool CONTIG, int U>
+// One chunk per lane per step, U steps in flight (the launcher uses U = 1).  LOG2B = 0 means "no rotation":
+// the quantizer alone, or (MODE_ROTATE with a producer) the gated activation alone, stored to y.
+template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool CONTIG, int U, bool PROD>
 __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
     const uint32_t lane = threadIdx.x & 63;
+    constexpr bool ROT = MODE != MODE_QUANT && LOG2B > 0;   // LOG2B = 0 with MODE_ROTATE: the producer alone
     constexpr uint32_t inwave_bits = (LOG2B >= 3) ? ((1u << (LOG2B - 3)) - 1u) : 0u;
     const float sigma = (__builtin_popcount(lane & inwave_bits) & 1) ? -1.0f : 1.0f;
     const float cs = as_f32(norm_bits(LOG2B)) * sigma;
     const uint32_t step = gridDim.x * 256u * U;
     uint32_t sm[U][8];
-    const bool presigned = MODE != MODE_QUANT && a.signs && a.sign_fixed;   // uniform
+    const bool presigned = ROT && a.signs && a.sign_fixed;   // uniform
     if (presigned) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -172,8 +189,9 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
         for (int u = 0; u < U; ++u) {
             uint32_t c = min(bb + u * 256u + threadIdx.x, a.nchunks - 1u);
             const char* p = (const char*)a.x + chunk_offset<CONTIG>(c, a.cpr, a.ldx) * (IN_BF16 ? 2 : 4);
-            load_chunk<IN_BF16>(p, v[u]);
-            if constexpr (MODE != MODE_QUANT) {
+            const char* p2 = PROD ? (const char*)a.x2 + chunk_offset<CONTIG>(c, a.cpr, a.ldx2) * (IN_BF16 ? 2 : 4) : nullptr;
+            load_input<IN_BF16, PROD>(p, p2, a.hround != 0, v[u]);
+            if constexpr (ROT) {
                 if (presigned) {
                     flip(v[u], sm[u]);
                 } else if (a.signs) {   // uniform
@@ -192,7 +210,7 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
         for (int u = 0; u < U; ++u) {
             const uint32_t c = bb + u * 256u + threadIdx.x;
             const bool live = c < a.nchunks;
-            if constexpr (MODE != MODE_QUANT) {
+            if constexpr (ROT) {
                 wht_inwave<LOG2B>(v[u], lane);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) v[u][i] *= cs;
@@ -238,7 +256,7 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
 // stage: lane l holds chunk (l & 15) of row 4 rq + (l >> 4), reads 4 x 256 contiguous bytes and
 // writes 256 contiguous bytes of codes (two whole lines).  Every address is a wavefront-uniform
 // base plus a per-lane constant.  Rotation blocks of up to 16 chunks stay inside one row's lanes.
-template <int LOG2B, bool IN_BF16, int MODE>
+template <int LOG2B, bool IN_BF16, int MODE, bool PROD>
 __global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, uint32_t nitems) {
     static_assert(LOG2B == 0 || (LOG2B >= 3 && LOG2B <= 7), "a rotation block must fit 16 lanes");
     constexpr int ES = IN_BF16 ? 2 : 4;
@@ -254,19 +272,25 @@ __global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, ui
     // Every address is a wavefront-uniform base plus a per-lane constant (the host checked that
     // 4 rows of pitch fit 32 bits): the loop body spends no vector instruction on addresses.
     const uint32_t in_lane = lrow * (uint32_t)a.ldx * ES + (lane & 15u) * (8u * ES);
+    const uint32_t in_lane2 = PROD ? lrow * (uint32_t)a.ldx2 * ES + (lane & 15u) * (8u * ES) : 0u;
     const uint32_t step = gridDim.x * 4u;
     for (uint32_t it = blockIdx.x * 4u + wave; it < nitems; it += step) {
         const uint32_t rq = it / spr, st = it - rq * spr;              // scalar
         const uint32_t row0 = rq * 4u;
         const char* rowbase = (const char*)a.x + ((uint64_t)row0 * (uint64_t)a.ldx + (uint64_t)st * 128u) * ES;   // scalar
         const char* p = rowbase + in_lane;
+        const char* p2 = nullptr;
+        if constexpr (PROD)
+            p2 = (const char*)a.x2 + ((uint64_t)row0 * (uint64_t)a.ldx2 + (uint64_t)st * 128u) * ES + in_lane2;
         if (row0 + 4u > rows) {   // uniform: M % 4 != 0, last item of a column; rows past the end
                                   // re-read the last row, their stores are masked below
             const uint32_t rrow = min(row0 + lrow, rows - 1u);
             p = (const char*)a.x + ((uint64_t)rrow * (uint64_t)a.ldx + (uint64_t)st * 128u + (lane & 15u) * 8u) * ES;
+            if constexpr (PROD)
+                p2 = (const char*)a.x2 + ((uint64_t)rrow * (uint64_t)a.ldx2 + (uint64_t)st * 128u + (lane & 15u) * 8u) * ES;
         }
         float v[8];
-        load_chunk<IN_BF16>(p, v);
+        load_input<IN_BF16, PROD>(p, p2, a.hround != 0, v);
         if constexpr (MODE != MODE_QUANT) {
             if (presigned) flip(v, sm);
             else if (a.signs) apply_signs(v, a.signs + ((size_t)st * 16u + (lane & 15u)) * 8);
@@ -292,7 +316,7 @@ __global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, ui
 // R = log2(B) - 9 stages (h = 512 ... B/2, still ascending) run as one radix-2^R pass
 // over LDS: a lane gathers the 2^R elements {g + 512 j}, does the R stages in registers
 // and scatters them back.  Then every lane re-reads its own chunks and finishes.
-template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
+template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool PROD>
 __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_per_row) {
     constexpr int B = 1 << LOG2B;
     constexpr int NT = (B / 8 < 256) ? B / 8 : 256;
@@ -305,13 +329,16 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
     const uint32_t tid = threadIdx.x, lane = tid & 63;
     const uint32_t row = blockIdx.x / blocks_per_row, blk = blockIdx.x - row * blocks_per_row;
     const int64_t xoff = (int64_t)row * a.ldx + (int64_t)blk * B;
+    const int64_t xoff2 = PROD ? (int64_t)row * a.ldx2 + (int64_t)blk * B : 0;
     const float sigma = (__builtin_popcount(lane) & 1) ? -1.0f : 1.0f;
 
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
         float v[8];
         uint32_t q = c * NT + tid;   // chunk index inside the block
-        load_chunk<IN_BF16>((const char*)a.x + (xoff + (int64_t)q * 8) * (IN_BF16 ? 2 : 4), v);
+        load_input<IN_BF16, PROD>((const char*)a.x + (xoff + (int64_t)q * 8) * (IN_BF16 ? 2 : 4),
+                                  PROD ? (const char*)a.x2 + (xoff2 + (int64_t)q * 8) * (IN_BF16 ? 2 : 4) : nullptr,
+                                  a.hround != 0, v);
         if (a.signs) apply_signs(v, a.signs + ((size_t)blk * B + (size_t)q * 8));
         wht_inwave<9>(v, lane);
 #pragma unroll
@@ -400,15 +427,16 @@ static uint32_t fix_columns(int& grid, uint32_t period, uint32_t per_wg) {
     return 1;
 }
 
-template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
+template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool PROD = false>
 static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
     if constexpr (MODE != MODE_ROTATE && LOG2B <= 7) {
-        if (a.stages != 0 && (a.cpr & 15u) == 0 && a.ldx * (IN_BF16 ? 2 : 4) * 4 < (int64_t(1) << 32)) {
+        if (a.stages != 0 && (a.cpr & 15u) == 0 && a.ldx * (IN_BF16 ? 2 : 4) * 4 < (int64_t(1) << 32) &&
+            (!PROD || a.ldx2 * (IN_BF16 ? 2 : 4) * 4 < (int64_t(1) << 32))) {
             const uint32_t rows = a.nchunks / a.cpr, nitems = ((rows + 3u) / 4u) * (a.cpr >> 4);
             int grid = rowwise_grid(nitems * 64u, 1);
             RowArgs b = a;
             b.sign_fixed = a.signs ? fix_columns(grid, a.cpr >> 4, 4) : 0;
-            hipLaunchKernelGGL((k_rowwise_t4<LOG2B, IN_BF16, MODE>), dim3(grid), dim3(256), 0, s, b, rows, nitems);
+            hipLaunchKernelGGL((k_rowwise_t4<LOG2B, IN_BF16, MODE, PROD>), dim3(grid), dim3(256), 0, s, b, rows, nitems);
             return hipGetLastError();
         }
     }
@@ -417,37 +445,37 @@ static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
     RowArgs b = a;
     b.sign_fixed = (a.signs && MODE != MODE_QUANT) ? fix_columns(grid, a.cpr, 256 * U) : 0;
     if (contig)
-        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, true, U>), dim3(grid), dim3(256), 0, s, b);
+        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, true, U, PROD>), dim3(grid), dim3(256), 0, s, b);
     else
-        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, false, U>), dim3(grid), dim3(256), 0, s, b);
+        hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, false, U, PROD>), dim3(grid), dim3(256), 0, s, b);
     return hipGetLastError();
 }
 
-template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16>
+template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool PROD = false>
 static hipError_t launch_lds(const RowArgs& a, int64_t M, int64_t K, hipStream_t s) {
     constexpr int B = 1 << LOG2B;
     constexpr int NT = (B / 8 < 256) ? B / 8 : 256;
     uint32_t bpr = (uint32_t)(K / B);
-    hipLaunchKernelGGL((k_rowwise_lds<LOG2B, IN_BF16, MODE, OUT_BF16>), dim3((uint32_t)(M * bpr)), dim3(NT),
+    hipLaunchKernelGGL((k_rowwise_lds<LOG2B, IN_BF16, MODE, OUT_BF16, PROD>), dim3((uint32_t)(M * bpr)), dim3(NT),
                        B * sizeof(float), s, a, bpr);
     return hipGetLastError();
 }
 
-template <bool IN_BF16, int MODE, bool OUT_BF16>
+template <bool IN_BF16, int MODE, bool OUT_BF16, bool PROD = false>
 static hipError_t dispatch_b(int log2b, const RowArgs& a, bool contig, int64_t M, int64_t K, hipStream_t s) {
     switch (log2b) {
-        case 3: return launch_inwave<3, IN_BF16, MODE, OUT_BF16>(a, contig, s);
-        case 4: return launch_inwave<4, IN_BF16, MODE, OUT_BF16>(a, contig, s);
-        case 5: return launch_inwave<5, IN_BF16, MODE, OUT_BF16>(a, contig, s);
-        case 6: return launch_inwave<6, IN_BF16, MODE, OUT_BF16>(a, contig, s);
-        case 7: return launch_inwave<7, IN_BF16, MODE, OUT_BF16>(a, contig, s);
-        case 8: return launch_inwave<8, IN_BF16, MODE, OUT_BF16>(a, contig, s);
-        case 9: return launch_inwave<9, IN_BF16, MODE, OUT_BF16>(a, contig, s);
-        case 10: return launch_lds<10, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
-        case 11: return launch_lds<11, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
-        case 12: return launch_lds<12, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
-        case 13: return launch_lds<13, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
-        case 14: return launch_lds<14, IN_BF16, MODE, OUT_BF16>(a, M, K, s);
+        case 3: return launch_inwave<3, IN_BF16, MODE, OUT_BF16, PROD>(a, contig, s);
+        case 4: return launch_inwave<4, IN_BF16, MODE, OUT_BF16, PROD>(a, contig, s);
+        case 5: return launch_inwave<5, IN_BF16, MODE, OUT_BF16, PROD>(a, contig, s);
+        case 6: return launch_inwave<6, IN_BF16, MODE, OUT_BF16, PROD>(a, contig, s);
+        case 7: return launch_inwave<7, IN_BF16, MODE, OUT_BF16, PROD>(a, contig, s);
+        case 8: return launch_inwave<8, IN_BF16, MODE, OUT_BF16, PROD>(a, contig, s);
+        case 9: return launch_inwave<9, IN_BF16, MODE, OUT_BF16, PROD>(a, contig, s);
+        case 10: return launch_lds<10, IN_BF16, MODE, OUT_BF16, PROD>(a, M, K, s);
+        case 11: return launch_lds<11, IN_BF16, MODE, OUT_BF16, PROD>(a, M, K, s);
+        case 12: return launch_lds<12, IN_BF16, MODE, OUT_BF16, PROD>(a, M, K, s);
+        case 13: return launch_lds<13, IN_BF16, MODE, OUT_BF16, PROD>(a, M, K, s);
+        case 14: return launch_lds<14, IN_BF16, MODE, OUT_BF16, PROD>(a, M, K, s);
         default: return hipErrorInvalidValue;
     }
 }
@@ -470,8 +498,11 @@ __global__ void __launch_bounds__(256) k_zero_kpad(uint8_t* __restrict__ codes, 
 // mode: RowMode; log2b: 0 for MODE_QUANT, else 3..14.  Arguments are already validated.
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
-                          bool tiled, const int8_t* signs, hipStream_t s) {
+                          bool tiled, const int8_t* signs, const Producer* prod, hipStream_t s) {
     RowArgs a;
+    a.x2 = prod ? prod->up : nullptr;
+    a.ldx2 = prod ? prod->ldu : 0;
+    a.hround = (prod && prod->through_bf16) ? 1u : 0u;
     a.signs = signs;
     a.sign_fixed = 0;
     a.x = x; a.y = y; a.codes = reinterpret_cast<uint32_t*>(codes); a.scales = scales;
@@ -479,7 +510,7 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
     const int64_t Kp = (K + 511) / 512 * 512;
     a.stages = tiled ? (uint32_t)(Kp / 128) : 0u;
     a.sstages = tiled ? (uint32_t)(Kp / 512) : 0u;
-    bool contig = (ldx == K) && (mode != MODE_ROTATE || ldy == K);
+    bool contig = (ldx == K) && (mode != MODE_ROTATE || ldy == K) && (!prod || prod->ldu == K);
     if (tiled && Kp != K && mode != MODE_ROTATE) {
         const uint32_t gpad = (uint32_t)((Kp - K) / 32);
         const int64_t want = (M * gpad + 255) / 256;
@@ -488,11 +519,24 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    if (prod && mode == MODE_ROTATE) {   // the activation alone, written to y (log2b = 0)
+        if (in_bf16) return out_bf16 ? launch_inwave<0, true, MODE_ROTATE, true, true>(a, contig, s)
+                                     : launch_inwave<0, true, MODE_ROTATE, false, true>(a, contig, s);
+        return out_bf16 ? launch_inwave<0, false, MODE_ROTATE, true, true>(a, contig, s)
+                        : launch_inwave<0, false, MODE_ROTATE, false, true>(a, contig, s);
+    }
     if (mode == MODE_ROTATE) {
         if (in_bf16) return out_bf16 ? dispatch_b<true, MODE_ROTATE, true>(log2b, a, contig, M, K, s)
                                      : dispatch_b<true, MODE_ROTATE, false>(log2b, a, contig, M, K, s);
         return out_bf16 ? dispatch_b<false, MODE_ROTATE, true>(log2b, a, contig, M, K, s)
                         : dispatch_b<false, MODE_ROTATE, false>(log2b, a, contig, M, K, s);
+    }
+    if (prod) {   // gated-activation producer in front of the quantizer / the fused step
+        if (mode == MODE_QUANT)
+            return in_bf16 ? launch_inwave<0, true, MODE_QUANT, false, true>(a, contig, s)
+                           : launch_inwave<0, false, MODE_QUANT, false, true>(a, contig, s);
+        return in_bf16 ? dispatch_b<true, MODE_FUSED, false, true>(log2b, a, contig, M, K, s)
+                       : dispatch_b<false, MODE_FUSED, false, true>(log2b, a, contig, M, K, s);
     }
     if (mode == MODE_QUANT)
         return in_bf16 ? launch_inwave<0, true, MODE_QUANT, false>(a, contig, s)

@@ -56,6 +56,17 @@ def test_argument_errors_before_any_launch(L):
     assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, None, q(p), None, 0, None) == NULL
     assert L.brq_block_rotate(q(p), 1, 4, 64, 64, 32, None, None, 0, 64, None) == NULL
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), None, 0, 4, 4, 64, q(p), 0, 4, None) == NULL
+    # the producer calls: (gate, up, xdt, M, K, ldg, ldu, ...)
+    assert L.brq_swiglu(q(p), None, 1, 4, 64, 64, 64, q(p), 0, 64, None) == NULL
+    assert L.brq_swiglu(q(p), q(p), 1, 4, 64, 64, 32, q(p), 0, 64, None) == SHAPE            # ldu < K
+    assert L.brq_swiglu(q(p), q(p), 1, 4, 64, 64, 64, q(p), 9, 64, None) == DTYPE
+    assert L.brq_swiglu_rotate_quantize_fused(q(p), None, 1, 4, 64, 64, 64, 1, 32, None, q(p), q(p), 0, None) == NULL
+    assert L.brq_swiglu_rotate_quantize_fused(q(p), q(p + 2), 1, 4, 64, 64, 64, 1, 32, None, q(p), q(p), 0, None) == ALIGN
+    assert L.brq_swiglu_rotate_quantize_fused(q(p), q(p), 1, 4, 64, 64, 64, 7, 32, None, q(p), q(p), 0, None) == DTYPE
+    assert L.brq_swiglu_rotate_quantize_fused(q(p), q(p), 1, 4, 64, 64, 64, 1, 24, None, q(p), q(p), 0, None) == BLOCK
+    assert L.brq_swiglu_rotate_quantize_fused(q(p), q(p), 1, 4, 64, 64, 64, 1, 1, q(p), q(p), q(p), 0, None) == BLOCK   # signs, no rotation
+    assert L.brq_swiglu_rotate_quantize_fused(q(p), q(p), 1, 4, 64, 64, 64, 1, 32, None, q(p), q(p), 5, None) == LAYOUT
+    assert L.brq_swiglu_rotate_quantize_fused(None, None, 1, 0, 64, 64, 64, 1, 32, None, None, None, 0, None) == OK     # empty
     # shapes
     assert L.brq_mxfp4_quantize(q(p), 1, 4, 48, 48, q(p), q(p), 0, None) == SHAPE      # K % 32
     assert L.brq_mxfp4_quantize(q(p), 1, 4, 64, 32, q(p), q(p), 0, None) == SHAPE      # ldx < K
