@@ -126,8 +126,11 @@ brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, in
  *     n = z rounded to the nearest integer, ties to even;  r = z - n
  *     p = fma(fma(fma(fma(fma(c5, r, c4), r, c3), r, c2), r, c1), r, 1)
  *         c1..c5 = 0x3F317215, 0x3E75FCDE, 0x3D635BA9, 0x3C1E753D, 0x3AADDCFA   (2^r on [-1/2, 1/2])
- *     e = p * 2^n (exact);  d = 1 + e;  s = gn / d;  h = s * u
- * |h - silu(g) u| <= (5 + 1.25 |g|) 2^-24 |silu(g) u| for |g| <= 86; below -86 silu is held at
+ *     e = p * 2^n (exact);  d = 1 + e
+ *     y = 1/d by Newton: y0 = the fp32 with bit pattern 0x7EF311C7 - bits(d), then three times
+ *         t = fma(-d, y, 1), y = fma(y, t, y)
+ *     s = gn * y;  h = s * u
+ * |h - silu(g) u| <= (6 + 1.25 |g|) 2^-24 |silu(g) u| for |g| <= 86; below -86 silu is held at
  * silu(-86) ~ -4e-36.  hdt = BRQ_BF16 rounds h to bf16 (nearest even) before the rotation, which
  * reproduces a separate activation kernel that stores bf16; BRQ_F32 keeps the fp32 value.
  * gate [M][ldg], up [M][ldu], both of xdt (they may be two halves of one buffer).

@@ -112,8 +112,11 @@ __device__ __forceinline__ void wht_cross_quad(float (&v)[8], float s1, float s2
 // compared bit for bit, so this is the fixed fp32 operation sequence that brq.h defines for
 // brq_swiglu_rotate_quantize_fused, one IEEE operation per step: clamp, z = g * -log2(e),
 // n = rint(z), r = z - n, a degree-5 polynomial of 2^r by fused multiply-adds, e = p * 2^n,
-// d = 1 + e, s = g / d (correctly rounded division), h = s * u.  No hardware approximation
-// (v_exp_f32, v_rcp_f32) takes part: their last bits are not reproducible elsewhere.
+// d = 1 + e, y = 1/d by three Newton steps from a bit-pattern seed, s = g * y, h = s * u.  No
+// hardware approximation (v_exp_f32, v_rcp_f32) takes part: their last bits are not
+// reproducible elsewhere; and the correctly rounded division (v_div_scale / v_rcp / fixups, 14
+// issue slots) is replaced by the 8-slot Newton reciprocal, on a kernel that this arithmetic
+// bounds.
 // The clamps are written as instructions: the compiler would put a canonicalising
 // v_max_f32 x, x, x in front of fmaxf/fminf on values it cannot prove to be quiet.
 __device__ __forceinline__ float swiglu_f32(float g, float u) {
@@ -131,7 +134,13 @@ __device__ __forceinline__ float swiglu_f32(float g, float u) {
     p = __builtin_fmaf(p, r, 1.0f);
     const float e = __builtin_ldexpf(p, (int)n);   // exact: p in [0.70, 1.42], |n| <= 125
     const float d = 1.0f + e;
-    const float s = gn / d;
+    float y = as_f32(0x7EF311C7u - as_u32(d));   // within 5.1% of 1/d for d >= 1
+#pragma unroll
+    for (int it = 0; it < 3; ++it) {
+        const float t = __builtin_fmaf(-d, y, 1.0f);
+        y = __builtin_fmaf(y, t, y);
+    }
+    const float s = gn * y;
     return s * u;
 }
 

@@ -104,10 +104,25 @@ __device__ __forceinline__ void store_chunk(void* p, const float (&v)[8]) {
 // (gate) and p2 (up), computed here so that it never visits HBM.
 template <bool BF16, bool PROD>
 __device__ __forceinline__ void load_input(const void* p, const void* p2, bool hround, float (&v)[8]) {
-    load_chunk<BF16>(p, v);
-    if constexpr (PROD) {
+    if constexpr (!PROD) {
+        load_chunk<BF16>(p, v);
+    } else if constexpr (BF16) {
+        // both loads first, then the arithmetic
+        const v4i a = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
+        const v4i b = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p2));
         float w[8];
-        load_chunk<BF16>(p2, w);
+        v[0] = bf16_lo((uint32_t)a.x); v[1] = bf16_hi((uint32_t)a.x); v[2] = bf16_lo((uint32_t)a.y); v[3] = bf16_hi((uint32_t)a.y);
+        v[4] = bf16_lo((uint32_t)a.z); v[5] = bf16_hi((uint32_t)a.z); v[6] = bf16_lo((uint32_t)a.w); v[7] = bf16_hi((uint32_t)a.w);
+        w[0] = bf16_lo((uint32_t)b.x); w[1] = bf16_hi((uint32_t)b.x); w[2] = bf16_lo((uint32_t)b.y); w[3] = bf16_hi((uint32_t)b.y);
+        w[4] = bf16_lo((uint32_t)b.z); w[5] = bf16_hi((uint32_t)b.z); w[6] = bf16_lo((uint32_t)b.w); w[7] = bf16_hi((uint32_t)b.w);
+        swiglu8(v, w, hround);
+    } else {
+        const v4f a0 = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+        const v4f a1 = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p) + 1);
+        const v4f b0 = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p2));
+        const v4f b1 = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p2) + 1);
+        const float w[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+        v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
         swiglu8(v, w, hround);
     }
 }

@@ -49,7 +49,9 @@ MUTANTS = [
      "int rc = oracle_block_rotate_signed(x, xdt, M, K, ldx, B, NULL, y, ORACLE_F32, K);"),
     ("swiglu_exp_sign", "const float neg_log2e = -f32_from_bits(0x3FB8AA3Bu);", "const float neg_log2e = f32_from_bits(0x3FB8AA3Bu);"),
     ("swiglu_forgets_up", "return s * u;", "return s;"),
-    ("swiglu_numerator_clamped_above", "float s = gn / d;", "float s = ge / d;"),
+    ("swiglu_numerator_clamped_above", "float s = gn * y;", "float s = ge * y;"),
+    ("swiglu_two_newton_steps", "for (int it = 0; it < 3; ++it) {", "for (int it = 0; it < 2; ++it) {"),
+    ("swiglu_newton_sign", "float t = fmaf(-d, y, 1.0f);", "float t = fmaf(d, y, 1.0f);"),
     ("swiglu_no_lower_clamp", "float gn = g > -86.0f ? g : -86.0f;", "float gn = g;"),
     ("swiglu_poly_drops_top_term", "float p = c5;", "float p = 0.0f;"),
     ("swiglu_poly_wrong_linear_term", "p = fmaf(p, r, c1);", "p = fmaf(p, r, 1.0f);"),
