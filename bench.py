@@ -6,7 +6,8 @@ already resident in HBM: fused block rotation + MXFP4 quantization of X (B = 32)
 W4A4 product against weights that were rotated and quantized offline.  The default
 workload is the 8B-shaped MLP layer (X 8192x4096 bf16, W 14336x4096), the largest product
 shape, which the MFMA target is quoted on; the HBM target of the rotate+quantize kernel is
-quoted on X 16384x8192, measured in the same run and reported under "rotate_quant_16384x8192".
+quoted on X 16384x8192, measured in the same run and reported under "rotate_quant_16384x8192";
+"swiglu_rotate_quant_8192x14336" is the same online step with its producer (silu(gate) * up) fused in.
 
 Prints ONE JSON line.
   value        whole-step throughput: 2*M*N*K useful flops of the layer per second of step
@@ -32,6 +33,13 @@ BYTES_PER_ELEM = 2 + 0.5 + 1.0 / 32     # bf16 in, 4-bit code out, one scale byt
 # Bytes per launch that leave the L2s (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, scaled by a plain copy
 # of known size), from the committed counter summary under profiles/; a counter run is not part of a
 # bench run, so other workloads (and the row-major layout) report null.
+VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3: one fp32 lane-operation per lane and cycle, 256 CUs x 4
+                                               # SIMDs x 16 lanes at 2.4 GHz (the 157.3 TFLOP/s figure counts an
+                                               # FMA as two and packed fp32 as two more; packed fp32 is not used)
+# fp32 lane-operations per element of the SwiGLU-fused online step, bf16 in, B = 32, activation through bf16:
+# 2 widenings, 22 of the activation's fixed sequence, 1.5 bf16 rounding, 5 butterfly stages + 1 normalisation,
+# 2.5 group maximum / scale / encode / zero fix
+SWIGLU_FUSED_OPS_PER_ELEM = 34.0
 PROFILED_TRAFFIC = {"mxfp4_gemm_mlp8b_bf16": 616.2e6, "rotate_quant_16384x8192": 339.7e6}
 
 
@@ -259,6 +267,54 @@ def main():
                "traffic": PROFILED_TRAFFIC["rotate_quant_16384x8192"] if LAY == "tiled" else None}
         del axs, ac, asc
 
+    # ---- the online step with its producer fused in: silu(gate) * up -> rotation -> MXFP4 on the
+    # down_proj input of the 8B MLP (8192 tokens x 14336), against the two-kernel path
+    aux2 = None
+    if not args.no_aux:
+        sM, sK = 8192, 14336
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(7)
+        gus = [(torch.randn((sM, 2 * sK), device="cuda", generator=gen) * 1.5).to(torch.bfloat16) for _ in range(2)]
+        scb, ssb = brq.operand_bytes(sM, sK, LAY)
+        sc = [torch.empty((sM, sK // 2) if LAY == "rowmajor" else (scb,), dtype=torch.uint8, device="cuda") for _ in range(2)]
+        ss = [torch.empty((sM, sK // 32) if LAY == "rowmajor" else (ssb,), dtype=torch.uint8, device="cuda") for _ in range(2)]
+        hbuf = torch.empty((sM, sK), dtype=torch.bfloat16, device="cuda")
+
+        def fused(i):
+            g = gus[i % 2]
+            brq.swiglu_rotate_quantize_fused(g[:, :sK], g[:, sK:], B, h_dtype=torch.bfloat16, codes=sc[i % 2],
+                                             scales=ss[i % 2], stream=stream, layout=LAY)
+
+        def two_kernels(i):
+            g = gus[i % 2]
+            brq.swiglu(g[:, :sK], g[:, sK:], out=hbuf, stream=stream)
+            brq.rotate_quantize_fused(hbuf, B, codes=sc[i % 2], scales=ss[i % 2], stream=stream, layout=LAY)
+
+        res = {}
+        for name, fn in (("fused", fused), ("two_kernels", two_kernels)):
+            for i in range(100):
+                fn(i)
+            stream.synchronize()
+            ts = []
+            for _ in range(5):
+                a, b = ev(), ev()
+                a.record(stream)
+                for i in range(args.steps):
+                    fn(i)
+                b.record(stream)
+                stream.synchronize()
+                ts.append(a.elapsed_time(b) / args.steps)
+            res[name] = float(np.mean(ts))
+        sb_ = sM * sK * (4 + 0.5 + 1.0 / 32)
+        ops = sM * sK * SWIGLU_FUSED_OPS_PER_ELEM
+        aux2 = {"kernel": "swiglu_rotate_quantize_fused", "shape": "gate, up 8192x14336 bf16 (one 8192x28672 buffer)",
+                "bound": "alu", "avg_ms": res["fused"], "ops_per_elem": SWIGLU_FUSED_OPS_PER_ELEM,
+                "achieved": ops / res["fused"] / 1e9, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s",
+                "frac": ops / res["fused"] / 1e9 / VALU_PEAK_TOPS,
+                "alg_bytes": sb_, "GB/s": sb_ / res["fused"] / 1e6, "frac_hbm_peak": sb_ / res["fused"] / 1e6 / HBM_PEAK_GBS,
+                "two_kernel_path_ms": res["two_kernels"], "traffic": None}
+        del gus, sc, ss, hbuf
+
     if args.calibrate_copy:
         src = torch.full((256 << 20,), 7, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -321,6 +377,7 @@ def main():
         "mfma_loop_ceiling": ceiling,
         "library_baseline": library,
         "rotate_quant_16384x8192": aux,
+        "swiglu_rotate_quant_8192x14336": aux2,
         "kernels": kernels,
         "cpu_baseline": cpu_baseline,
     }
