@@ -62,6 +62,9 @@ def _bind(path):
     L.oracle_swiglu_elem.restype = ctypes.c_float
     L.oracle_swiglu.argtypes = [vp, vp, i32, i64, i64, i64, i64, vp, i32, i64]
     L.oracle_swiglu_rotate_quantize_fused.argtypes = [vp, vp, i32, i64, i64, i64, i64, i32, i64, vp, vp, vp]
+    L.oracle_matrix_rotate_f64.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
+    L.oracle_matrix_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
+    L.oracle_mxfp4_encode_with_scales.argtypes = [vp, vp, i64, i64, vp]
     L.oracle_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, vp]
     L.oracle_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_matmul_nt_f64.argtypes = [vp, vp, i64, i64, i64, vp]
@@ -211,6 +214,42 @@ class Oracle:
                                                           None if sg is None else _p(sg), _p(codes), _p(scales)),
                "swiglu_rotate_quantize_fused")
         return codes, scales
+
+    @staticmethod
+    def _blocks(R, K):
+        R = np.ascontiguousarray(R, dtype=np.float32)
+        if R.ndim == 2:
+            R = R[None]
+        if R.shape[1:] != (32, 32) or R.shape[0] not in (1, K // 32):
+            raise ValueError("R must be [32, 32] or [K/32, 32, 32]")
+        return R
+
+    def matrix_rotate_f64(self, x, R, want_bound=False):
+        """y = x diag(R_1..R_n) in fp64 (R[b][i][j]: input i -> output j); optionally sum |x||R|."""
+        x, M, K, ldx = _rows(x)
+        R = self._blocks(R, K)
+        y = np.empty((M, K), dtype=np.float64)
+        bound = np.empty((M, K), dtype=np.float64) if want_bound else None
+        _check(self.L.oracle_matrix_rotate_f64(_p(x), _dt(x), M, K, ldx, _p(R), R.shape[0], _p(y),
+                                               _p(bound) if want_bound else None), "matrix_rotate_f64")
+        return (y, bound) if want_bound else y
+
+    def matrix_rotate_quantize_fused(self, x, R):
+        x, M, K, ldx = _rows(x)
+        R = self._blocks(R, K)
+        codes = np.empty((M, K // 2), dtype=np.uint8)
+        scales = np.empty((M, K // 32), dtype=np.uint8)
+        _check(self.L.oracle_matrix_rotate_quantize_fused(_p(x), _dt(x), M, K, ldx, _p(R), R.shape[0], _p(codes),
+                                                          _p(scales)), "matrix_rotate_quantize_fused")
+        return codes, scales
+
+    def mxfp4_encode_with_scales(self, y, scales):
+        y = np.ascontiguousarray(y, dtype=np.float32)
+        scales = np.ascontiguousarray(scales, dtype=np.uint8)
+        M, K = y.shape
+        codes = np.empty((M, K // 2), dtype=np.uint8)
+        _check(self.L.oracle_mxfp4_encode_with_scales(_p(y), _p(scales), M, K, _p(codes)), "mxfp4_encode_with_scales")
+        return codes
 
     def mxfp4_dequantize(self, codes, scales):
         codes = np.ascontiguousarray(codes, dtype=np.uint8)

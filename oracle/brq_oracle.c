@@ -20,6 +20,8 @@
  *   - Sec. 4.3 ("reduced online computing"): the online rotation sits in front of down_proj,
  *     whose input in the evaluated LLaMA models is silu(gate) * up; oracle_swiglu* produce
  *     that input and feed it to the same rotation and quantizer.
+ *   - Eq. (1) with arbitrary orthogonal 32 x 32 blocks (oracle_matrix_rotate*): the dense
+ *     per-block product in fp64.
  *   - Sec. 2 ("equivalent transformations"): Y = (X R)(W R)^T = X W^T, evaluated on the
  *     quantized operands: Y[m][n] = sum_k deq(A)[m][k] * deq(W)[n][k].
  *
@@ -402,6 +404,71 @@ int oracle_swiglu_rotate_quantize_fused(const void *gate, const void *up, int dt
     }
     free(h);
     return rc;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Block rotation with arbitrary orthogonal blocks (Eq. (1): R_block = diag(R_1, ..., R_n) with
+ * every R_i an orthogonal 32 x 32 matrix; the conclusion names learned block rotations for the
+ * online step as the next thing to try).  The definition written out, in fp64:
+ *     y[r][32 b + j] = sum_i x[r][32 b + i] * R[b][i][j]
+ * R: [nR][32][32] fp32, nR = K/32 (one matrix per block) or 1 (the same matrix for every block).
+ * bound (optional): sum_i |x_i| |R_ij|, the scale of the rounding error of any evaluation.
+ * ---------------------------------------------------------------------------------- */
+int oracle_matrix_rotate_f64(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx, const float *R,
+                             int64_t nR, double *y, double *bound) {
+    if (!x || !R || !y || K % 32 || ldx < K || (nR != 1 && nR != K / 32)) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; ++r) {
+        for (int64_t b = 0; b < K / 32; ++b) {
+            const float *Rb = R + (nR == 1 ? 0 : b) * 1024;
+            for (int j = 0; j < 32; ++j) {
+                double acc = 0.0, mag = 0.0;
+                for (int i = 0; i < 32; ++i) {
+                    double xv = (double)load_elem(x, xdt, r * ldx + b * 32 + i);
+                    double rv = (double)Rb[i * 32 + j];
+                    acc += xv * rv;
+                    mag += fabs(xv) * fabs(rv);
+                }
+                y[r * K + b * 32 + j] = acc;
+                if (bound) bound[r * K + b * 32 + j] = mag;
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* The online step with such blocks: quantize(fl32(y)), y as above.  The rotated value is the
+ * exact one rounded once to fp32; an implementation that sums in fp32 lands within a few ulp
+ * of it, and the parity tests allow for exactly that (codes are checked against the interval
+ * that the error bound leaves open, not for equality). */
+int oracle_matrix_rotate_quantize_fused(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx,
+                                        const float *R, int64_t nR, uint8_t *codes, uint8_t *scales) {
+    if (!codes || !scales) return ORACLE_ERR_ARG;
+    size_t n = (size_t)(M > 0 ? M : 1) * (size_t)K;
+    double *y = (double *)malloc(n * sizeof(double));
+    float *yf = (float *)malloc(n * sizeof(float));
+    int rc = (y && yf) ? oracle_matrix_rotate_f64(x, xdt, M, K, ldx, R, nR, y, NULL) : ORACLE_ERR_ARG;
+    if (rc == ORACLE_OK) {
+        for (int64_t i = 0; i < M * K; ++i) yf[i] = (float)y[i];
+        rc = oracle_mxfp4_quantize(yf, ORACLE_F32, M, K, K, codes, scales);
+    }
+    free(y);
+    free(yf);
+    return rc;
+}
+
+/* Codes of y [M][K] fp32 under GIVEN scale bytes [M][K/32] (the element rule alone; used to ask
+ * which codes a value interval allows under the scale an implementation chose). */
+int oracle_mxfp4_encode_with_scales(const float *y, const uint8_t *scales, int64_t M, int64_t K, uint8_t *codes) {
+    if (!y || !scales || !codes || K % 32) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; ++r)
+        for (int64_t j = 0; j < K / 2; ++j) {
+            uint8_t sb = scales[r * (K / 32) + j / 16];
+            uint8_t lo = oracle_e2m1_encode(y[r * K + 2 * j], sb), hi = oracle_e2m1_encode(y[r * K + 2 * j + 1], sb);
+            codes[r * (K / 2) + j] = (uint8_t)((hi << 4) | lo); /* element 2j in the low nibble */
+        }
+    return ORACLE_OK;
 }
 
 /* deq[r][k] = value(code) * 2^(scale - 127), fp64 (exact). */

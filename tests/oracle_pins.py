@@ -438,6 +438,88 @@ def pin_swiglu_fused_is_the_composition(o):
                               o.swiglu_rotate_quantize_fused(big_g, big_u, 32, h_bf16=True)[0])
 
 
+# --------------------------------------------------------------------------- arbitrary orthogonal blocks
+
+def _random_orthogonal_blocks(rng, n):
+    q = np.stack([np.linalg.qr(rng.standard_normal((32, 32)))[0] for _ in range(n)])
+    return q.astype(np.float32)
+
+
+def pin_matrix_rotation_is_the_per_block_product(o):
+    # Eq. (1) with arbitrary blocks: y_b = x_b R_b.  numpy's matmul per block (a library routine
+    # the oracle does not call) on non-symmetric, per-block different matrices: a transposed R, a
+    # wrong block or a wrong pitch all show.
+    rng = np.random.default_rng(41)
+    M, K = 7, 128
+    wide = (rng.standard_t(4, size=(M, K + 32)) * 2).astype(np.float32)
+    x = wide[:, :K]                                   # pitch K + 32
+    R = rng.standard_normal((K // 32, 32, 32)).astype(np.float32)
+    y, bound = o.matrix_rotate_f64(x, R, want_bound=True)
+    want = np.concatenate([np.float64(x[:, 32 * b:32 * b + 32]) @ np.float64(R[b]) for b in range(K // 32)], axis=1)
+    mag = np.concatenate([np.abs(np.float64(x[:, 32 * b:32 * b + 32])) @ np.abs(np.float64(R[b])) for b in range(K // 32)], axis=1)
+    assert np.allclose(y, want, rtol=0, atol=1e-13 * mag.max())
+    assert np.allclose(bound, mag, rtol=1e-14)
+    # one shared matrix = that matrix repeated
+    y1 = o.matrix_rotate_f64(x, R[2])
+    assert np.array_equal(y1, o.matrix_rotate_f64(x, np.repeat(R[2:3], K // 32, axis=0)))
+    assert not np.array_equal(y1, y)
+    # identity and a signed permutation are exact
+    assert np.array_equal(o.matrix_rotate_f64(x, np.eye(32, dtype=np.float32)), np.float64(x))
+    perm = rng.permutation(32)
+    sgn = rng.choice([-1.0, 1.0], size=32)
+    P = np.zeros((32, 32), dtype=np.float32)
+    P[perm, np.arange(32)] = sgn                      # output j takes input perm[j], times sgn[j]
+    yp = o.matrix_rotate_f64(x, P)
+    for b in range(K // 32):
+        assert np.array_equal(yp[:, 32 * b:32 * b + 32], np.float64(x[:, 32 * b:32 * b + 32])[:, perm] * sgn)
+    # the Hadamard block is one such R: same result as the dense Hadamard rotation (R holds the
+    # fp32 rounding of 1/sqrt(32), hence the 1e-7)
+    H = (scipy.linalg.hadamard(32) / math.sqrt(32)).astype(np.float32)
+    assert np.allclose(o.matrix_rotate_f64(x, H), o.rotate_dense_f64(np.float64(x), 32), rtol=0, atol=1e-6)
+    # orthogonal blocks preserve the norm of every block, and the product X W^T (Sec. 2)
+    Q = _random_orthogonal_blocks(rng, K // 32)
+    yq = o.matrix_rotate_f64(x, Q)
+    for b in range(K // 32):
+        assert np.allclose(np.linalg.norm(yq[:, 32 * b:32 * b + 32], axis=1),
+                           np.linalg.norm(np.float64(x[:, 32 * b:32 * b + 32]), axis=1), rtol=1e-5)
+    w = (rng.standard_normal((5, K)) * 0.02).astype(np.float32)
+    assert np.allclose(yq @ o.matrix_rotate_f64(w, Q).T, np.float64(x) @ np.float64(w).T, rtol=0, atol=1e-5)
+
+
+def pin_matrix_rotation_fused_and_encode_with_scales(o):
+    rng = np.random.default_rng(42)
+    M, K = 6, 96
+    x = (rng.standard_t(4, size=(M, K)) * 3).astype(np.float32)
+    Q = _random_orthogonal_blocks(rng, K // 32)
+    c, s = o.matrix_rotate_quantize_fused(x, Q)
+    c2, s2 = o.mxfp4_quantize(np.float32(o.matrix_rotate_f64(x, Q)))
+    assert np.array_equal(c, c2) and np.array_equal(s, s2)
+    assert not np.array_equal(c, o.mxfp4_quantize(x)[0])
+    # a signed permutation only moves and flips the codes of the plain quantizer inside each group
+    perm = rng.permutation(32)
+    sgn = rng.choice([-1.0, 1.0], size=32)
+    P = np.zeros((32, 32), dtype=np.float32)
+    P[perm, np.arange(32)] = sgn
+    cp, sp = o.matrix_rotate_quantize_fused(x, P)
+    xp = np.concatenate([x[:, 32 * b:32 * b + 32][:, perm] * np.float32(sgn) for b in range(K // 32)], axis=1)
+    cq, sq = o.mxfp4_quantize(np.ascontiguousarray(xp, dtype=np.float32))
+    assert np.array_equal(cp, cq) and np.array_equal(sp, sq) and np.array_equal(sp, o.mxfp4_quantize(x)[1])
+    # encode under given scales: the quantizer's own scales give its codes back; every
+    # representable value under any scale returns its own code (table from the golden file)
+    assert np.array_equal(o.mxfp4_encode_with_scales(xp, sq), cq)
+    g = golden_e2m1()
+    for sb in (100, 127, 140):
+        vals = np.array([[g[cde] * 2.0 ** (sb - 127) for cde in range(16)] * 2], dtype=np.float32)
+        got = _unpack(o.mxfp4_encode_with_scales(vals, np.array([[sb]], dtype=np.uint8)))[0]
+        want = np.array(list(range(16)) * 2)
+        want[want == 8] = 0                           # a zero magnitude is code 0 whatever the sign
+        assert np.array_equal(got, want)
+    # the scale byte is looked up per group of 32, not per row
+    two = np.concatenate([np.full((1, 32), 1.0, np.float32), np.full((1, 32), 4.0, np.float32)], axis=1)
+    got = _unpack(o.mxfp4_encode_with_scales(two, np.array([[127, 129]], dtype=np.uint8)))[0]
+    assert (got == 2).all()
+
+
 # --------------------------------------------------------------------------- product
 
 def pin_equivalent_transformation(o):

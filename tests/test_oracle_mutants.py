@@ -61,6 +61,14 @@ MUTANTS = [
     ("swiglu_fused_never_rotates", "        if (B == 1)\n            rc = signs ?", "        if (B >= 1)\n            rc = signs ?"),
     ("swiglu_fused_drops_signs", "rc = oracle_rotate_quantize_fused_signed(h, ORACLE_F32, M, K, K, B, signs, codes, scales);",
      "rc = oracle_rotate_quantize_fused_signed(h, ORACLE_F32, M, K, K, B, NULL, codes, scales);"),
+    ("matrot_transposed", "double rv = (double)Rb[i * 32 + j];", "double rv = (double)Rb[j * 32 + i];"),
+    ("matrot_always_first_block", "const float *Rb = R + (nR == 1 ? 0 : b) * 1024;", "const float *Rb = R;"),
+    ("matrot_block_pitch", "const float *Rb = R + (nR == 1 ? 0 : b) * 1024;", "const float *Rb = R + (nR == 1 ? 0 : b) * 32;"),
+    ("matrot_bound_without_abs", "mag += fabs(xv) * fabs(rv);", "mag += xv * rv;"),
+    ("matrot_fused_skips_rotation", "for (int64_t i = 0; i < M * K; ++i) yf[i] = (float)y[i];",
+     "for (int64_t i = 0; i < M * K; ++i) yf[i] = load_elem(x, xdt, (i / K) * ldx + i % K);"),
+    ("encode_nibbles_swapped", "(uint8_t)((hi << 4) | lo);", "(uint8_t)((lo << 4) | hi);"),
+    ("encode_scale_per_row", "uint8_t sb = scales[r * (K / 32) + j / 16];", "uint8_t sb = scales[r * (K / 32)];"),
     ("fused_skips_rotation", "if (rc == ORACLE_OK) rc = oracle_mxfp4_quantize(y, ORACLE_F32, M, K, K, codes, scales);",
      "rc = oracle_mxfp4_quantize(x, xdt, M, K, ldx, codes, scales);"),
 ]
