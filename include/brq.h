@@ -152,6 +152,34 @@ brq_status brq_swiglu_rotate_quantize_fused(const void* gate, const void* up, br
                                             void* stream);
 
 /*
+ * Block rotation with caller-supplied blocks (Sec. 4.3, Eq. 1 as written: R_block =
+ * diag(R_1, ..., R_n) with every R_i an orthogonal 32 x 32 matrix; the Hadamard block of
+ * brq_block_rotate is one choice, learned blocks are what the conclusion proposes for the
+ * online step):      y[m][32 b + j] = sum_i x[m][32 b + i] * R[b][i][j].
+ * R: device pointer, [nR][32][32] fp32, nR = K/32 (one matrix per block) or 1 (shared).
+ * Orthogonality is the caller's business; any matrix is multiplied as given.
+ * Arithmetic: on the matrix cores, with R (and fp32 x) split into three bf16 parts and the
+ * partial products accumulated in fp32: |y - exact| <= 2^-20 * sum_i |x_i| |R_ij|.  The order of
+ * the additions is the hardware's, so unlike brq_block_rotate the last bits are not defined
+ * here; ydt = BRQ_BF16 stores the round-to-nearest-even of the fp32 result.
+ * K % 128 == 0.  x [M][ldx] of xdt, y [M][ldy] of ydt, no overlap.
+ */
+brq_status brq_matrix_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx,
+                             const float* R, int64_t nR, void* y, brq_dtype ydt, int64_t ldy,
+                             void* stream);
+
+/*
+ * The online step with such blocks: brq_mxfp4_quantize(brq_matrix_rotate(x, R) kept in fp32) in
+ * one pass over x.  Codes and scales are those of a rotated value within the error bound above:
+ * they equal the codes of the exact rotation except where that value lies within the bound of a
+ * rounding boundary of the encoder (or the group maximum within it of a power of two).
+ */
+brq_status brq_matrix_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K,
+                                            int64_t ldx, const float* R, int64_t nR,
+                                            uint8_t* codes, uint8_t* scales, brq_layout layout,
+                                            void* stream);
+
+/*
  * W4A4 product on MXFP4 operands (Sec. 2; Sec. 4.1 "scaling factor integrated into
  * hardware"):   y[m][n] = sum_g 2^(as[m][g]-127 + ws[n][g]-127) *
  *                          sum_{j<32} val(aq[m][32g+j]) * val(wq[n][32g+j]),  fp32 accumulate.

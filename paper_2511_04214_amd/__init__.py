@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libbrq.so")
 BRQ_F32, BRQ_BF16 = 0, 1
 LAYOUTS = {"rowmajor": 0, "tiled": 1}
 EXPORTS = ["brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
-           "brq_swiglu", "brq_swiglu_rotate_quantize_fused", "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_strerror", "brq_version"]
+           "brq_swiglu", "brq_swiglu_rotate_quantize_fused", "brq_matrix_rotate",
+           "brq_matrix_rotate_quantize_fused", "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_strerror", "brq_version"]
 
 _lib = None
 
@@ -49,6 +50,10 @@ def lib():
         L.brq_swiglu.restype = i32
         L.brq_swiglu_rotate_quantize_fused.argtypes = [vp, vp, i32, i64, i64, i64, i64, i32, i64, vp, vp, vp, i32, vp]
         L.brq_swiglu_rotate_quantize_fused.restype = i32
+        L.brq_matrix_rotate.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, i32, i64, vp]
+        L.brq_matrix_rotate.restype = i32
+        L.brq_matrix_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp, i32, vp]
+        L.brq_matrix_rotate_quantize_fused.restype = i32
         L.brq_mxfp4_gemm.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp]
         L.brq_mxfp4_gemm.restype = i32
         L.brq_to_rowmajor.argtypes = [vp, vp, i64, i64, vp, vp, vp]
@@ -193,6 +198,39 @@ def swiglu_rotate_quantize_fused(gate, up, B, h_dtype=torch.float32, codes=None,
                                                   BRQ_BF16 if h_dtype == torch.bfloat16 else BRQ_F32, B,
                                                   _signs_ptr(signs, K), codes.data_ptr(), scales.data_ptr(), lc,
                                                   _stream(stream)))
+    return codes, scales
+
+
+def _blocks(R, K):
+    """R: float32 GPU tensor [32, 32] (shared) or [K/32, 32, 32] -> (tensor, nR)."""
+    if not (R.is_cuda and R.is_contiguous() and R.dtype == torch.float32):
+        raise ValueError("R must be a contiguous float32 GPU tensor")
+    if R.dim() == 2:
+        R = R.unsqueeze(0)
+    if R.dim() != 3 or tuple(R.shape[1:]) != (32, 32):
+        raise ValueError("R must be [32, 32] or [K/32, 32, 32]")
+    return R, R.shape[0]
+
+
+def matrix_rotate(x, R, out_dtype=torch.float32, out=None, stream=None):
+    """y = x * diag(R_1..R_n), 32 x 32 blocks given by the caller (brq_matrix_rotate)."""
+    M, K, ldx = _rows(x, "x")
+    R, nR = _blocks(R, K)
+    y = torch.empty((M, K), dtype=out_dtype, device=x.device) if out is None else out
+    _, _, ldy = _rows(y, "out")
+    _check(lib().brq_matrix_rotate(x.data_ptr(), _dtype_code(x), M, K, ldx, R.data_ptr(), nR, y.data_ptr(),
+                                   _dtype_code(y), ldy, _stream(stream)))
+    return y
+
+
+def matrix_rotate_quantize_fused(x, R, codes=None, scales=None, stream=None, layout="rowmajor"):
+    """Rotation by caller-supplied blocks fused with MXFP4 quantization (brq_matrix_rotate_quantize_fused)."""
+    M, K, ldx = _rows(x, "x")
+    R, nR = _blocks(R, K)
+    lc = _layout_code(layout)
+    codes, scales = _alloc_q(x, M, K, codes, scales, layout)
+    _check(lib().brq_matrix_rotate_quantize_fused(x.data_ptr(), _dtype_code(x), M, K, ldx, R.data_ptr(), nR,
+                                                  codes.data_ptr(), scales.data_ptr(), lc, _stream(stream)))
     return codes, scales
 
 

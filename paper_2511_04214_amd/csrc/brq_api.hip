@@ -132,6 +132,42 @@ brq_status brq_swiglu_rotate_quantize_fused(const void* gate, const void* up, br
                                         static_cast<hipStream_t>(stream)));
 }
 
+static brq_status check_blocks(const float* R, int64_t nR, int64_t K) {
+    if (K % 128 != 0) return BRQ_ERR_SHAPE;
+    if (nR != 1 && nR != K / 32) return BRQ_ERR_BLOCK;
+    if (!R) return BRQ_ERR_NULL;
+    if (!aligned16(R)) return BRQ_ERR_ALIGN;
+    return BRQ_OK;
+}
+
+brq_status brq_matrix_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, const float* R, int64_t nR,
+                             void* y, brq_dtype ydt, int64_t ldy, void* stream) {
+    brq_status st = check_rows(x, xdt, M, K, ldx);
+    if (st != BRQ_OK) return st;
+    st = check_rows(y, ydt, M, K, ldy);
+    if (st != BRQ_OK) return st;
+    st = check_blocks(R, nR, K);
+    if (st != BRQ_OK) return st;
+    if (M == 0) return BRQ_OK;
+    return launched(brq::launch_matrix_rotate(0, xdt == BRQ_BF16, ydt == BRQ_BF16, x, M, K, ldx, R, nR, y, ldy, nullptr,
+                                              nullptr, false, static_cast<hipStream_t>(stream)));
+}
+
+brq_status brq_matrix_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx,
+                                            const float* R, int64_t nR, uint8_t* codes, uint8_t* scales,
+                                            brq_layout layout, void* stream) {
+    brq_status st = check_rows(x, xdt, M, K, ldx);
+    if (st != BRQ_OK) return st;
+    if (!layout_ok(layout)) return BRQ_ERR_LAYOUT;
+    st = check_out(codes, scales, M);
+    if (st != BRQ_OK) return st;
+    st = check_blocks(R, nR, K);
+    if (st != BRQ_OK) return st;
+    if (M == 0) return BRQ_OK;
+    return launched(brq::launch_matrix_rotate(2, xdt == BRQ_BF16, false, x, M, K, ldx, R, nR, nullptr, 0, codes, scales,
+                                              layout == BRQ_LAYOUT_TILED, static_cast<hipStream_t>(stream)));
+}
+
 brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
                           const uint8_t* ws, brq_layout w_layout, int64_t M, int64_t N, int64_t K, void* y,
                           brq_dtype ydt, int64_t ldy, void* stream) {
@@ -175,7 +211,7 @@ const char* brq_strerror(brq_status s) {
         case BRQ_OK: return "ok";
         case BRQ_ERR_NULL: return "a required pointer is NULL";
         case BRQ_ERR_SHAPE: return "bad shape: negative size, K not a multiple of 32, pitch below row length, or too large";
-        case BRQ_ERR_BLOCK: return "bad rotation block: need a power of two, 8 <= B <= 16384, B dividing K";
+        case BRQ_ERR_BLOCK: return "bad rotation block: need a power of two, 8 <= B <= 16384, B dividing K (matrix blocks: 1 or K/32 of them)";
         case BRQ_ERR_ALIGN: return "pointer or row pitch not 16-byte aligned";
         case BRQ_ERR_DTYPE: return "unknown dtype";
         case BRQ_ERR_LAUNCH: return "kernel launch failed";
@@ -184,6 +220,6 @@ const char* brq_strerror(brq_status s) {
     return "unknown status";
 }
 
-int brq_version(void) { return 310; }
+int brq_version(void) { return 320; }
 
 }  // extern "C"

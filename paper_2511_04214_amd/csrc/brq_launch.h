@@ -19,6 +19,15 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
                           bool tiled, const int8_t* signs, const Producer* prod, hipStream_t s);
 
+// Tiled operand whose K is not a multiple of 512: writes the K padding of rows 0..M-1 as zeros.
+hipError_t launch_zero_kpad(uint8_t* codes, uint8_t* scales, int64_t M, int64_t K, hipStream_t s);
+
+// Rotation by caller-supplied 32 x 32 blocks R[nR][32][32] (nR = 1 or K/32) on the matrix cores.
+// mode 0: y = x R_block (y fp32 or bf16); mode 2: fused with the quantizer.  K % 128 == 0.
+hipError_t launch_matrix_rotate(int mode, bool in_bf16, bool out_bf16, const void* x, int64_t M, int64_t K, int64_t ldx,
+                                const float* R, int64_t nR, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
+                                bool tiled, hipStream_t s);
+
 // A quantized [rows][K] operand as the product kernels see it.
 struct Operand {
     const uint8_t* codes;

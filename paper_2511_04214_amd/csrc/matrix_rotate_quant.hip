@@ -1,0 +1,220 @@
+// Block rotation with caller-supplied orthogonal 32 x 32 blocks (Sec. 4.3, Eq. 1 in full:
+// R_block = diag(R_1, ..., R_n), every R_i orthogonal; the Hadamard block of the other kernels
+// is one choice, learned blocks are what the conclusion proposes for the online step), alone or
+// fused with the MXFP4 quantizer of Sec. 4.1.  A dense contraction, so it runs on the matrix
+// cores: y_b = x_b R_b is computed as D = R_b^T X_b^T with v_mfma_f32_32x32x16_bf16.
+//
+// Precision.  bf16 activations are exact MFMA operands.  The fp32 entries of R are split into
+// three bf16 parts (hi + mid + lo = R up to 2^-27 relative; each remainder is exact in fp32), fp32
+// activations likewise, and the partial products are accumulated in fp32 from the smallest to
+// the largest: the result is within a few fp32 roundings of the exact sum, |err| <= 2^-20 *
+// sum_i |x_i| |R_ij|.  The order of the additions inside an MFMA is the hardware's, so the
+// last bits are not reproducible elsewhere; parity for this kernel is stated with that bound.
+//
+// Work decomposition.  A wavefront owns 64 columns (two blocks) for the whole launch and keeps
+// the three bf16 parts of their R (48 VGPRs) in registers; it walks down the rows in tiles of 32.
+// Operand layout of the 32x32x16 MFMA: lane (m = lane & 31, h = lane >> 5) supplies, as the
+// column operand, 8 consecutive k of token row m; MFMA step t = 0, 1 of a block takes
+// k = 16 h + 8 t + {0..7} (any assignment of k to lanes and steps is valid as long as R^T uses
+// the same one), so a lane reads 32 contiguous bytes of its row per block.  The result leaves
+// the matrix core with lane (m, h) holding outputs j = 8 q + 4 h + {0..3}, q = 0..3, of row m:
+// half of a 32-element quantization group; the group maximum and the packed codes are
+// completed with v_permlane32_swap.
+#include "brq_device.h"
+#include "brq_launch.h"
+
+namespace brq {
+namespace matrot {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct Args {
+    const void* x;          // [M][ldx]
+    int64_t ldx;
+    const float* R;         // [nR][32][32]
+    uint32_t shared;        // nR == 1
+    uint32_t M, K;
+    void* y;                // rotate: [M][ldy] fp32 or bf16
+    int64_t ldy;
+    uint8_t* codes;
+    uint8_t* scales;
+    uint32_t stages, sstages;   // tiled output: blocks per slab; 0 = row-major
+    uint32_t ntiles, nsplits, ncols;   // row tiles of 32, row walkers per column pair, K / 64
+};
+
+// fp32 -> three bf16 (bits) with hi + mid + lo = f up to 2^-27 |f|; every remainder is exact
+__device__ __forceinline__ void split3(float f, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
+    hi = f32_to_bf16_bits(f);
+    const float r1 = f - as_f32(hi << 16);
+    mid = f32_to_bf16_bits(r1);
+    const float r2 = r1 - as_f32(mid << 16);
+    lo = f32_to_bf16_bits(r2);
+}
+
+// 8 fp32 -> three MFMA operands (8 bf16 each, element kk in half (kk & 1) of dword kk >> 1)
+__device__ __forceinline__ void split3x8(const float (&f)[8], v4i (&part)[3]) {
+    uint32_t p[3][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) split3(f[i], p[0][i], p[1][i], p[2][i]);
+#pragma unroll
+    for (int s = 0; s < 3; ++s)
+        part[s] = v4i{(int)(p[s][0] | (p[s][1] << 16)), (int)(p[s][2] | (p[s][3] << 16)),
+                      (int)(p[s][4] | (p[s][5] << 16)), (int)(p[s][6] | (p[s][7] << 16))};
+}
+
+__device__ __forceinline__ v16f mfma_bf16(const v4i& a, const v4i& b, const v16f& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// MODE 0: rotation alone (y out), MODE 2: fused with the quantizer.
+template <bool IN_BF16, int MODE, bool OUT_BF16>
+__global__ void __launch_bounds__(256) k_matrot(Args a) {
+    const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t m = lane & 31, h = lane >> 5;
+    const uint32_t wid = blockIdx.x * 4u + wave;
+    if (wid >= a.ncols * a.nsplits) return;          // uniform per wavefront; no barrier below
+    const uint32_t colpair = wid % a.ncols, split = wid / a.ncols;
+    const uint32_t col0 = colpair * 64u;
+    constexpr int ES = IN_BF16 ? 2 : 4;
+
+    // R^T operands of the two blocks: lane (j = m, h), step t: R[b][16 h + 8 t + kk][j], kk = 0..7
+    v4i rp[2][2][3];
+#pragma unroll
+    for (int bb = 0; bb < 2; ++bb) {
+        const float* Rb = a.R + (a.shared ? 0u : (size_t)(col0 / 32u + bb) * 1024u);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            float f[8];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) f[kk] = Rb[(16u * h + 8u * t + kk) * 32u + m];
+            split3x8(f, rp[bb][t]);
+        }
+    }
+
+    for (uint32_t tile = split; tile < a.ntiles; tile += a.nsplits) {
+        const uint32_t row = tile * 32u + m;
+        const uint32_t lrow = min(row, a.M - 1u);     // rows past the end re-read the last row; stores are masked
+        const char* xp = (const char*)a.x + ((uint64_t)lrow * (uint64_t)a.ldx + col0 + 16u * h) * ES;
+#pragma unroll
+        for (int bb = 0; bb < 2; ++bb) {
+            v16f acc = {};
+            if constexpr (IN_BF16) {
+                const v4i x0 = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(xp + bb * 64));
+                const v4i x1 = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(xp + bb * 64 + 16));
+#pragma unroll
+                for (int s = 2; s >= 0; --s) {        // smallest part first
+                    acc = mfma_bf16(rp[bb][0][s], x0, acc);
+                    acc = mfma_bf16(rp[bb][1][s], x1, acc);
+                }
+            } else {
+                v4i xs[2][3];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const v4f lo = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xp + bb * 128 + t * 32));
+                    const v4f hi = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xp + bb * 128 + t * 32 + 16));
+                    const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    split3x8(f, xs[t]);
+                }
+                // the six products whose parts' orders add up to at most 2 (the rest is below 2^-27)
+                constexpr int PX[6] = {2, 0, 1, 1, 0, 0}, PR[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+                for (int i = 0; i < 6; ++i) {
+                    acc = mfma_bf16(rp[bb][0][PR[i]], xs[0][PX[i]], acc);
+                    acc = mfma_bf16(rp[bb][1][PR[i]], xs[1][PX[i]], acc);
+                }
+            }
+            // acc[4 q + i] = y[row][col0 + 32 bb + 8 q + 4 h + i]
+            const uint32_t cb = col0 + 32u * bb;
+            if constexpr (MODE == 0) {
+                if (row < a.M) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint64_t e = (uint64_t)row * (uint64_t)a.ldy + cb + 8u * q + 4u * h;
+                        if constexpr (OUT_BF16) {
+                            uint2 o = make_uint2(pack_bf16x2(acc[4 * q], acc[4 * q + 1]), pack_bf16x2(acc[4 * q + 2], acc[4 * q + 3]));
+                            *reinterpret_cast<uint2*>((char*)a.y + e * 2) = o;
+                        } else {
+                            *reinterpret_cast<float4*>((char*)a.y + e * 4) = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+                        }
+                    }
+                }
+            } else {
+                const float lo8[8] = {acc[0], acc[1], acc[2], acc[3], acc[4], acc[5], acc[6], acc[7]};
+                const float hi8[8] = {acc[8], acc[9], acc[10], acc[11], acc[12], acc[13], acc[14], acc[15]};
+                // group maximum: own 16 values, then the other half of the row's group (lane ^ 32);
+                // non-negative floats order like their bit patterns
+                const uint32_t am = as_u32(fmaxf(absmax8(lo8), absmax8(hi8)));
+                const auto ex = __builtin_amdgcn_permlane32_swap(am, am, false, false);
+                const uint32_t sb = e8m0_from_amax(as_f32(max(ex[0], ex[1])));
+                // U: codes of q = 0, 1 (two 16-bit pieces), V: of q = 2, 3.  After the swap lane h = 0
+                // holds both lanes' U (group bytes 0..7), lane h = 1 both lanes' V (bytes 8..15);
+                // piece (q, h) belongs at byte 4 q + 2 h of the group
+                const uint32_t U = encode8_e2m1(lo8, sb), V = encode8_e2m1(hi8, sb);
+                const auto sw = __builtin_amdgcn_permlane32_swap(U, V, false, false);
+                const uint2 o = make_uint2((sw[0] & 0xffffu) | (sw[1] << 16), (sw[0] >> 16) | (sw[1] & 0xffff0000u));
+                if (row < a.M) {
+                    const uint32_t g = cb / 32u;
+                    if (a.stages == 0) {
+                        *reinterpret_cast<uint2*>(a.codes + (uint64_t)row * (a.K / 2u) + g * 16u + 8u * h) = o;
+                        if (h == 0) a.scales[(uint64_t)row * (a.K / 32u) + g] = (uint8_t)sb;
+                    } else {
+                        *reinterpret_cast<uint2*>(a.codes + ((uint64_t)(row >> 6) * a.stages + (g >> 2)) * 4096u +
+                                                  (row & 63u) * 64u + (g & 3u) * 16u + 8u * h) = o;
+                        if (h == 0)
+                            a.scales[((uint64_t)(row >> 6) * a.sstages + (g >> 4)) * 1024u + (row & 63u) * 16u + (g & 15u)] = (uint8_t)sb;
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace matrot
+
+// mode 0: rotation alone into y; mode 2: fused with the quantizer into codes / scales.
+// K % 128 == 0 (checked by the caller), nR = 1 or K / 32.
+hipError_t launch_matrix_rotate(int mode, bool in_bf16, bool out_bf16, const void* x, int64_t M, int64_t K, int64_t ldx,
+                                const float* R, int64_t nR, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
+                                bool tiled, hipStream_t s) {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
+    }
+    matrot::Args a;
+    a.x = x; a.ldx = ldx; a.R = R; a.shared = nR == 1 ? 1u : 0u;
+    a.M = (uint32_t)M; a.K = (uint32_t)K; a.y = y; a.ldy = ldy; a.codes = codes; a.scales = scales;
+    const int64_t Kp = (K + 511) / 512 * 512;
+    a.stages = tiled ? (uint32_t)(Kp / 128) : 0u;
+    a.sstages = tiled ? (uint32_t)(Kp / 512) : 0u;
+    a.ntiles = (uint32_t)((M + 31) / 32);
+    a.ncols = (uint32_t)(K / 64);
+    // about 16 wavefronts per CU; a wavefront keeps its R for at least 4 row tiles when there are that many
+    uint32_t want = (uint32_t)cus * 16u / a.ncols;
+    if (want < 1) want = 1;
+    const uint32_t most = (a.ntiles + 3u) / 4u;
+    a.nsplits = want < most ? want : most;
+    if (mode == 2 && tiled && Kp != K) {
+        hipError_t e = launch_zero_kpad(codes, scales, M, K, s);
+        if (e != hipSuccess) return e;
+    }
+    const dim3 grid((a.ncols * a.nsplits + 3u) / 4u), block(256);
+    if (mode == 0) {
+        if (in_bf16) {
+            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 0, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((matrot::k_matrot<true, 0, false>), grid, block, 0, s, a);
+        } else {
+            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<false, 0, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((matrot::k_matrot<false, 0, false>), grid, block, 0, s, a);
+        }
+    } else {
+        if (in_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 2, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((matrot::k_matrot<false, 2, false>), grid, block, 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace brq

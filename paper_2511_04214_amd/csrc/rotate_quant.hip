@@ -510,6 +510,16 @@ __global__ void __launch_bounds__(256) k_zero_kpad(uint8_t* __restrict__ codes, 
     }
 }
 
+hipError_t launch_zero_kpad(uint8_t* codes, uint8_t* scales, int64_t M, int64_t K, hipStream_t s) {
+    const int64_t Kp = (K + 511) / 512 * 512;
+    if (Kp == K || M == 0) return hipSuccess;
+    const uint32_t gpad = (uint32_t)((Kp - K) / 32);
+    const int64_t want = (M * gpad + 255) / 256;
+    hipLaunchKernelGGL(k_zero_kpad, dim3((uint32_t)(want < 4096 ? want : 4096)), dim3(256), 0, s, codes, scales,
+                       (uint32_t)M, (uint32_t)(K / 32), gpad, (uint32_t)(Kp / 128), (uint32_t)(Kp / 512));
+    return hipGetLastError();
+}
+
 // mode: RowMode; log2b: 0 for MODE_QUANT, else 3..14.  Arguments are already validated.
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
@@ -527,11 +537,7 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
     a.sstages = tiled ? (uint32_t)(Kp / 512) : 0u;
     bool contig = (ldx == K) && (mode != MODE_ROTATE || ldy == K) && (!prod || prod->ldu == K);
     if (tiled && Kp != K && mode != MODE_ROTATE) {
-        const uint32_t gpad = (uint32_t)((Kp - K) / 32);
-        const int64_t want = (M * gpad + 255) / 256;
-        hipLaunchKernelGGL(k_zero_kpad, dim3((uint32_t)(want < 4096 ? want : 4096)), dim3(256), 0, s, codes, scales,
-                           (uint32_t)M, (uint32_t)(K / 32), gpad, a.stages, a.sstages);
-        hipError_t e = hipGetLastError();
+        hipError_t e = launch_zero_kpad(codes, scales, M, K, s);
         if (e != hipSuccess) return e;
     }
     if (prod && mode == MODE_ROTATE) {   // the activation alone, written to y (log2b = 0)

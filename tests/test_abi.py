@@ -56,6 +56,14 @@ def test_argument_errors_before_any_launch(L):
     assert L.brq_rotate_quantize_fused(q(p), 1, 4, 64, 64, 32, None, q(p), None, 0, None) == NULL
     assert L.brq_block_rotate(q(p), 1, 4, 64, 64, 32, None, None, 0, 64, None) == NULL
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), None, 0, 4, 4, 64, q(p), 0, 4, None) == NULL
+    # caller-supplied blocks: (x, xdt, M, K, ldx, R, nR, ...)
+    assert L.brq_matrix_rotate(q(p), 1, 4, 128, 128, None, 4, q(p), 0, 128, None) == NULL
+    assert L.brq_matrix_rotate(q(p), 1, 4, 128, 128, q(p), 3, q(p), 0, 128, None) == BLOCK          # 1 or K/32 blocks
+    assert L.brq_matrix_rotate(q(p), 1, 4, 96, 96, q(p), 3, q(p), 0, 96, None) == SHAPE             # K % 128
+    assert L.brq_matrix_rotate_quantize_fused(q(p), 1, 4, 128, 128, q(p + 4), 1, q(p), q(p), 0, None) == ALIGN
+    assert L.brq_matrix_rotate_quantize_fused(q(p), 1, 4, 128, 128, q(p), 1, q(p), q(p), 9, None) == LAYOUT
+    assert L.brq_matrix_rotate_quantize_fused(q(p), 1, 4, 128, 128, q(p), 1, None, q(p), 0, None) == NULL
+    assert L.brq_matrix_rotate_quantize_fused(None, 1, 0, 128, 128, q(p), 1, None, None, 0, None) == OK
     # the producer calls: (gate, up, xdt, M, K, ldg, ldu, ...)
     assert L.brq_swiglu(q(p), None, 1, 4, 64, 64, 64, q(p), 0, 64, None) == NULL
     assert L.brq_swiglu(q(p), q(p), 1, 4, 64, 64, 32, q(p), 0, 64, None) == SHAPE            # ldu < K

@@ -1,0 +1,232 @@
+"""GPU parity of the rotation by caller-supplied orthogonal 32 x 32 blocks (Eq. 1 in full) and of
+its fusion with the MXFP4 quantizer, through the C ABI, against the CPU oracle's fp64 definition.
+
+The kernel sums on the matrix cores in an order the hardware chooses, so the rule is the error
+bound the interface states: |y - exact| <= 2^-20 * sum_i |x_i| |R_ij|.  For the fused call every
+scale byte and every code must be one that SOME value within that bound of the exact rotation
+produces (interval check with the oracle's scale rule and element encoder); cases with exact
+arithmetic (identity, signed permutations) must match bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import to_dev, to_host
+from paper_2511_04214_amd.inputs import f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2.0 ** -20
+
+
+@pytest.fixture(scope="module")
+def brq():
+    import paper_2511_04214_amd as b
+    b.lib()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return b
+
+
+def make_x(M, K, seed, dtype):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_t(4, size=(M, K)).astype(np.float32)
+    x[:, rng.choice(K, size=max(1, K // 100), replace=False)] *= 20.0
+    return f32_to_bf16_bits(x) if dtype == "bf16" else x
+
+
+def orthogonal_blocks(n, seed):
+    rng = np.random.default_rng(seed)
+    return np.stack([np.linalg.qr(rng.standard_normal((32, 32)))[0] for _ in range(n)]).astype(np.float32)
+
+
+def signed_permutation(seed):
+    rng = np.random.default_rng(seed)
+    P = np.zeros((32, 32), dtype=np.float32)
+    P[rng.permutation(32), np.arange(32)] = rng.choice([-1.0, 1.0], size=32)
+    return P
+
+
+def outward32(lo, hi):
+    """float64 interval -> float32 interval that contains it."""
+    l32, h32 = lo.astype(np.float32), hi.astype(np.float32)
+    l32 = np.where(l32.astype(np.float64) > lo, np.nextafter(l32, np.float32(-np.inf)), l32)
+    h32 = np.where(h32.astype(np.float64) < hi, np.nextafter(h32, np.float32(np.inf)), h32)
+    return l32, h32
+
+
+def unpack(codes):
+    out = np.empty((codes.shape[0], codes.shape[1] * 2), dtype=np.uint8)
+    out[:, 0::2] = codes & 0xF
+    out[:, 1::2] = codes >> 4
+    return out
+
+
+def check_fused_within_bound(orc, x_np, R_np, codes, scales):
+    """codes / scales (row-major, from the GPU) are reachable from a value within TOL * bound of the
+    exact rotation; returns the fraction of code bytes equal to the oracle's nominal ones."""
+    M, K = x_np.shape
+    y, bound = orc.matrix_rotate_f64(x_np, R_np, want_bound=True)
+    d = TOL * bound + 2.0 ** -140
+    lo32, hi32 = outward32(y - d, y + d)
+    # scale bytes: the group maximum lies between max(|y| - d) and max(|y| + d)
+    a_lo = np.maximum(np.abs(y) - d, 0).reshape(M, K // 32, 32).max(axis=2)
+    a_hi = (np.abs(y) + d).reshape(M, K // 32, 32).max(axis=2)
+    a_lo32, a_hi32 = outward32(a_lo, a_hi)
+    a_lo32 = np.maximum(a_lo32, 0)
+    s_lo = orc.mxfp4_quantize(np.repeat(a_lo32, 32, axis=1))[1]
+    s_hi = orc.mxfp4_quantize(np.repeat(a_hi32, 32, axis=1))[1]
+    assert ((s_lo <= scales) & (scales <= s_hi)).all(), "scale bytes outside the interval in %d groups" % int(
+        ((scales < s_lo) | (scales > s_hi)).sum())
+    # codes under the GPU's own scale bytes: between the codes of the interval's ends (the encoder is monotone)
+    val = np.array([orc.e2m1_value(c) for c in range(16)])
+    v_lo = val[unpack(orc.mxfp4_encode_with_scales(lo32, scales))]
+    v_hi = val[unpack(orc.mxfp4_encode_with_scales(hi32, scales))]
+    v = val[unpack(codes)]
+    bad = (v < v_lo) | (v > v_hi)
+    assert not bad.any(), "%d codes outside their interval, first at %s" % (int(bad.sum()), np.argwhere(bad)[0])
+    nz = unpack(codes)
+    assert not (nz == 8).any()        # a zero magnitude is code 0
+    rc, rs = orc.matrix_rotate_quantize_fused(x_np, R_np)
+    return float((rc == codes).mean()), float((rs == scales).mean())
+
+
+# ------------------------------------------------------------------ rotation alone
+
+@pytest.mark.parametrize("M,K,dtype,shared", [(64, 128, "bf16", False), (100, 640, "bf16", False), (33, 256, "f32", False),
+                                              (257, 1024, "bf16", True), (40, 384, "f32", True)])
+def test_rotation_within_bound(brq, orc, M, K, dtype, shared):
+    x = make_x(M, K, 500 + M + K, dtype)
+    R = orthogonal_blocks(1 if shared else K // 32, 501 + K)
+    y = to_host(brq.matrix_rotate(to_dev(x), to_dev(R[0] if shared else R)))
+    want, bound = orc.matrix_rotate_f64(x, R[0] if shared else R, want_bound=True)
+    err = np.abs(y.astype(np.float64) - want)
+    assert (err <= TOL * bound + 2.0 ** -140).all(), "max err/bound = %.3g" % float((err / (bound + 1e-300)).max())
+    # and not trivially: the error is that of fp32 accumulation, far below bf16 resolution of R
+    assert float((err / (bound + 1e-300)).max()) < 2.0 ** -21
+    # bf16 output = RNE of the fp32 output
+    yb = brq.matrix_rotate(to_dev(x), to_dev(R[0] if shared else R), out_dtype=torch.bfloat16)
+    assert np.array_equal(to_host(yb), f32_to_bf16_bits(y))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_exact_cases(brq, orc, dtype):
+    # identity and signed permutations have exact arithmetic: every partial product is x or 0
+    M, K = 70, 256
+    x = make_x(M, K, 510, dtype)
+    x32 = orc.bf16_to_f32(x) if dtype == "bf16" else x
+    y = to_host(brq.matrix_rotate(to_dev(x), to_dev(np.eye(32, dtype=np.float32))))
+    assert np.array_equal(y, x32)
+    Ps = np.stack([signed_permutation(511 + b) for b in range(K // 32)])
+    y = to_host(brq.matrix_rotate(to_dev(x), to_dev(Ps)))
+    assert np.array_equal(y.astype(np.float64), orc.matrix_rotate_f64(x, Ps))
+    # fused: bit-identical to the oracle, in both layouts
+    rc, rs = orc.matrix_rotate_quantize_fused(x, Ps)
+    for layout in ("rowmajor", "tiled"):
+        c, s = brq.matrix_rotate_quantize_fused(to_dev(x), to_dev(Ps), layout=layout)
+        if layout == "tiled":
+            c, s = brq.to_rowmajor(c, s, M, K)
+        assert np.array_equal(to_host(c), rc) and np.array_equal(to_host(s), rs)
+
+
+def test_hadamard_block_agrees_with_the_butterfly(brq, orc):
+    # R = H_32 / sqrt(32) as a matrix: same rotation as brq_block_rotate up to the two error bounds
+    import scipy.linalg
+    M, K = 128, 512
+    x = make_x(M, K, 520, "bf16")
+    H = (scipy.linalg.hadamard(32) / np.sqrt(32.0)).astype(np.float32)
+    a = to_host(brq.matrix_rotate(to_dev(x), to_dev(H))).astype(np.float64)
+    b = to_host(brq.block_rotate(to_dev(x), 32)).astype(np.float64)
+    _, bound = orc.matrix_rotate_f64(x, H, want_bound=True)
+    assert (np.abs(a - b) <= 2.0 ** -19 * bound).all()
+
+
+def test_rotation_strided(brq, orc):
+    M, K = 45, 256
+    wide = make_x(M, K + 128, 530, "bf16")
+    R = orthogonal_blocks(K // 32, 531)
+    xd = to_dev(wide)[:, 64:64 + K]
+    out = torch.zeros((M, K + 32), dtype=torch.float32, device="cuda")
+    brq.matrix_rotate(xd, to_dev(R), out=out[:, :K])
+    want, bound = orc.matrix_rotate_f64(np.ascontiguousarray(wide[:, 64:64 + K]), R, want_bound=True)
+    got = to_host(out)
+    assert (np.abs(got[:, :K] - want) <= TOL * bound + 2.0 ** -140).all()
+    assert not got[:, K:].any()
+
+
+# ------------------------------------------------------------------ fused with the quantizer
+
+@pytest.mark.parametrize("layout", ["rowmajor", "tiled"])
+@pytest.mark.parametrize("M,K,dtype,shared", [(64, 128, "bf16", False), (130, 640, "bf16", False), (37, 256, "f32", False),
+                                              (300, 1024, "bf16", True), (1, 128, "bf16", False), (96, 2048, "bf16", False)])
+def test_fused_within_bound(brq, orc, M, K, dtype, shared, layout):
+    x = make_x(M, K, 540 + M + K, dtype)
+    R = orthogonal_blocks(1 if shared else K // 32, 541 + K)
+    Rn = R[0] if shared else R
+    c, s = brq.matrix_rotate_quantize_fused(to_dev(x), to_dev(Rn), layout=layout)
+    if layout == "tiled":
+        c, s = brq.to_rowmajor(c, s, M, K)
+    same_c, same_s = check_fused_within_bound(orc, x, Rn, to_host(c), to_host(s))
+    assert same_c > 0.995 and same_s > 0.995      # nearly all of them are simply the oracle's
+
+
+def test_fused_tiled_k_padding_is_zero(brq):
+    # K = 640: the tiled buffers cover K = 1024; the padding groups must read as zeros
+    M, K = 100, 640
+    x = make_x(M, K, 550, "bf16")
+    R = orthogonal_blocks(K // 32, 551)
+    cb, sb = brq.operand_bytes(M, K, "tiled")
+    c = torch.full((cb,), 0xEE, dtype=torch.uint8, device="cuda")
+    s = torch.full((sb,), 0xEE, dtype=torch.uint8, device="cuda")
+    brq.matrix_rotate_quantize_fused(to_dev(x), to_dev(R), codes=c, scales=s, layout="tiled")
+    c2, s2 = brq.to_rowmajor(c, s, M, 1024)
+    assert not to_host(c2)[:, K // 2:].any() and not to_host(s2)[:, K // 32:].any()
+
+
+def test_fused_feeds_the_product(brq, orc):
+    # (X R)(W R)^T = X W^T for orthogonal R (Sec. 2): the quantized product with rotated operands
+    # approximates X W^T about as well as with the Hadamard block
+    M, N, K = 128, 256, 1024
+    x = make_x(M, K, 560, "bf16")
+    rng = np.random.default_rng(561)
+    w = f32_to_bf16_bits((rng.standard_normal((N, K)) * 0.02).astype(np.float32))
+    R = to_dev(orthogonal_blocks(K // 32, 562))
+    ref = orc.bf16_to_f32(x).astype(np.float64) @ orc.bf16_to_f32(w).astype(np.float64).T
+    errs = {}
+    for name, q in (("blocks", lambda t: brq.matrix_rotate_quantize_fused(t, R, layout="tiled")),
+                    ("hadamard", lambda t: brq.rotate_quantize_fused(t, 32, layout="tiled"))):
+        aq, as_ = q(to_dev(x))
+        wq, ws = q(to_dev(w))
+        y = brq.mxfp4_gemm(aq, as_, wq, ws, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)
+        errs[name] = float(np.linalg.norm(to_host(y) - ref) / np.linalg.norm(ref))
+    assert errs["blocks"] < 0.25 and errs["blocks"] < 1.5 * errs["hadamard"], errs
+
+
+def test_fused_full_size_sampled_rows(brq, orc):
+    # X 16384 x 8192 in the benchmark's launch configuration; the oracle checks a sample of rows
+    M, K = 16384, 8192
+    gen = torch.Generator(device="cuda").manual_seed(570)
+    xd = torch.randn((M, K), device="cuda", generator=gen).to(torch.bfloat16)
+    xd[:, ::97] *= 20
+    R = orthogonal_blocks(K // 32, 571)
+    c, s = brq.matrix_rotate_quantize_fused(xd, to_dev(R), layout="tiled")
+    c, s = brq.to_rowmajor(c, s, M, K)
+    rng = np.random.default_rng(572)
+    rows = np.sort(rng.choice(M, size=16, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    idx = torch.from_numpy(rows).cuda()
+    same_c, same_s = check_fused_within_bound(orc, to_host(xd[idx].contiguous()), R, to_host(c[idx]), to_host(s[idx]))
+    assert same_c > 0.995 and same_s > 0.995
+
+
+def test_argument_errors(brq):
+    x = torch.zeros((4, 128), dtype=torch.bfloat16, device="cuda")
+    R = torch.zeros((4, 32, 32), dtype=torch.float32, device="cuda")
+    with pytest.raises(brq.BrqError) as e:
+        brq.matrix_rotate_quantize_fused(x, R[:3])               # neither 1 nor K/32 blocks
+    assert e.value.status == 3
+    with pytest.raises(brq.BrqError) as e:
+        brq.matrix_rotate_quantize_fused(x[:, :96], R[:3])       # K % 128
+    assert e.value.status == 2
+    with pytest.raises(ValueError):
+        brq.matrix_rotate(x, R.double())
+    c, s = brq.matrix_rotate_quantize_fused(x[:0], R)
+    assert c.numel() == 0
