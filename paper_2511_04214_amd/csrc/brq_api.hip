@@ -132,8 +132,8 @@ brq_status brq_swiglu_rotate_quantize_fused(const void* gate, const void* up, br
                                         static_cast<hipStream_t>(stream)));
 }
 
-static brq_status check_blocks(const float* R, int64_t nR, int64_t K) {
-    if (K % 128 != 0) return BRQ_ERR_SHAPE;
+static brq_status check_blocks(const float* R, int64_t nR, int64_t K, int64_t ld_bytes) {
+    if (K % 128 != 0 || ld_bytes * 32 >= (int64_t(1) << 32)) return BRQ_ERR_SHAPE;   // 32 rows of pitch: 32-bit offsets
     if (nR != 1 && nR != K / 32) return BRQ_ERR_BLOCK;
     if (!R) return BRQ_ERR_NULL;
     if (!aligned16(R)) return BRQ_ERR_ALIGN;
@@ -146,7 +146,7 @@ brq_status brq_matrix_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K,
     if (st != BRQ_OK) return st;
     st = check_rows(y, ydt, M, K, ldy);
     if (st != BRQ_OK) return st;
-    st = check_blocks(R, nR, K);
+    st = check_blocks(R, nR, K, ldx * dtype_size(xdt));
     if (st != BRQ_OK) return st;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_matrix_rotate(0, xdt == BRQ_BF16, ydt == BRQ_BF16, x, M, K, ldx, R, nR, y, ldy, nullptr,
@@ -161,7 +161,7 @@ brq_status brq_matrix_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_
     if (!layout_ok(layout)) return BRQ_ERR_LAYOUT;
     st = check_out(codes, scales, M);
     if (st != BRQ_OK) return st;
-    st = check_blocks(R, nR, K);
+    st = check_blocks(R, nR, K, ldx * dtype_size(xdt));
     if (st != BRQ_OK) return st;
     if (M == 0) return BRQ_OK;
     return launched(brq::launch_matrix_rotate(2, xdt == BRQ_BF16, false, x, M, K, ldx, R, nR, nullptr, 0, codes, scales,

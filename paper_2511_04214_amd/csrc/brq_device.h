@@ -205,4 +205,22 @@ __device__ __forceinline__ uint32_t encode8_e2m1(const float (&y)[8], uint32_t s
     return w & (nz | 0x77777777u);
 }
 
+// ---- LDS-DMA loads (global memory -> LDS without passing through VGPRs)
+
+// One LDS-DMA load: 64 lanes x 16 bytes from base + voff(lane) to LDS lds_base + LDS_OFF +
+// 16 * lane (M0 carries the LDS address).  lds_base and base must be wavefront-uniform.
+template <int LDS_OFF>
+__device__ __forceinline__ void dma16(uint32_t lds_base, const uint8_t* base, uint32_t voff) {
+    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2\n\t"
+                 :: "s"(lds_base), "v"(voff), "s"(base), "n"(LDS_OFF)
+                 : "memory", "scc", "m0");
+}
+
+// A pointer that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p) {
+    uint64_t b = (uint64_t)p;
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    return (const uint8_t*)(((uint64_t)hi << 32) | lo);
+}
+
 }  // namespace brq

@@ -66,9 +66,26 @@ __device__ __forceinline__ v16f mfma_bf16(const v4i& a, const v4i& b, const v16f
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+constexpr int WAVE_LDS = 2 * 4096 + 1024;   // two operand buffers (32 rows x 128 bytes) + the code block
+constexpr int LDS_BYTES = 4 * WAVE_LDS;
+
 // MODE 0: rotation alone (y out), MODE 2: fused with the quantizer.
+//
+// Data movement of the bf16 path.  The texture-address unit charges a 64-lane access by the
+// cache lines it touches and merges only neighbouring lanes, and in the MFMA's operand layout
+// neighbouring lanes are different rows: loading operands straight into that layout (32 lines
+// per instruction) and storing codes from it (8 bytes per lane, rows apart) made this kernel
+// address-bound at half the memory rate.  So a tile's 32 rows x 128 bytes come in by LDS-DMA, 8
+// whole lines per instruction (lane l fetches 16-byte chunk (l & 7) ^ (row & 7) of row l >> 3 into
+// LDS slot l, the XOR spreading the MFMA-side reads over the banks), one tile ahead of the
+// arithmetic; and the packed codes go through a 1 KB LDS block so that lanes 2 r and 2 r + 1 store
+// the 32 contiguous code bytes of row r.  All LDS is private to the wavefront: no barriers.
+// Loads and stores share one counter and complete out of order with each other, so the wait for
+// the next tile's data is a wait for everything, placed just before this tile's stores: by then
+// the loads are a whole tile old and the previous stores older still.
 template <bool IN_BF16, int MODE, bool OUT_BF16>
 __global__ void __launch_bounds__(256) k_matrot(Args a) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t m = lane & 31, h = lane >> 5;
     const uint32_t wid = blockIdx.x * 4u + wave;
@@ -76,6 +93,9 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
     const uint32_t colpair = wid % a.ncols, split = wid / a.ncols;
     const uint32_t col0 = colpair * 64u;
     constexpr int ES = IN_BF16 ? 2 : 4;
+    uint8_t* const wl = lds + wave * WAVE_LDS;
+    const uint32_t wl0 = (uint32_t)(uintptr_t)wl;
+    uint8_t* const ep = wl + 8192;
 
     // R^T operands of the two blocks: lane (j = m, h), step t: R[b][16 h + 8 t + kk][j], kk = 0..7
     v4i rp[2][2][3];
@@ -91,27 +111,60 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
         }
     }
 
+    // bf16: LDS-DMA of a tile into buffer `buf`.  Instruction i brings rows 8 i + (lane >> 3); the
+    // host checked that 32 rows of pitch fit 32 bits.  Rows past the end re-read the last row.
+    const uint32_t pitch = (uint32_t)a.ldx * ES;
+    const uint32_t dsw = ((lane & 7u) ^ ((lane >> 3) & 7u)) << 4;
+    uint32_t voff[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) voff[i] = (8u * i + (lane >> 3)) * pitch + dsw;
+    auto dma_tile = [&](uint32_t tile, uint32_t buf) {
+        const uint8_t* base = uniform_ptr((const uint8_t*)a.x + ((uint64_t)tile * 32u * (uint64_t)a.ldx + col0) * ES);
+        const uint32_t lb = wl0 + buf * 4096u;
+        if (tile * 32u + 32u <= a.M) {                // uniform
+            dma16<0>(lb, base, voff[0]); dma16<1024>(lb, base, voff[1]);
+            dma16<2048>(lb, base, voff[2]); dma16<3072>(lb, base, voff[3]);
+        } else {
+            const uint32_t last = a.M - 1u - tile * 32u;
+            dma16<0>(lb, base, min(lane >> 3, last) * pitch + dsw);
+            dma16<1024>(lb, base, min(8u + (lane >> 3), last) * pitch + dsw);
+            dma16<2048>(lb, base, min(16u + (lane >> 3), last) * pitch + dsw);
+            dma16<3072>(lb, base, min(24u + (lane >> 3), last) * pitch + dsw);
+        }
+    };
+    uint32_t buf = 0;
+    if constexpr (IN_BF16) {
+        dma_tile(split, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+
     for (uint32_t tile = split; tile < a.ntiles; tile += a.nsplits) {
         const uint32_t row = tile * 32u + m;
-        const uint32_t lrow = min(row, a.M - 1u);     // rows past the end re-read the last row; stores are masked
-        const char* xp = (const char*)a.x + ((uint64_t)lrow * (uint64_t)a.ldx + col0 + 16u * h) * ES;
+        if constexpr (IN_BF16) {
+            if (tile + a.nsplits < a.ntiles) dma_tile(tile + a.nsplits, buf ^ 1u);   // uniform
+        }
+        uint32_t sbv[2] = {0, 0};
 #pragma unroll
         for (int bb = 0; bb < 2; ++bb) {
             v16f acc = {};
             if constexpr (IN_BF16) {
-                const v4i x0 = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(xp + bb * 64));
-                const v4i x1 = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(xp + bb * 64 + 16));
+                const uint8_t* src = wl + buf * 4096u + m * 128u;
+                const v4i x0 = *reinterpret_cast<const v4i*>(src + (((uint32_t)(bb * 4) + 2u * h) ^ (m & 7u)) * 16u);
+                const v4i x1 = *reinterpret_cast<const v4i*>(src + (((uint32_t)(bb * 4) + 2u * h + 1u) ^ (m & 7u)) * 16u);
 #pragma unroll
                 for (int s = 2; s >= 0; --s) {        // smallest part first
                     acc = mfma_bf16(rp[bb][0][s], x0, acc);
                     acc = mfma_bf16(rp[bb][1][s], x1, acc);
                 }
             } else {
+                // fp32 activations (not the fast path): straight from global into the operand layout
+                const uint32_t lrow = min(row, a.M - 1u);
+                const char* xp = (const char*)a.x + ((uint64_t)lrow * (uint64_t)a.ldx + col0 + 16u * h) * ES;
                 v4i xs[2][3];
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    const v4f lo = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xp + bb * 128 + t * 32));
-                    const v4f hi = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xp + bb * 128 + t * 32 + 16));
+                    const v4f lo = *reinterpret_cast<const v4f*>(xp + bb * 128 + t * 32);
+                    const v4f hi = *reinterpret_cast<const v4f*>(xp + bb * 128 + t * 32 + 16);
                     const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                     split3x8(f, xs[t]);
                 }
@@ -126,6 +179,7 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
             // acc[4 q + i] = y[row][col0 + 32 bb + 8 q + 4 h + i]
             const uint32_t cb = col0 + 32u * bb;
             if constexpr (MODE == 0) {
+                if constexpr (IN_BF16) { if (bb == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
                 if (row < a.M) {
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -146,26 +200,36 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
                 const uint32_t am = as_u32(fmaxf(absmax8(lo8), absmax8(hi8)));
                 const auto ex = __builtin_amdgcn_permlane32_swap(am, am, false, false);
                 const uint32_t sb = e8m0_from_amax(as_f32(max(ex[0], ex[1])));
+                sbv[bb] = sb;
                 // U: codes of q = 0, 1 (two 16-bit pieces), V: of q = 2, 3.  After the swap lane h = 0
                 // holds both lanes' U (group bytes 0..7), lane h = 1 both lanes' V (bytes 8..15);
                 // piece (q, h) belongs at byte 4 q + 2 h of the group
                 const uint32_t U = encode8_e2m1(lo8, sb), V = encode8_e2m1(hi8, sb);
                 const auto sw = __builtin_amdgcn_permlane32_swap(U, V, false, false);
                 const uint2 o = make_uint2((sw[0] & 0xffffu) | (sw[1] << 16), (sw[0] >> 16) | (sw[1] & 0xffff0000u));
-                if (row < a.M) {
-                    const uint32_t g = cb / 32u;
-                    if (a.stages == 0) {
-                        *reinterpret_cast<uint2*>(a.codes + (uint64_t)row * (a.K / 2u) + g * 16u + 8u * h) = o;
-                        if (h == 0) a.scales[(uint64_t)row * (a.K / 32u) + g] = (uint8_t)sb;
-                    } else {
-                        *reinterpret_cast<uint2*>(a.codes + ((uint64_t)(row >> 6) * a.stages + (g >> 2)) * 4096u +
-                                                  (row & 63u) * 64u + (g & 3u) * 16u + 8u * h) = o;
-                        if (h == 0)
-                            a.scales[((uint64_t)(row >> 6) * a.sstages + (g >> 4)) * 1024u + (row & 63u) * 16u + (g & 15u)] = (uint8_t)sb;
-                    }
-                }
+                *reinterpret_cast<uint2*>(ep + m * 32u + (uint32_t)bb * 16u + 8u * h) = o;   // row m, block bb, half h
             }
         }
+        if constexpr (MODE == 2) {
+            // lane l now takes row l >> 1, block l & 1: 16 contiguous code bytes, 32 per lane pair
+            const uint4 w = *reinterpret_cast<const uint4*>(ep + lane * 16u);
+            if constexpr (IN_BF16) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // next tile landed, earlier stores done
+            const uint32_t srow = tile * 32u + (lane >> 1), g = col0 / 32u + (lane & 1u);
+            const uint32_t g0 = col0 / 32u;
+            const uint32_t s2 = sbv[0] | (sbv[1] << 8);
+            if (a.stages == 0) {
+                if (srow < a.M) *reinterpret_cast<uint4*>(a.codes + (uint64_t)srow * (a.K / 2u) + g * 16u) = w;
+                if (h == 0 && row < a.M) *reinterpret_cast<uint16_t*>(a.scales + (uint64_t)row * (a.K / 32u) + g0) = (uint16_t)s2;
+            } else {
+                if (srow < a.M)
+                    *reinterpret_cast<uint4*>(a.codes + ((uint64_t)(srow >> 6) * a.stages + (g >> 2)) * 4096u +
+                                              (srow & 63u) * 64u + (g & 3u) * 16u) = w;
+                if (h == 0 && row < a.M)
+                    *reinterpret_cast<uint16_t*>(a.scales + ((uint64_t)(row >> 6) * a.sstages + (g0 >> 4)) * 1024u +
+                                                 (row & 63u) * 16u + (g0 & 15u)) = (uint16_t)s2;
+            }
+        }
+        buf ^= 1u;
     }
 }
 
@@ -202,17 +266,18 @@ hipError_t launch_matrix_rotate(int mode, bool in_bf16, bool out_bf16, const voi
         if (e != hipSuccess) return e;
     }
     const dim3 grid((a.ncols * a.nsplits + 3u) / 4u), block(256);
+    constexpr int LDS = matrot::LDS_BYTES;
     if (mode == 0) {
         if (in_bf16) {
-            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 0, true>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((matrot::k_matrot<true, 0, false>), grid, block, 0, s, a);
+            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 0, true>), grid, block, LDS, s, a);
+            else hipLaunchKernelGGL((matrot::k_matrot<true, 0, false>), grid, block, LDS, s, a);
         } else {
-            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<false, 0, true>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((matrot::k_matrot<false, 0, false>), grid, block, 0, s, a);
+            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<false, 0, true>), grid, block, LDS, s, a);
+            else hipLaunchKernelGGL((matrot::k_matrot<false, 0, false>), grid, block, LDS, s, a);
         }
     } else {
-        if (in_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 2, false>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((matrot::k_matrot<false, 2, false>), grid, block, 0, s, a);
+        if (in_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 2, false>), grid, block, LDS, s, a);
+        else hipLaunchKernelGGL((matrot::k_matrot<false, 2, false>), grid, block, LDS, s, a);
     }
     return hipGetLastError();
 }

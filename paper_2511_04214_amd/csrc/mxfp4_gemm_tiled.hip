@@ -53,15 +53,6 @@ constexpr int LDS_BYTES = EPI_BASE + 4 * 4096;          // 163840, all of the CU
 template <int V>
 struct IC { static constexpr int value = V; };
 
-// One LDS-DMA load: 64 lanes x 16 bytes from base + voff(lane) to LDS lds_base + LDS_OFF +
-// 16 * lane (M0 carries the LDS address).  lds_base and base must be wavefront-uniform.
-template <int LDS_OFF>
-__device__ __forceinline__ void dma16(uint32_t lds_base, const uint8_t* base, uint32_t voff) {
-    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2\n\t"
-                 :: "s"(lds_base), "v"(voff), "s"(base), "n"(LDS_OFF)
-                 : "memory", "scc");
-}
-
 // Wait until at most N of this wavefront's vector-memory operations are outstanding and all
 // its LDS reads have returned, then meet the other wavefronts.
 template <int N>
@@ -76,12 +67,6 @@ __device__ __forceinline__ void wait_vm_unless_and_barrier(int skip_vm) {
                  "s_waitcnt vmcnt(%0)\n"
                  ".Lbrq_novm%=:\n\t"
                  "s_waitcnt lgkmcnt(0)\n\ts_barrier\n\t" ::"n"(N), "s"(skip_vm) : "memory", "scc");
-}
-
-__device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p) {
-    uint64_t b = (uint64_t)p;
-    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-    return (const uint8_t*)(((uint64_t)hi << 32) | lo);
 }
 
 // Tiles of one workgroup.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its
