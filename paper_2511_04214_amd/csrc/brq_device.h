@@ -216,6 +216,14 @@ __device__ __forceinline__ void dma16(uint32_t lds_base, const uint8_t* base, ui
                  : "memory", "scc", "m0");
 }
 
+// The same with the non-temporal hint, for data that is read once.
+template <int LDS_OFF>
+__device__ __forceinline__ void dma16_stream(uint32_t lds_base, const uint8_t* base, uint32_t voff) {
+    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2 nt\n\t"
+                 :: "s"(lds_base), "v"(voff), "s"(base), "n"(LDS_OFF)
+                 : "memory", "scc", "m0");
+}
+
 // A pointer that is the same in every lane, moved to scalar registers.
 __device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p) {
     uint64_t b = (uint64_t)p;

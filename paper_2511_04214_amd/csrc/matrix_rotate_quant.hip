@@ -122,14 +122,14 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
         const uint8_t* base = uniform_ptr((const uint8_t*)a.x + ((uint64_t)tile * 32u * (uint64_t)a.ldx + col0) * ES);
         const uint32_t lb = wl0 + buf * 4096u;
         if (tile * 32u + 32u <= a.M) {                // uniform
-            dma16<0>(lb, base, voff[0]); dma16<1024>(lb, base, voff[1]);
-            dma16<2048>(lb, base, voff[2]); dma16<3072>(lb, base, voff[3]);
+            dma16_stream<0>(lb, base, voff[0]); dma16_stream<1024>(lb, base, voff[1]);
+            dma16_stream<2048>(lb, base, voff[2]); dma16_stream<3072>(lb, base, voff[3]);
         } else {
             const uint32_t last = a.M - 1u - tile * 32u;
-            dma16<0>(lb, base, min(lane >> 3, last) * pitch + dsw);
-            dma16<1024>(lb, base, min(8u + (lane >> 3), last) * pitch + dsw);
-            dma16<2048>(lb, base, min(16u + (lane >> 3), last) * pitch + dsw);
-            dma16<3072>(lb, base, min(24u + (lane >> 3), last) * pitch + dsw);
+            dma16_stream<0>(lb, base, min(lane >> 3, last) * pitch + dsw);
+            dma16_stream<1024>(lb, base, min(8u + (lane >> 3), last) * pitch + dsw);
+            dma16_stream<2048>(lb, base, min(16u + (lane >> 3), last) * pitch + dsw);
+            dma16_stream<3072>(lb, base, min(24u + (lane >> 3), last) * pitch + dsw);
         }
     };
     uint32_t buf = 0;
@@ -212,18 +212,18 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
         }
         if constexpr (MODE == 2) {
             // lane l now takes row l >> 1, block l & 1: 16 contiguous code bytes, 32 per lane pair
-            const uint4 w = *reinterpret_cast<const uint4*>(ep + lane * 16u);
+            const v4i wv = *reinterpret_cast<const v4i*>(ep + lane * 16u);
             if constexpr (IN_BF16) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // next tile landed, earlier stores done
             const uint32_t srow = tile * 32u + (lane >> 1), g = col0 / 32u + (lane & 1u);
             const uint32_t g0 = col0 / 32u;
             const uint32_t s2 = sbv[0] | (sbv[1] << 8);
             if (a.stages == 0) {
-                if (srow < a.M) *reinterpret_cast<uint4*>(a.codes + (uint64_t)srow * (a.K / 2u) + g * 16u) = w;
+                if (srow < a.M) *reinterpret_cast<v4i*>(a.codes + (uint64_t)srow * (a.K / 2u) + g * 16u) = wv;
                 if (h == 0 && row < a.M) *reinterpret_cast<uint16_t*>(a.scales + (uint64_t)row * (a.K / 32u) + g0) = (uint16_t)s2;
             } else {
                 if (srow < a.M)
-                    *reinterpret_cast<uint4*>(a.codes + ((uint64_t)(srow >> 6) * a.stages + (g >> 2)) * 4096u +
-                                              (srow & 63u) * 64u + (g & 3u) * 16u) = w;
+                    *reinterpret_cast<v4i*>(a.codes + ((uint64_t)(srow >> 6) * a.stages + (g >> 2)) * 4096u +
+                                            (srow & 63u) * 64u + (g & 3u) * 16u) = wv;
                 if (h == 0 && row < a.M)
                     *reinterpret_cast<uint16_t*>(a.scales + ((uint64_t)(row >> 6) * a.sstages + (g0 >> 4)) * 1024u +
                                                  (row & 63u) * 16u + (g0 & 15u)) = (uint16_t)s2;
