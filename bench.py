@@ -235,6 +235,7 @@ def main():
 
     # ---- the rotate+quantize kernel on the shape its HBM target is quoted on
     aux = None
+    aux_m = None
     if not args.no_aux:
         del xs, codes, scales, ys, wqs, wss
         torch.cuda.empty_cache()
@@ -265,7 +266,29 @@ def main():
                "min_ms": float(ams.min()), "alg_bytes": ab, "achieved": ab / float(ams.mean()) / 1e6,
                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ab / float(ams.mean()) / 1e6 / HBM_PEAK_GBS,
                "traffic": PROFILED_TRAFFIC["rotate_quant_16384x8192"] if LAY == "tiled" else None}
-        del axs, ac, asc
+        # the same step with caller-supplied orthogonal 32x32 blocks (one per block of K) on the matrix cores
+        rng_r = np.random.default_rng(11)
+        Rb = torch.from_numpy(np.stack([np.linalg.qr(rng_r.standard_normal((32, 32)))[0]
+                                        for _ in range(aK // 32)]).astype(np.float32)).cuda()
+        for i in range(200):
+            brq.matrix_rotate_quantize_fused(axs[i % 3], Rb, codes=ac[i % 3], scales=asc[i % 3], stream=stream, layout=LAY)
+        stream.synchronize()
+        mms = []
+        for _ in range(5):
+            a, b = ev(), ev()
+            a.record(stream)
+            for i in range(args.steps):
+                brq.matrix_rotate_quantize_fused(axs[i % 3], Rb, codes=ac[i % 3], scales=asc[i % 3], stream=stream, layout=LAY)
+            b.record(stream)
+            stream.synchronize()
+            mms.append(a.elapsed_time(b) / args.steps)
+        mms = np.array(mms)
+        aux_m = {"kernel": "matrix_rotate_quantize_fused", "blocks": "%d orthogonal 32x32 fp32 matrices" % (aK // 32),
+                 "bound": "hbm", "avg_ms": float(mms.mean()), "min_ms": float(mms.min()), "alg_bytes": ab,
+                 "achieved": ab / float(mms.mean()) / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                 "frac": ab / float(mms.mean()) / 1e6 / HBM_PEAK_GBS, "traffic": None,
+                 "mfma_flops": 3 * 2.0 * aM * aK * 32}
+        del axs, ac, asc, Rb
 
     # ---- the online step with its producer fused in: silu(gate) * up -> rotation -> MXFP4 on the
     # down_proj input of the 8B MLP (8192 tokens x 14336), against the two-kernel path
@@ -377,6 +400,7 @@ def main():
         "mfma_loop_ceiling": ceiling,
         "library_baseline": library,
         "rotate_quant_16384x8192": aux,
+        "matrix_rotate_quant_16384x8192": aux_m,
         "swiglu_rotate_quant_8192x14336": aux2,
         "kernels": kernels,
         "cpu_baseline": cpu_baseline,

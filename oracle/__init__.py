@@ -65,6 +65,7 @@ def _bind(path):
     L.oracle_matrix_rotate_f64.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_matrix_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_mxfp4_encode_with_scales.argtypes = [vp, vp, i64, i64, vp]
+    L.oracle_block_stats.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i32, vp, vp, vp]
     L.oracle_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, vp]
     L.oracle_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_matmul_nt_f64.argtypes = [vp, vp, i64, i64, i64, vp]
@@ -250,6 +251,20 @@ class Oracle:
         codes = np.empty((M, K // 2), dtype=np.uint8)
         _check(self.L.oracle_mxfp4_encode_with_scales(_p(y), _p(scales), M, K, _p(codes)), "mxfp4_encode_with_scales")
         return codes
+
+    def block_stats(self, x, B, thresholds=(), signs=None):
+        """(amax [M, K/32] f32, counts [nt] u64, sqerr [M, K/32] f64) of x after the rotation with block B
+        (B = 1: no rotation)."""
+        x, M, K, ldx = _rows(x)
+        th = np.ascontiguousarray(thresholds, dtype=np.float32)
+        amax = np.empty((M, K // 32), dtype=np.float32)
+        sqerr = np.empty((M, K // 32), dtype=np.float64)
+        count = np.zeros(th.size, dtype=np.uint64)
+        sg = None if signs is None else _signs(signs, K)
+        _check(self.L.oracle_block_stats(_p(x), _dt(x), M, K, ldx, B, None if sg is None else _p(sg),
+                                         _p(th) if th.size else None, th.size, _p(amax), _p(count), _p(sqerr)),
+               "block_stats")
+        return amax, count, sqerr
 
     def mxfp4_dequantize(self, codes, scales):
         codes = np.ascontiguousarray(codes, dtype=np.uint8)

@@ -22,6 +22,9 @@
  *     that input and feed it to the same rotation and quantizer.
  *   - Eq. (1) with arbitrary orthogonal 32 x 32 blocks (oracle_matrix_rotate*): the dense
  *     per-block product in fp64.
+ *   - Sec. 4.1 / 4.2 / Appendix "Rotation Comparison": the block statistics behind the paper's
+ *     analysis (block-wise scale, share of data above a threshold, per-block MXFP4 loss),
+ *     oracle_block_stats.
  *   - Sec. 2 ("equivalent transformations"): Y = (X R)(W R)^T = X W^T, evaluated on the
  *     quantized operands: Y[m][n] = sum_k deq(A)[m][k] * deq(W)[n][k].
  *
@@ -469,6 +472,61 @@ int oracle_mxfp4_encode_with_scales(const float *y, const uint8_t *scales, int64
             codes[r * (K / 2) + j] = (uint8_t)((hi << 4) | lo); /* element 2j in the low nibble */
         }
     return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Block statistics of the paper's analysis (Sec. 4.1, 4.2 and the Appendix "Rotation
+ * Comparison"), on y = the activation after a transformation: none (B = 1), block rotation
+ * (B = 32 ...), global rotation (B = K):
+ *   amax[r][g]  = max_j |y[r][32 g + j]|        the "block-wise scale" whose distribution the
+ *                                               Appendix compares across transformations
+ *   count[t]   += #{ (r, k) : |y[r][k]| > thresholds[t] }    the share of data above a threshold
+ *                                               (Sec. 4.2: above 1.5 and above 3, before/after)
+ *   sqerr[r][g] = sum_j (y_j - deq(q(y))_j)^2   the block's MXFP4 quantization loss (Sec. 4.1,
+ *                                               4.2: loss of regular vs outlier blocks)
+ * y is the canonical fp32 rotation (oracle_block_rotate_signed); amax and the comparisons are
+ * fp32, the loss is summed in fp64.  Which blocks are "outlier blocks" is the caller's choice
+ * of a threshold on amax (the paper: the top 0.1 % of magnitudes).
+ * Any of amax, count, sqerr may be NULL.  count is accumulated into (the caller zeroes it).
+ * ---------------------------------------------------------------------------------- */
+int oracle_block_stats(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx, int64_t B, const int8_t *signs,
+                       const float *thresholds, int nt, float *amax, uint64_t *count, double *sqerr) {
+    if (!x || K % 32 || ldx < K || B < 1 || nt < 0 || (nt > 0 && count && !thresholds)) return ORACLE_ERR_ARG;
+    if (B == 1 && signs) return ORACLE_ERR_ARG;
+    size_t n = (size_t)(M > 0 ? M : 1) * (size_t)K;
+    float *y = (float *)malloc(n * sizeof(float));
+    if (!y) return ORACLE_ERR_ARG;
+    int rc = ORACLE_OK;
+    if (B == 1) {
+        for (int64_t r = 0; r < M; ++r)
+            for (int64_t k = 0; k < K; ++k) y[r * K + k] = load_elem(x, xdt, r * ldx + k);
+    } else {
+        rc = oracle_block_rotate_signed(x, xdt, M, K, ldx, B, signs, y, ORACLE_F32, K);
+    }
+    if (rc == ORACLE_OK) {
+        for (int64_t r = 0; r < M; ++r) {
+            for (int64_t g = 0; g < K / 32; ++g) {
+                const float *v = y + r * K + g * 32;
+                uint8_t codes16[16], sb;
+                quantize_group(v, codes16, &sb);
+                float am = 0.0f;
+                double loss = 0.0;
+                for (int j = 0; j < 32; ++j) {
+                    float a = fabsf(v[j]);
+                    if (a > am) am = a;
+                    for (int t = 0; t < nt && count; ++t)
+                        if (a > thresholds[t]) count[t] += 1;
+                    int code = (j & 1) ? (codes16[j / 2] >> 4) : (codes16[j / 2] & 0xF);
+                    double d = (double)v[j] - oracle_e2m1_value(code) * oracle_e8m0_value(sb);
+                    loss += d * d;
+                }
+                if (amax) amax[r * (K / 32) + g] = am;
+                if (sqerr) sqerr[r * (K / 32) + g] = loss;
+            }
+        }
+    }
+    free(y);
+    return rc;
 }
 
 /* deq[r][k] = value(code) * 2^(scale - 127), fp64 (exact). */

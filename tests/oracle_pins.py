@@ -520,6 +520,51 @@ def pin_matrix_rotation_fused_and_encode_with_scales(o):
     assert (got == 2).all()
 
 
+# --------------------------------------------------------------------------- block statistics
+
+def pin_block_stats(o):
+    # The three statistics against numpy reductions over the oracle's separately pinned rotation,
+    # quantizer and dequantizer, and against hand-worked blocks.
+    rng = np.random.default_rng(51)
+    M, K = 9, 256
+    x = (rng.standard_t(4, size=(M, K)) * 1.2).astype(np.float32)
+    x[:, [7, 130]] *= 25.0                                       # two outlier channels
+    th = np.array([0.5, 1.5, 3.0, 1.0e9], dtype=np.float32)
+    for B in (1, 32, 256):
+        y = x if B == 1 else o.block_rotate(x, B)
+        amax, count, sqerr = o.block_stats(x, B, th)
+        assert np.array_equal(amax, np.abs(y).reshape(M, K // 32, 32).max(axis=2))
+        assert np.array_equal(count, [(np.abs(y) > t).sum() for t in th])
+        c, s = o.mxfp4_quantize(y)
+        d = np.float64(y) - o.mxfp4_dequantize(c, s)
+        assert np.allclose(sqerr, (d * d).reshape(M, K // 32, 32).sum(axis=2), rtol=1e-13, atol=0)
+    # signs pass through to the rotation
+    sg = rng.choice([-1, 1], size=K).astype(np.int8)
+    a1, _, _ = o.block_stats(x, 32, (), signs=sg)
+    assert np.array_equal(a1, np.abs(o.block_rotate(x, 32, signs=sg)).reshape(M, K // 32, 32).max(axis=2))
+    # hand-worked block: values 1 (x29), 5, -7.5, 0.2 -> amax 7.5 = 1.875 * 2^2, scale 2^0;
+    # 5 ties to 4 (loss 1), -7.5 saturates to -6 (loss 2.25), 0.2 rounds to 0 (loss 0.04), ones are exact
+    blk = np.ones((1, 32), dtype=np.float32)
+    blk[0, 3], blk[0, 17], blk[0, 30] = 5.0, -7.5, 0.2
+    amax, count, sqerr = o.block_stats(blk, 1, [1.0, 0.2, 7.5, 7.4])
+    assert amax[0, 0] == 7.5
+    assert list(count) == [2, 31, 0, 1]                          # strictly greater: 1.0, 0.2 and 7.5 themselves do not count
+    assert abs(sqerr[0, 0] - (1.0 + 2.25 + np.float64(np.float32(0.2)) ** 2)) < 1e-15
+    # the paper's observations on activations with outlier channels (Sec. 4.2, Appendix): a global
+    # rotation removes the largest values but raises the share of mid-size ones and the scale of most
+    # regular blocks; a block rotation leaves the blocks without an outlier channel as they were in scale
+    X = (rng.standard_t(4, size=(64, 1024))).astype(np.float32)
+    X[:, [5, 700]] *= 40.0
+    a_none, c_none, _ = o.block_stats(X, 1, [1.5, 20.0])
+    a_glob, c_glob, _ = o.block_stats(X, 1024, [1.5, 20.0])
+    a_blk, c_blk, _ = o.block_stats(X, 32, [1.5, 20.0])
+    assert c_glob[1] < c_none[1] and c_glob[0] > 1.5 * c_none[0]
+    regular = np.ones(1024 // 32, dtype=bool)
+    regular[[5 // 32, 700 // 32]] = False
+    assert (a_glob[:, regular] > a_none[:, regular]).mean() > 0.7
+    assert np.median(a_blk[:, regular] / a_none[:, regular]) < 1.2 < np.median(a_glob[:, regular] / a_none[:, regular])
+
+
 # --------------------------------------------------------------------------- product
 
 def pin_equivalent_transformation(o):

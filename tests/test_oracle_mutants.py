@@ -69,6 +69,12 @@ MUTANTS = [
      "for (int64_t i = 0; i < M * K; ++i) yf[i] = load_elem(x, xdt, (i / K) * ldx + i % K);"),
     ("encode_nibbles_swapped", "(uint8_t)((hi << 4) | lo);", "(uint8_t)((lo << 4) | hi);"),
     ("encode_scale_per_row", "uint8_t sb = scales[r * (K / 32) + j / 16];", "uint8_t sb = scales[r * (K / 32)];"),
+    ("stats_not_strict", "if (a > thresholds[t]) count[t] += 1;", "if (a >= thresholds[t]) count[t] += 1;"),
+    ("stats_amax_signed", "float a = fabsf(v[j]);\n                    if (a > am) am = a;", "float a = v[j];\n                    if (a > am) am = a;"),
+    ("stats_loss_ignores_scale", "oracle_e2m1_value(code) * oracle_e8m0_value(sb);", "oracle_e2m1_value(code);"),
+    ("stats_loss_not_squared", "loss += d * d;", "loss += fabs(d);"),
+    ("stats_never_rotates", "    if (B == 1) {\n        for (int64_t r = 0; r < M; ++r)\n            for (int64_t k = 0; k < K; ++k) y[r * K + k]", "    if (B >= 1) {\n        for (int64_t r = 0; r < M; ++r)\n            for (int64_t k = 0; k < K; ++k) y[r * K + k]"),
+    ("stats_nibbles_swapped", "int code = (j & 1) ? (codes16[j / 2] >> 4) : (codes16[j / 2] & 0xF);", "int code = (j & 1) ? (codes16[j / 2] & 0xF) : (codes16[j / 2] >> 4);"),
     ("fused_skips_rotation", "if (rc == ORACLE_OK) rc = oracle_mxfp4_quantize(y, ORACLE_F32, M, K, K, codes, scales);",
      "rc = oracle_mxfp4_quantize(x, xdt, M, K, ldx, codes, scales);"),
 ]
