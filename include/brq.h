@@ -180,6 +180,24 @@ brq_status brq_matrix_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_
                                             void* stream);
 
 /*
+ * Block statistics of the paper's analysis (Sec. 4.1, 4.2, Appendix "Rotation Comparison") of
+ * y = x after a transformation: B = 1 none, else the block rotation of brq_block_rotate (B = K:
+ * the global rotation).  Per row and per block of 32 consecutive elements:
+ *     amax[m][g]  = max_j |y[m][32 g + j]|               (the "block-wise scale")
+ *     sqerr[m][g] = sum_j (y_j - deq(q(y))_j)^2          (the block's MXFP4 quantization loss)
+ * and over the whole matrix, for each of nt <= 8 thresholds,
+ *     count_gt[t] += #{ (m, k) : |y[m][k]| > thresholds[t] }   (strictly greater; ADDED to the
+ *                                                             counter, which the caller zeroes)
+ * amax and the comparisons are exact (fp32 values of the canonical rotation); sqerr is summed in
+ * fp32 (within 4e-6 relative of the exact sum).  Which blocks count as "outlier blocks" is the
+ * caller's threshold on amax.  thresholds is a HOST pointer read during the call; amax, sqerr
+ * (device, [M][K/32] fp32) and count_gt (device, [nt] uint64) may each be NULL.
+ */
+brq_status brq_block_stats(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx,
+                           int64_t B, const int8_t* signs, const float* thresholds, int64_t nt,
+                           float* amax, uint64_t* count_gt, float* sqerr, void* stream);
+
+/*
  * W4A4 product on MXFP4 operands (Sec. 2; Sec. 4.1 "scaling factor integrated into
  * hardware"):   y[m][n] = sum_g 2^(as[m][g]-127 + ws[n][g]-127) *
  *                          sum_{j<32} val(aq[m][32g+j]) * val(wq[n][32g+j]),  fp32 accumulate.

@@ -18,7 +18,7 @@ BRQ_F32, BRQ_BF16 = 0, 1
 LAYOUTS = {"rowmajor": 0, "tiled": 1}
 EXPORTS = ["brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
            "brq_swiglu", "brq_swiglu_rotate_quantize_fused", "brq_matrix_rotate",
-           "brq_matrix_rotate_quantize_fused", "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_strerror", "brq_version"]
+           "brq_matrix_rotate_quantize_fused", "brq_block_stats", "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_strerror", "brq_version"]
 
 _lib = None
 
@@ -54,6 +54,8 @@ def lib():
         L.brq_matrix_rotate.restype = i32
         L.brq_matrix_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp, i32, vp]
         L.brq_matrix_rotate_quantize_fused.restype = i32
+        L.brq_block_stats.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i64, vp, vp, vp, vp]
+        L.brq_block_stats.restype = i32
         L.brq_mxfp4_gemm.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp]
         L.brq_mxfp4_gemm.restype = i32
         L.brq_to_rowmajor.argtypes = [vp, vp, i64, i64, vp, vp, vp]
@@ -232,6 +234,25 @@ def matrix_rotate_quantize_fused(x, R, codes=None, scales=None, stream=None, lay
     _check(lib().brq_matrix_rotate_quantize_fused(x.data_ptr(), _dtype_code(x), M, K, ldx, R.data_ptr(), nR,
                                                   codes.data_ptr(), scales.data_ptr(), lc, _stream(stream)))
     return codes, scales
+
+
+def block_stats(x, B, thresholds=(), signs=None, counts=None, want_amax=True, want_sqerr=True, stream=None):
+    """(amax [M, K/32] f32 or None, counts [nt] int64 or None, sqerr [M, K/32] f32 or None) of x after the
+    rotation with block B (1 = none, K = global) (brq_block_stats).  `counts` is added to when given."""
+    M, K, ldx = _rows(x, "x")
+    th = (ctypes.c_float * max(1, len(thresholds)))(*[float(t) for t in thresholds])
+    amax = torch.empty((M, K // 32), dtype=torch.float32, device=x.device) if want_amax else None
+    sqerr = torch.empty((M, K // 32), dtype=torch.float32, device=x.device) if want_sqerr else None
+    if counts is None and len(thresholds):
+        counts = torch.zeros((len(thresholds),), dtype=torch.int64, device=x.device)
+    if counts is not None and not (counts.is_cuda and counts.is_contiguous() and counts.dtype == torch.int64
+                                   and counts.numel() == len(thresholds)):
+        raise ValueError("counts must be a contiguous int64 GPU tensor with one element per threshold")
+    _check(lib().brq_block_stats(x.data_ptr(), _dtype_code(x), M, K, ldx, B, _signs_ptr(signs, K), th,
+                                 len(thresholds), None if amax is None else amax.data_ptr(),
+                                 None if counts is None else counts.data_ptr(),
+                                 None if sqerr is None else sqerr.data_ptr(), _stream(stream)))
+    return amax, counts, sqerr
 
 
 def to_rowmajor(codes_tiled, scales_tiled, rows, K, stream=None):

@@ -15,9 +15,19 @@ struct Producer {
     int64_t ldu;
     bool through_bf16;   // the activation is rounded to bf16 before the rotation
 };
+// stats: outputs of mode 3 (block statistics of the transformed activation), else null.
+struct StatsOut {
+    float* amax;                  // [M][K/32] or null
+    float* sqerr;                 // [M][K/32] or null
+    unsigned long long* counts;   // [nt], added to, or null
+    int nt;                       // 0..8
+    const float* thresholds;      // host, nt values
+};
+// mode 3: statistics (log2b = 0 for "no rotation").
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
-                          bool tiled, const int8_t* signs, const Producer* prod, hipStream_t s);
+                          bool tiled, const int8_t* signs, const Producer* prod, hipStream_t s,
+                          const StatsOut* stats = nullptr);
 
 // Tiled operand whose K is not a multiple of 512: writes the K padding of rows 0..M-1 as zeros.
 hipError_t launch_zero_kpad(uint8_t* codes, uint8_t* scales, int64_t M, int64_t K, hipStream_t s);

@@ -12,7 +12,7 @@
 
 namespace brq {
 
-enum RowMode { MODE_ROTATE = 0, MODE_QUANT = 1, MODE_FUSED = 2 };
+enum RowMode { MODE_ROTATE = 0, MODE_QUANT = 1, MODE_FUSED = 2, MODE_STATS = 3 };
 
 struct RowArgs {
     const void* x;      // [M][ldx]
@@ -30,6 +30,12 @@ struct RowArgs {
     const void* x2;        // producer kernels: the `up` matrix [M][ldx2] (x is then `gate`)
     int64_t ldx2;
     uint32_t hround;       // producer kernels: the activation passes through bf16
+    // MODE_STATS outputs (any may be null) and thresholds
+    float* amax;                   // [M][K/32]
+    float* sqerr;                  // [M][K/32]
+    unsigned long long* counts;    // [nt], added to
+    uint32_t nt;
+    float th[8];
     uint32_t sign_fixed;   // the grid was sized so that a lane's column is the same in every pass
 };
 
@@ -178,12 +184,70 @@ __device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t row, u
     }
 }
 
+// ---- block statistics (Sec. 4.1, 4.2, Appendix "Rotation Comparison") ----------------------
+// For the lane's 8 (rotated) values, quad = one 32-element block: the block-wise scale max|y|, the
+// block's MXFP4 quantization loss sum (y - deq(q(y)))^2 (fp32; each difference is exact, the
+// squares and the 32-term sum round), and per threshold the number of values with |y| above it,
+// counted over the wavefront with ballots into scalar counters.
+__device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, bool live, uint32_t lane,
+                                            const RowArgs& a, uint32_t (&cnt)[8]) {
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const float am = quad_max(absmax8(y));
+    const uint32_t sb = e8m0_from_amax(am);
+    const uint32_t w = encode8_e2m1(y, sb);
+    const int ex = (int)sb - 127;
+    float e2 = 0.0f;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        f2 d;   // the two codes of byte p as fp32 (scale 1), then times 2^(sb - 127), exact
+        if (p == 0) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 0);
+        if (p == 1) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 1);
+        if (p == 2) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 2);
+        if (p == 3) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 3);
+        const float e0 = y[2 * p] - __builtin_ldexpf(d.x, ex), e1 = y[2 * p + 1] - __builtin_ldexpf(d.y, ex);
+        e2 += e0 * e0;
+        e2 += e1 * e1;
+    }
+    e2 += lane_xor<1>(e2);
+    e2 += lane_xor<2>(e2);
+    if (live && (lane & 3) == 0) {
+        if (a.amax) a.amax[gidx] = am;
+        if (a.sqerr) a.sqerr[gidx] = e2;
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        if (t < (int)a.nt) {   // uniform
+            const float th = a.th[t];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) cnt[t] += (uint32_t)__builtin_popcountll(__ballot(live && fabsf(y[i]) > th));
+        }
+    }
+}
+
+// The workgroup's wavefronts add their counters in LDS (`red`: 8 words, zeroed by the caller before
+// a barrier), then one lane per threshold adds the sum to the global counter.
+__device__ __forceinline__ void stats_flush(const uint32_t (&cnt)[8], uint32_t* red, const RowArgs& a) {
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            if (t < (int)a.nt && cnt[t]) atomicAdd(&red[t], cnt[t]);
+    }
+    __syncthreads();
+    if (threadIdx.x < a.nt && red[threadIdx.x]) atomicAdd(&a.counts[threadIdx.x], (unsigned long long)red[threadIdx.x]);
+}
+
 // One chunk per lane per step, U steps in flight (the launcher uses U = 1).  LOG2B = 0 means "no rotation":
 // the quantizer alone, or (MODE_ROTATE with a producer) the gated activation alone, stored to y.
 template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool CONTIG, int U, bool PROD>
 __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
     const uint32_t lane = threadIdx.x & 63;
     constexpr bool ROT = MODE != MODE_QUANT && LOG2B > 0;   // LOG2B = 0 with MODE_ROTATE: the producer alone
+    __shared__ uint32_t red[8];
+    uint32_t cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (MODE == MODE_STATS) {
+        if (threadIdx.x < 8) red[threadIdx.x] = 0;
+        __syncthreads();
+    }
     constexpr uint32_t inwave_bits = (LOG2B >= 3) ? ((1u << (LOG2B - 3)) - 1u) : 0u;
     const float sigma = (__builtin_popcount(lane & inwave_bits) & 1) ? -1.0f : 1.0f;
     const float cs = as_f32(norm_bits(LOG2B)) * sigma;
@@ -235,6 +299,8 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
                     char* p = (char*)a.y + chunk_offset<CONTIG>(c, a.cpr, a.ldy) * (OUT_BF16 ? 2 : 4);
                     store_chunk<OUT_BF16>(p, v[u]);
                 }
+            } else if constexpr (MODE == MODE_STATS) {
+                stats_chunk(v[u], c >> 2, live, lane, a, cnt);
             } else {
                 uint32_t sb = e8m0_from_amax(quad_max(absmax8(v[u])));
                 uint32_t w = encode8_e2m1(v[u], sb);
@@ -262,6 +328,9 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
                 }
             }
         }
+    }
+    if constexpr (MODE == MODE_STATS) {
+        if (a.counts) stats_flush(cnt, red, a);   // uniform
     }
 }
 
@@ -346,6 +415,11 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
     const int64_t xoff = (int64_t)row * a.ldx + (int64_t)blk * B;
     const int64_t xoff2 = PROD ? (int64_t)row * a.ldx2 + (int64_t)blk * B : 0;
     const float sigma = (__builtin_popcount(lane) & 1) ? -1.0f : 1.0f;
+    __shared__ uint32_t red[8];
+    uint32_t cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (MODE == MODE_STATS) {
+        if (tid < 8) red[tid] = 0;    // a barrier follows below before anyone adds
+    }
 
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
@@ -394,9 +468,14 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
         if constexpr (MODE == MODE_ROTATE) {
             int64_t yoff = (int64_t)row * a.ldy + (int64_t)blk * B + (int64_t)q * 8;
             store_chunk<OUT_BF16>((char*)a.y + yoff * (OUT_BF16 ? 2 : 4), y);
+        } else if constexpr (MODE == MODE_STATS) {
+            stats_chunk(y, (row * a.cpr + blk * (B / 8) + q) >> 2, true, lane, a, cnt);
         } else {
             quant_store(y, row, blk * (B / 8) + q, lane, a);
         }
+    }
+    if constexpr (MODE == MODE_STATS) {
+        if (a.counts) stats_flush(cnt, red, a);   // uniform
     }
 }
 
@@ -444,7 +523,7 @@ static uint32_t fix_columns(int& grid, uint32_t period, uint32_t per_wg) {
 
 template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool PROD = false>
 static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
-    if constexpr (MODE != MODE_ROTATE && LOG2B <= 7) {
+    if constexpr ((MODE == MODE_QUANT || MODE == MODE_FUSED) && LOG2B <= 7) {
         if (a.stages != 0 && (a.cpr & 15u) == 0 && a.ldx * (IN_BF16 ? 2 : 4) * 4 < (int64_t(1) << 32) &&
             (!PROD || a.ldx2 * (IN_BF16 ? 2 : 4) * 4 < (int64_t(1) << 32))) {
             const uint32_t rows = a.nchunks / a.cpr, nitems = ((rows + 3u) / 4u) * (a.cpr >> 4);
@@ -457,8 +536,12 @@ static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
     }
     constexpr int U = 1;
     int grid = rowwise_grid(a.nchunks, U);
+    if constexpr (MODE == MODE_STATS) {   // fewer, longer-lived workgroups: each ends with atomics on the counters
+        const int cap = g_rowwise_cus * 8;
+        if (grid > cap) grid = cap;
+    }
     RowArgs b = a;
-    b.sign_fixed = (a.signs && MODE != MODE_QUANT) ? fix_columns(grid, a.cpr, 256 * U) : 0;
+    b.sign_fixed = (a.signs && MODE != MODE_QUANT && LOG2B > 0) ? fix_columns(grid, a.cpr, 256 * U) : 0;
     if (contig)
         hipLaunchKernelGGL((k_rowwise<LOG2B, IN_BF16, MODE, OUT_BF16, true, U, PROD>), dim3(grid), dim3(256), 0, s, b);
     else
@@ -523,8 +606,13 @@ hipError_t launch_zero_kpad(uint8_t* codes, uint8_t* scales, int64_t M, int64_t 
 // mode: RowMode; log2b: 0 for MODE_QUANT, else 3..14.  Arguments are already validated.
 hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, const void* x, int64_t M,
                           int64_t K, int64_t ldx, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
-                          bool tiled, const int8_t* signs, const Producer* prod, hipStream_t s) {
+                          bool tiled, const int8_t* signs, const Producer* prod, hipStream_t s, const StatsOut* stats) {
     RowArgs a;
+    a.amax = stats ? stats->amax : nullptr;
+    a.sqerr = stats ? stats->sqerr : nullptr;
+    a.counts = stats ? stats->counts : nullptr;
+    a.nt = stats ? (uint32_t)stats->nt : 0u;
+    for (int t = 0; t < 8; ++t) a.th[t] = (stats && t < stats->nt) ? stats->thresholds[t] : 0.0f;
     a.x2 = prod ? prod->up : nullptr;
     a.ldx2 = prod ? prod->ldu : 0;
     a.hround = (prod && prod->through_bf16) ? 1u : 0u;
@@ -539,6 +627,13 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
     if (tiled && Kp != K && mode != MODE_ROTATE) {
         hipError_t e = launch_zero_kpad(codes, scales, M, K, s);
         if (e != hipSuccess) return e;
+    }
+    if (mode == MODE_STATS) {   // log2b = 0: no rotation
+        if (log2b == 0)
+            return in_bf16 ? launch_inwave<0, true, MODE_STATS, false>(a, contig, s)
+                           : launch_inwave<0, false, MODE_STATS, false>(a, contig, s);
+        return in_bf16 ? dispatch_b<true, MODE_STATS, false>(log2b, a, contig, M, K, s)
+                       : dispatch_b<false, MODE_STATS, false>(log2b, a, contig, M, K, s);
     }
     if (prod && mode == MODE_ROTATE) {   // the activation alone, written to y (log2b = 0)
         if (in_bf16) return out_bf16 ? launch_inwave<0, true, MODE_ROTATE, true, true>(a, contig, s)
