@@ -188,7 +188,7 @@ __device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t row, u
 // For the lane's 8 (rotated) values, quad = one 32-element block: the block-wise scale max|y|, the
 // block's MXFP4 quantization loss sum (y - deq(q(y)))^2 (fp32; each difference is exact, the
 // squares and the 32-term sum round), and per threshold the number of values with |y| above it,
-// counted over the wavefront with ballots into scalar counters.
+// counted per lane (a lane's counter cannot overflow: fewer than 2^31 chunks per launch).
 __device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, bool live, uint32_t lane,
                                             const RowArgs& a, uint32_t (&cnt)[8]) {
     typedef float f2 __attribute__((ext_vector_type(2)));
@@ -219,19 +219,17 @@ __device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, 
         if (t < (int)a.nt) {   // uniform
             const float th = a.th[t];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) cnt[t] += (uint32_t)__builtin_popcountll(__ballot(live && fabsf(y[i]) > th));
+            for (int i = 0; i < 8; ++i) cnt[t] += (live && fabsf(y[i]) > th) ? 1u : 0u;   // compare + add-with-carry
         }
     }
 }
 
-// The workgroup's wavefronts add their counters in LDS (`red`: 8 words, zeroed by the caller before
-// a barrier), then one lane per threshold adds the sum to the global counter.
+// Every lane adds its counters in LDS (`red`: 8 words, zeroed by the caller before a barrier), then
+// one lane per threshold adds the workgroup's sum to the global counter.
 __device__ __forceinline__ void stats_flush(const uint32_t (&cnt)[8], uint32_t* red, const RowArgs& a) {
-    if ((threadIdx.x & 63) == 0) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
-            if (t < (int)a.nt && cnt[t]) atomicAdd(&red[t], cnt[t]);
-    }
+    for (int t = 0; t < 8; ++t)
+        if (t < (int)a.nt && cnt[t]) atomicAdd(&red[t], cnt[t]);
     __syncthreads();
     if (threadIdx.x < a.nt && red[threadIdx.x]) atomicAdd(&a.counts[threadIdx.x], (unsigned long long)red[threadIdx.x]);
 }
@@ -401,7 +399,7 @@ __global__ void __launch_bounds__(256) k_rowwise_t4(RowArgs a, uint32_t rows, ui
 // over LDS: a lane gathers the 2^R elements {g + 512 j}, does the R stages in registers
 // and scatters them back.  Then every lane re-reads its own chunks and finishes.
 template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool PROD>
-__global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_per_row) {
+__global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_per_row, uint32_t nblocks) {
     constexpr int B = 1 << LOG2B;
     constexpr int NT = (B / 8 < 256) ? B / 8 : 256;
     constexpr int CH = B / 8 / NT;
@@ -411,68 +409,73 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
     extern __shared__ float lds[];   // B floats
 
     const uint32_t tid = threadIdx.x, lane = tid & 63;
-    const uint32_t row = blockIdx.x / blocks_per_row, blk = blockIdx.x - row * blocks_per_row;
-    const int64_t xoff = (int64_t)row * a.ldx + (int64_t)blk * B;
-    const int64_t xoff2 = PROD ? (int64_t)row * a.ldx2 + (int64_t)blk * B : 0;
     const float sigma = (__builtin_popcount(lane) & 1) ? -1.0f : 1.0f;
     __shared__ uint32_t red[8];
     uint32_t cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if constexpr (MODE == MODE_STATS) {
-        if (tid < 8) red[tid] = 0;    // a barrier follows below before anyone adds
+        if (tid < 8) red[tid] = 0;    // barriers follow below before anyone adds
     }
+    // One block per pass; the launcher gives every block its own workgroup except for the
+    // statistics, where fewer workgroups mean fewer atomics on the counters.
+    for (uint32_t bid = blockIdx.x; bid < nblocks; bid += gridDim.x) {
+        const uint32_t row = bid / blocks_per_row, blk = bid - row * blocks_per_row;
+        const int64_t xoff = (int64_t)row * a.ldx + (int64_t)blk * B;
+        const int64_t xoff2 = PROD ? (int64_t)row * a.ldx2 + (int64_t)blk * B : 0;
 
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        float v[8];
-        uint32_t q = c * NT + tid;   // chunk index inside the block
-        load_input<IN_BF16, PROD>((const char*)a.x + (xoff + (int64_t)q * 8) * (IN_BF16 ? 2 : 4),
-                                  PROD ? (const char*)a.x2 + (xoff2 + (int64_t)q * 8) * (IN_BF16 ? 2 : 4) : nullptr,
-                                  a.hround != 0, v);
-        if (a.signs) apply_signs(v, a.signs + ((size_t)blk * B + (size_t)q * 8));
-        wht_inwave<9>(v, lane);
+        for (int c = 0; c < CH; ++c) {
+            float v[8];
+            uint32_t q = c * NT + tid;   // chunk index inside the block
+            load_input<IN_BF16, PROD>((const char*)a.x + (xoff + (int64_t)q * 8) * (IN_BF16 ? 2 : 4),
+                                      PROD ? (const char*)a.x2 + (xoff2 + (int64_t)q * 8) * (IN_BF16 ? 2 : 4) : nullptr,
+                                      a.hround != 0, v);
+            if (a.signs) apply_signs(v, a.signs + ((size_t)blk * B + (size_t)q * 8));
+            wht_inwave<9>(v, lane);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] *= sigma;   // exact: back to the true sign
-        float4* dst = reinterpret_cast<float4*>(lds + q * 8);
-        dst[0] = make_float4(v[0], v[1], v[2], v[3]);
-        dst[1] = make_float4(v[4], v[5], v[6], v[7]);
-    }
-    __syncthreads();
+            for (int i = 0; i < 8; ++i) v[i] *= sigma;   // exact: back to the true sign
+            float4* dst = reinterpret_cast<float4*>(lds + q * 8);
+            dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+            dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+        }
+        __syncthreads();
 #pragma unroll
-    for (int gi = 0; gi < GROUPS_PER_LANE; ++gi) {
-        uint32_t g = gi * NT + tid;   // 0 .. 511
-        float r[RADIX];
+        for (int gi = 0; gi < GROUPS_PER_LANE; ++gi) {
+            uint32_t g = gi * NT + tid;   // 0 .. 511
+            float r[RADIX];
 #pragma unroll
-        for (int j = 0; j < RADIX; ++j) r[j] = lds[g + 512 * j];
+            for (int j = 0; j < RADIX; ++j) r[j] = lds[g + 512 * j];
 #pragma unroll
-        for (int h = 1; h < RADIX; h *= 2) {
+            for (int h = 1; h < RADIX; h *= 2) {
 #pragma unroll
-            for (int j = 0; j < RADIX; ++j) {
-                if ((j & h) == 0) {
-                    float p = r[j], m = r[j + h];
-                    r[j] = p + m;
-                    r[j + h] = p - m;
+                for (int j = 0; j < RADIX; ++j) {
+                    if ((j & h) == 0) {
+                        float p = r[j], m = r[j + h];
+                        r[j] = p + m;
+                        r[j + h] = p - m;
+                    }
                 }
             }
-        }
 #pragma unroll
-        for (int j = 0; j < RADIX; ++j) lds[g + 512 * j] = r[j];
-    }
-    __syncthreads();
-    const float cn = as_f32(norm_bits(LOG2B));
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        uint32_t q = c * NT + tid;
-        const float4* src = reinterpret_cast<const float4*>(lds + q * 8);
-        float4 lo = src[0], hi = src[1];
-        float y[8] = {lo.x * cn, lo.y * cn, lo.z * cn, lo.w * cn, hi.x * cn, hi.y * cn, hi.z * cn, hi.w * cn};
-        if constexpr (MODE == MODE_ROTATE) {
-            int64_t yoff = (int64_t)row * a.ldy + (int64_t)blk * B + (int64_t)q * 8;
-            store_chunk<OUT_BF16>((char*)a.y + yoff * (OUT_BF16 ? 2 : 4), y);
-        } else if constexpr (MODE == MODE_STATS) {
-            stats_chunk(y, (row * a.cpr + blk * (B / 8) + q) >> 2, true, lane, a, cnt);
-        } else {
-            quant_store(y, row, blk * (B / 8) + q, lane, a);
+            for (int j = 0; j < RADIX; ++j) lds[g + 512 * j] = r[j];
         }
+        __syncthreads();
+        const float cn = as_f32(norm_bits(LOG2B));
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            uint32_t q = c * NT + tid;
+            const float4* src = reinterpret_cast<const float4*>(lds + q * 8);
+            float4 lo = src[0], hi = src[1];
+            float y[8] = {lo.x * cn, lo.y * cn, lo.z * cn, lo.w * cn, hi.x * cn, hi.y * cn, hi.z * cn, hi.w * cn};
+            if constexpr (MODE == MODE_ROTATE) {
+                int64_t yoff = (int64_t)row * a.ldy + (int64_t)blk * B + (int64_t)q * 8;
+                store_chunk<OUT_BF16>((char*)a.y + yoff * (OUT_BF16 ? 2 : 4), y);
+            } else if constexpr (MODE == MODE_STATS) {
+                stats_chunk(y, (row * a.cpr + blk * (B / 8) + q) >> 2, true, lane, a, cnt);
+            } else {
+                quant_store(y, row, blk * (B / 8) + q, lane, a);
+            }
+        }
+        __syncthreads();   // the next pass overwrites the LDS this pass has just read
     }
     if constexpr (MODE == MODE_STATS) {
         if (a.counts) stats_flush(cnt, red, a);   // uniform
@@ -554,8 +557,15 @@ static hipError_t launch_lds(const RowArgs& a, int64_t M, int64_t K, hipStream_t
     constexpr int B = 1 << LOG2B;
     constexpr int NT = (B / 8 < 256) ? B / 8 : 256;
     uint32_t bpr = (uint32_t)(K / B);
-    hipLaunchKernelGGL((k_rowwise_lds<LOG2B, IN_BF16, MODE, OUT_BF16, PROD>), dim3((uint32_t)(M * bpr)), dim3(NT),
-                       B * sizeof(float), s, a, bpr);
+    const uint32_t nblocks = (uint32_t)(M * bpr);
+    uint32_t grid = nblocks;
+    if (MODE == MODE_STATS) {
+        rowwise_grid(1, 1);   // (fills g_rowwise_cus)
+        const uint32_t cap = (uint32_t)g_rowwise_cus * 8u;
+        if (grid > cap) grid = cap;
+    }
+    hipLaunchKernelGGL((k_rowwise_lds<LOG2B, IN_BF16, MODE, OUT_BF16, PROD>), dim3(grid), dim3(NT),
+                       B * sizeof(float), s, a, bpr, nblocks);
     return hipGetLastError();
 }
 
