@@ -40,7 +40,9 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3: one fp32 lane-operation p
 # 2 widenings, 22 of the activation's fixed sequence, 1.5 bf16 rounding, 5 butterfly stages + 1 normalisation,
 # 2.5 group maximum / scale / encode / zero fix
 SWIGLU_FUSED_OPS_PER_ELEM = 34.0
-PROFILED_TRAFFIC = {"mxfp4_gemm_mlp8b_bf16": 616.2e6, "rotate_quant_16384x8192": 339.7e6}
+PROFILED_TRAFFIC = {"mxfp4_gemm_mlp8b_bf16": 616.1e6, "rotate_quant_16384x8192": 339.7e6,
+                    "matrix_rotate_quant_16384x8192": 345.6e6, "block_stats_16384x8192": 302.1e6,
+                    "swiglu_rotate_quant_8192x14336": 532.2e6}
 
 
 def main():
@@ -236,6 +238,7 @@ def main():
     # ---- the rotate+quantize kernel on the shape its HBM target is quoted on
     aux = None
     aux_m = None
+    aux_s = None
     if not args.no_aux:
         del xs, codes, scales, ys, wqs, wss
         torch.cuda.empty_cache()
@@ -286,8 +289,29 @@ def main():
         aux_m = {"kernel": "matrix_rotate_quantize_fused", "blocks": "%d orthogonal 32x32 fp32 matrices" % (aK // 32),
                  "bound": "hbm", "avg_ms": float(mms.mean()), "min_ms": float(mms.min()), "alg_bytes": ab,
                  "achieved": ab / float(mms.mean()) / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                 "frac": ab / float(mms.mean()) / 1e6 / HBM_PEAK_GBS, "traffic": None,
+                 "frac": ab / float(mms.mean()) / 1e6 / HBM_PEAK_GBS,
+                 "traffic": PROFILED_TRAFFIC["matrix_rotate_quant_16384x8192"] if LAY == "tiled" else None,
                  "mfma_flops": 3 * 2.0 * aM * aK * 32}
+        # block statistics of the same activations after the block rotation (scales, loss, two thresholds)
+        st_counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+        for i in range(100):
+            brq.block_stats(axs[i % 3], B, (1.5, 3.0), counts=st_counts, stream=stream)
+        stream.synchronize()
+        sms = []
+        for _ in range(5):
+            a, b = ev(), ev()
+            a.record(stream)
+            for i in range(args.steps):
+                brq.block_stats(axs[i % 3], B, (1.5, 3.0), counts=st_counts, stream=stream)
+            b.record(stream)
+            stream.synchronize()
+            sms.append(a.elapsed_time(b) / args.steps)
+        sbytes = aM * aK * (2 + 8.0 / 32)
+        aux_s = {"kernel": "block_stats", "what": "block-wise scale + MXFP4 loss per block + counts above 1.5 and 3.0, B = 32",
+                 "bound": "hbm", "avg_ms": float(np.mean(sms)), "alg_bytes": sbytes,
+                 "achieved": sbytes / float(np.mean(sms)) / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                 "frac": sbytes / float(np.mean(sms)) / 1e6 / HBM_PEAK_GBS,
+                 "traffic": PROFILED_TRAFFIC["block_stats_16384x8192"]}
         del axs, ac, asc, Rb
 
     # ---- the online step with its producer fused in: silu(gate) * up -> rotation -> MXFP4 on the
@@ -335,7 +359,8 @@ def main():
                 "achieved": ops / res["fused"] / 1e9, "peak": VALU_PEAK_TOPS, "unit": "Tlane-op/s",
                 "frac": ops / res["fused"] / 1e9 / VALU_PEAK_TOPS,
                 "alg_bytes": sb_, "GB/s": sb_ / res["fused"] / 1e6, "frac_hbm_peak": sb_ / res["fused"] / 1e6 / HBM_PEAK_GBS,
-                "two_kernel_path_ms": res["two_kernels"], "traffic": None}
+                "two_kernel_path_ms": res["two_kernels"],
+                "traffic": PROFILED_TRAFFIC["swiglu_rotate_quant_8192x14336"] if LAY == "tiled" else None}
         del gus, sc, ss, hbuf
 
     if args.calibrate_copy:
@@ -401,6 +426,7 @@ def main():
         "library_baseline": library,
         "rotate_quant_16384x8192": aux,
         "matrix_rotate_quant_16384x8192": aux_m,
+        "block_stats_16384x8192": aux_s,
         "swiglu_rotate_quant_8192x14336": aux2,
         "kernels": kernels,
         "cpu_baseline": cpu_baseline,
