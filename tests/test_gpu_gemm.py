@@ -166,10 +166,11 @@ def test_gemm_half_tiles_several_per_workgroup(brq, orc):
 
 
 # 16 < M <= 64: the weight-streaming kernel that shares the activations through LDS (ragged M inside
-# the last 16-row tile, ragged N inside the last 64-column workgroup and 16-column wavefront, one
-# and several superstages)
+# the last 16-row tile, ragged N inside the last workgroup and wavefront, one and several
+# superstages); the shapes above 64 rows take the neighbouring code paths
 @pytest.mark.parametrize("M,N,K", [(17, 1000, 512), (32, 256, 1024), (33, 320, 1536), (64, 4096, 2048), (50, 130, 512),
-                                   (48, 64, 512), (20, 16, 3584), (63, 75, 1024)])
+                                   (48, 64, 512), (20, 16, 3584), (63, 75, 1024), (65, 1000, 512), (128, 384, 2048),
+                                   (100, 130, 1536), (96, 40, 1024)])
 def test_gemm_small_batches(brq, orc, M, N, K):
     from paper_2511_04214_amd import inputs
     aq, as_ = inputs.random_mxfp4(M, K, seed=51)
