@@ -236,13 +236,21 @@ def matrix_rotate_quantize_fused(x, R, codes=None, scales=None, stream=None, lay
     return codes, scales
 
 
-def block_stats(x, B, thresholds=(), signs=None, counts=None, want_amax=True, want_sqerr=True, stream=None):
+def block_stats(x, B, thresholds=(), signs=None, counts=None, want_amax=True, want_sqerr=True, stream=None,
+                amax=None, sqerr=None):
     """(amax [M, K/32] f32 or None, counts [nt] int64 or None, sqerr [M, K/32] f32 or None) of x after the
-    rotation with block B (1 = none, K = global) (brq_block_stats).  `counts` is added to when given."""
+    rotation with block B (1 = none, K = global) (brq_block_stats).  `counts` is added to when given;
+    `amax` / `sqerr` may be given as output tensors."""
     M, K, ldx = _rows(x, "x")
     th = (ctypes.c_float * max(1, len(thresholds)))(*[float(t) for t in thresholds])
-    amax = torch.empty((M, K // 32), dtype=torch.float32, device=x.device) if want_amax else None
-    sqerr = torch.empty((M, K // 32), dtype=torch.float32, device=x.device) if want_sqerr else None
+    for t, n in ((amax, "amax"), (sqerr, "sqerr")):
+        if t is not None and not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32
+                                  and tuple(t.shape) == (M, K // 32)):
+            raise ValueError("%s must be a contiguous float32 GPU tensor [M, K/32]" % n)
+    if amax is None and want_amax:
+        amax = torch.empty((M, K // 32), dtype=torch.float32, device=x.device)
+    if sqerr is None and want_sqerr:
+        sqerr = torch.empty((M, K // 32), dtype=torch.float32, device=x.device)
     if counts is None and len(thresholds):
         counts = torch.zeros((len(thresholds),), dtype=torch.int64, device=x.device)
     if counts is not None and not (counts.is_cuda and counts.is_contiguous() and counts.dtype == torch.int64

@@ -305,3 +305,59 @@ def test_step_in_a_hip_graph(brq):
                 step()                     # eager work between the replays
                 st.synchronize()
                 assert torch.equal(y, want)
+
+
+def test_other_entry_points_in_a_hip_graph(brq):
+    """The producer-fused step, the rotation by caller-supplied blocks (LDS-DMA loads, LDS-staged
+    stores), the small-batch product and the block statistics (atomics on caller-zeroed counters)
+    captured together in one HIP graph: every replay gives the eager result."""
+    from paper_2511_04214_amd.inputs import f32_to_bf16_bits
+    rng = np.random.default_rng(72)
+    M, N, K = 40, 640, 1024
+    w = to_dev(f32_to_bf16_bits((rng.standard_normal((N, K)) * 0.05).astype(np.float32)))
+    wct, wst = brq.rotate_quantize_fused(w, 32, layout="tiled")
+    R = to_dev(np.stack([np.linalg.qr(rng.standard_normal((32, 32)))[0] for _ in range(K // 32)]).astype(np.float32))
+    gus = [to_dev(f32_to_bf16_bits(rng.standard_normal((M, 2 * K)).astype(np.float32))) for _ in range(3)]
+    gu = gus[0].clone()
+    cb, sb = brq.operand_bytes(M, K, "tiled")
+    c1, c2 = (torch.empty((cb,), dtype=torch.uint8, device="cuda") for _ in range(2))
+    s1, s2 = (torch.empty((sb,), dtype=torch.uint8, device="cuda") for _ in range(2))
+    y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    amax = torch.empty((M, K // 32), dtype=torch.float32, device="cuda")
+    sqerr = torch.empty((M, K // 32), dtype=torch.float32, device="cuda")
+    st = torch.cuda.Stream()
+
+    def step():
+        brq.swiglu_rotate_quantize_fused(gu[:, :K], gu[:, K:], 32, h_dtype=torch.bfloat16, codes=c1, scales=s1,
+                                         layout="tiled", stream=st)
+        brq.mxfp4_gemm(c1, s1, wct, wst, out=y, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K, stream=st)
+        brq.matrix_rotate_quantize_fused(gu[:, :K], R, codes=c2, scales=s2, layout="tiled", stream=st)
+        with torch.cuda.stream(st):
+            counts.zero_()                 # a fill kernel, not a memset node
+        brq.block_stats(gu[:, K:], 32, (0.5, 2.0), counts=counts, amax=amax, sqerr=sqerr, stream=st)
+
+    def snapshot():
+        return [t.clone() for t in (y, c2, s2, counts, amax, sqerr)]
+
+    eager = []
+    for g_ in gus:
+        gu.copy_(g_)
+        torch.cuda.synchronize()
+        step()
+        st.synchronize()
+        eager.append(snapshot())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st):
+        step()
+    for rep in range(2):
+        for g_, want in zip(gus, eager):
+            gu.copy_(g_)
+            y.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for got, w_ in zip(snapshot(), want):
+                assert torch.equal(got, w_), rep
+            step()                         # eager work between the replays
+            st.synchronize()

@@ -285,3 +285,20 @@ def test_fused_down_sweep_full_size(brq, orc):
     x = inputs.make_x(cfg)
     for B in cfg["B"]:
         check_q(brq, orc, x, B)
+
+
+def test_many_rows_sampled(brq, orc):
+    # 4 194 309 rows x 128: row and chunk indices far beyond 2^21 (and a ragged last group of 4 rows),
+    # row-major and tiled; the oracle checks the first, the last and a sample of rows
+    M, K = (1 << 22) + 5, 128
+    gen = torch.Generator(device="cuda").manual_seed(900)
+    x = torch.randn((M, K), device="cuda", generator=gen).to(torch.bfloat16)
+    rng = np.random.default_rng(901)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, M - 6, M - 5, M - 4, M - 1], rng.integers(0, M, 50)]))
+    idx = torch.from_numpy(rows).cuda()
+    rc, rs = orc.rotate_quantize_fused(to_host(x[idx].contiguous()), 32)
+    c, s = brq.rotate_quantize_fused(x, 32)
+    assert np.array_equal(to_host(c[idx]), rc) and np.array_equal(to_host(s[idx]), rs)
+    ct, st_ = brq.rotate_quantize_fused(x, 32, layout="tiled")
+    c2, s2 = brq.to_rowmajor(ct, st_, M, K)
+    assert torch.equal(c2, c) and torch.equal(s2, s)
