@@ -91,6 +91,9 @@ def main():
     x_np = inputs.make_x(cfg)
     w_np = inputs.make_w(cfg)
     LAY = args.layout
+    import hashlib
+    input_sha256 = {"x": hashlib.sha256(np.ascontiguousarray(x_np).tobytes()).hexdigest(),
+                    "w": hashlib.sha256(np.ascontiguousarray(w_np).tobytes()).hexdigest()}
     wq0, ws0 = brq.rotate_quantize_fused(to_dev(w_np), B, layout=LAY)          # offline weight preparation
     del w_np
     set_bytes = M * K * BYTES_PER_ELEM + N * K * 0.53125 + gemm_M * N * out_es
@@ -430,7 +433,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: X %dx%d bf16 -> block Hadamard B=32 + MXFP4; product M=%d N=%d K=%d, %s out"
                                % (args.workload, M, K, gemm_M, N, K, args.out_dtype), "buffer_sets": nsets,
-                   "operand_layout": LAY},
+                   "operand_layout": LAY, "input_sha256": input_sha256},
         "rotate_quant_GBps": kernels["rotate_quantize_fused"]["GB/s"],
         "gemm_TFLOPs": kernels["mxfp4_gemm"]["TFLOP/s"],
         "roofline": roofline,
