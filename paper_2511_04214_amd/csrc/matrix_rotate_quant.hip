@@ -11,8 +11,9 @@
 // sum_i |x_i| |R_ij|.  The order of the additions inside an MFMA is the hardware's, so the
 // last bits are not reproducible elsewhere; parity for this kernel is stated with that bound.
 //
-// Work decomposition.  A wavefront owns 64 columns (two blocks) for the whole launch and keeps
-// the three bf16 parts of their R (48 VGPRs) in registers; it walks down the rows in tiles of 32.
+// Work decomposition.  A wavefront owns 128 columns (four blocks, one stage of the tiled layout) for
+// the whole launch and keeps the three bf16 parts of their R (96 VGPRs) in registers; it walks down
+// the rows in tiles of 32.
 // Operand layout of the 32x32x16 MFMA: lane (m = lane & 31, h = lane >> 5) supplies, as the
 // column operand, 8 consecutive k of token row m; MFMA step t = 0, 1 of a block takes
 // k = 16 h + 8 t + {0..7} (any assignment of k to lanes and steps is valid as long as R^T uses
@@ -39,7 +40,7 @@ struct Args {
     uint8_t* codes;
     uint8_t* scales;
     uint32_t stages, sstages;   // tiled output: blocks per slab; 0 = row-major
-    uint32_t ntiles, nsplits, ncols;   // row tiles of 32, row walkers per column pair, K / 64
+    uint32_t ntiles, nsplits, ncols;   // row tiles of 32, row walkers per column group, column groups (32 NB columns each)
 };
 
 // fp32 -> three bf16 (bits) with hi + mid + lo = f up to 2^-27 |f|; every remainder is exact
@@ -66,41 +67,49 @@ __device__ __forceinline__ v16f mfma_bf16(const v4i& a, const v4i& b, const v16f
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-constexpr int WAVE_LDS = 2 * 4096 + 1024;   // two operand buffers (32 rows x 128 bytes) + the code block
-constexpr int LDS_BYTES = 4 * WAVE_LDS;
+// LDS of one wavefront with NB blocks (32 NB columns): two operand buffers of 32 rows x 64 NB bytes and
+// the block the packed codes pass through (32 rows x 16 NB bytes)
+constexpr int wave_lds(int NB) { return 2 * (2048 * NB) + 512 * NB; }
 
-// MODE 0: rotation alone (y out), MODE 2: fused with the quantizer.
+// MODE 0: rotation alone (y out), MODE 2: fused with the quantizer.  NB: blocks per wavefront.
 //
 // Data movement of the bf16 path.  The texture-address unit charges a 64-lane access by the
 // cache lines it touches and merges only neighbouring lanes, and in the MFMA's operand layout
 // neighbouring lanes are different rows: loading operands straight into that layout (32 lines
 // per instruction) and storing codes from it (8 bytes per lane, rows apart) made this kernel
-// address-bound at half the memory rate.  So a tile's 32 rows x 128 bytes come in by LDS-DMA, 8
-// whole lines per instruction (lane l fetches 16-byte chunk (l & 7) ^ (row & 7) of row l >> 3 into
-// LDS slot l, the XOR spreading the MFMA-side reads over the banks), one tile ahead of the
-// arithmetic; and the packed codes go through a 1 KB LDS block so that lanes 2 r and 2 r + 1 store
-// the 32 contiguous code bytes of row r.  All LDS is private to the wavefront: no barriers.
-// Loads and stores share one counter and complete out of order with each other, so the wait for
-// the next tile's data is a wait for everything, placed just before this tile's stores: by then
-// the loads are a whole tile old and the previous stores older still.
-template <bool IN_BF16, int MODE, bool OUT_BF16>
+// address-bound at half the memory rate.  So a tile's 32 rows x 64 NB bytes come in by LDS-DMA, 8
+// whole lines per instruction (a lane fetches 16-byte chunk p ^ (row & 7) of its row into slot p,
+// the XOR spreading the MFMA-side reads over the banks), one tile ahead of the arithmetic; and
+// the packed codes go through an LDS block so that NB consecutive lanes store the 16 NB contiguous
+// code bytes of a row.  With NB = 4 a wavefront owns a whole 128-element stage: in the tiled
+// layout its 32 rows x 64 code bytes are 2 KB of contiguous, whole cache lines (with two blocks it
+// wrote half lines that the L2 had to merge with a neighbour's).  All LDS is private to the
+// wavefront: no barriers.  Loads and stores share one counter and complete out of order with each
+// other, so the wait for the next tile's data is a wait for everything, placed just before this
+// tile's stores: by then the loads are a whole tile old and the previous stores older still.
+template <bool IN_BF16, int MODE, bool OUT_BF16, int NB>
 __global__ void __launch_bounds__(256) k_matrot(Args a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr uint32_t ROWB = 64u * NB;               // bytes of a tile row (bf16)
+    constexpr uint32_t CPR = 4u * NB;                 // 16-byte chunks per tile row
+    constexpr uint32_t RPI = 64u / CPR;               // rows per LDS-DMA instruction
+    constexpr int NDMA = 32 / RPI;                    // instructions per tile
+    constexpr uint32_t TILE = 32u * ROWB;
     const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t m = lane & 31, h = lane >> 5;
     const uint32_t wid = blockIdx.x * 4u + wave;
     if (wid >= a.ncols * a.nsplits) return;          // uniform per wavefront; no barrier below
-    const uint32_t colpair = wid % a.ncols, split = wid / a.ncols;
-    const uint32_t col0 = colpair * 64u;
+    const uint32_t colgrp = wid % a.ncols, split = wid / a.ncols;
+    const uint32_t col0 = colgrp * (32u * NB);
     constexpr int ES = IN_BF16 ? 2 : 4;
-    uint8_t* const wl = lds + wave * WAVE_LDS;
+    uint8_t* const wl = lds + wave * wave_lds(NB);
     const uint32_t wl0 = (uint32_t)(uintptr_t)wl;
-    uint8_t* const ep = wl + 8192;
+    uint8_t* const ep = wl + 2 * TILE;
 
-    // R^T operands of the two blocks: lane (j = m, h), step t: R[b][16 h + 8 t + kk][j], kk = 0..7
-    v4i rp[2][2][3];
+    // R^T operands of the wavefront's blocks: lane (j = m, h), step t: R[b][16 h + 8 t + kk][j], kk = 0..7
+    v4i rp[NB][2][3];
 #pragma unroll
-    for (int bb = 0; bb < 2; ++bb) {
+    for (int bb = 0; bb < NB; ++bb) {
         const float* Rb = a.R + (a.shared ? 0u : (size_t)(col0 / 32u + bb) * 1024u);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -111,25 +120,33 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
         }
     }
 
-    // bf16: LDS-DMA of a tile into buffer `buf`.  Instruction i brings rows 8 i + (lane >> 3); the
+    // bf16: LDS-DMA of a tile into buffer `buf`.  Instruction i brings rows RPI i + lane / CPR; the
     // host checked that 32 rows of pitch fit 32 bits.  Rows past the end re-read the last row.
     const uint32_t pitch = (uint32_t)a.ldx * ES;
-    const uint32_t dsw = ((lane & 7u) ^ ((lane >> 3) & 7u)) << 4;
-    uint32_t voff[4];
+    const uint32_t rin = lane / CPR, pos = lane % CPR;
+    auto lane_off = [&](uint32_t i, uint32_t last) -> uint32_t {
+        const uint32_t row = RPI * i + rin;
+        return min(row, last) * pitch + ((pos ^ (row & 7u)) << 4);
+    };
+    uint32_t voff[NDMA];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) voff[i] = (8u * i + (lane >> 3)) * pitch + dsw;
+    for (int i = 0; i < NDMA; ++i) voff[i] = lane_off(i, 31u);
     auto dma_tile = [&](uint32_t tile, uint32_t buf) {
         const uint8_t* base = uniform_ptr((const uint8_t*)a.x + ((uint64_t)tile * 32u * (uint64_t)a.ldx + col0) * ES);
-        const uint32_t lb = wl0 + buf * 4096u;
-        if (tile * 32u + 32u <= a.M) {                // uniform
-            dma16_stream<0>(lb, base, voff[0]); dma16_stream<1024>(lb, base, voff[1]);
-            dma16_stream<2048>(lb, base, voff[2]); dma16_stream<3072>(lb, base, voff[3]);
-        } else {
-            const uint32_t last = a.M - 1u - tile * 32u;
-            dma16_stream<0>(lb, base, min(lane >> 3, last) * pitch + dsw);
-            dma16_stream<1024>(lb, base, min(8u + (lane >> 3), last) * pitch + dsw);
-            dma16_stream<2048>(lb, base, min(16u + (lane >> 3), last) * pitch + dsw);
-            dma16_stream<3072>(lb, base, min(24u + (lane >> 3), last) * pitch + dsw);
+        const uint32_t lb = wl0 + buf * TILE;
+        const bool whole = tile * 32u + 32u <= a.M;   // uniform
+        const uint32_t last = whole ? 31u : a.M - 1u - tile * 32u;
+#pragma unroll
+        for (int i = 0; i < NDMA; ++i) {
+            const uint32_t vo = whole ? voff[i] : lane_off(i, last);
+            if (i == 0) dma16_stream<0>(lb, base, vo);
+            if (i == 1) dma16_stream<1024>(lb, base, vo);
+            if (i == 2) dma16_stream<2048>(lb, base, vo);
+            if (i == 3) dma16_stream<3072>(lb, base, vo);
+            if (i == 4) dma16_stream<4096>(lb, base, vo);
+            if (i == 5) dma16_stream<5120>(lb, base, vo);
+            if (i == 6) dma16_stream<6144>(lb, base, vo);
+            if (i == 7) dma16_stream<7168>(lb, base, vo);
         }
     };
     uint32_t buf = 0;
@@ -143,12 +160,13 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
         if constexpr (IN_BF16) {
             if (tile + a.nsplits < a.ntiles) dma_tile(tile + a.nsplits, buf ^ 1u);   // uniform
         }
-        uint32_t sbv[2] = {0, 0};
+        uint32_t sbv[NB];
 #pragma unroll
-        for (int bb = 0; bb < 2; ++bb) {
+        for (int bb = 0; bb < NB; ++bb) {
+            sbv[bb] = 0;
             v16f acc = {};
             if constexpr (IN_BF16) {
-                const uint8_t* src = wl + buf * 4096u + m * 128u;
+                const uint8_t* src = wl + buf * TILE + m * ROWB;
                 const v4i x0 = *reinterpret_cast<const v4i*>(src + (((uint32_t)(bb * 4) + 2u * h) ^ (m & 7u)) * 16u);
                 const v4i x1 = *reinterpret_cast<const v4i*>(src + (((uint32_t)(bb * 4) + 2u * h + 1u) ^ (m & 7u)) * 16u);
 #pragma unroll
@@ -179,7 +197,7 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
             // acc[4 q + i] = y[row][col0 + 32 bb + 8 q + 4 h + i]
             const uint32_t cb = col0 + 32u * bb;
             if constexpr (MODE == 0) {
-                if constexpr (IN_BF16) { if (bb == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+                if constexpr (IN_BF16) { if (bb == NB - 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
                 if (row < a.M) {
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -207,26 +225,35 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
                 const uint32_t U = encode8_e2m1(lo8, sb), V = encode8_e2m1(hi8, sb);
                 const auto sw = __builtin_amdgcn_permlane32_swap(U, V, false, false);
                 const uint2 o = make_uint2((sw[0] & 0xffffu) | (sw[1] << 16), (sw[0] >> 16) | (sw[1] & 0xffff0000u));
-                *reinterpret_cast<uint2*>(ep + m * 32u + (uint32_t)bb * 16u + 8u * h) = o;   // row m, block bb, half h
+                *reinterpret_cast<uint2*>(ep + m * (16u * NB) + (uint32_t)bb * 16u + 8u * h) = o;   // row m, block bb, half h
             }
         }
         if constexpr (MODE == 2) {
-            // lane l now takes row l >> 1, block l & 1: 16 contiguous code bytes, 32 per lane pair
-            const v4i wv = *reinterpret_cast<const v4i*>(ep + lane * 16u);
+            // 16-byte piece L of the code block is row L / NB, block L % NB: lane l takes pieces l, l + 64, ...
+            v4i wv[NB / 2];
+#pragma unroll
+            for (int k = 0; k < NB / 2; ++k) wv[k] = *reinterpret_cast<const v4i*>(ep + (lane + 64u * k) * 16u);
             if constexpr (IN_BF16) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // next tile landed, earlier stores done
-            const uint32_t srow = tile * 32u + (lane >> 1), g = col0 / 32u + (lane & 1u);
             const uint32_t g0 = col0 / 32u;
-            const uint32_t s2 = sbv[0] | (sbv[1] << 8);
-            if (a.stages == 0) {
-                if (srow < a.M) *reinterpret_cast<v4i*>(a.codes + (uint64_t)srow * (a.K / 2u) + g * 16u) = wv;
-                if (h == 0 && row < a.M) *reinterpret_cast<uint16_t*>(a.scales + (uint64_t)row * (a.K / 32u) + g0) = (uint16_t)s2;
-            } else {
-                if (srow < a.M)
-                    *reinterpret_cast<v4i*>(a.codes + ((uint64_t)(srow >> 6) * a.stages + (g >> 2)) * 4096u +
-                                            (srow & 63u) * 64u + (g & 3u) * 16u) = wv;
-                if (h == 0 && row < a.M)
-                    *reinterpret_cast<uint16_t*>(a.scales + ((uint64_t)(row >> 6) * a.sstages + (g0 >> 4)) * 1024u +
-                                                 (row & 63u) * 16u + (g0 & 15u)) = (uint16_t)s2;
+#pragma unroll
+            for (int k = 0; k < NB / 2; ++k) {
+                const uint32_t piece = lane + 64u * k;
+                const uint32_t srow = tile * 32u + piece / NB, g = g0 + piece % NB;
+                if (srow < a.M) {
+                    uint8_t* dst = a.stages == 0
+                                       ? a.codes + (uint64_t)srow * (a.K / 2u) + g * 16u
+                                       : a.codes + ((uint64_t)(srow >> 6) * a.stages + (g >> 2)) * 4096u + (srow & 63u) * 64u + (g & 3u) * 16u;
+                    if constexpr (NB == 4) __builtin_nontemporal_store(wv[k], reinterpret_cast<v4i*>(dst));   // whole lines
+                    else *reinterpret_cast<v4i*>(dst) = wv[k];
+                }
+            }
+            if (h == 0 && row < a.M) {
+                uint8_t* dst = a.stages == 0 ? a.scales + (uint64_t)row * (a.K / 32u) + g0
+                                             : a.scales + ((uint64_t)(row >> 6) * a.sstages + (g0 >> 4)) * 1024u + (row & 63u) * 16u + (g0 & 15u);
+                if constexpr (NB == 4)
+                    *reinterpret_cast<uint32_t*>(dst) = sbv[0] | (sbv[1] << 8) | (sbv[2 % NB] << 16) | (sbv[3 % NB] << 24);
+                else
+                    *reinterpret_cast<uint16_t*>(dst) = (uint16_t)(sbv[0] | (sbv[1] << 8));
             }
         }
         buf ^= 1u;
@@ -255,9 +282,11 @@ hipError_t launch_matrix_rotate(int mode, bool in_bf16, bool out_bf16, const voi
     a.stages = tiled ? (uint32_t)(Kp / 128) : 0u;
     a.sstages = tiled ? (uint32_t)(Kp / 512) : 0u;
     a.ntiles = (uint32_t)((M + 31) / 32);
-    a.ncols = (uint32_t)(K / 64);
-    // about 16 wavefronts per CU; a wavefront keeps its R for at least 4 row tiles when there are that many
-    uint32_t want = (uint32_t)cus * 16u / a.ncols;
+    constexpr int NB = 4;                                  // blocks per wavefront: one 128-element stage
+    a.ncols = (uint32_t)(K / (32 * NB));
+    // about 8 wavefronts per CU (two workgroups fit its LDS); a wavefront keeps its R for at least 4 row
+    // tiles when there are that many
+    uint32_t want = (uint32_t)cus * 8u / a.ncols;
     if (want < 1) want = 1;
     const uint32_t most = (a.ntiles + 3u) / 4u;
     a.nsplits = want < most ? want : most;
@@ -265,19 +294,30 @@ hipError_t launch_matrix_rotate(int mode, bool in_bf16, bool out_bf16, const voi
         hipError_t e = launch_zero_kpad(codes, scales, M, K, s);
         if (e != hipSuccess) return e;
     }
+    constexpr int LDS = 4 * matrot::wave_lds(NB);          // 72 KB: above the default limit
+    static bool attr_set = false;
+    if (!attr_set) {
+        const void* kernels[6] = {(const void*)matrot::k_matrot<true, 0, true, NB>, (const void*)matrot::k_matrot<true, 0, false, NB>,
+                                  (const void*)matrot::k_matrot<false, 0, true, NB>, (const void*)matrot::k_matrot<false, 0, false, NB>,
+                                  (const void*)matrot::k_matrot<true, 2, false, NB>, (const void*)matrot::k_matrot<false, 2, false, NB>};
+        for (const void* k : kernels) {
+            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+            if (e != hipSuccess) return e;
+        }
+        attr_set = true;
+    }
     const dim3 grid((a.ncols * a.nsplits + 3u) / 4u), block(256);
-    constexpr int LDS = matrot::LDS_BYTES;
     if (mode == 0) {
         if (in_bf16) {
-            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 0, true>), grid, block, LDS, s, a);
-            else hipLaunchKernelGGL((matrot::k_matrot<true, 0, false>), grid, block, LDS, s, a);
+            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 0, true, NB>), grid, block, LDS, s, a);
+            else hipLaunchKernelGGL((matrot::k_matrot<true, 0, false, NB>), grid, block, LDS, s, a);
         } else {
-            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<false, 0, true>), grid, block, LDS, s, a);
-            else hipLaunchKernelGGL((matrot::k_matrot<false, 0, false>), grid, block, LDS, s, a);
+            if (out_bf16) hipLaunchKernelGGL((matrot::k_matrot<false, 0, true, NB>), grid, block, LDS, s, a);
+            else hipLaunchKernelGGL((matrot::k_matrot<false, 0, false, NB>), grid, block, LDS, s, a);
         }
     } else {
-        if (in_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 2, false>), grid, block, LDS, s, a);
-        else hipLaunchKernelGGL((matrot::k_matrot<false, 2, false>), grid, block, LDS, s, a);
+        if (in_bf16) hipLaunchKernelGGL((matrot::k_matrot<true, 2, false, NB>), grid, block, LDS, s, a);
+        else hipLaunchKernelGGL((matrot::k_matrot<false, 2, false, NB>), grid, block, LDS, s, a);
     }
     return hipGetLastError();
 }
