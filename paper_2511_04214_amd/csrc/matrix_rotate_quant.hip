@@ -78,7 +78,7 @@ constexpr int wave_lds(int NB) { return 2 * (2048 * NB) + 512 * NB; }
 // neighbouring lanes are different rows: loading operands straight into that layout (32 lines
 // per instruction) and storing codes from it (8 bytes per lane, rows apart) made this kernel
 // address-bound at half the memory rate.  So a tile's 32 rows x 64 NB bytes come in by LDS-DMA, 8
-// whole lines per instruction (a lane fetches 16-byte chunk p ^ (row & 7) of its row into slot p,
+// whole lines per instruction (a lane fetches 16-byte chunk p ^ (row & 15) of its row into slot p,
 // the XOR spreading the MFMA-side reads over the banks), one tile ahead of the arithmetic; and
 // the packed codes go through an LDS block so that NB consecutive lanes store the 16 NB contiguous
 // code bytes of a row.  With NB = 4 a wavefront owns a whole 128-element stage: in the tiled
@@ -95,6 +95,8 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
     constexpr uint32_t RPI = 64u / CPR;               // rows per LDS-DMA instruction
     constexpr int NDMA = 32 / RPI;                    // instructions per tile
     constexpr uint32_t TILE = 32u * ROWB;
+    constexpr uint32_t SWZ = CPR - 1u;                // chunk p of row i sits in slot p ^ (i & SWZ): 16 consecutive
+                                                      // rows of one chunk then cover all 64 banks
     const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t m = lane & 31, h = lane >> 5;
     const uint32_t wid = blockIdx.x * 4u + wave;
@@ -126,7 +128,7 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
     const uint32_t rin = lane / CPR, pos = lane % CPR;
     auto lane_off = [&](uint32_t i, uint32_t last) -> uint32_t {
         const uint32_t row = RPI * i + rin;
-        return min(row, last) * pitch + ((pos ^ (row & 7u)) << 4);
+        return min(row, last) * pitch + ((pos ^ (row & SWZ)) << 4);
     };
     uint32_t voff[NDMA];
 #pragma unroll
@@ -167,8 +169,8 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
             v16f acc = {};
             if constexpr (IN_BF16) {
                 const uint8_t* src = wl + buf * TILE + m * ROWB;
-                const v4i x0 = *reinterpret_cast<const v4i*>(src + (((uint32_t)(bb * 4) + 2u * h) ^ (m & 7u)) * 16u);
-                const v4i x1 = *reinterpret_cast<const v4i*>(src + (((uint32_t)(bb * 4) + 2u * h + 1u) ^ (m & 7u)) * 16u);
+                const v4i x0 = *reinterpret_cast<const v4i*>(src + (((uint32_t)(bb * 4) + 2u * h) ^ (m & SWZ)) * 16u);
+                const v4i x1 = *reinterpret_cast<const v4i*>(src + (((uint32_t)(bb * 4) + 2u * h + 1u) ^ (m & SWZ)) * 16u);
 #pragma unroll
                 for (int s = 2; s >= 0; --s) {        // smallest part first
                     acc = mfma_bf16(rp[bb][0][s], x0, acc);
