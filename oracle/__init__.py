@@ -65,7 +65,9 @@ def _bind(path):
     L.oracle_matrix_rotate_f64.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_matrix_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_mxfp4_encode_with_scales.argtypes = [vp, vp, i64, i64, vp]
-    L.oracle_block_stats.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i32, vp, vp, vp]
+    L.oracle_block_stats.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i32, vp, vp, vp, vp]
+    L.oracle_round_to_f16.argtypes = [ctypes.c_float]
+    L.oracle_round_to_f16.restype = ctypes.c_float
     L.oracle_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, vp]
     L.oracle_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_matmul_nt_f64.argtypes = [vp, vp, i64, i64, i64, vp]
@@ -252,19 +254,23 @@ class Oracle:
         _check(self.L.oracle_mxfp4_encode_with_scales(_p(y), _p(scales), M, K, _p(codes)), "mxfp4_encode_with_scales")
         return codes
 
-    def block_stats(self, x, B, thresholds=(), signs=None):
-        """(amax [M, K/32] f32, counts [nt] u64, sqerr [M, K/32] f64) of x after the rotation with block B
-        (B = 1: no rotation)."""
+    def round_to_f16(self, f):
+        return np.float32(self.L.oracle_round_to_f16(float(np.float32(f))))
+
+    def block_stats(self, x, B, thresholds=(), signs=None, want_bfp4=False):
+        """(amax [M, K/32] f32, counts [nt] u64, sqerr [M, K/32] f64[, sqerr_bfp4 [M, K/32] f64]) of x after the
+        rotation with block B (B = 1: no rotation)."""
         x, M, K, ldx = _rows(x)
         th = np.ascontiguousarray(thresholds, dtype=np.float32)
         amax = np.empty((M, K // 32), dtype=np.float32)
         sqerr = np.empty((M, K // 32), dtype=np.float64)
+        bfp4 = np.empty((M, K // 32), dtype=np.float64) if want_bfp4 else None
         count = np.zeros(th.size, dtype=np.uint64)
         sg = None if signs is None else _signs(signs, K)
         _check(self.L.oracle_block_stats(_p(x), _dt(x), M, K, ldx, B, None if sg is None else _p(sg),
-                                         _p(th) if th.size else None, th.size, _p(amax), _p(count), _p(sqerr)),
-               "block_stats")
-        return amax, count, sqerr
+                                         _p(th) if th.size else None, th.size, _p(amax), _p(count), _p(sqerr),
+                                         None if bfp4 is None else _p(bfp4)), "block_stats")
+        return (amax, count, sqerr, bfp4) if want_bfp4 else (amax, count, sqerr)
 
     def mxfp4_dequantize(self, codes, scales):
         codes = np.ascontiguousarray(codes, dtype=np.uint8)

@@ -489,8 +489,42 @@ int oracle_mxfp4_encode_with_scales(const float *y, const uint8_t *scales, int64
  * of a threshold on amax (the paper: the top 0.1 % of magnitudes).
  * Any of amax, count, sqerr may be NULL.  count is accumulated into (the caller zeroes it).
  * ---------------------------------------------------------------------------------- */
+/* fp32 -> IEEE binary16 value (returned as fp32), round to nearest even, finite results only: values
+ * beyond the largest half (65504) saturate to it.  Written out on the bit pattern. */
+float oracle_round_to_f16(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint32_t sign = u & 0x80000000u, mag = u & 0x7FFFFFFFu;
+    float a;
+    memcpy(&a, &mag, 4);
+    if (a >= 65520.0f) a = 65504.0f; /* 65520 is the midpoint to 2^16: it and everything above saturate */
+    else if (a < 6.103515625e-05f) {
+        /* below the smallest normal half (2^-14): multiples of 2^-24, nearest even */
+        a = (float)(rint((double)a * 16777216.0) / 16777216.0);
+    } else {
+        uint32_t b;
+        memcpy(&b, &a, 4);
+        uint32_t lsb = (b >> 13) & 1u;
+        b += 0xFFFu + lsb; /* keep 10 mantissa bits */
+        b &= ~0x1FFFu;
+        memcpy(&a, &b, 4);
+    }
+    uint32_t r;
+    memcpy(&r, &a, 4);
+    r |= sign;
+    memcpy(&a, &r, 4);
+    return a;
+}
+
+/* sqerr_bfp4 (optional): the same loss under the FP16-scale counterpart of MXFP4 that Sec. 3 and 4.1
+ * compare it with ("BFP4": E2M1 elements, one FP16 scale per block).  The paper does not spell the
+ * format out; taken: blocks of 32, scale s = half(fl32(amax / 6)) so that the block maximum maps onto
+ * the largest E2M1 value, element code = E2M1 rounding (ties to the even code, saturation) of
+ * fl32(y / s), dequantized value = code value * s.  s = 0 (an all-zero or vanishing block) encodes
+ * every element as 0. */
 int oracle_block_stats(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx, int64_t B, const int8_t *signs,
-                       const float *thresholds, int nt, float *amax, uint64_t *count, double *sqerr) {
+                       const float *thresholds, int nt, float *amax, uint64_t *count, double *sqerr,
+                       double *sqerr_bfp4) {
     if (!x || K % 32 || ldx < K || B < 1 || nt < 0 || (nt > 0 && count && !thresholds)) return ORACLE_ERR_ARG;
     if (B == 1 && signs) return ORACLE_ERR_ARG;
     size_t n = (size_t)(M > 0 ? M : 1) * (size_t)K;
@@ -522,6 +556,17 @@ int oracle_block_stats(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx
                 }
                 if (amax) amax[r * (K / 32) + g] = am;
                 if (sqerr) sqerr[r * (K / 32) + g] = loss;
+                if (sqerr_bfp4) {
+                    const float s = oracle_round_to_f16(am / 6.0f);
+                    double lb = 0.0;
+                    for (int j = 0; j < 32; ++j) {
+                        int code = 0;
+                        if (s > 0.0f) code = oracle_e2m1_encode(v[j] / s, 127); /* scale byte 127 = 2^0 */
+                        double d = (double)v[j] - oracle_e2m1_value(code) * (double)s;
+                        lb += d * d;
+                    }
+                    sqerr_bfp4[r * (K / 32) + g] = lb;
+                }
             }
         }
     }

@@ -565,6 +565,48 @@ def pin_block_stats(o):
     assert np.median(a_blk[:, regular] / a_none[:, regular]) < 1.2 < np.median(a_glob[:, regular] / a_none[:, regular])
 
 
+def pin_bfp4_loss(o):
+    # The FP16-scale counterpart (Sec. 3, 4.1): half-precision rounding against numpy's float16 (a
+    # conversion the oracle does not call), the loss against a composition of separately pinned
+    # parts, hand-worked blocks, and the paper's observation that the power-of-two scale loses more.
+    rng = np.random.default_rng(61)
+    f = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-9, 6, 20000),
+                        [0.0, 65504.0, 65519.9, 65520.0, 1.0e9, 6.1e-5, 5.96e-8, 2.9e-8, 3.0e-8, -1.0009765625]]).astype(np.float32)
+    want = np.clip(f.astype(np.float64), -65519.99, 65519.99).astype(np.float16).astype(np.float32)
+    want = np.where(np.abs(f) >= 65520.0, np.sign(f) * np.float32(65504.0), want)
+    got = np.array([o.round_to_f16(v) for v in f], dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    M, K = 7, 128
+    x = (rng.standard_t(4, size=(M, K)) * 1.3).astype(np.float32)
+    x[:, 9] *= 30.0
+    for B in (1, 32):
+        y = x if B == 1 else o.block_rotate(x, B)
+        amax, _, sq, sqb = o.block_stats(x, B, (), want_bfp4=True)
+        s = np.array([[o.round_to_f16(np.float32(a) / np.float32(6.0)) for a in row] for row in amax], dtype=np.float32)
+        r = (y.reshape(M, K // 32, 32) / s[:, :, None]).astype(np.float32).reshape(M, K)     # IEEE fp32 division
+        codes = o.mxfp4_encode_with_scales(r, np.full((M, K // 32), 127, dtype=np.uint8))
+        deq = o.mxfp4_dequantize(codes, np.full((M, K // 32), 127, dtype=np.uint8)) * np.repeat(np.float64(s), 32, axis=1)
+        d = np.float64(y) - deq
+        assert np.allclose(sqb, (d * d).reshape(M, K // 32, 32).sum(axis=2), rtol=1e-13, atol=0)
+    # Sec. 3, finding E: over many blocks the power-of-two scale loses more than the FP16 scale, with
+    # and without rotation
+    big = rng.standard_t(3, size=(256, 1024)).astype(np.float32)
+    for B in (1, 32):
+        _, _, sq, sqb = o.block_stats(big, B, (), want_bfp4=True)
+        assert sqb.mean() < 0.9 * sq.mean()
+    # hand-worked: maximum 7.5 -> s = 1.25: 7.5 is exactly 6 s (no saturation loss, where MXFP4 loses
+    # 2.25); the ones become 0.8 -> code 1.0 -> 1.25, each 0.0625 off in square
+    blk = np.ones((1, 32), dtype=np.float32)
+    blk[0, 17] = -7.5
+    _, _, sq, sqb = o.block_stats(blk, 1, (), want_bfp4=True)
+    assert abs(sq[0, 0] - 2.25) < 1e-15 and abs(sqb[0, 0] - 31 * 0.0625) < 1e-12
+    # an all-zero block, and one whose scale vanishes in half precision: nothing is representable
+    z = np.zeros((1, 64), dtype=np.float32)
+    z[0, 32:] = 1.0e-9
+    _, _, _, sqb = o.block_stats(z, 1, (), want_bfp4=True)
+    assert sqb[0, 0] == 0.0 and abs(sqb[0, 1] - 32 * np.float64(np.float32(1.0e-9)) ** 2) < 1e-30
+
+
 # --------------------------------------------------------------------------- product
 
 def pin_equivalent_transformation(o):

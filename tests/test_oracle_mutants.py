@@ -75,6 +75,11 @@ MUTANTS = [
     ("stats_loss_not_squared", "loss += d * d;", "loss += fabs(d);"),
     ("stats_never_rotates", "    if (B == 1) {\n        for (int64_t r = 0; r < M; ++r)\n            for (int64_t k = 0; k < K; ++k) y[r * K + k]", "    if (B >= 1) {\n        for (int64_t r = 0; r < M; ++r)\n            for (int64_t k = 0; k < K; ++k) y[r * K + k]"),
     ("stats_nibbles_swapped", "int code = (j & 1) ? (codes16[j / 2] >> 4) : (codes16[j / 2] & 0xF);", "int code = (j & 1) ? (codes16[j / 2] & 0xF) : (codes16[j / 2] >> 4);"),
+    ("bfp4_scale_max_4", "const float s = oracle_round_to_f16(am / 6.0f);", "const float s = oracle_round_to_f16(am / 4.0f);"),
+    ("bfp4_scale_not_rounded", "const float s = oracle_round_to_f16(am / 6.0f);", "const float s = am / 6.0f;"),
+    ("bfp4_dequant_without_scale", "oracle_e2m1_value(code) * (double)s;", "oracle_e2m1_value(code);"),
+    ("f16_truncates", "b += 0xFFFu + lsb; /* keep 10 mantissa bits */", "/* keep 10 mantissa bits */"),
+    ("f16_no_saturation", "if (a >= 65520.0f) a = 65504.0f;", "if (0) a = 65504.0f;"),
     ("fused_skips_rotation", "if (rc == ORACLE_OK) rc = oracle_mxfp4_quantize(y, ORACLE_F32, M, K, K, codes, scales);",
      "rc = oracle_mxfp4_quantize(x, xdt, M, K, ldx, codes, scales);"),
 ]
