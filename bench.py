@@ -320,13 +320,26 @@ def main():
             b.record(stream)
             stream.synchronize()
             sms.append(a.elapsed_time(b) / args.steps)
+        # the same call with the FP16-scale loss as a fourth output (8 divisions per 8 values more)
+        st_b = torch.empty((aM, aK // 32), dtype=torch.float32, device="cuda")
+        st_a, st_q = torch.empty_like(st_b), torch.empty_like(st_b)
+        bms = []
+        for _ in range(3):
+            a, b = ev(), ev()
+            a.record(stream)
+            for i in range(args.steps):
+                brq.block_stats(axs[i % 3], B, (1.5, 3.0), counts=st_counts, amax=st_a, sqerr=st_q, sqerr_bfp4=st_b, stream=stream)
+            b.record(stream)
+            stream.synchronize()
+            bms.append(a.elapsed_time(b) / args.steps)
         sbytes = aM * aK * (2 + 8.0 / 32)
         aux_s = {"kernel": "block_stats", "what": "block-wise scale + MXFP4 loss per block + counts above 1.5 and 3.0, B = 32",
                  "bound": "hbm", "avg_ms": float(np.mean(sms)), "alg_bytes": sbytes,
                  "achieved": sbytes / float(np.mean(sms)) / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                  "frac": sbytes / float(np.mean(sms)) / 1e6 / HBM_PEAK_GBS,
-                 "traffic": PROFILED_TRAFFIC["block_stats_16384x8192"]}
-        del axs, ac, asc, Rb
+                 "traffic": PROFILED_TRAFFIC["block_stats_16384x8192"],
+                 "with_fp16_scale_loss_ms": float(np.mean(bms))}
+        del axs, ac, asc, Rb, st_a, st_q, st_b
 
     # ---- the online step with its producer fused in: silu(gate) * up -> rotation -> MXFP4 on the
     # down_proj input of the 8B MLP (8192 tokens x 14336), against the two-kernel path

@@ -190,12 +190,19 @@ brq_status brq_matrix_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_
  *                                                             counter, which the caller zeroes)
  * amax and the comparisons are exact (fp32 values of the canonical rotation); sqerr is summed in
  * fp32 (within 4e-6 relative of the exact sum).  Which blocks count as "outlier blocks" is the
- * caller's threshold on amax.  thresholds is a HOST pointer read during the call; amax, sqerr
- * (device, [M][K/32] fp32) and count_gt (device, [nt] uint64) may each be NULL.
+ * caller's threshold on amax.
+ *     sqerr_bfp4[m][g] = the same loss under the FP16-scale counterpart that Sec. 3 (findings D, E)
+ *         and Sec. 4.1 compare MXFP4 with (E2M1 elements, one half-precision scale per block of 32;
+ *         the paper does not spell the format out, taken here): s = half(fl32(amax / 6)) rounded to
+ *         nearest even and saturating at 65504, code_j = E2M1 rounding (ties to the even code,
+ *         saturating) of fl32(y_j / s), dequantized value = val(code_j) * s; s = 0 encodes zeros.
+ * thresholds is a HOST pointer read during the call; amax, sqerr, sqerr_bfp4 (device, [M][K/32]
+ * fp32) and count_gt (device, [nt] uint64) may each be NULL.
  */
 brq_status brq_block_stats(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx,
                            int64_t B, const int8_t* signs, const float* thresholds, int64_t nt,
-                           float* amax, uint64_t* count_gt, float* sqerr, void* stream);
+                           float* amax, uint64_t* count_gt, float* sqerr, float* sqerr_bfp4,
+                           void* stream);
 
 /*
  * W4A4 product on MXFP4 operands (Sec. 2; Sec. 4.1 "scaling factor integrated into

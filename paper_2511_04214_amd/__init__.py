@@ -54,7 +54,7 @@ def lib():
         L.brq_matrix_rotate.restype = i32
         L.brq_matrix_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp, i32, vp]
         L.brq_matrix_rotate_quantize_fused.restype = i32
-        L.brq_block_stats.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i64, vp, vp, vp, vp]
+        L.brq_block_stats.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i64, vp, vp, vp, vp, vp]
         L.brq_block_stats.restype = i32
         L.brq_mxfp4_gemm.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp]
         L.brq_mxfp4_gemm.restype = i32
@@ -237,13 +237,14 @@ def matrix_rotate_quantize_fused(x, R, codes=None, scales=None, stream=None, lay
 
 
 def block_stats(x, B, thresholds=(), signs=None, counts=None, want_amax=True, want_sqerr=True, stream=None,
-                amax=None, sqerr=None):
+                amax=None, sqerr=None, sqerr_bfp4=None, want_bfp4=False):
     """(amax [M, K/32] f32 or None, counts [nt] int64 or None, sqerr [M, K/32] f32 or None) of x after the
     rotation with block B (1 = none, K = global) (brq_block_stats).  `counts` is added to when given;
-    `amax` / `sqerr` may be given as output tensors."""
+    `amax` / `sqerr` / `sqerr_bfp4` may be given as output tensors.  With want_bfp4 (or sqerr_bfp4) a fourth
+    element is returned: the loss under the FP16-scale counterpart of MXFP4."""
     M, K, ldx = _rows(x, "x")
     th = (ctypes.c_float * max(1, len(thresholds)))(*[float(t) for t in thresholds])
-    for t, n in ((amax, "amax"), (sqerr, "sqerr")):
+    for t, n in ((amax, "amax"), (sqerr, "sqerr"), (sqerr_bfp4, "sqerr_bfp4")):
         if t is not None and not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32
                                   and tuple(t.shape) == (M, K // 32)):
             raise ValueError("%s must be a contiguous float32 GPU tensor [M, K/32]" % n)
@@ -251,6 +252,9 @@ def block_stats(x, B, thresholds=(), signs=None, counts=None, want_amax=True, wa
         amax = torch.empty((M, K // 32), dtype=torch.float32, device=x.device)
     if sqerr is None and want_sqerr:
         sqerr = torch.empty((M, K // 32), dtype=torch.float32, device=x.device)
+    four = want_bfp4 or sqerr_bfp4 is not None
+    if sqerr_bfp4 is None and want_bfp4:
+        sqerr_bfp4 = torch.empty((M, K // 32), dtype=torch.float32, device=x.device)
     if counts is None and len(thresholds):
         counts = torch.zeros((len(thresholds),), dtype=torch.int64, device=x.device)
     if counts is not None and not (counts.is_cuda and counts.is_contiguous() and counts.dtype == torch.int64
@@ -259,8 +263,9 @@ def block_stats(x, B, thresholds=(), signs=None, counts=None, want_amax=True, wa
     _check(lib().brq_block_stats(x.data_ptr(), _dtype_code(x), M, K, ldx, B, _signs_ptr(signs, K), th,
                                  len(thresholds), None if amax is None else amax.data_ptr(),
                                  None if counts is None else counts.data_ptr(),
-                                 None if sqerr is None else sqerr.data_ptr(), _stream(stream)))
-    return amax, counts, sqerr
+                                 None if sqerr is None else sqerr.data_ptr(),
+                                 None if sqerr_bfp4 is None else sqerr_bfp4.data_ptr(), _stream(stream)))
+    return (amax, counts, sqerr, sqerr_bfp4) if four else (amax, counts, sqerr)
 
 
 def to_rowmajor(codes_tiled, scales_tiled, rows, K, stream=None):

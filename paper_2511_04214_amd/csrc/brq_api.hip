@@ -134,17 +134,17 @@ brq_status brq_swiglu_rotate_quantize_fused(const void* gate, const void* up, br
 
 brq_status brq_block_stats(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
                            const int8_t* signs, const float* thresholds, int64_t nt, float* amax,
-                           uint64_t* count_gt, float* sqerr, void* stream) {
+                           uint64_t* count_gt, float* sqerr, float* sqerr_bfp4, void* stream) {
     brq_status st = check_rows(x, xdt, M, K, ldx);
     if (st != BRQ_OK) return st;
     if (nt < 0 || nt > 8) return BRQ_ERR_SHAPE;
     if (nt > 0 && count_gt && !thresholds) return BRQ_ERR_NULL;
-    if (!aligned16(signs) || !aligned16(amax) || !aligned16(sqerr) || (reinterpret_cast<uintptr_t>(count_gt) & 7u))
+    if (!aligned16(signs) || !aligned16(amax) || !aligned16(sqerr) || !aligned16(sqerr_bfp4) || (reinterpret_cast<uintptr_t>(count_gt) & 7u))
         return BRQ_ERR_ALIGN;
     const int l2 = (B == 1) ? 0 : block_log2(B, K);
     if (l2 < 0 || (B == 1 && signs)) return BRQ_ERR_BLOCK;
     if (M == 0) return BRQ_OK;
-    const brq::StatsOut so{amax, sqerr, reinterpret_cast<unsigned long long*>(count_gt), count_gt ? (int)nt : 0, thresholds};
+    const brq::StatsOut so{amax, sqerr, sqerr_bfp4, reinterpret_cast<unsigned long long*>(count_gt), count_gt ? (int)nt : 0, thresholds};
     return launched(brq::launch_rowwise(3, l2, xdt == BRQ_BF16, false, x, M, K, ldx, nullptr, 0, nullptr, nullptr, false,
                                         signs, nullptr, static_cast<hipStream_t>(stream), &so));
 }
@@ -237,6 +237,6 @@ const char* brq_strerror(brq_status s) {
     return "unknown status";
 }
 
-int brq_version(void) { return 330; }
+int brq_version(void) { return 340; }
 
 }  // extern "C"

@@ -19,6 +19,7 @@ struct Producer {
 struct StatsOut {
     float* amax;                  // [M][K/32] or null
     float* sqerr;                 // [M][K/32] or null
+    float* sqerr_bfp4;            // [M][K/32] or null
     unsigned long long* counts;   // [nt], added to, or null
     int nt;                       // 0..8
     const float* thresholds;      // host, nt values

@@ -33,6 +33,7 @@ struct RowArgs {
     // MODE_STATS outputs (any may be null) and thresholds
     float* amax;                   // [M][K/32]
     float* sqerr;                  // [M][K/32]
+    float* sqerr_bfp4;             // [M][K/32]
     unsigned long long* counts;    // [nt], added to
     uint32_t nt;
     float th[8];
@@ -213,6 +214,30 @@ __device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, 
     if (live && (lane & 3) == 0) {
         if (a.amax) a.amax[gidx] = am;
         if (a.sqerr) a.sqerr[gidx] = e2;
+    }
+    if (a.sqerr_bfp4) {   // uniform
+        // The FP16-scale counterpart (Sec. 3, 4.1): scale s = half(max / 6), codes = E2M1 rounding of
+        // the correctly rounded quotient y / s, loss against code value * s (an exact product).
+        const float s = (float)(_Float16)fminf(am / 6.0f, 65504.0f);
+        float r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = (s > 0.0f) ? y[i] / s : 0.0f;
+        const uint32_t wb = encode8_e2m1(r, 127u);
+        float eb = 0.0f;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            f2 d;
+            if (p == 0) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(wb, 1.0f, 0);
+            if (p == 1) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(wb, 1.0f, 1);
+            if (p == 2) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(wb, 1.0f, 2);
+            if (p == 3) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(wb, 1.0f, 3);
+            const float e0 = y[2 * p] - d.x * s, e1 = y[2 * p + 1] - d.y * s;
+            eb += e0 * e0;
+            eb += e1 * e1;
+        }
+        eb += lane_xor<1>(eb);
+        eb += lane_xor<2>(eb);
+        if (live && (lane & 3) == 0) a.sqerr_bfp4[gidx] = eb;
     }
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
@@ -620,6 +645,7 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
     RowArgs a;
     a.amax = stats ? stats->amax : nullptr;
     a.sqerr = stats ? stats->sqerr : nullptr;
+    a.sqerr_bfp4 = stats ? stats->sqerr_bfp4 : nullptr;
     a.counts = stats ? stats->counts : nullptr;
     a.nt = stats ? (uint32_t)stats->nt : 0u;
     for (int t = 0; t < 8; ++t) a.th[t] = (stats && t < stats->nt) ? stats->thresholds[t] : 0.0f;

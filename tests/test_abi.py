@@ -58,12 +58,13 @@ def test_argument_errors_before_any_launch(L):
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), None, 0, 4, 4, 64, q(p), 0, 4, None) == NULL
     # block statistics: (x, xdt, M, K, ldx, B, signs, thresholds, nt, amax, count_gt, sqerr, stream)
     th = (ctypes.c_float * 8)()
-    assert L.brq_block_stats(None, 1, 4, 64, 64, 32, None, th, 2, q(p), q(p), q(p), None) == NULL
-    assert L.brq_block_stats(q(p), 1, 4, 64, 64, 32, None, None, 2, q(p), q(p), q(p), None) == NULL   # thresholds
-    assert L.brq_block_stats(q(p), 1, 4, 64, 64, 32, None, th, 9, q(p), q(p), q(p), None) == SHAPE    # nt > 8
-    assert L.brq_block_stats(q(p), 1, 4, 64, 64, 24, None, th, 2, q(p), q(p), q(p), None) == BLOCK
-    assert L.brq_block_stats(q(p), 1, 4, 64, 64, 32, None, th, 2, q(p), q(p + 4), q(p), None) == ALIGN
-    assert L.brq_block_stats(None, 1, 0, 64, 64, 32, None, th, 2, None, None, None, None) == OK
+    assert L.brq_block_stats(None, 1, 4, 64, 64, 32, None, th, 2, q(p), q(p), q(p), q(p), None) == NULL
+    assert L.brq_block_stats(q(p), 1, 4, 64, 64, 32, None, None, 2, q(p), q(p), q(p), q(p), None) == NULL   # thresholds
+    assert L.brq_block_stats(q(p), 1, 4, 64, 64, 32, None, th, 9, q(p), q(p), q(p), q(p), None) == SHAPE    # nt > 8
+    assert L.brq_block_stats(q(p), 1, 4, 64, 64, 24, None, th, 2, q(p), q(p), q(p), q(p), None) == BLOCK
+    assert L.brq_block_stats(q(p), 1, 4, 64, 64, 32, None, th, 2, q(p), q(p + 4), q(p), q(p), None) == ALIGN
+    assert L.brq_block_stats(q(p), 1, 4, 64, 64, 32, None, th, 2, q(p), q(p), q(p), q(p + 4), None) == ALIGN
+    assert L.brq_block_stats(None, 1, 0, 64, 64, 32, None, th, 2, None, None, None, None, None) == OK
     # caller-supplied blocks: (x, xdt, M, K, ldx, R, nR, ...)
     assert L.brq_matrix_rotate(q(p), 1, 4, 128, 128, None, 4, q(p), 0, 128, None) == NULL
     assert L.brq_matrix_rotate(q(p), 1, 4, 128, 128, q(p), 3, q(p), 0, 128, None) == BLOCK          # 1 or K/32 blocks

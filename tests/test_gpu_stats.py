@@ -33,13 +33,16 @@ def make_x(M, K, seed, dtype):
 def check(brq, orc, x, B, signs=None, xd=None):
     xd = to_dev(x) if xd is None else xd
     sg = None if signs is None else torch.from_numpy(signs).cuda()
-    amax, counts, sqerr = brq.block_stats(xd, B, TH, signs=sg)
-    ra, rc, rs = orc.block_stats(x, B, TH, signs=signs)
+    amax, counts, sqerr, bfp4 = brq.block_stats(xd, B, TH, signs=sg, want_bfp4=True)
+    ra, rc, rs, rb = orc.block_stats(x, B, TH, signs=signs, want_bfp4=True)
     assert np.array_equal(to_host(amax).view(np.uint32), ra.view(np.uint32)), "block scales differ"
     assert np.array_equal(to_host(counts).astype(np.uint64), rc), (to_host(counts), rc)
     got = to_host(sqerr).astype(np.float64)
     assert (np.abs(got - rs) <= 4e-6 * rs + 1e-44).all(), "loss off by up to %.3g relative" % float(
         (np.abs(got - rs) / (rs + 1e-300)).max())
+    got = to_host(bfp4).astype(np.float64)     # FP16-scale counterpart: same codes (fp32 decisions), fp32 sum
+    assert (np.abs(got - rb) <= 4e-6 * rb + 1e-44).all(), "FP16-scale loss off by up to %.3g relative" % float(
+        (np.abs(got - rb) / (rb + 1e-300)).max())
 
 
 @pytest.mark.parametrize("M,K,B,dtype", [(64, 512, 1, "bf16"), (64, 512, 32, "bf16"), (257, 544, 32, "bf16"),
@@ -47,6 +50,36 @@ def check(brq, orc, x, B, signs=None, xd=None):
                                          (19, 2048, 1024, "bf16"), (7, 8192, 8192, "bf16"), (301, 96, 1, "f32")])
 def test_stats_match_oracle(brq, orc, M, K, B, dtype):
     check(brq, orc, make_x(M, K, 600 + M + K + B, dtype), B)
+
+
+def test_fp16_scale_loss_at_the_ends_of_half_precision(brq, orc):
+    # blocks whose FP16 scale is a subnormal half, rounds to zero, or saturates at 65504, next to
+    # ordinary ones; and quotients on the encoder's rounding boundaries (scale exactly 1, 0.5, 1.25)
+    rng = np.random.default_rng(640)
+    M, K = 48, 256
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    mags = [1.0e-4, 3.0e-6, 2.0e-7, 1.0e-7, 1.0e-9, 3.9e5, 4.0e5, 1.0e7, 1.0e12]   # fp32 squares stay finite
+    for i, m in enumerate(mags):
+        x[i] *= np.float32(m) / 3
+    grid = np.array([0.0, 0.25, 0.5, 0.75, 1.0, 1.25, 1.5, 1.75, 2.0, 2.5, 3.0, 3.5, 4.0, 5.0, 6.0], dtype=np.float32)
+    for i, smax in enumerate((6.0, 3.0, 7.5)):
+        row = rng.choice(grid, size=K) * np.float32(smax / 6.0) * rng.choice([-1, 1], size=K)
+        row[::32] = smax                                   # every block's maximum
+        x[len(mags) + i] = row.astype(np.float32)
+    check(brq, orc, x, 1)
+    _, _, sq, sqb = brq.block_stats(to_dev(x), 1, (), want_bfp4=True)
+    assert torch.isfinite(sqb).all() and torch.isfinite(sq).all()
+
+
+def test_fp16_scale_loss_optional_and_given_output(brq, orc):
+    x = make_x(40, 512, 641, "bf16")
+    xd = to_dev(x)
+    out = torch.full((40, 16), -1.0, dtype=torch.float32, device="cuda")
+    r = brq.block_stats(xd, 32, (), sqerr_bfp4=out, want_amax=False, want_sqerr=False)
+    assert len(r) == 4 and r[0] is None and r[2] is None and r[3] is out
+    rb = orc.block_stats(x, 32, (), want_bfp4=True)[3]
+    assert (np.abs(to_host(out).astype(np.float64) - rb) <= 4e-6 * rb + 1e-44).all()
+    assert len(brq.block_stats(xd, 32, ())) == 3
 
 
 def test_stats_signed_and_strided(brq, orc):
