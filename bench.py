@@ -225,6 +225,7 @@ def main():
         b.record(stream)
         stream.synchronize()
         c_ms.append(a.elapsed_time(b) / 3)
+    c_clk = sink[:2].tolist()
     zops = torch.zeros_like(ops)
     z_ms = []
     for _ in range(3):
@@ -235,8 +236,11 @@ def main():
         b.record(stream)
         stream.synchronize()
         z_ms.append(a.elapsed_time(b) / 3)
+    z_clk = sink[:2].tolist()
     ceiling = {"TFLOP/s": c_flops / (sum(c_ms) / len(c_ms)) / 1e9,
                "frac_mxfp4_peak": c_flops / (sum(c_ms) / len(c_ms)) / 1e9 / MXFP4_PEAK_TFLOPS,
+               "shader_clock_GHz": 0.1 * c_clk[0] / max(c_clk[1], 1.0),
+               "zero_operands_shader_clock_GHz": 0.1 * z_clk[0] / max(z_clk[1], 1.0),
                "zero_operands_TFLOP/s": c_flops / (sum(z_ms) / len(z_ms)) / 1e9,
                "zero_operands_frac_mxfp4_peak": c_flops / (sum(z_ms) / len(z_ms)) / 1e9 / MXFP4_PEAK_TFLOPS,
                "note": "v_mfma_scale_f32_32x32x64 fp4 back to back from registers on every CU, operand "

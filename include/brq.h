@@ -231,7 +231,10 @@ brq_status brq_to_rowmajor(const uint8_t* codes_tiled, const uint8_t* scales_til
  * workgroups * 4 * iters * 16 * 131072 flops.  Operand fragments are read once from
  * `operands` (2048 bytes: 16 bytes per lane for each of the two operands, e.g. the first bytes
  * of a quantized matrix, so that the arithmetic sees realistic bit patterns); `sink` receives
- * workgroups * 256 floats.  Timing a launch gives the rate the chip sustains on this
+ * workgroups * 256 floats, of which sink[0] is the number of shader-clock cycles and sink[1] the
+ * number of 100 MHz reference-clock ticks that workgroup 0's first wavefront spent in the loop
+ * (10 * sink[0] / sink[1] = the clock in MHz that the chip held), the rest without meaning.
+ * Timing a launch gives the rate the chip sustains on this
  * instruction alone, the ceiling against which a product kernel's own losses can be read.
  */
 brq_status brq_diag_mfma_ceiling(const uint8_t* operands, int64_t iters, int64_t workgroups,

@@ -316,7 +316,8 @@ def mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.float32, out=None, stream=None, 
 
 
 def diag_mfma_ceiling(operands, iters, workgroups, sink=None, stream=None):
-    """Launch the MFMA-only measurement loop (brq_diag_mfma_ceiling); returns the flops it does."""
+    """Launch the MFMA-only measurement loop (brq_diag_mfma_ceiling); returns the flops it does.  After the
+    launch has finished, 0.1 * sink[0] / sink[1] is the shader clock in GHz that the chip held in the loop."""
     if not (operands.is_cuda and operands.is_contiguous() and operands.dtype == torch.uint8 and operands.numel() >= 2048):
         raise ValueError("operands must be a contiguous uint8 GPU tensor of at least 2048 bytes")
     if sink is None:

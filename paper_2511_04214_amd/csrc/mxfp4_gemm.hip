@@ -332,6 +332,11 @@ __global__ void __launch_bounds__(256, 1) k_mfma_ceiling(const uint8_t* __restri
     v16f acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = v16f{};
+    // Shader-clock cycles and 100 MHz reference ticks around the loop give the clock the chip held.
+    // The loop bound passes through an asm statement after the first pair of timestamps and the
+    // accumulators' sum through one before the second, so the loop cannot move across either.
+    const uint64_t c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+    asm volatile("" : "+s"(iters) : "s"(c0), "s"(r0));
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < 16; ++i)
@@ -342,6 +347,9 @@ __global__ void __launch_bounds__(256, 1) k_mfma_ceiling(const uint8_t* __restri
     for (int i = 0; i < 16; ++i)
 #pragma unroll
         for (int j = 0; j < 16; ++j) t += acc[i][j];
+    asm volatile("" : "+v"(t));
+    const uint64_t c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+    if (blockIdx.x == 0 && threadIdx.x < 2) t = (float)(threadIdx.x == 0 ? c1 - c0 : r1 - r0);
     sink[blockIdx.x * 256 + threadIdx.x] = t;
 }
 

@@ -189,3 +189,15 @@ def test_gemm_decode_full_size(brq, orc, M):
     aq, as_ = brq.rotate_quantize_fused(to_dev(x), 32)
     wq, ws = brq.rotate_quantize_fused(to_dev(w), 32)
     check_gemm(brq, orc, to_host(aq), to_host(as_), to_host(wq), to_host(ws))
+
+
+def test_measurement_loop_reports_its_clock(brq):
+    # the MFMA-only loop: sink[0] shader-clock cycles, sink[1] 100 MHz ticks of workgroup 0's loop
+    ops = torch.randint(0, 256, (2048,), dtype=torch.uint8, device="cuda")
+    sink = torch.zeros((8 * 256,), dtype=torch.float32, device="cuda")
+    flops = brq.diag_mfma_ceiling(ops, 400, 8, sink=sink)
+    torch.cuda.synchronize()
+    cycles, ticks = sink[:2].tolist()
+    assert flops == 8 * 4 * 400 * 16 * 131072
+    assert cycles >= 400 * 16 * 32 and ticks > 0          # at least the MFMAs' own 32 cycles apiece
+    assert 0.2 < 0.1 * cycles / ticks < 3.0               # GHz
