@@ -7,6 +7,7 @@
 // one E8M0 byte for exactly that group; accumulator register i of lane l is element
 // (row 8*(i/4) + 4*(l>>5) + i%4, column l & 31).  The 16x16x128 form: row (l & 15), group
 // (l >> 4); accumulator i is (row 4*(l>>4) + i, column l & 15).
+#include <type_traits>
 #include "brq_device.h"
 #include "brq_launch.h"
 
@@ -315,6 +316,182 @@ __global__ void __launch_bounds__(256) k_gemm_smallm(const uint8_t* __restrict__
         }
 }
 
+// ---- 64 < M <= 128 (medium decode batches): the same scheme on the 32x32x64 MFMA -------------
+// With 8 tiles of 16 rows the kernel above is bound by its LDS fragment reads (every wavefront
+// reads all of A for 16 weight rows).  Here a wavefront owns 32 weight rows, which halves the A
+// bytes read per weight row, and the persistent tiled kernel's problem at these sizes - one
+// 128 x 256 tile per CU on fewer than half of the CUs, each with only its 4-stage ring of
+// weights in flight - does not arise: 4 x N/128 wavefronts each keep three superstages of their
+// own weight rows in flight in registers.
+// Operand fragments (32x32x64: lane (r, h) = (lane & 31, lane >> 5) supplies 32 consecutive K
+// elements of row r): within a 128-element stage (64 code bytes per row) lane half h owns bytes
+// [32 h, 32 h + 32), MFMA step j of the stage takes bytes 32 h + 16 j, i.e. group 2 h + j of the
+// stage, for both operands and both scales.  A in LDS: [stage][row][64 bytes] with the 16-byte
+// chunks of row i XOR-swizzled by (i >> 2) & 3 (lanes r = 0..31 of one read then spread over all
+// banks), scales [row][16 bytes].  Output: lane (r, h) holds D[8 q + 4 h + i][r] for weight row
+// n0 + r, so the 32 lanes of a half store 32 consecutive columns of one output row.
+constexpr int smallm32_lds_bytes(int MT) { return 3 * (MT * 8192 + 4096); }
+
+// TAIL = (K / 512) % 3: the superstages left after the main loop, which takes them three at a time in
+// one basic block (no load behind a branch: the compiler's count of the outstanding weight loads is
+// then exact; with early exits inside the loop it falls back to waiting for all of them).
+template <int MT, int TAIL>
+__global__ void __launch_bounds__(256) k_gemm_smallm32(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
+                                                       int a_tiled, const uint8_t* __restrict__ wq,
+                                                       const uint8_t* __restrict__ ws, int w_tiled, int M, int N, int K,
+                                                       void* __restrict__ y, int out_bf16, int64_t ldy) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int STG = MT * 2048;                      // one stage of A codes: MT * 32 rows x 64 bytes
+    constexpr int BUF = 4 * STG + 4096;                 // codes [4 stages][MT * 32 rows][64], then scales [4 tiles][64 rows][16]
+    constexpr int NA = 2 * MT + 1;                      // LDS-DMA instructions per wavefront and superstage
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, h = lane >> 5;
+    const int n0 = blockIdx.x * 128 + wave * 32;
+    const int nss = (K + 511) / 512;                    // tiled operands are zero-padded to whole superstages
+    const int64_t Kp = (int64_t)nss * 512;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    const RowView vw(wq, ws, w_tiled != 0, min(n0 + r, N - 1), K);
+
+    const uint32_t a_cstep = a_tiled ? 4096u : 64u, a_sstep = a_tiled ? 1024u : 16u;
+    auto row_off_c = [&](int row) -> uint32_t {
+        row = min(row, M - 1);
+        return a_tiled ? (uint32_t)((row >> 6) * (Kp / 128) * 4096 + (row & 63) * 64) : (uint32_t)((int64_t)row * (K / 2));
+    };
+    auto row_off_s = [&](int row) -> uint32_t {
+        row = min(row, M - 1);
+        return a_tiled ? (uint32_t)((row >> 6) * (Kp / 512) * 1024 + (row & 63) * 16) : (uint32_t)((int64_t)row * (K / 32));
+    };
+    // one DMA instruction = 16 rows x 64 bytes; lane i brings chunk (i & 3) ^ ((i >> 4) & 3) of row i >> 2
+    uint32_t voc[2 * MT];
+#pragma unroll
+    for (int j = 0; j < 2 * MT; ++j)
+        voc[j] = row_off_c(16 * j + (lane >> 2)) + (uint32_t)((lane & 3) ^ ((lane >> 4) & 3)) * 16u;
+    // ... and one the scale rows of 32-row tile `wave` (lanes 32..63 repeat them into the second half of
+    // the tile's 1 KB slot; a wavefront without a tile of its own repeats row M - 1): every wavefront
+    // issues the same number of loads, which the counted waits below rely on
+    const uint32_t vos = row_off_s(32 * wave + r);
+    // wavefront `wave` brings stage `wave` of the superstage
+    auto dma_a = [&](int ss, uint32_t buf) {
+        const uint8_t* cb = uniform_ptr(aq + (int64_t)(4 * ss + wave) * a_cstep);
+        const uint32_t lb = lds0 + buf * BUF + (uint32_t)wave * STG;
+#pragma unroll
+        for (int j = 0; j < 2 * MT; ++j) {
+            if (j == 0) dma16<0>(lb, cb, voc[0]);
+            if (j == 1) dma16<1024>(lb, cb, voc[1]);
+            if (j == 2) dma16<2048>(lb, cb, voc[j]);
+            if (j == 3) dma16<3072>(lb, cb, voc[j]);
+            if (j == 4) dma16<4096>(lb, cb, voc[j]);
+            if (j == 5) dma16<5120>(lb, cb, voc[j]);
+            if (j == 6) dma16<6144>(lb, cb, voc[j]);
+            if (j == 7) dma16<7168>(lb, cb, voc[j]);
+        }
+        dma16<0>(lds0 + buf * BUF + 4 * STG + (uint32_t)wave * 1024, uniform_ptr(as + (int64_t)ss * a_sstep), vos);
+    };
+    // a superstage of this lane's weight row: per stage t its two steps (32 bytes at 32 h), and the 16 scale bytes.
+    // Plain loads: one instruction takes half of every cache line it touches and the next one the other half,
+    // and a streaming load does not leave the line in the cache for it (the weights would cross HBM twice).
+    auto load_w = [&](int ss, v4i (&c)[8], v4i& sc) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                c[2 * t + j] = *reinterpret_cast<const v4i*>(vw.codes + (int64_t)(4 * ss + t) * vw.cstep + h * 32 + j * 16);
+        sc = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(vw.scales + (int64_t)ss * vw.sstep));
+    };
+    v16f acc[MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j) acc[j] = v16f{};
+    const uint32_t sw = (uint32_t)(r >> 2) & 3u;
+    // The 8 steps (stage t, half-step j) of a superstage, each over the MT row tiles: consecutive MFMAs go
+    // to different accumulators, and the A fragments of step s + 1 are read while those of step s multiply.
+    auto superstage = [&](uint32_t buf, const v4i (&c)[8], const v4i& sc) {
+        const uint8_t* cb = lds + buf * BUF + r * 64;
+        const uint8_t* sb = lds + buf * BUF + 4 * STG + r * 16;
+        v4i asc[MT], af[2][MT];
+#pragma unroll
+        for (int jt = 0; jt < MT; ++jt) asc[jt] = *reinterpret_cast<const v4i*>(sb + jt * 1024);
+        auto read_step = [&](int st, v4i (&f)[MT]) {
+            const int t = st >> 1, j = st & 1;
+#pragma unroll
+            for (int jt = 0; jt < MT; ++jt)
+                f[jt] = *reinterpret_cast<const v4i*>(cb + t * STG + jt * 2048 + (((uint32_t)(2 * h + j) ^ sw) << 4));
+        };
+        read_step(0, af[0]);
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+            const int t = st >> 1, j = st & 1;
+            if (st + 1 < 8) read_step(st + 1, af[(st + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);   // keeps the reads ahead of this step's MFMAs
+            // group 4 t + 2 h + j of the superstage: byte 2 h + j of scale dword t
+            const int scb = (int)(((uint32_t)sc[t] >> (16 * h + 8 * j)) & 0xffu);
+            v8i b = {};
+            b[0] = c[st][0]; b[1] = c[st][1]; b[2] = c[st][2]; b[3] = c[st][3];
+#pragma unroll
+            for (int jt = 0; jt < MT; ++jt) {
+                v8i a = {};
+                a[0] = af[st & 1][jt][0]; a[1] = af[st & 1][jt][1]; a[2] = af[st & 1][jt][2]; a[3] = af[st & 1][jt][3];
+                const int sca = (int)(((uint32_t)asc[jt][t] >> (16 * h + 8 * j)) & 0xffu);
+                acc[jt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[jt], 4, 4, 0, sca, 0, scb);
+            }
+        }
+    };
+    // Issue order per wavefront: A(0), W(0), A(1), W(1); then turn ss issues A(ss + 2), W(ss + 2) - A into the
+    // third LDS buffer, W into the register set that turn ss - 1 consumed - and computes superstage ss.
+    // Loads return in order: at the top of turn ss everything younger than W(ss) is the NA + 9 loads of
+    // superstage ss + 1, so waiting until at most that many are outstanding means A(ss) and W(ss) have
+    // landed while a whole superstage stays in flight across the barrier.  Every turn of the main loop
+    // issues its loads, past the end of K those of the last superstage once more (into a free buffer and
+    // register set, and out of the L2), so the turns are all alike; the TAIL turns after it issue none.
+    v4i c0[8], c1[8], c2[8], s0, s1, s2;
+    dma_a(0, 0);
+    load_w(0, c0, s0);
+    dma_a(min(1, nss - 1), 1);
+    load_w(min(1, nss - 1), c1, s1);
+    auto turn = [&](auto HasNext, auto Issue, int ss, uint32_t buf, const v4i (&c)[8], const v4i& sc, v4i (&cn)[8], v4i& sn) {
+        if constexpr (decltype(HasNext)::value) asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(NA + 9) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        // The compiler counts only the weight loads it can see, not the LDS-DMA ones: where it first needs
+        // W(ss) it waits until no more loads are outstanding than the weight loads it knows to be younger.
+        // Asking for W(ss) here, before this turn's loads are issued, makes that count the 9 of W(ss + 1)
+        // (which also asks for A(ss + 1), fetched from the L2 a whole turn ago); asked for after them it
+        // would be 18, less than the 18 + NA really outstanding, and W(ss + 1) would have to land first.
+        asm volatile("" ::"v"(c[0]), "v"(c[1]), "v"(c[2]), "v"(c[3]), "v"(c[4]), "v"(c[5]), "v"(c[6]), "v"(c[7]), "v"(sc));
+        // (scheduling fences: without them the compiler sinks the weight loads below the turn's MFMAs and
+        // lifts the next turn's scale arithmetic, which needs the youngest load, up into this one)
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(Issue)::value) {
+            const int nx = min(ss + 2, nss - 1);
+            dma_a(nx, (buf + 2) % 3);
+            load_w(nx, cn, sn);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        superstage(buf, c, sc);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using Yes = std::true_type;
+    using No = std::false_type;
+    int ss = 0;
+    for (; ss + 3 <= nss; ss += 3) {
+        turn(Yes{}, Yes{}, ss, 0, c0, s0, c2, s2);
+        turn(Yes{}, Yes{}, ss + 1, 1, c1, s1, c0, s0);
+        turn(Yes{}, Yes{}, ss + 2, 2, c2, s2, c1, s1);
+    }
+    // TAIL superstages are left; the loads of superstage ss + 1, real or repeated, are in flight
+    if constexpr (TAIL >= 1) turn(Yes{}, No{}, ss, 0, c0, s0, c2, s2);
+    if constexpr (TAIL >= 2) turn(No{}, No{}, ss + 1, 1, c1, s1, c0, s0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated loads land before the LDS is released
+    const int col = n0 + r;
+#pragma unroll
+    for (int jt = 0; jt < MT; ++jt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = 32 * jt + 8 * q + 4 * h + i;
+                if (row < M && col < N) store_out(y, out_bf16, (int64_t)row * ldy + col, acc[jt][4 * q + i]);
+            }
+}
+
 // ---- measurement aid: the block-scaled fp4 MFMA back to back from registers ------------------
 // 4 wavefronts per workgroup, one per SIMD, 16 independent 32x32 accumulators each; operands are
 // 16 bytes per lane from `operands` (W fragment from bytes [0, 1024), A fragment from [1024, 2048)),
@@ -372,6 +549,28 @@ hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int6
         else
             hipLaunchKernelGGL(k_gemm_smallm<4>, grid, block, smallm_lds_bytes(4), s, a.codes, a.scales, (int)a.tiled,
                                w.codes, w.scales, (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
+        return hipGetLastError();
+    }
+    if (M > 64 && M <= 128 && (K == Kp || (a.tiled && w.tiled)) && Kp < (int64_t(1) << 26)) {
+        // medium batches: the same on the 32x32x64 MFMA, a wavefront per 32 weight rows
+        using Kern = void (*)(const uint8_t*, const uint8_t*, int, const uint8_t*, const uint8_t*, int, int, int, int, void*,
+                              int, int64_t);
+        static const Kern kern[2][3] = {{k_gemm_smallm32<3, 0>, k_gemm_smallm32<3, 1>, k_gemm_smallm32<3, 2>},
+                                        {k_gemm_smallm32<4, 0>, k_gemm_smallm32<4, 1>, k_gemm_smallm32<4, 2>}};
+        static bool attr_set = false;
+        if (!attr_set) {
+            for (int m = 0; m < 2; ++m)
+                for (int t = 0; t < 3; ++t) {
+                    hipError_t e = hipFuncSetAttribute((const void*)kern[m][t], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       smallm32_lds_bytes(3 + m));
+                    if (e != hipSuccess) return e;
+                }
+            attr_set = true;
+        }
+        const int mi = M <= 96 ? 0 : 1, tail = (int)((Kp / 512) % 3);
+        const dim3 grid((uint32_t)((N + 127) / 128)), block(256);
+        hipLaunchKernelGGL(kern[mi][tail], grid, block, smallm32_lds_bytes(3 + mi), s, a.codes, a.scales, (int)a.tiled,
+                           w.codes, w.scales, (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
         return hipGetLastError();
     }
     if (M > 16 && tiled_gemm_supported(M, N, K, out_bf16, ldy, a.tiled && w.tiled)) {
