@@ -190,146 +190,26 @@ __global__ void __launch_bounds__(64) k_gemm_skinny_stream(const uint8_t* __rest
     }
 }
 
-// ---- 16 < M <= 64 (small decode batches): weight streaming with the activations in LDS ------
-// Like the kernel above a wavefront owns 16 weight rows for the whole of K and streams them
-// through registers, three superstages in rotation; but with MT tiles of 16 activation rows
-// every wavefront would re-read all of A (M x K/2 bytes, against its own 16 x K/2 of weights),
-// so the 4 wavefronts of a workgroup share the activations: one 512-element superstage of A
-// (MT x 16 rows x 256 code bytes + 16 scale bytes per row) goes into LDS by LDS-DMA, double
-// buffered, wavefront w bringing stage w of every tile; one barrier per superstage.  The LDS
-// image of a stage is [row][64 bytes], so a tile's fragment read (row = lane & 15, 16 bytes at
-// (lane >> 4) * 16) covers 1 KB linearly.  Loads return in order: the DMA of the next superstage
-// is always followed by the 5 weight loads of a later one, which is what the counted wait relies
-// on (and the compiler's own counts for the weight registers can only be too strict).
-constexpr int smallm_lds_bytes(int MT) { return 2 * (MT * 4096 + ((MT + 3) / 4) * 1024); }
-
-template <int MT>
-__global__ void __launch_bounds__(256) k_gemm_smallm(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
-                                                     int a_tiled, const uint8_t* __restrict__ wq,
-                                                     const uint8_t* __restrict__ ws, int w_tiled, int M, int N, int K,
-                                                     void* __restrict__ y, int out_bf16, int64_t ldy) {
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    constexpr int NSC = (MT + 3) / 4;                   // scale loads per superstage (64 rows x 16 bytes each)
-    constexpr int BUF = MT * 4096 + NSC * 1024;         // codes [4 stages][MT * 16 rows][64], then scales [NSC * 64 rows][16]
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int r = lane & 15, kq = lane >> 4;
-    const int n0 = blockIdx.x * 64 + wave * 16;
-    const int nss = (K + 511) / 512;                    // tiled operands are zero-padded to whole superstages
-    const int64_t Kp = (int64_t)nss * 512;
-    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
-    const RowView vw(wq, ws, w_tiled != 0, min(n0 + r, N - 1), K);
-
-    // A by LDS-DMA: per-lane offsets from the operand's base (the host checked that they fit 32 bits)
-    const uint32_t a_cstep = a_tiled ? 4096u : 64u, a_sstep = a_tiled ? 1024u : 16u;
-    auto row_off_c = [&](int row) -> uint32_t {
-        row = min(row, M - 1);
-        return a_tiled ? (uint32_t)((row >> 6) * (Kp / 128) * 4096 + (row & 63) * 64) : (uint32_t)((int64_t)row * (K / 2));
-    };
-    auto row_off_s = [&](int row) -> uint32_t {
-        row = min(row, M - 1);
-        return a_tiled ? (uint32_t)((row >> 6) * (Kp / 512) * 1024 + (row & 63) * 16) : (uint32_t)((int64_t)row * (K / 32));
-    };
-    uint32_t voc[MT], vos[NSC];
-#pragma unroll
-    for (int j = 0; j < MT; ++j) voc[j] = row_off_c(16 * j + (lane >> 2)) + (uint32_t)(lane & 3) * 16u;
-#pragma unroll
-    for (int i = 0; i < NSC; ++i) vos[i] = row_off_s(64 * i + lane);
-    // wavefront `wave` brings stage `wave` of every tile; wavefronts 0 .. NSC-1 one scale load each
-    auto dma_a = [&](int ss, uint32_t buf) {
-        const uint8_t* cb = uniform_ptr(aq + (int64_t)(4 * ss + wave) * a_cstep);
-        const uint32_t lb = lds0 + buf * BUF + (uint32_t)wave * (MT * 1024);
-#pragma unroll
-        for (int j = 0; j < MT; ++j) {
-            if (j == 0) dma16<0>(lb, cb, voc[0]);
-            if (j == 1) dma16<1024>(lb, cb, voc[1]);
-            if (j == 2) dma16<2048>(lb, cb, voc[j]);
-            if (j == 3) dma16<3072>(lb, cb, voc[j]);
-            if (j == 4) dma16<4096>(lb, cb, voc[j]);
-            if (j == 5) dma16<5120>(lb, cb, voc[j]);
-            if (j == 6) dma16<6144>(lb, cb, voc[j]);
-            if (j == 7) dma16<7168>(lb, cb, voc[j]);
-        }
-        if (wave < NSC) {   // uniform
-            const uint8_t* sb = uniform_ptr(as + (int64_t)ss * a_sstep);
-            const uint32_t ls = lds0 + buf * BUF + MT * 4096;
-            if (wave == 0) dma16<0>(ls, sb, vos[0]);
-            if constexpr (NSC > 1) { if (wave == 1) dma16<1024>(ls, sb, vos[1]); }
-        }
-    };
-    auto load_w = [&](int ss, v4i (&c)[4], v4i& sc) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-            c[t] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(vw.codes + (int64_t)(4 * ss + t) * vw.cstep + kq * 16));
-        sc = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(vw.scales + (int64_t)ss * vw.sstep));
-    };
-    v4f acc[MT];
-#pragma unroll
-    for (int j = 0; j < MT; ++j) acc[j] = v4f{};
-    auto superstage = [&](uint32_t buf, const v4i (&c)[4], const v4i& sc) {
-        const uint8_t* cb = lds + buf * BUF + r * 64 + kq * 16;
-        const uint8_t* sb = lds + buf * BUF + MT * 4096 + r * 16;
-#pragma unroll
-        for (int j = 0; j < MT; ++j) {
-            const v4i asc = *reinterpret_cast<const v4i*>(sb + j * 256);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const v4i ac = *reinterpret_cast<const v4i*>(cb + t * (MT * 1024) + j * 1024);
-                v8i a = {}, b = {};
-                a[0] = ac[0]; a[1] = ac[1]; a[2] = ac[2]; a[3] = ac[3];
-                b[0] = c[t][0]; b[1] = c[t][1]; b[2] = c[t][2]; b[3] = c[t][3];
-                const int sca = (int)(((uint32_t)asc[t] >> (8 * kq)) & 0xffu);
-                const int scb = (int)(((uint32_t)sc[t] >> (8 * kq)) & 0xffu);
-                acc[j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc[j], 4, 4, 0, sca, 0, scb);
-            }
-        }
-    };
-    // Issue order per wavefront: A(0), W(0), W(1); then in turn ss: A(ss + 1), W(ss + 2).  At the top of
-    // turn ss the loads younger than A(ss) are the 5 of W(ss + 1), if that superstage exists: waiting
-    // until at most 5 are outstanding means this wavefront's share of A(ss), and W(ss), have landed.
-    // Then the workgroup meets (everyone's share is in LDS, and everyone has finished reading the other
-    // buffer in the previous turn), the next loads are started, and the turn's MFMAs run.
-    v4i c0[4], c1[4], c2[4], s0, s1, s2;
-    dma_a(0, 0);
-    load_w(0, c0, s0);
-    if (1 < nss) load_w(1, c1, s1);
-    auto turn = [&](int ss, const v4i (&c)[4], const v4i& sc, v4i (&cn)[4], v4i& sn) {
-        if (ss + 1 < nss) asm volatile("s_waitcnt vmcnt(5)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if (ss + 1 < nss) dma_a(ss + 1, (uint32_t)((ss + 1) & 1));
-        if (ss + 2 < nss) load_w(ss + 2, cn, sn);
-        superstage((uint32_t)(ss & 1), c, sc);
-    };
-    for (int ss = 0; ss < nss; ss += 3) {
-        turn(ss, c0, s0, c2, s2);
-        if (ss + 1 >= nss) break;
-        turn(ss + 1, c1, s1, c0, s0);
-        if (ss + 2 >= nss) break;
-        turn(ss + 2, c2, s2, c1, s1);
-    }
-    const int col = n0 + r;
-#pragma unroll
-    for (int j = 0; j < MT; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = 16 * j + 4 * kq + i;
-            if (row < M && col < N) store_out(y, out_bf16, (int64_t)row * ldy + col, acc[j][i]);
-        }
-}
-
-// ---- 64 < M <= 128 (medium decode batches): the same scheme on the 32x32x64 MFMA -------------
-// With 8 tiles of 16 rows the kernel above is bound by its LDS fragment reads (every wavefront
-// reads all of A for 16 weight rows).  Here a wavefront owns 32 weight rows, which halves the A
-// bytes read per weight row, and the persistent tiled kernel's problem at these sizes - one
-// 128 x 256 tile per CU on fewer than half of the CUs, each with only its 4-stage ring of
-// weights in flight - does not arise: 4 x N/128 wavefronts each keep three superstages of their
-// own weight rows in flight in registers.
+// ---- 16 < M <= 128 (decode batches): weight streaming with the activations in LDS -----------
+// Like the M <= 16 kernel above a wavefront owns its weight rows for the whole of K and streams
+// them through registers, three 512-element superstages in rotation; but with several tiles of
+// activation rows every wavefront would re-read all of A (M x K/2 bytes against its own weight
+// bytes), so the 4 wavefronts of a workgroup share the activations: one superstage of A at a time
+// goes into LDS by LDS-DMA (three buffers, one barrier per superstage), wavefront w bringing stage
+// w.  The MFMA is the 32x32x64 one, a wavefront per 32 weight rows and MT tiles of 32 activation
+// rows: with the 16x16x128 form every wavefront reads all of A out of LDS for only 16 weight rows
+// and the fragment reads bound the kernel (28 us at M = 64, 40 at M = 128 on the 28672 x 8192
+// decode shape, against 23 and 31 here); the persistent tiled kernel at these sizes has one
+// 128 x 256 tile on fewer than half of the CUs, each with only its 4-stage ring of weights in
+// flight (44 us), where 4 x N/128 wavefronts here each keep two superstages of their own rows in
+// flight.
 // Operand fragments (32x32x64: lane (r, h) = (lane & 31, lane >> 5) supplies 32 consecutive K
 // elements of row r): within a 128-element stage (64 code bytes per row) lane half h owns bytes
 // [32 h, 32 h + 32), MFMA step j of the stage takes bytes 32 h + 16 j, i.e. group 2 h + j of the
 // stage, for both operands and both scales.  A in LDS: [stage][row][64 bytes] with the 16-byte
 // chunks of row i XOR-swizzled by (i >> 2) & 3 (lanes r = 0..31 of one read then spread over all
-// banks), scales [row][16 bytes].  Output: lane (r, h) holds D[8 q + 4 h + i][r] for weight row
-// n0 + r, so the 32 lanes of a half store 32 consecutive columns of one output row.
+// banks), scales [tile][64 rows][16 bytes].  Output: lane (r, h) holds D[8 q + 4 h + i][r] for
+// weight row n0 + r, so the 32 lanes of a half store 32 consecutive columns of one output row.
 constexpr int smallm32_lds_bytes(int MT) { return 3 * (MT * 8192 + 4096); }
 
 // TAIL = (K / 512) % 3: the superstages left after the main loop, which takes them three at a time in
@@ -538,38 +418,27 @@ hipError_t launch_mfma_ceiling(const uint8_t* operands, int iters, int workgroup
 hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
                              bool out_bf16, int64_t ldy, hipStream_t s) {
     const int64_t Kp = (K + 511) / 512 * 512;
-    if (M > 16 && M <= 64 && (K == Kp || (a.tiled && w.tiled)) && Kp < (int64_t(1) << 26)) {
-        // small batches: weight streaming with the activations shared through LDS.  (With 8 tiles of 16
-        // rows the fragment reads of the four wavefronts saturate the LDS: 39-41 us at M = 128 on the
-        // 28672 x 8192 decode shape, no better than the tiled kernel, so M > 64 goes there.)
-        const dim3 grid((uint32_t)((N + 63) / 64)), block(256);
-        if (M <= 32)
-            hipLaunchKernelGGL(k_gemm_smallm<2>, grid, block, smallm_lds_bytes(2), s, a.codes, a.scales, (int)a.tiled,
-                               w.codes, w.scales, (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
-        else
-            hipLaunchKernelGGL(k_gemm_smallm<4>, grid, block, smallm_lds_bytes(4), s, a.codes, a.scales, (int)a.tiled,
-                               w.codes, w.scales, (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
-        return hipGetLastError();
-    }
-    if (M > 64 && M <= 128 && (K == Kp || (a.tiled && w.tiled)) && Kp < (int64_t(1) << 26)) {
-        // medium batches: the same on the 32x32x64 MFMA, a wavefront per 32 weight rows
+    if (M > 16 && M <= 128 && (K == Kp || (a.tiled && w.tiled)) && Kp < (int64_t(1) << 26)) {
+        // decode batches: weight streaming with the activations shared through LDS
         using Kern = void (*)(const uint8_t*, const uint8_t*, int, const uint8_t*, const uint8_t*, int, int, int, int, void*,
                               int, int64_t);
-        static const Kern kern[2][3] = {{k_gemm_smallm32<3, 0>, k_gemm_smallm32<3, 1>, k_gemm_smallm32<3, 2>},
+        static const Kern kern[4][3] = {{k_gemm_smallm32<1, 0>, k_gemm_smallm32<1, 1>, k_gemm_smallm32<1, 2>},
+                                        {k_gemm_smallm32<2, 0>, k_gemm_smallm32<2, 1>, k_gemm_smallm32<2, 2>},
+                                        {k_gemm_smallm32<3, 0>, k_gemm_smallm32<3, 1>, k_gemm_smallm32<3, 2>},
                                         {k_gemm_smallm32<4, 0>, k_gemm_smallm32<4, 1>, k_gemm_smallm32<4, 2>}};
         static bool attr_set = false;
         if (!attr_set) {
-            for (int m = 0; m < 2; ++m)
+            for (int m = 0; m < 4; ++m)
                 for (int t = 0; t < 3; ++t) {
                     hipError_t e = hipFuncSetAttribute((const void*)kern[m][t], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                       smallm32_lds_bytes(3 + m));
+                                                       smallm32_lds_bytes(1 + m));
                     if (e != hipSuccess) return e;
                 }
             attr_set = true;
         }
-        const int mi = M <= 96 ? 0 : 1, tail = (int)((Kp / 512) % 3);
+        const int mi = (int)((M - 1) / 32), tail = (int)((Kp / 512) % 3);
         const dim3 grid((uint32_t)((N + 127) / 128)), block(256);
-        hipLaunchKernelGGL(kern[mi][tail], grid, block, smallm32_lds_bytes(3 + mi), s, a.codes, a.scales, (int)a.tiled,
+        hipLaunchKernelGGL(kern[mi][tail], grid, block, smallm32_lds_bytes(1 + mi), s, a.codes, a.scales, (int)a.tiled,
                            w.codes, w.scales, (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
         return hipGetLastError();
     }
