@@ -13,6 +13,9 @@
 
 namespace brq {
 
+template <int V>
+struct IC { static constexpr int value = V; };
+
 // Addressing of one row of a quantized operand, valid for both layouts: the 16 code bytes of
 // group g sit at codes + (g >> 2) * cstep + (g & 3) * 16 and its scale at scales + (g >> 4) * sstep
 // + (g & 15), with (cstep, sstep) = (64, 16) for row-major rows and (4096, 1024) for the tiled
@@ -210,13 +213,15 @@ __global__ void __launch_bounds__(64) k_gemm_skinny_stream(const uint8_t* __rest
 // chunks of row i XOR-swizzled by (i >> 2) & 3 (lanes r = 0..31 of one read then spread over all
 // banks), scales [tile][64 rows][16 bytes].  Output: lane (r, h) holds D[8 q + 4 h + i][r] for
 // weight row n0 + r, so the 32 lanes of a half store 32 consecutive columns of one output row.
-constexpr int smallm32_lds_bytes(int MT) { return 3 * (MT * 8192 + 4096); }
+// weight register sets = LDS buffers of A; SETS - 1 superstages are in flight (4 sets measured no faster)
+constexpr int SMALLM_SETS = 3;
+constexpr int smallm_lds_bytes(int MT) { return SMALLM_SETS * (MT * 8192 + 4096); }
 
-// TAIL = (K / 512) % 3: the superstages left after the main loop, which takes them three at a time in
+// TAIL = (K / 512) % SETS: the superstages left after the main loop, which takes them SETS at a time in
 // one basic block (no load behind a branch: the compiler's count of the outstanding weight loads is
 // then exact; with early exits inside the loop it falls back to waiting for all of them).
 template <int MT, int TAIL>
-__global__ void __launch_bounds__(256) k_gemm_smallm32(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
+__global__ void __launch_bounds__(256) k_gemm_smallm(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
                                                        int a_tiled, const uint8_t* __restrict__ wq,
                                                        const uint8_t* __restrict__ ws, int w_tiled, int M, int N, int K,
                                                        void* __restrict__ y, int out_bf16, int64_t ldy) {
@@ -315,50 +320,58 @@ __global__ void __launch_bounds__(256) k_gemm_smallm32(const uint8_t* __restrict
             }
         }
     };
-    // Issue order per wavefront: A(0), W(0), A(1), W(1); then turn ss issues A(ss + 2), W(ss + 2) - A into the
-    // third LDS buffer, W into the register set that turn ss - 1 consumed - and computes superstage ss.
-    // Loads return in order: at the top of turn ss everything younger than W(ss) is the NA + 9 loads of
-    // superstage ss + 1, so waiting until at most that many are outstanding means A(ss) and W(ss) have
-    // landed while a whole superstage stays in flight across the barrier.  Every turn of the main loop
-    // issues its loads, past the end of K those of the last superstage once more (into a free buffer and
-    // register set, and out of the L2), so the turns are all alike; the TAIL turns after it issue none.
-    v4i c0[8], c1[8], c2[8], s0, s1, s2;
-    dma_a(0, 0);
-    load_w(0, c0, s0);
-    dma_a(min(1, nss - 1), 1);
-    load_w(min(1, nss - 1), c1, s1);
-    auto turn = [&](auto HasNext, auto Issue, int ss, uint32_t buf, const v4i (&c)[8], const v4i& sc, v4i (&cn)[8], v4i& sn) {
-        if constexpr (decltype(HasNext)::value) asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(NA + 9) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // D = SETS - 1 superstages ahead.  Issue order per wavefront: A(0), W(0), .., A(D - 1), W(D - 1); then turn
+    // ss issues A(ss + D), W(ss + D) - A into the LDS buffer, W into the register set that turn ss - 1
+    // consumed - and computes superstage ss.  Loads return in order: at the top of turn ss everything
+    // younger than W(ss) is the (D - 1) x (NA + 9) loads of the superstages after it, so waiting until at
+    // most that many are outstanding means A(ss) and W(ss) have landed while D - 1 superstages stay in
+    // flight across the barrier.  Every turn of the main loop issues its loads, past the end of K those of
+    // the last superstage once more (into a free buffer and register set, and out of the L2), so the turns
+    // are all alike; the TAIL turns after it issue none.
+    constexpr int SETS = SMALLM_SETS, D = SETS - 1;
+    v4i c[SETS][8], s4[SETS];
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+        dma_a(min(i, nss - 1), (uint32_t)i);
+        load_w(min(i, nss - 1), c[i], s4[i]);
+    }
+    // k = the turn's register set and LDS buffer (superstage mod SETS), G = superstages in flight behind it
+    auto turn = [&](auto Kc, auto Gc, auto Issue, int ss) {
+        constexpr int k = decltype(Kc)::value, G = decltype(Gc)::value, kn = (k + D) % SETS;
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(G * (NA + 9)) : "memory");
         // The compiler counts only the weight loads it can see, not the LDS-DMA ones: where it first needs
         // W(ss) it waits until no more loads are outstanding than the weight loads it knows to be younger.
-        // Asking for W(ss) here, before this turn's loads are issued, makes that count the 9 of W(ss + 1)
-        // (which also asks for A(ss + 1), fetched from the L2 a whole turn ago); asked for after them it
-        // would be 18, less than the 18 + NA really outstanding, and W(ss + 1) would have to land first.
-        asm volatile("" ::"v"(c[0]), "v"(c[1]), "v"(c[2]), "v"(c[3]), "v"(c[4]), "v"(c[5]), "v"(c[6]), "v"(c[7]), "v"(sc));
+        // Asking for W(ss) here, before this turn's loads are issued, makes that count the 9 G of the
+        // superstages in flight (which also asks for their A shares, fetched from the L2 long ago); asked
+        // for after this turn's loads it would be 9 more, fewer than are really outstanding, and the oldest
+        // superstage in flight would have to land first.
+        asm volatile("" ::"v"(c[k][0]), "v"(c[k][1]), "v"(c[k][2]), "v"(c[k][3]), "v"(c[k][4]), "v"(c[k][5]), "v"(c[k][6]),
+                     "v"(c[k][7]), "v"(s4[k]));
         // (scheduling fences: without them the compiler sinks the weight loads below the turn's MFMAs and
         // lifts the next turn's scale arithmetic, which needs the youngest load, up into this one)
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (decltype(Issue)::value) {
-            const int nx = min(ss + 2, nss - 1);
-            dma_a(nx, (buf + 2) % 3);
-            load_w(nx, cn, sn);
+            const int nx = min(ss + D, nss - 1);
+            dma_a(nx, (uint32_t)kn);
+            load_w(nx, c[kn], s4[kn]);
         }
         __builtin_amdgcn_sched_barrier(0);
-        superstage(buf, c, sc);
+        superstage((uint32_t)k, c[k], s4[k]);
         __builtin_amdgcn_sched_barrier(0);
     };
     using Yes = std::true_type;
     using No = std::false_type;
     int ss = 0;
-    for (; ss + 3 <= nss; ss += 3) {
-        turn(Yes{}, Yes{}, ss, 0, c0, s0, c2, s2);
-        turn(Yes{}, Yes{}, ss + 1, 1, c1, s1, c0, s0);
-        turn(Yes{}, Yes{}, ss + 2, 2, c2, s2, c1, s1);
+    for (; ss + SETS <= nss; ss += SETS) {
+        turn(IC<0>{}, IC<D - 1>{}, Yes{}, ss);
+        turn(IC<1>{}, IC<D - 1>{}, Yes{}, ss + 1);
+        turn(IC<2>{}, IC<D - 1>{}, Yes{}, ss + 2);
+        if constexpr (SETS > 3) turn(IC<3 % SETS>{}, IC<D - 1>{}, Yes{}, ss + 3);
     }
-    // TAIL superstages are left; the loads of superstage ss + 1, real or repeated, are in flight
-    if constexpr (TAIL >= 1) turn(Yes{}, No{}, ss, 0, c0, s0, c2, s2);
-    if constexpr (TAIL >= 2) turn(No{}, No{}, ss + 1, 1, c1, s1, c0, s0);
+    // TAIL superstages are left; the loads of the D - 1 after superstage ss, real or repeated, are in flight
+    if constexpr (TAIL >= 1) turn(IC<0>{}, IC<D - 1>{}, No{}, ss);
+    if constexpr (TAIL >= 2) turn(IC<1>{}, IC<(D >= 2 ? D - 2 : 0)>{}, No{}, ss + 1);
+    if constexpr (TAIL >= 3) turn(IC<2>{}, IC<(D >= 3 ? D - 3 : 0)>{}, No{}, ss + 2);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated loads land before the LDS is released
     const int col = n0 + r;
 #pragma unroll
@@ -422,23 +435,24 @@ hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int6
         // decode batches: weight streaming with the activations shared through LDS
         using Kern = void (*)(const uint8_t*, const uint8_t*, int, const uint8_t*, const uint8_t*, int, int, int, int, void*,
                               int, int64_t);
-        static const Kern kern[4][3] = {{k_gemm_smallm32<1, 0>, k_gemm_smallm32<1, 1>, k_gemm_smallm32<1, 2>},
-                                        {k_gemm_smallm32<2, 0>, k_gemm_smallm32<2, 1>, k_gemm_smallm32<2, 2>},
-                                        {k_gemm_smallm32<3, 0>, k_gemm_smallm32<3, 1>, k_gemm_smallm32<3, 2>},
-                                        {k_gemm_smallm32<4, 0>, k_gemm_smallm32<4, 1>, k_gemm_smallm32<4, 2>}};
+        static const Kern kern[4][4] = {
+            {k_gemm_smallm<1, 0>, k_gemm_smallm<1, 1>, k_gemm_smallm<1, 2>, k_gemm_smallm<1, 3 % SMALLM_SETS>},
+            {k_gemm_smallm<2, 0>, k_gemm_smallm<2, 1>, k_gemm_smallm<2, 2>, k_gemm_smallm<2, 3 % SMALLM_SETS>},
+            {k_gemm_smallm<3, 0>, k_gemm_smallm<3, 1>, k_gemm_smallm<3, 2>, k_gemm_smallm<3, 3 % SMALLM_SETS>},
+            {k_gemm_smallm<4, 0>, k_gemm_smallm<4, 1>, k_gemm_smallm<4, 2>, k_gemm_smallm<4, 3 % SMALLM_SETS>}};
         static bool attr_set = false;
         if (!attr_set) {
             for (int m = 0; m < 4; ++m)
-                for (int t = 0; t < 3; ++t) {
+                for (int t = 0; t < 4; ++t) {
                     hipError_t e = hipFuncSetAttribute((const void*)kern[m][t], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                       smallm32_lds_bytes(1 + m));
+                                                       smallm_lds_bytes(1 + m));
                     if (e != hipSuccess) return e;
                 }
             attr_set = true;
         }
-        const int mi = (int)((M - 1) / 32), tail = (int)((Kp / 512) % 3);
+        const int mi = (int)((M - 1) / 32), tail = (int)((Kp / 512) % SMALLM_SETS);
         const dim3 grid((uint32_t)((N + 127) / 128)), block(256);
-        hipLaunchKernelGGL(kern[mi][tail], grid, block, smallm32_lds_bytes(1 + mi), s, a.codes, a.scales, (int)a.tiled,
+        hipLaunchKernelGGL(kern[mi][tail], grid, block, smallm_lds_bytes(1 + mi), s, a.codes, a.scales, (int)a.tiled,
                            w.codes, w.scales, (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
         return hipGetLastError();
     }

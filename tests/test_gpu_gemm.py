@@ -165,12 +165,14 @@ def test_gemm_half_tiles_several_per_workgroup(brq, orc):
         check_gemm(brq, orc, aq, as_, wq, ws, rows=rows)
 
 
-# 16 < M <= 64: the weight-streaming kernel that shares the activations through LDS (ragged M inside
-# the last 16-row tile, ragged N inside the last workgroup and wavefront, one and several
-# superstages); the shapes above 64 rows take the neighbouring code paths
+# 16 < M <= 128: the weight-streaming kernel that shares the activations through LDS (1 to 4 tiles of 32
+# rows, ragged M inside the last tile, ragged N inside the last workgroup and wavefront; K of 1 to 7
+# superstages, so that the main loop runs 0, 1 and 2 times with 0, 1 and 2 superstages left over);
+# 129 rows take the neighbouring code path
 @pytest.mark.parametrize("M,N,K", [(17, 1000, 512), (32, 256, 1024), (33, 320, 1536), (64, 4096, 2048), (50, 130, 512),
                                    (48, 64, 512), (20, 16, 3584), (63, 75, 1024), (65, 1000, 512), (128, 384, 2048),
-                                   (100, 130, 1536), (96, 40, 1024)])
+                                   (100, 130, 1536), (96, 40, 1024), (17, 200, 1536), (33, 128, 2560), (97, 256, 3072),
+                                   (128, 129, 512), (127, 128, 3584), (80, 257, 2560), (129, 256, 1024)])
 def test_gemm_small_batches(brq, orc, M, N, K):
     from paper_2511_04214_amd import inputs
     aq, as_ = inputs.random_mxfp4(M, K, seed=51)
