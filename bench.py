@@ -419,6 +419,45 @@ def main():
                 "traffic": PROFILED_TRAFFIC["swiglu_rotate_quant_8192x14336"] if LAY == "tiled" else None}
         del gus, sc, ss, hbuf
 
+    # ---- decode batches: the product M x 28672 x 8192 (gate_up of the 8B MLP against one batch of tokens),
+    # weight streaming, HBM bound: two weight copies alternate so that no launch finds them in the cache
+    aux3 = None
+    if not args.no_aux:
+        dN, dK = 28672, 8192
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(8)
+        dws = []
+        for _ in range(2):
+            wbf = (torch.randn((dN, dK), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+            dws.append(brq.rotate_quantize_fused(wbf, B, layout=LAY))
+            del wbf
+        dx = torch.randn((128, dK), device="cuda", generator=gen).to(torch.bfloat16)
+        aux3 = {"kernel": "mxfp4_gemm", "shape": "M x 28672 x 8192, bf16 out", "bound": "hbm", "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "alg_bytes_weights": dN * dK * 0.53125, "batches": {}}
+        for dM in (16, 32, 64, 128):
+            dq = brq.rotate_quantize_fused(dx[:dM].contiguous(), B, layout=LAY)
+            dy = torch.empty((dM, dN), dtype=torch.bfloat16, device="cuda")
+
+            def dgemm(i):
+                brq.mxfp4_gemm(dq[0], dq[1], dws[i % 2][0], dws[i % 2][1], out=dy, stream=stream, a_layout=LAY,
+                               w_layout=LAY, M=dM, N=dN, K=dK)
+            for i in range(60):
+                dgemm(i)
+            stream.synchronize()
+            ts = []
+            for _ in range(3):
+                a, b = ev(), ev()
+                a.record(stream)
+                for i in range(args.steps):
+                    dgemm(i)
+                b.record(stream)
+                stream.synchronize()
+                ts.append(a.elapsed_time(b) / args.steps)
+            t = float(np.mean(ts))
+            by = (dN + dM) * dK * 0.53125 + dM * dN * 2
+            aux3["batches"][str(dM)] = {"avg_ms": t, "achieved": by / t / 1e6, "frac": by / t / 1e6 / HBM_PEAK_GBS}
+        del dws, dx
+
     if args.calibrate_copy:
         src = torch.full((256 << 20,), 7, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -484,6 +523,7 @@ def main():
         "rotate_quant_16384x8192": aux,
         "matrix_rotate_quant_16384x8192": aux_m,
         "block_stats_16384x8192": aux_s,
+        "decode_batches_28672x8192": aux3,
         "swiglu_rotate_quant_8192x14336": aux2,
         "kernels": kernels,
         "cpu_baseline": cpu_baseline,
