@@ -128,78 +128,13 @@ __global__ void __launch_bounds__(256) k_gemm_skinny(const uint8_t* __restrict__
 }
 
 
-// ---- M <= 16, K % 512 == 0: the same product, shaped for the weight stream --------------------
-// HBM-bound: every weight byte is read exactly once.  One wavefront per workgroup owns 16 weight
-// rows (16 output columns) over the whole of K, so there is no cross-wavefront reduction and the
-// summation order is fixed.  Per 512-element superstage it needs 4 x 1 KB of codes (16 rows x 64
-// bytes, contiguous in the tiled layout) and one 16-byte scale row per lane; the loads run two
-// superstages ahead of the MFMAs (8.5 KB in flight per wavefront, 7 wavefronts per CU on the
-// 28672-column decode shape).  Weights are read once: non-temporal.
-__global__ void __launch_bounds__(64) k_gemm_skinny_stream(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
-                                                           int a_tiled, const uint8_t* __restrict__ wq,
-                                                           const uint8_t* __restrict__ ws, int w_tiled, int M, int N,
-                                                           int K, void* __restrict__ y, int out_bf16, int64_t ldy) {
-    const int lane = threadIdx.x;
-    const int r = lane & 15, kq = lane >> 4;
-    const int n0 = blockIdx.x * 16;
-    const int nss = K / 512;
-    const int64_t rw = min(n0 + r, N - 1);
-    const bool arow = r < M;
-    const RowView va(aq, as, a_tiled != 0, arow ? r : 0, K), vw(wq, ws, w_tiled != 0, rw, K);
-    // superstage ss of a row: 4 stages of 64 code bytes (lane: 16 bytes at kq * 16), 16 scale bytes
-    auto load_w = [&](int ss, v4i (&c)[4], v4i& sc) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-            c[t] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(vw.codes + (int64_t)(4 * ss + t) * vw.cstep + kq * 16));
-        sc = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(vw.scales + (int64_t)ss * vw.sstep));
-    };
-    auto superstage = [&](int ss, const v4i (&c)[4], const v4i& sc, v4f& acc) {
-        v4i ac[4] = {}, asc = {};   // the 16 rows of A stay in the caches
-        if (arow) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) ac[t] = *reinterpret_cast<const v4i*>(va.codes + (int64_t)(4 * ss + t) * va.cstep + kq * 16);
-            asc = *reinterpret_cast<const v4i*>(va.scales + (int64_t)ss * va.sstep);
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            v8i a = {}, b = {};
-            a[0] = ac[t][0]; a[1] = ac[t][1]; a[2] = ac[t][2]; a[3] = ac[t][3];
-            b[0] = c[t][0]; b[1] = c[t][1]; b[2] = c[t][2]; b[3] = c[t][3];
-            // group 4 t + kq of the superstage: byte kq of scale dword t
-            const int sca = (int)(((uint32_t)asc[t] >> (8 * kq)) & 0xffu);
-            const int scb = (int)(((uint32_t)sc[t] >> (8 * kq)) & 0xffu);
-            acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc, 4, 4, 0, sca, 0, scb);
-        }
-    };
-    v4f acc = {};
-    v4i c0[4], c1[4], c2[4], s0, s1, s2;   // three superstages of W in rotation
-    if (0 < nss) load_w(0, c0, s0);
-    if (1 < nss) load_w(1, c1, s1);
-    for (int ss = 0; ss < nss; ss += 3) {
-        if (ss + 2 < nss) load_w(ss + 2, c2, s2);
-        superstage(ss, c0, s0, acc);
-        if (ss + 1 >= nss) break;
-        if (ss + 3 < nss) load_w(ss + 3, c0, s0);
-        superstage(ss + 1, c1, s1, acc);
-        if (ss + 2 >= nss) break;
-        if (ss + 4 < nss) load_w(ss + 4, c1, s1);
-        superstage(ss + 2, c2, s2, acc);
-    }
-    const int col = n0 + r;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int row = 4 * kq + i;
-        if (row < M && col < N) store_out(y, out_bf16, (int64_t)row * ldy + col, acc[i]);
-    }
-}
-
-// ---- 16 < M <= 128 (decode batches): weight streaming with the activations in LDS -----------
-// Like the M <= 16 kernel above a wavefront owns its weight rows for the whole of K and streams
-// them through registers, three 512-element superstages in rotation; but with several tiles of
-// activation rows every wavefront would re-read all of A (M x K/2 bytes against its own weight
-// bytes), so the 4 wavefronts of a workgroup share the activations: one superstage of A at a time
-// goes into LDS by LDS-DMA (three buffers, one barrier per superstage), wavefront w bringing stage
-// w.  The MFMA is the 32x32x64 one, a wavefront per 32 weight rows and MT tiles of 32 activation
+// ---- M <= 128 (decode batches): weight streaming with the activations in LDS ----------------
+// HBM-bound: every weight byte is read exactly once.  A wavefront owns its weight rows for the whole
+// of K (no cross-wavefront reduction, fixed summation order) and streams them through registers,
+// three 512-element superstages in rotation.  With several tiles of activation rows every wavefront
+// would re-read all of A (M x K/2 bytes against its own weight bytes), so the 4 wavefronts of a
+// workgroup share the activations: one superstage of A at a time goes into LDS by LDS-DMA (three
+// buffers, one barrier per superstage), wavefront w bringing stage w.  The MFMA is the 32x32x64 one, a wavefront per 32 weight rows and MT tiles of 32 activation
 // rows: with the 16x16x128 form every wavefront reads all of A out of LDS for only 16 weight rows
 // and the fragment reads bound the kernel (28 us at M = 64, 40 at M = 128 on the 28672 x 8192
 // decode shape, against 23 and 31 here); the persistent tiled kernel at these sizes has one
@@ -431,7 +366,7 @@ hipError_t launch_mfma_ceiling(const uint8_t* operands, int iters, int workgroup
 hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
                              bool out_bf16, int64_t ldy, hipStream_t s) {
     const int64_t Kp = (K + 511) / 512 * 512;
-    if (M > 16 && M <= 128 && (K == Kp || (a.tiled && w.tiled)) && Kp < (int64_t(1) << 26)) {
+    if (M <= 128 && (K == Kp || (a.tiled && w.tiled)) && Kp < (int64_t(1) << 26)) {
         // decode batches: weight streaming with the activations shared through LDS
         using Kern = void (*)(const uint8_t*, const uint8_t*, int, const uint8_t*, const uint8_t*, int, int, int, int, void*,
                               int, int64_t);
@@ -460,11 +395,6 @@ hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int6
         return launch_gemm_tiled(a, w, M, N, K, y, out_bf16, ldy, s);
     } else if (M <= 16) {
         dim3 grid((uint32_t)((N + 15) / 16));
-        if (K % 512 == 0) {
-            hipLaunchKernelGGL(k_gemm_skinny_stream, grid, dim3(64), 0, s, a.codes, a.scales, (int)a.tiled, w.codes,
-                               w.scales, (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
-            return hipGetLastError();
-        }
         hipLaunchKernelGGL(k_gemm_skinny, grid, dim3(256), 0, s, a.codes, a.scales, (int)a.tiled, w.codes, w.scales,
                            (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy);
     } else {
