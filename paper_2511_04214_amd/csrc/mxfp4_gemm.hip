@@ -127,20 +127,19 @@ __global__ void __launch_bounds__(256) k_gemm_skinny(const uint8_t* __restrict__
     }
 }
 
-
 // ---- M <= 128 (decode batches): weight streaming with the activations in LDS ----------------
 // HBM-bound: every weight byte is read exactly once.  A wavefront owns its weight rows for the whole
 // of K (no cross-wavefront reduction, fixed summation order) and streams them through registers,
 // three 512-element superstages in rotation.  With several tiles of activation rows every wavefront
 // would re-read all of A (M x K/2 bytes against its own weight bytes), so the 4 wavefronts of a
 // workgroup share the activations: one superstage of A at a time goes into LDS by LDS-DMA (three
-// buffers, one barrier per superstage), wavefront w bringing stage w.  The MFMA is the 32x32x64 one, a wavefront per 32 weight rows and MT tiles of 32 activation
-// rows: with the 16x16x128 form every wavefront reads all of A out of LDS for only 16 weight rows
-// and the fragment reads bound the kernel (28 us at M = 64, 40 at M = 128 on the 28672 x 8192
-// decode shape, against 23 and 31 here); the persistent tiled kernel at these sizes has one
-// 128 x 256 tile on fewer than half of the CUs, each with only its 4-stage ring of weights in
-// flight (44 us), where 4 x N/128 wavefronts here each keep two superstages of their own rows in
-// flight.
+// buffers, one barrier per superstage), wavefront w bringing stage w.  The MFMA is the 32x32x64
+// one, a wavefront per 32 weight rows and MT tiles of 32 activation rows: with the 16x16x128 form
+// every wavefront reads all of A out of LDS for only 16 weight rows and the fragment reads bound the
+// kernel (28 us at M = 64, 40 at M = 128 on the 28672 x 8192 decode shape, against 23 and 31 here);
+// the persistent tiled kernel at these sizes has one 128 x 256 tile on fewer than half of the CUs,
+// each with only its 4-stage ring of weights in flight (44 us), where 4 x N/128 wavefronts here
+// each keep two superstages of their own rows in flight.
 // Operand fragments (32x32x64: lane (r, h) = (lane & 31, lane >> 5) supplies 32 consecutive K
 // elements of row r): within a 128-element stage (64 code bytes per row) lane half h owns bytes
 // [32 h, 32 h + 32), MFMA step j of the stage takes bytes 32 h + 16 j, i.e. group 2 h + j of the
@@ -148,7 +147,8 @@ __global__ void __launch_bounds__(256) k_gemm_skinny(const uint8_t* __restrict__
 // chunks of row i XOR-swizzled by (i >> 2) & 3 (lanes r = 0..31 of one read then spread over all
 // banks), scales [tile][64 rows][16 bytes].  Output: lane (r, h) holds D[8 q + 4 h + i][r] for
 // weight row n0 + r, so the 32 lanes of a half store 32 consecutive columns of one output row.
-// weight register sets = LDS buffers of A; SETS - 1 superstages are in flight (4 sets measured no faster)
+
+// Weight register sets = LDS buffers of A; SETS - 1 superstages are in flight (4 sets measured no faster).
 constexpr int SMALLM_SETS = 3;
 constexpr int smallm_lds_bytes(int MT) { return SMALLM_SETS * (MT * 8192 + 4096); }
 
@@ -157,9 +157,9 @@ constexpr int smallm_lds_bytes(int MT) { return SMALLM_SETS * (MT * 8192 + 4096)
 // then exact; with early exits inside the loop it falls back to waiting for all of them).
 template <int MT, int TAIL>
 __global__ void __launch_bounds__(256) k_gemm_smallm(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
-                                                       int a_tiled, const uint8_t* __restrict__ wq,
-                                                       const uint8_t* __restrict__ ws, int w_tiled, int M, int N, int K,
-                                                       void* __restrict__ y, int out_bf16, int64_t ldy) {
+                                                     int a_tiled, const uint8_t* __restrict__ wq,
+                                                     const uint8_t* __restrict__ ws, int w_tiled, int M, int N, int K,
+                                                     void* __restrict__ y, int out_bf16, int64_t ldy) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     constexpr int STG = MT * 2048;                      // one stage of A codes: MT * 32 rows x 64 bytes
     constexpr int BUF = 4 * STG + 4096;                 // codes [4 stages][MT * 32 rows][64], then scales [4 tiles][64 rows][16]
@@ -186,7 +186,7 @@ __global__ void __launch_bounds__(256) k_gemm_smallm(const uint8_t* __restrict__
 #pragma unroll
     for (int j = 0; j < 2 * MT; ++j)
         voc[j] = row_off_c(16 * j + (lane >> 2)) + (uint32_t)((lane & 3) ^ ((lane >> 4) & 3)) * 16u;
-    // ... and one the scale rows of 32-row tile `wave` (lanes 32..63 repeat them into the second half of
+    // ... and one more the scale rows of 32-row tile `wave` (lanes 32..63 repeat them into the second half of
     // the tile's 1 KB slot; a wavefront without a tile of its own repeats row M - 1): every wavefront
     // issues the same number of loads, which the counted waits below rely on
     const uint32_t vos = row_off_s(32 * wave + r);
