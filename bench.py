@@ -177,6 +177,30 @@ def main():
         a_c, a_s = (zc[:gemm_M], zs[:gemm_M]) if LAY == "rowmajor" else (zc, zs)
         brq.mxfp4_gemm(a_c, a_s, zwc, zws, out=ys[0], stream=stream, a_layout=LAY, w_layout=LAY, M=gemm_M, N=N, K=K)
     gm_const_ms = train(gemm_const, reps=3)
+    # the shader clock the chip holds during the product (cycle and 100 MHz counters of the kernel's first
+    # workgroup), on the workload's operands and on the constant ones
+    gm_clock = {}
+    if gemm_M > 128 and N % 256 == 0:
+        clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+
+        def clocked(a_c, a_s, w_c, w_s):
+            vals = []
+            for _ in range(3):      # the last launch of a train of back-to-back ones (every launch overwrites clk)
+                for i in range(20):
+                    brq.mxfp4_gemm(a_c, a_s, w_c, w_s, out=ys[0], stream=stream, a_layout=LAY, w_layout=LAY, M=gemm_M, N=N,
+                                   K=K, clock=clk)
+                stream.synchronize()
+                c, t = clk.tolist()
+                vals.append(0.1 * c / max(t, 1))
+            return float(np.mean(vals))
+        for i in range(40):
+            gemm(i % nsets)
+        a_c, a_s = (codes[0][:gemm_M], scales[0][:gemm_M]) if LAY == "rowmajor" else (codes[0], scales[0])
+        gm_clock["shader_clock_GHz"] = clocked(a_c, a_s, wqs[0], wss[0])
+        for i in range(40):
+            gemm_const(0)
+        a_c, a_s = (zc[:gemm_M], zs[:gemm_M]) if LAY == "rowmajor" else (zc, zs)
+        gm_clock["constant_operands_shader_clock_GHz"] = clocked(a_c, a_s, zwc, zws)
     del zc, zs, zwc, zws
 
     ms_per_step = wall * 1e3 / args.steps
@@ -184,6 +208,9 @@ def main():
     gemm_flops = 2.0 * gemm_M * N * K
     gemm_bytes = (gemm_M + N) * K * 0.53125 + gemm_M * N * out_es
     rq_avg, gm_avg = float(rq_ms.mean()), float(gm_ms.mean())
+    if "shader_clock_GHz" in gm_clock:   # the published peak is quoted at 2.4 GHz: the same ratio at the clock held
+        gm_clock["frac_mxfp4_peak_at_held_clock"] = (2.0 * gemm_M * N * K / float(gm_ms.mean()) / 1e9 / MXFP4_PEAK_TFLOPS
+                                                     * 2.4 / gm_clock["shader_clock_GHz"])
     kernels = {
         "rotate_quantize_fused": {"avg_ms": rq_avg, "median_ms": float(np.median(rq_ms)), "min_ms": float(rq_ms.min()),
                                   "alg_bytes": rq_bytes,
@@ -193,6 +220,7 @@ def main():
                        "warm_cache_avg_ms": float(gm_warm_ms.mean()),
                        "constant_operands_avg_ms": float(gm_const_ms.mean()),
                        "constant_operands_frac_mxfp4_peak": gemm_flops / float(gm_const_ms.mean()) / 1e9 / MXFP4_PEAK_TFLOPS,
+                       **gm_clock,
                        "flops": gemm_flops, "alg_bytes": gemm_bytes,
                        "TFLOP/s": gemm_flops / gm_avg / 1e9,
                        "frac_mxfp4_peak": gemm_flops / gm_avg / 1e9 / MXFP4_PEAK_TFLOPS,

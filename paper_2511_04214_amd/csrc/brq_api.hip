@@ -185,9 +185,9 @@ brq_status brq_matrix_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_
                                               layout == BRQ_LAYOUT_TILED, static_cast<hipStream_t>(stream)));
 }
 
-brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
-                          const uint8_t* ws, brq_layout w_layout, int64_t M, int64_t N, int64_t K, void* y,
-                          brq_dtype ydt, int64_t ldy, void* stream) {
+static brq_status check_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
+                             const uint8_t* ws, brq_layout w_layout, int64_t M, int64_t N, int64_t K, const void* y,
+                             brq_dtype ydt, int64_t ldy) {
     int es = dtype_size(ydt);
     if (es == 0) return BRQ_ERR_DTYPE;
     if (!layout_ok(a_layout) || !layout_ok(w_layout)) return BRQ_ERR_LAYOUT;
@@ -196,6 +196,28 @@ brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_lay
     if (M > 0 && N > 0 && (!aq || !as || !wq || !ws || !y)) return BRQ_ERR_NULL;
     if (!aligned16(aq) || !aligned16(as) || !aligned16(wq) || !aligned16(ws) || !aligned16(y))
         return BRQ_ERR_ALIGN;
+    return BRQ_OK;
+}
+
+brq_status brq_diag_mxfp4_gemm_clock(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
+                                     const uint8_t* ws, brq_layout w_layout, int64_t M, int64_t N, int64_t K, void* y,
+                                     brq_dtype ydt, int64_t ldy, uint64_t* clock2, void* stream) {
+    brq_status st = check_gemm(aq, as, a_layout, wq, ws, w_layout, M, N, K, y, ydt, ldy);
+    if (st != BRQ_OK) return st;
+    if (!clock2) return BRQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(clock2) & 7u) return BRQ_ERR_ALIGN;
+    const bool both = a_layout == BRQ_LAYOUT_TILED && w_layout == BRQ_LAYOUT_TILED;
+    if (M <= 128 || !brq::tiled_gemm_supported(M, N, K, ydt == BRQ_BF16, ldy, both)) return BRQ_ERR_SHAPE;
+    const brq::Operand a{aq, as, a_layout == BRQ_LAYOUT_TILED}, w{wq, ws, w_layout == BRQ_LAYOUT_TILED};
+    return launched(brq::launch_gemm_tiled(a, w, M, N, K, y, ydt == BRQ_BF16, ldy, static_cast<hipStream_t>(stream),
+                                           reinterpret_cast<unsigned long long*>(clock2)));
+}
+
+brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
+                          const uint8_t* ws, brq_layout w_layout, int64_t M, int64_t N, int64_t K, void* y,
+                          brq_dtype ydt, int64_t ldy, void* stream) {
+    brq_status st = check_gemm(aq, as, a_layout, wq, ws, w_layout, M, N, K, y, ydt, ldy);
+    if (st != BRQ_OK) return st;
     if (M == 0 || N == 0) return BRQ_OK;
     const brq::Operand a{aq, as, a_layout == BRQ_LAYOUT_TILED}, w{wq, ws, w_layout == BRQ_LAYOUT_TILED};
     return launched(brq::launch_mxfp4_gemm(a, w, M, N, K, y, ydt == BRQ_BF16, ldy, static_cast<hipStream_t>(stream)));
@@ -237,6 +259,6 @@ const char* brq_strerror(brq_status s) {
     return "unknown status";
 }
 
-int brq_version(void) { return 340; }
+int brq_version(void) { return 350; }
 
 }  // extern "C"

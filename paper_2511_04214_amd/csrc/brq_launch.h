@@ -52,8 +52,9 @@ hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int6
 // Persistent LDS-staged kernel for large shapes (N a multiple of 256, any M; K a multiple of 512,
 // or any K when both operands are tiled, whose K padding is zero).
 bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy, bool both_tiled);
+// clk (optional, device): receives {shader-clock cycles, 100 MHz ticks} that workgroup 0 ran for.
 hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
-                             bool out_bf16, int64_t ldy, hipStream_t s);
+                             bool out_bf16, int64_t ldy, hipStream_t s, unsigned long long* clk = nullptr);
 
 // Tiled -> row-major copy of a quantized operand.
 hipError_t launch_to_rowmajor(const uint8_t* codes_t, const uint8_t* scales_t, int64_t rows, int64_t K,

@@ -109,10 +109,15 @@ __device__ __forceinline__ void mfma_fp4(v16f& acc, const v4i& wf, const v4i& af
 template <bool OUT_BF16, int MB>
 __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
                                                        const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
-                                                       int M, int N, int K, void* __restrict__ y, int64_t ldy, int a_tiled, int w_tiled) {
+                                                       int M, int N, int K, void* __restrict__ y, int64_t ldy, int a_tiled, int w_tiled,
+                                                       unsigned long long* __restrict__ clk) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // measurement aid: workgroup 0 reports the shader-clock cycles and 100 MHz ticks it ran for
+    const bool timed = clk != nullptr && blockIdx.x == 0;
+    unsigned long long t_c0 = 0, t_r0 = 0;
+    if (timed) { t_c0 = __builtin_readcyclecounter(); t_r0 = __builtin_amdgcn_s_memrealtime(); }
     const int r = lane & 31, h = lane >> 5;
     const int wn = wave >> 1, wm = wave & 1;   // this wavefront's 128 W rows / 32 MB A rows inside the tile
     constexpr int TMv = 64 * MB;               // output rows per tile
@@ -490,6 +495,10 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     }
     // the throw-away superstage is still in flight: let it land before the LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (timed) {
+        const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+        if (tid == 0) { clk[0] = c1 - t_c0; clk[1] = r1 - t_r0; }
+    }
 }
 
 #undef BRQ_MFMA
@@ -508,7 +517,7 @@ bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_
 }
 
 hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
-                             bool out_bf16, int64_t ldy, hipStream_t s) {
+                             bool out_bf16, int64_t ldy, hipStream_t s, unsigned long long* clk) {
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, v = 0;
@@ -536,17 +545,17 @@ hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int6
     if (half) {
         if (out_bf16)
             hipLaunchKernelGGL((tiled::k_gemm_tiled<true, 2>), g, b, tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
-                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi);
+                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi, clk);
         else
             hipLaunchKernelGGL((tiled::k_gemm_tiled<false, 2>), g, b, tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
-                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi);
+                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi, clk);
     } else {
         if (out_bf16)
             hipLaunchKernelGGL((tiled::k_gemm_tiled<true, 4>), g, b, tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
-                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi);
+                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi, clk);
         else
             hipLaunchKernelGGL((tiled::k_gemm_tiled<false, 4>), g, b, tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
-                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi);
+                               w.scales, (int)M, (int)N, (int)K, y, ldy, ai, wi, clk);
     }
     return hipGetLastError();
 }

@@ -117,6 +117,13 @@ def test_argument_errors_before_any_launch(L):
     assert L.brq_mxfp4_quantize(q(p), 1, 0, 64, 64, q(p), q(p), 0, None) == OK
     assert L.brq_rotate_quantize_fused(q(p), 1, 0, 64, 64, 32, None, q(p), q(p), 0, None) == OK
     assert L.brq_block_rotate(q(p), 1, 0, 64, 64, 64, None, q(p), 0, 64, None) == OK
+    # the product with the clock read-out: large shapes only, and it needs somewhere to write
+    assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 256, 512, q(p), 0, 256, None, None) == NULL
+    assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 256, 512, q(p), 0, 256, q(p + 4), None) == ALIGN
+    assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 128, 256, 512, q(p), 0, 256, q(p), None) == SHAPE
+    assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 200, 512, q(p), 0, 200, q(p), None) == SHAPE
+    assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 256, 544, q(p), 0, 256, q(p), None) == SHAPE
+    assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 0, 256, 512, q(p), 0, 256, q(p), None) == SHAPE
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 0, 8, 64, q(p), 0, 8, None) == OK
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 8, 0, 64, q(p), 0, 0, None) == OK
 

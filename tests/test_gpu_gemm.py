@@ -203,3 +203,23 @@ def test_measurement_loop_reports_its_clock(brq):
     assert flops == 8 * 4 * 400 * 16 * 131072
     assert cycles >= 400 * 16 * 32 and ticks > 0          # at least the MFMAs' own 32 cycles apiece
     assert 0.2 < 0.1 * cycles / ticks < 3.0               # GHz
+
+
+def test_product_reports_its_clock(brq):
+    # the large-shape kernel with the clock read-out: same product, plausible clock
+    from paper_2511_04214_amd import inputs
+    M, N, K = 512, 512, 2048
+    aq, as_ = inputs.random_mxfp4(M, K, seed=71)
+    wq, ws = inputs.random_mxfp4(N, K, seed=72)
+    ops = [to_dev(t) for t in (aq, as_, wq, ws)]
+    clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+    y0 = brq.mxfp4_gemm(*ops, out_dtype=torch.bfloat16)
+    y1 = brq.mxfp4_gemm(*ops, out_dtype=torch.bfloat16, clock=clk)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    cycles, ticks = clk.tolist()
+    assert cycles >= 16 * 32 * 32 and ticks > 0           # at least the MFMAs of one tile's K loop
+    assert 0.2 < 0.1 * cycles / ticks < 3.0               # GHz
+    with pytest.raises(brq.BrqError) as e:                # a shape that another kernel takes
+        brq.mxfp4_gemm(ops[0][:64], ops[1][:64], ops[2], ops[3], clock=clk)
+    assert e.value.status == 2
