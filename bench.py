@@ -340,6 +340,30 @@ def main():
                "min_ms": float(ams.min()), "alg_bytes": ab, "achieved": ab / float(ams.mean()) / 1e6,
                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ab / float(ams.mean()) / 1e6 / HBM_PEAK_GBS,
                "traffic": PROFILED_TRAFFIC["rotate_quant_16384x8192"] if LAY == "tiled" else None}
+        # what the online rotation costs (Sec. 4.2 "reduced online computing", Table "latency overhead"): the same
+        # activations through the quantizer alone, with the block rotation, and with the global one (B = K)
+        rot = {}
+        for name, fn in (("quantize_only", lambda i: brq.mxfp4_quantize(axs[i % 3], codes=ac[i % 3], scales=asc[i % 3],
+                                                                      stream=stream, layout=LAY)),
+                         ("block_128", lambda i: brq.rotate_quantize_fused(axs[i % 3], 128, codes=ac[i % 3], scales=asc[i % 3],
+                                                                          stream=stream, layout=LAY)),
+                         ("global_%d" % aK, lambda i: brq.rotate_quantize_fused(axs[i % 3], aK, codes=ac[i % 3],
+                                                                               scales=asc[i % 3], stream=stream, layout=LAY))):
+            for i in range(100):
+                fn(i)
+            stream.synchronize()
+            ts = []
+            for _ in range(3):
+                a, b = ev(), ev()
+                a.record(stream)
+                for i in range(args.steps):
+                    fn(i)
+                b.record(stream)
+                stream.synchronize()
+                ts.append(a.elapsed_time(b) / args.steps)
+            rot[name + "_ms"] = float(np.mean(ts))
+        rot["block_%d_ms" % B] = float(ams.mean())
+        aux["online_rotation_cost"] = rot
         # the same step with caller-supplied orthogonal 32x32 blocks (one per block of K) on the matrix cores
         rng_r = np.random.default_rng(11)
         Rb = torch.from_numpy(np.stack([np.linalg.qr(rng_r.standard_normal((32, 32)))[0]
