@@ -88,6 +88,8 @@ brq_status brq_operand_bytes(int64_t rows, int64_t K, brq_layout layout, int64_t
  * Arithmetic: inputs widened exactly to fp32; stages h = 1, 2, ..., B/2 in ascending
  * order, pair (i, i+h) -> (a+b, a-b), each one IEEE fp32 operation; one fp32 multiply by
  * fl(1/sqrt(B)).  ydt = BRQ_F32 stores that value, BRQ_BF16 its round-to-nearest-even.
+ * Every nonzero result has exactly these bits; a result that is an exact zero (operands that
+ * cancel) may come out as +0 or -0 (the quantizers store either as code 0).
  * x [M][ldx] of xdt, y [M][ldy] of ydt; x and y must not overlap.
  * B: power of two, 8 <= B <= 16384, B divides K.
  */
