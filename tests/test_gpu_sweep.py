@@ -93,3 +93,89 @@ def test_rotate_quantize_sweep(brq, orc, M, K, B, bf16, tiled, signed, pad):
         ry = orc.block_rotate(xv, B, signs=signs)
         ua, ub = y.view(np.uint32), ry.view(np.uint32)      # the sign of an exact zero is not defined
         assert ((ua == ub) | (((ua | ub) & np.uint32(0x7FFFFFFF)) == 0)).all(), "rotated values differ"
+
+
+def producer_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        M = int(rng.integers(1, 200))
+        K = int(rng.choice([32 * rng.integers(1, 65), 2 ** rng.integers(5, 12)]))
+        pows = [b for b in (8, 16, 32, 64, 128, 256, 512, 1024) if K % b == 0]
+        out.append((M, K, int(rng.choice(pows + [1])), bool(rng.integers(2)), bool(rng.integers(2)), bool(rng.integers(2)),
+                    bool(rng.integers(2))))
+    return out
+
+
+@pytest.mark.parametrize("M,K,B,bf16,h_bf16,tiled,shared", producer_cases(20, 9003))
+def test_swiglu_fused_sweep(brq, orc, M, K, B, bf16, h_bf16, tiled, shared):
+    # gate and up as two matrices or as the halves of one [M, 2K] buffer
+    from paper_2511_04214_amd.inputs import f32_to_bf16_bits
+    rng = np.random.default_rng(M * 5 + K + B)
+    gu = (rng.standard_t(4, size=(M, 2 * K)) * 1.5).astype(np.float32)
+    gu[:, rng.choice(K, size=max(1, K // 100), replace=False)] *= 8.0
+    gh = f32_to_bf16_bits(gu) if bf16 else gu
+    g, u = np.ascontiguousarray(gh[:, :K]), np.ascontiguousarray(gh[:, K:])
+    if shared:
+        buf = to_dev(gh)
+        gd, ud = buf[:, :K], buf[:, K:]
+    else:
+        gd, ud = to_dev(g), to_dev(u)
+    lay = "tiled" if tiled else "rowmajor"
+    c, s = brq.swiglu_rotate_quantize_fused(gd, ud, B, h_dtype=torch.bfloat16 if h_bf16 else torch.float32, layout=lay)
+    if tiled:
+        c, s = brq.to_rowmajor(c, s, M, K)
+    rc, rs = orc.swiglu_rotate_quantize_fused(g, u, B, h_bf16=h_bf16)
+    assert np.array_equal(to_host(s), rs), "scales differ"
+    assert np.array_equal(to_host(c), rc), "codes differ"
+    h = to_host(brq.swiglu(gd, ud))
+    assert np.array_equal(h.view(np.uint32), orc.swiglu(g, u).view(np.uint32)), "activation differs"
+
+
+def stats_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        M = int(rng.integers(1, 200))
+        K = int(rng.choice([32 * rng.integers(1, 65), 2 ** rng.integers(5, 12)]))
+        pows = [b for b in (8, 16, 32, 64, 128, 256, 512, 1024, 2048) if K % b == 0]
+        out.append((M, K, int(rng.choice(pows + [1])), bool(rng.integers(2)), int(rng.integers(0, 9)), bool(rng.integers(2))))
+    return out
+
+
+@pytest.mark.parametrize("M,K,B,bf16,nt,signed", stats_cases(16, 9004))
+def test_block_stats_sweep(brq, orc, M, K, B, bf16, nt, signed):
+    from paper_2511_04214_amd.inputs import f32_to_bf16_bits
+    rng = np.random.default_rng(M * 3 + K + B + nt)
+    x = rng.standard_t(4, size=(M, K)).astype(np.float32)
+    x[:, rng.choice(K, size=max(1, K // 100), replace=False)] *= 20.0
+    xh = f32_to_bf16_bits(x) if bf16 else x
+    th = tuple(float(t) for t in np.sort(rng.uniform(0.1, 8.0, size=nt)).astype(np.float32))
+    signs = rng.choice([-1, 1], size=K).astype(np.int8) if (signed and B > 1) else None
+    sg = None if signs is None else torch.from_numpy(signs).cuda()
+    amax, counts, sq, sqb = brq.block_stats(to_dev(xh), B, th, signs=sg, want_bfp4=True)
+    ra, rc, rs, rb = orc.block_stats(xh, B, th, signs=signs, want_bfp4=True)
+    assert np.array_equal(to_host(amax).view(np.uint32), ra.view(np.uint32)), "block scales differ"
+    if nt:
+        assert np.array_equal(to_host(counts).astype(np.uint64), rc)
+    for got, want in ((sq, rs), (sqb, rb)):
+        g = to_host(got).astype(np.float64)
+        assert (np.abs(g - want) <= 4e-6 * want + 1e-44).all()
+
+
+@pytest.mark.parametrize("M,K,bf16,shared,tiled", [(37, 128, True, False, False), (150, 896, True, True, True),
+                                                   (64, 2048, False, False, True), (9, 384, False, True, False),
+                                                   (200, 1152, True, False, True), (1, 256, True, True, False)])
+def test_matrix_blocks_sweep(brq, orc, M, K, bf16, shared, tiled):
+    from test_gpu_matrix_rotate import check_fused_within_bound, orthogonal_blocks
+    from paper_2511_04214_amd.inputs import f32_to_bf16_bits
+    rng = np.random.default_rng(M + K)
+    x = rng.standard_t(4, size=(M, K)).astype(np.float32)
+    x[:, rng.choice(K, size=max(1, K // 100), replace=False)] *= 20.0
+    xh = f32_to_bf16_bits(x) if bf16 else x
+    R = orthogonal_blocks(1 if shared else K // 32, seed=M * 11 + K)
+    c, s = brq.matrix_rotate_quantize_fused(to_dev(xh), torch.from_numpy(R).cuda(), layout="tiled" if tiled else "rowmajor")
+    if tiled:
+        c, s = brq.to_rowmajor(c, s, M, K)
+    same_c, same_s = check_fused_within_bound(orc, xh, R, to_host(c), to_host(s))
+    assert same_c > 0.995 and same_s > 0.995
