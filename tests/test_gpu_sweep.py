@@ -10,8 +10,12 @@ import torch
 from gpu_util import to_dev, to_host
 from test_gpu_layout import to_tiled
 
+import os
+
 pytestmark = pytest.mark.gpu
 
+# BRQ_SWEEP_SCALE=k draws k times as many cases from other seeds (a longer run by hand; default 1)
+SCALE = max(1, int(os.environ.get("BRQ_SWEEP_SCALE", "1")))
 RTOL = 1e-5
 FLOOR = 2.0 ** -126
 
@@ -35,7 +39,7 @@ def gemm_cases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("M,N,K,a_tiled,w_tiled,bf16,pad", gemm_cases(40, 9001))
+@pytest.mark.parametrize("M,N,K,a_tiled,w_tiled,bf16,pad", gemm_cases(40 * SCALE, 9001 + SCALE - 1))
 def test_product_sweep(brq, orc, M, N, K, a_tiled, w_tiled, bf16, pad):
     from paper_2511_04214_amd import inputs
     aq, as_ = inputs.random_mxfp4(M, K, seed=M * 31 + K)
@@ -66,7 +70,7 @@ def rowwise_cases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("M,K,B,bf16,tiled,signed,pad", rowwise_cases(40, 9002))
+@pytest.mark.parametrize("M,K,B,bf16,tiled,signed,pad", rowwise_cases(40 * SCALE, 9002 + SCALE - 1))
 def test_rotate_quantize_sweep(brq, orc, M, K, B, bf16, tiled, signed, pad):
     from paper_2511_04214_amd.inputs import f32_to_bf16_bits
     rng = np.random.default_rng(M * 7 + K + B)
@@ -107,7 +111,7 @@ def producer_cases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("M,K,B,bf16,h_bf16,tiled,shared", producer_cases(20, 9003))
+@pytest.mark.parametrize("M,K,B,bf16,h_bf16,tiled,shared", producer_cases(20 * SCALE, 9003 + SCALE - 1))
 def test_swiglu_fused_sweep(brq, orc, M, K, B, bf16, h_bf16, tiled, shared):
     # gate and up as two matrices or as the halves of one [M, 2K] buffer
     from paper_2511_04214_amd.inputs import f32_to_bf16_bits
@@ -143,7 +147,7 @@ def stats_cases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("M,K,B,bf16,nt,signed", stats_cases(16, 9004))
+@pytest.mark.parametrize("M,K,B,bf16,nt,signed", stats_cases(16 * SCALE, 9004 + SCALE - 1))
 def test_block_stats_sweep(brq, orc, M, K, B, bf16, nt, signed):
     from paper_2511_04214_amd.inputs import f32_to_bf16_bits
     rng = np.random.default_rng(M * 3 + K + B + nt)
