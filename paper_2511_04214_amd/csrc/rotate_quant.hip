@@ -107,6 +107,31 @@ __device__ __forceinline__ void store_chunk(void* p, const float (&v)[8]) {
     }
 }
 
+// fp32 output of the rotation: a lane's 8 values are 32 contiguous bytes, and two 16-byte stores per
+// lane would leave the lanes of either instruction 32 bytes apart - the store path then takes them
+// one lane at a time (178 us on X 16384 x 8192, where a plain conversion copy of the same traffic takes
+// 137).  The four lanes of a quad hold 128 contiguous bytes (consecutive lanes = consecutive chunks of
+// one row): the 16-byte pieces are traded inside the quad so that store A writes pieces 0..3 and store
+// B pieces 4..7, lane t piece t - 64 contiguous bytes per quad and instruction.  Piece k sits in lane
+// k >> 1, half k & 1.  Every lane of the quad must be active.
+__device__ __forceinline__ void store_chunk_f32_quad(char* p, const float (&v)[8], uint32_t lane) {
+    const uint32_t t = lane & 3u;
+    const bool odd = (t & 1u) != 0;
+    v4f a, b;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int lo = __builtin_bit_cast(int, v[k]), hi = __builtin_bit_cast(int, v[4 + k]);
+        const int a_lo = __builtin_amdgcn_update_dpp(lo, lo, 0x50 /* quad_perm [0,0,1,1] */, 0xF, 0xF, true);
+        const int a_hi = __builtin_amdgcn_update_dpp(hi, hi, 0x50, 0xF, 0xF, true);
+        const int b_lo = __builtin_amdgcn_update_dpp(lo, lo, 0xFA /* quad_perm [2,2,3,3] */, 0xF, 0xF, true);
+        const int b_hi = __builtin_amdgcn_update_dpp(hi, hi, 0xFA, 0xF, 0xF, true);
+        a[k] = __builtin_bit_cast(float, odd ? a_hi : a_lo);
+        b[k] = __builtin_bit_cast(float, odd ? b_hi : b_lo);
+    }
+    __builtin_nontemporal_store(a, reinterpret_cast<v4f*>(p - 16 * (int)t));
+    __builtin_nontemporal_store(b, reinterpret_cast<v4f*>(p + 64 - 16 * (int)t));
+}
+
 // The lane's 8 input values: the chunk at p, or (PROD) the gated activation of the chunks at p
 // (gate) and p2 (up), computed here so that it never visits HBM.
 template <bool BF16, bool PROD>
@@ -320,7 +345,9 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
             if constexpr (MODE == MODE_ROTATE) {
                 if (live) {
                     char* p = (char*)a.y + chunk_offset<CONTIG>(c, a.cpr, a.ldy) * (OUT_BF16 ? 2 : 4);
-                    store_chunk<OUT_BF16>(p, v[u]);
+                    // (a quad's four chunks are live together: the chunk count is a multiple of 4)
+                    if constexpr (OUT_BF16) store_chunk<true>(p, v[u]);
+                    else store_chunk_f32_quad(p, v[u], lane);
                 }
             } else if constexpr (MODE == MODE_STATS) {
                 stats_chunk(v[u], c >> 2, live, lane, a, cnt);
@@ -493,7 +520,8 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
             float y[8] = {lo.x * cn, lo.y * cn, lo.z * cn, lo.w * cn, hi.x * cn, hi.y * cn, hi.z * cn, hi.w * cn};
             if constexpr (MODE == MODE_ROTATE) {
                 int64_t yoff = (int64_t)row * a.ldy + (int64_t)blk * B + (int64_t)q * 8;
-                store_chunk<OUT_BF16>((char*)a.y + yoff * (OUT_BF16 ? 2 : 4), y);
+                if constexpr (OUT_BF16) store_chunk<true>((char*)a.y + yoff * 2, y);
+                else store_chunk_f32_quad((char*)a.y + yoff * 4, y, lane);
             } else if constexpr (MODE == MODE_STATS) {
                 stats_chunk(y, (row * a.cpr + blk * (B / 8) + q) >> 2, true, lane, a, cnt);
             } else {
