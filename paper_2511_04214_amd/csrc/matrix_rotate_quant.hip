@@ -163,6 +163,7 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
             if (tile + a.nsplits < a.ntiles) dma_tile(tile + a.nsplits, buf ^ 1u);   // uniform
         }
         uint32_t sbv[NB];
+        v16f accs[MODE == 0 ? NB : 1];
 #pragma unroll
         for (int bb = 0; bb < NB; ++bb) {
             sbv[bb] = 0;
@@ -199,19 +200,7 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
             // acc[4 q + i] = y[row][col0 + 32 bb + 8 q + 4 h + i]
             const uint32_t cb = col0 + 32u * bb;
             if constexpr (MODE == 0) {
-                if constexpr (IN_BF16) { if (bb == NB - 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-                if (row < a.M) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const uint64_t e = (uint64_t)row * (uint64_t)a.ldy + cb + 8u * q + 4u * h;
-                        if constexpr (OUT_BF16) {
-                            uint2 o = make_uint2(pack_bf16x2(acc[4 * q], acc[4 * q + 1]), pack_bf16x2(acc[4 * q + 2], acc[4 * q + 3]));
-                            *reinterpret_cast<uint2*>((char*)a.y + e * 2) = o;
-                        } else {
-                            *reinterpret_cast<float4*>((char*)a.y + e * 4) = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
-                        }
-                    }
-                }
+                accs[bb] = acc;
             } else {
                 const float lo8[8] = {acc[0], acc[1], acc[2], acc[3], acc[4], acc[5], acc[6], acc[7]};
                 const float hi8[8] = {acc[8], acc[9], acc[10], acc[11], acc[12], acc[13], acc[14], acc[15]};
@@ -228,6 +217,53 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
                 const auto sw = __builtin_amdgcn_permlane32_swap(U, V, false, false);
                 const uint2 o = make_uint2((sw[0] & 0xffffu) | (sw[1] << 16), (sw[0] >> 16) | (sw[1] & 0xffff0000u));
                 *reinterpret_cast<uint2*>(ep + m * (16u * NB) + (uint32_t)bb * 16u + 8u * h) = o;   // row m, block bb, half h
+            }
+        }
+        if constexpr (MODE == 0) {
+            // The rotated values leave through LDS too: in the accumulator layout a lane holds 4 consecutive
+            // columns of its own row, rows apart between neighbouring lanes (stored from there the kernel ran
+            // at a third of the memory rate).  The tile goes, 256 bytes of every row at a time (all 128 bf16
+            // columns, or 64 fp32 columns = two of the four blocks), into the operand buffer that this tile's
+            // MFMAs have finished reading (LDS operations of a wavefront execute in order; fp32 input has no
+            // operand buffers), 16-byte piece p of row i at i * 256 + ((p ^ (i & 15)) << 4); it is read back
+            // with 16 consecutive lanes per row and stored as 4 rows x 256 contiguous bytes per instruction.
+            static_assert(NB == 4, "the staging below is laid out for 128 columns per wavefront");
+            uint8_t* const st = wl + (IN_BF16 ? buf * TILE : 0u);
+            constexpr int ROUNDS = OUT_BF16 ? 1 : 2;
+            constexpr int OES = OUT_BF16 ? 2 : 4;
+            const uint32_t rrow = lane >> 4, rp16 = lane & 15u;
+#pragma unroll
+            for (int rd = 0; rd < ROUNDS; ++rd) {
+#pragma unroll
+                for (int b2 = 0; b2 < NB / ROUNDS; ++b2) {
+                    const v16f& c = accs[rd * (NB / ROUNDS) + b2];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if constexpr (OUT_BF16) {      // 8 bytes: half h of piece 4 b2 + q
+                            const uint2 o = make_uint2(pack_bf16x2(c[4 * q], c[4 * q + 1]), pack_bf16x2(c[4 * q + 2], c[4 * q + 3]));
+                            *reinterpret_cast<uint2*>(st + m * 256u + ((((uint32_t)(4 * b2 + q)) ^ (m & 15u)) << 4) + 8u * h) = o;
+                        } else {                       // 16 bytes: piece 8 b2 + 2 q + h
+                            *reinterpret_cast<float4*>(st + m * 256u + ((((uint32_t)(8 * b2 + 2 * q) + h) ^ (m & 15u)) << 4)) =
+                                make_float4(c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]);
+                        }
+                    }
+                }
+                v4i o[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t r = rrow + 4u * j;
+                    o[j] = *reinterpret_cast<const v4i*>(st + r * 256u + ((rp16 ^ (r & 15u)) << 4));
+                }
+                // next tile landed, earlier stores done (loads and stores share one counter)
+                if constexpr (IN_BF16) { if (rd == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t orow = tile * 32u + rrow + 4u * j;
+                    if (orow < a.M) {
+                        char* dst = (char*)a.y + ((uint64_t)orow * (uint64_t)a.ldy + col0) * OES + rd * 256 + rp16 * 16u;
+                        __builtin_nontemporal_store(o[j], reinterpret_cast<v4i*>(dst));
+                    }
+                }
             }
         }
         if constexpr (MODE == 2) {
