@@ -221,18 +221,18 @@ __device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, 
     const float am = quad_max(absmax8(y));
     const uint32_t sb = e8m0_from_amax(am);
     const uint32_t w = encode8_e2m1(y, sb);
-    const int ex = (int)sb - 127;
+    const float sc = as_f32(sb ? sb << 23 : 0x00400000u);   // 2^(sb - 127); scale byte 0 is the subnormal 2^-127
     float e2 = 0.0f;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        f2 d;   // the two codes of byte p as fp32 (scale 1), then times 2^(sb - 127), exact
+        f2 d;   // the two codes of byte p as fp32 (scale 1); value * 2^(sb - 127) is exact, and so is y - that
         if (p == 0) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 0);
         if (p == 1) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 1);
         if (p == 2) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 2);
         if (p == 3) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, 1.0f, 3);
-        const float e0 = y[2 * p] - __builtin_ldexpf(d.x, ex), e1 = y[2 * p + 1] - __builtin_ldexpf(d.y, ex);
-        e2 += e0 * e0;
-        e2 += e1 * e1;
+        const float e0 = __builtin_fmaf(-d.x, sc, y[2 * p]), e1 = __builtin_fmaf(-d.y, sc, y[2 * p + 1]);
+        e2 = __builtin_fmaf(e0, e0, e2);
+        e2 = __builtin_fmaf(e1, e1, e2);
     }
     e2 += lane_xor<1>(e2);
     e2 += lane_xor<2>(e2);
@@ -256,9 +256,9 @@ __device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, 
             if (p == 1) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(wb, 1.0f, 1);
             if (p == 2) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(wb, 1.0f, 2);
             if (p == 3) d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(wb, 1.0f, 3);
-            const float e0 = y[2 * p] - d.x * s, e1 = y[2 * p + 1] - d.y * s;
-            eb += e0 * e0;
-            eb += e1 * e1;
+            const float e0 = __builtin_fmaf(-d.x, s, y[2 * p]), e1 = __builtin_fmaf(-d.y, s, y[2 * p + 1]);
+            eb = __builtin_fmaf(e0, e0, eb);
+            eb = __builtin_fmaf(e1, e1, eb);
         }
         eb += lane_xor<1>(eb);
         eb += lane_xor<2>(eb);
