@@ -40,7 +40,7 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3: one fp32 lane-operation p
 # 2 widenings, 22 of the activation's fixed sequence, 1.5 bf16 rounding, 5 butterfly stages + 1 normalisation,
 # 2.5 group maximum / scale / encode / zero fix
 SWIGLU_FUSED_OPS_PER_ELEM = 34.0
-PROFILED_TRAFFIC = {"mxfp4_gemm_mlp8b_bf16": 616.1e6, "rotate_quant_16384x8192": 339.7e6,
+PROFILED_TRAFFIC = {"mxfp4_gemm_mlp8b_bf16": 617.2e6, "rotate_quant_16384x8192": 340.8e6,
                     "matrix_rotate_quant_16384x8192": 340.9e6, "block_stats_16384x8192": 302.1e6,
                     "swiglu_rotate_quant_8192x14336": 532.2e6}
 
