@@ -80,7 +80,7 @@ brq_status brq_operand_bytes(int64_t rows, int64_t K, brq_layout layout, int64_t
 /*
  * y = x * diag(s) * diag(H_B, ..., H_B) / sqrt(B)   (Sec. 4.3, Eq. 1 with R_i = Sylvester
  * Hadamard of order B, normalised so that R_i^T R_i = I; B = K is the global rotation
- * the paper compares with; B = 8 ... 128 is the rotation-dimension sweep of Sec. 5.3).
+ * the paper compares with; B = 8 ... 128 is the rotation-dimension sweep of Sec. 5.2).
  * signs: NULL, or K sign bytes s_k (device memory, 16-byte aligned): element k of every row is
  * negated before the butterfly where signs[k] < 0 -- the random sign diagonal of the
  * "randomized Hadamard" rotations of Sec. 5.1; diag(s) H_B / sqrt(B) is still orthogonal, and

@@ -60,7 +60,12 @@ def _bind(path):
     L.oracle_rotate_quantize_fused_signed.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
     L.oracle_swiglu_elem.argtypes = [ctypes.c_float, ctypes.c_float]
     L.oracle_swiglu_elem.restype = ctypes.c_float
+    L.oracle_swiglu_f64.argtypes = [ctypes.c_double, ctypes.c_double]
+    L.oracle_swiglu_f64.restype = ctypes.c_double
+    L.oracle_f64_to_bf16.argtypes = [ctypes.c_double]
+    L.oracle_f64_to_bf16.restype = ctypes.c_uint16
     L.oracle_swiglu.argtypes = [vp, vp, i32, i64, i64, i64, i64, vp, i32, i64]
+    L.oracle_swiglu_f64_array.argtypes = [vp, vp, i32, i64, i64, i64, i64, vp]
     L.oracle_swiglu_rotate_quantize_fused.argtypes = [vp, vp, i32, i64, i64, i64, i64, i32, i64, vp, vp, vp]
     L.oracle_matrix_rotate_f64.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_matrix_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
@@ -193,8 +198,24 @@ class Oracle:
     def swiglu_elem(self, g, u):
         return np.float32(self.L.oracle_swiglu_elem(float(np.float32(g)), float(np.float32(u))))
 
+    def swiglu_f64(self, g, u):
+        return float(self.L.oracle_swiglu_f64(float(g), float(u)))
+
+    def f64_to_bf16(self, x):
+        return int(self.L.oracle_f64_to_bf16(float(x)))
+
+    def swiglu_exact(self, gate, up):
+        """h = silu(gate) * up in fp64, unrounded."""
+        gate, M, K, ldg = _rows(gate)
+        up, M2, K2, ldu = _rows(up)
+        if (M, K) != (M2, K2) or gate.dtype != up.dtype:
+            raise ValueError("gate and up must agree in shape and type")
+        h = np.empty((M, K), dtype=np.float64)
+        _check(self.L.oracle_swiglu_f64_array(_p(gate), _p(up), _dt(gate), M, K, ldg, ldu, _p(h)), "swiglu_f64_array")
+        return h
+
     def swiglu(self, gate, up, out_bf16=False):
-        """h = silu(gate) * up in the oracle's fixed fp32 sequence; fp32, or bf16 bits."""
+        """h = silu(gate) * up: the fp64 definition rounded once to fp32, or once to bf16 (bits)."""
         gate, M, K, ldg = _rows(gate)
         up, M2, K2, ldu = _rows(up)
         if (M, K) != (M2, K2) or gate.dtype != up.dtype:

@@ -18,8 +18,8 @@
  *     Hadamard, no learned rotation).  This file follows the benchmark's naming and
  *     calls the block SIZE "B" (the paper's g).
  *   - Sec. 4.3 ("reduced online computing"): the online rotation sits in front of down_proj,
- *     whose input in the evaluated LLaMA models is silu(gate) * up; oracle_swiglu* produce
- *     that input and feed it to the same rotation and quantizer.
+ *     whose input in the evaluated LLaMA models is silu(gate) * up; oracle_swiglu* are that
+ *     definition in fp64, rounded once, fed to the same rotation and quantizer.
  *   - Eq. (1) with arbitrary orthogonal 32 x 32 blocks (oracle_matrix_rotate*): the dense
  *     per-block product in fp64.
  *   - Sec. 4.1 / 4.2 / Appendix "Rotation Comparison": the block statistics behind the paper's
@@ -36,8 +36,9 @@
  * products; one-hot rows; norm preservation; involution; block independence; the E2M1
  * value table from the 1/2/1 bit split; hand-worked rounding / tie / saturation /
  * scale cases; round trip of representable blocks; (XH)(WH)^T = XW^T; brute-force GEMM;
- * the SwiGLU producer against g / (1 + exp(-g)) * u in fp64 within its stated error, its
- * exact special values, and the fused call against the composition of the pinned parts.
+ * the SwiGLU producer against torch's float64 silu, the identity silu(g) - silu(-g) = g,
+ * known values and limits, the single rounding to bf16 against a hand-worked double-rounding
+ * case, and the fused call against the composition of the pinned parts.
  * parity unpinned: the paper prints no quantized block, code, scale or kernel output,
  * so the whole pipeline has no paper-printed value to be compared with.
  *
@@ -292,7 +293,7 @@ int oracle_mxfp4_quantize(const void *x, int xdt, int64_t M, int64_t K, int64_t 
 /* Fused call = quantize(block_rotate(x) kept in fp32): the composition, nothing else. */
 int oracle_rotate_quantize_fused_signed(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx,
                                         int64_t B, const int8_t *signs, uint8_t *codes, uint8_t *scales) {
-    /* B may be smaller than the quantization group (rotation-dimension sweep, Sec. 5.3): the
+    /* B may be smaller than the quantization group (rotation-dimension sweep, Sec. 5.2): the
        rotation block and the 32-element group are independent */
     if (!x || !codes || !scales || K % 32 || B < 2) return ORACLE_ERR_ARG;
     float *y = (float *)malloc((size_t)M * (size_t)K * sizeof(float));
@@ -311,94 +312,84 @@ int oracle_rotate_quantize_fused(const void *x, int xdt, int64_t M, int64_t K, i
 /* ------------------------------------------------------------------------------------
  * The producer of the rotated layer's input (Sec. 4.3, "reduced online computing": the
  * online rotation R_4 sits in front of down_proj).  In the LLaMA models the paper evaluates,
- * down_proj reads h = silu(gate) * up, silu(g) = g / (1 + exp(-g)).  The paper does not say
- * how h is computed; because h feeds a quantizer whose codes are compared bit for bit, the
- * fp32 operation sequence is fixed here (every step one IEEE round-to-nearest-even fp32
- * operation; fma = fused multiply-add with a single rounding):
+ * down_proj reads the gated activation
  *
- *   gn = max(g, -86)                 silu below -86 is taken as silu(-86) ~ -4e-36
- *   ge = min(gn, 86)                 keeps 2^n inside the normal range
- *   z  = ge * (-log2(e))             -log2(e) as fp32 = -0x3FB8AA3B
- *   n  = z rounded to the nearest integer, ties to even;  r = z - n   (exact, |r| <= 1/2)
- *   p  = 1 + r (c1 + r (c2 + r (c3 + r (c4 + r c5))))     five fma, innermost first
- *   e  = p * 2^n                     exact: p in [0.70, 1.42], |n| <= 125
- *   d  = 1 + e
- *   y  = 1/d by Newton's iteration: y0 = the fp32 whose bit pattern is 0x7EF311C7 - bits(d)
- *        (within 5.1 % of 1/d for every d >= 1), then three times t = fma(-d, y, 1),
- *        y = fma(y, t, y); the error squares each time and ends at one ulp
- *   s  = gn * y
- *   h  = s * u
- *   h  = bf16(h), round to nearest even, when the intermediate type is bf16 (what a
- *        separate bf16 activation kernel would have stored); else h stays fp32
+ *     h = silu(gate) * up,      silu(g) = g * sigmoid(g) = g / (1 + exp(-g)).
  *
- * c1..c5 approximate 2^r on [-1/2, 1/2] to 1.7e-7 relative (own minimax fit).  A division
- * would do for s; the Newton reciprocal is what the GPU kernel can afford (the correctly
- * rounded division costs it twice as many instructions), and both sides must agree.
+ * The paper says nothing about how h is computed, so the oracle is the definition itself,
+ * written out in fp64 (libm's exp) and rounded ONCE to the type h is kept in: fp32, or bf16
+ * when a separate activation kernel would have stored bf16.  An implementation that works in
+ * fp32 (hardware exp and reciprocal, say) lands within a few ulp of this value; it is judged
+ * by an error bound on h and, for the codes and scales behind it, by the interval that bound
+ * leaves open -- not by bit equality with one particular fp32 operation sequence.
  * ---------------------------------------------------------------------------------- */
-static float f32_from_bits(uint32_t u) {
-    float f;
-    memcpy(&f, &u, 4);
-    return f;
+double oracle_swiglu_f64(double g, double u) { return g / (1.0 + exp(-g)) * u; }
+
+float oracle_swiglu_elem(float g, float u) { return (float)oracle_swiglu_f64((double)g, (double)u); }
+
+/* fp64 -> bf16, one rounding to nearest, ties to even (finite values inside the bf16 range).
+ * bf16 keeps 8 significant bits down to 2^-126 and a fixed quantum of 2^-133 below. */
+uint16_t oracle_f64_to_bf16(double x) {
+    double a = fabs(x), q;
+    int ex;
+    (void)frexp(a, &ex); /* a = m * 2^ex, m in [0.5, 1) */
+    int quantum = ex - 8; /* exponent of the last kept bit */
+    if (quantum < -133) quantum = -133;
+    q = ldexp(rint(ldexp(a, -quantum)), quantum); /* rint: to nearest, ties to even */
+    float f = (float)q; /* exact: q has at most 8 significant bits */
+    uint32_t bits;
+    memcpy(&bits, &f, 4);
+    return (uint16_t)((bits >> 16) | (signbit(x) ? 0x8000u : 0u));
 }
 
-float oracle_swiglu_elem(float g, float u) {
-    const float c1 = f32_from_bits(0x3F317215u), c2 = f32_from_bits(0x3E75FCDEu), c3 = f32_from_bits(0x3D635BA9u),
-                c4 = f32_from_bits(0x3C1E753Du), c5 = f32_from_bits(0x3AADDCFAu);
-    const float neg_log2e = -f32_from_bits(0x3FB8AA3Bu);
-    float gn = g > -86.0f ? g : -86.0f;
-    float ge = gn < 86.0f ? gn : 86.0f;
-    float z = ge * neg_log2e;
-    float n = rintf(z); /* default rounding mode: to nearest, ties to even */
-    float r = z - n;
-    float p = c5;
-    p = fmaf(p, r, c4);
-    p = fmaf(p, r, c3);
-    p = fmaf(p, r, c2);
-    p = fmaf(p, r, c1);
-    p = fmaf(p, r, 1.0f);
-    float e = ldexpf(p, (int)n);
-    float d = 1.0f + e;
-    uint32_t dbits;
-    memcpy(&dbits, &d, 4);
-    float y = f32_from_bits(0x7EF311C7u - dbits);
-    for (int it = 0; it < 3; ++it) {
-        float t = fmaf(-d, y, 1.0f);
-        y = fmaf(y, t, y);
-    }
-    float s = gn * y;
-    return s * u;
-}
-
-/* h[r][k] = swiglu(gate[r][k], up[r][k]); gate, up: [M][ldg], [M][ldu] of dt; h: [M][ldh] of
- * hdt (bf16 = RNE of the fp32 value). */
+/* h[r][k] = silu(gate[r][k]) * up[r][k]; gate, up: [M][ldg], [M][ldu] of dt; h: [M][ldh] of
+ * hdt: the fp64 value rounded once to fp32, or once to bf16. */
 int oracle_swiglu(const void *gate, const void *up, int dt, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
                   void *h, int hdt, int64_t ldh) {
     if (!gate || !up || !h || ldg < K || ldu < K || ldh < K) return ORACLE_ERR_ARG;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < M; ++r) {
         for (int64_t k = 0; k < K; ++k) {
-            float v = oracle_swiglu_elem(load_elem(gate, dt, r * ldg + k), load_elem(up, dt, r * ldu + k));
+            double v = oracle_swiglu_f64((double)load_elem(gate, dt, r * ldg + k), (double)load_elem(up, dt, r * ldu + k));
             if (hdt == ORACLE_BF16)
-                ((uint16_t *)h)[r * ldh + k] = oracle_f32_to_bf16(v);
+                ((uint16_t *)h)[r * ldh + k] = oracle_f64_to_bf16(v);
             else
-                ((float *)h)[r * ldh + k] = v;
+                ((float *)h)[r * ldh + k] = (float)v;
         }
     }
     return ORACLE_OK;
 }
 
-/* Producer fused with the online step: quantize(block_rotate(h)) with h as above, the
- * composition and nothing else.  hdt says whether h passes through bf16 on the way (the
- * value is then widened again, exactly).  B = 1 means no rotation (H_1 = [1]). */
+/* The same in fp64, unrounded (the value an error bound is stated against). */
+int oracle_swiglu_f64_array(const void *gate, const void *up, int dt, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                            double *h) {
+    if (!gate || !up || !h || ldg < K || ldu < K) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < M; ++r)
+        for (int64_t k = 0; k < K; ++k)
+            h[r * K + k] = oracle_swiglu_f64((double)load_elem(gate, dt, r * ldg + k), (double)load_elem(up, dt, r * ldu + k));
+    return ORACLE_OK;
+}
+
+/* Producer fused with the online step: quantize(block_rotate(h)) with h as above (rounded once
+ * to hdt, then widened exactly), the composition and nothing else.  B = 1 means no rotation
+ * (H_1 = [1]). */
 int oracle_swiglu_rotate_quantize_fused(const void *gate, const void *up, int dt, int64_t M, int64_t K,
                                         int64_t ldg, int64_t ldu, int hdt, int64_t B, const int8_t *signs,
                                         uint8_t *codes, uint8_t *scales) {
     if (!codes || !scales || K % 32 || B < 1) return ORACLE_ERR_ARG;
-    float *h = (float *)malloc((size_t)(M > 0 ? M : 1) * (size_t)K * sizeof(float));
-    if (!h) return ORACLE_ERR_ARG;
-    int rc = oracle_swiglu(gate, up, dt, M, K, ldg, ldu, h, ORACLE_F32, K);
-    if (rc == ORACLE_OK && hdt == ORACLE_BF16)
-        for (int64_t i = 0; i < M * K; ++i) h[i] = oracle_bf16_to_f32(oracle_f32_to_bf16(h[i]));
+    size_t n = (size_t)(M > 0 ? M : 1) * (size_t)K;
+    float *h = (float *)malloc(n * sizeof(float));
+    uint16_t *hb = (hdt == ORACLE_BF16) ? (uint16_t *)malloc(n * sizeof(uint16_t)) : NULL;
+    int rc = (h && (hdt != ORACLE_BF16 || hb)) ? ORACLE_OK : ORACLE_ERR_ARG;
+    if (rc == ORACLE_OK) {
+        if (hdt == ORACLE_BF16) {
+            rc = oracle_swiglu(gate, up, dt, M, K, ldg, ldu, hb, ORACLE_BF16, K);
+            if (rc == ORACLE_OK) oracle_bf16_to_f32_array(hb, M * K, h);
+        } else {
+            rc = oracle_swiglu(gate, up, dt, M, K, ldg, ldu, h, ORACLE_F32, K);
+        }
+    }
     if (rc == ORACLE_OK) {
         if (B == 1)
             rc = signs ? ORACLE_ERR_ARG : oracle_mxfp4_quantize(h, ORACLE_F32, M, K, K, codes, scales);
@@ -406,6 +397,7 @@ int oracle_swiglu_rotate_quantize_fused(const void *gate, const void *up, int dt
             rc = oracle_rotate_quantize_fused_signed(h, ORACLE_F32, M, K, K, B, signs, codes, scales);
     }
     free(h);
+    free(hb);
     return rc;
 }
 

@@ -331,7 +331,7 @@ def pin_signed_rotation(o):
 
 
 def pin_fused_small_blocks_and_signs(o):
-    # Rotation blocks smaller than the 32-element quantization group (Sec. 5.3 sweeps the
+    # Rotation blocks smaller than the 32-element quantization group (Sec. 5.2 sweeps the
     # rotation dimension) and signed rotations: still the composition, group stays 32.
     rng = np.random.default_rng(22)
     x = (rng.standard_t(4, size=(5, 128)) * 3).astype(np.float32)
@@ -366,42 +366,67 @@ def _bf16_bits_torch(x32):
     return torch.from_numpy(np.ascontiguousarray(x32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
 
 
-def pin_swiglu_against_closed_form(o):
-    # h = g / (1 + exp(-g)) * u, the definition, in fp64 (numpy's exp, which the oracle does not
-    # call).  The oracle's fp32 sequence promises |h - exact| <= (6 + 1.25 |g|) 2^-24 |exact| on
-    # |g| <= 86: 1.7e-7 from the polynomial; z = g log2(e) carries half an ulp of its own size
-    # plus the rounding of log2(e) (1.22 |z| 2^-24 together), which exp turns into a relative
-    # error of ln(2) times that = 1.22 |g| 2^-24; the Newton reciprocal ends within one ulp; the
-    # rest are single roundings.
+def pin_swiglu_is_the_definition(o):
+    # h = silu(g) * u with silu(g) = g * sigmoid(g) (the gated activation in front of down_proj,
+    # Sec. 4.3).  Against torch's float64 silu (a library routine the oracle does not call), against
+    # values and identities that the mathematics fixes, and the roundings against numpy's / torch's.
+    import torch
     rng = np.random.default_rng(31)
-    g = np.concatenate([np.linspace(-86, 86, 400001), rng.standard_normal(200000) * 4]).astype(np.float32)
+    g = np.concatenate([np.linspace(-100, 100, 200001), rng.standard_normal(100000) * 4,
+                        [0.0, -0.0, 1e-30, -1e-30, 700.0, -700.0, 3.0e38, -3.0e38]]).astype(np.float32)
     u = (rng.standard_normal(g.size) * 2).astype(np.float32)
-    h = o.swiglu(g[None, :], u[None, :])[0]
-    exact = np.float64(g) / (1.0 + np.exp(-np.float64(g))) * np.float64(u)
-    assert np.all(np.abs(h - exact) <= (6 + 1.25 * np.abs(np.float64(g))) * 2.0 ** -24 * np.abs(exact))
+    u[-2:] = 0.5                                           # keeps the product of the largest gates finite in fp32
+    exact = o.swiglu_exact(g[None, :], u[None, :])[0]
+    want = (torch.nn.functional.silu(torch.from_numpy(g.astype(np.float64))) * torch.from_numpy(u.astype(np.float64))).numpy()
+    assert np.all(np.abs(exact - want) <= 1e-15 * np.abs(want))        # a few fp64 ulp between two evaluations
+    # rounded once to fp32: numpy's conversion of the fp64 value; torch's own value rounds to the same
+    # fp32 except where the two fp64 evaluations straddle a rounding boundary
+    h32 = o.swiglu(g[None, :], u[None, :])[0]
+    assert np.array_equal(h32.view(np.uint32), exact.astype(np.float32).view(np.uint32))
+    assert (h32.view(np.uint32) == want.astype(np.float32).view(np.uint32)).mean() > 0.99999
     # not symmetric in its arguments: silu acts on the first one
-    assert abs(float(o.swiglu_elem(1.0, 3.0)) - 3.0 / (1 + math.exp(-1.0))) < 1e-6
-    assert abs(float(o.swiglu_elem(3.0, 1.0)) - 3.0 / (1 + math.exp(-3.0))) < 1e-6
-    # exact cases: silu(0) = 0; exp(-g) < 2^-24 makes the denominator 1 (whose Newton reciprocal
-    # is exactly 1), so silu(g) = g for
-    # g >= 17; a power-of-two u scales exactly; far below zero the value is pinned at silu(-86)
-    assert float(o.swiglu_elem(0.0, 7.0)) == 0.0
-    for gv in (17.0, 20.5, 86.0, 100.0, 3.0e38):
-        assert float(o.swiglu_elem(gv, 1.0)) == float(np.float32(gv))
-        assert float(o.swiglu_elem(gv, -0.5)) == -0.5 * float(np.float32(gv))
+    assert abs(o.swiglu_f64(1.0, 3.0) - 3.0 * 0.7310585786300049) < 1e-15         # sigmoid(1) = 0.73105857863...
+    assert abs(o.swiglu_f64(3.0, 1.0) - 3.0 * 0.9525741268224334) < 1e-15         # sigmoid(3) = 0.95257412682...
+    assert abs(o.swiglu_f64(-1.0, 1.0) + 0.2689414213699951) < 1e-16              # -sigmoid(-1)
+    # silu(g) - silu(-g) = g sigmoid(g) + g (1 - sigmoid(g)) = g
+    for gv in (0.1, 0.5, 1.0, 2.5, 7.0, 20.0, 50.0):
+        assert abs((o.swiglu_f64(gv, 1.0) - o.swiglu_f64(-gv, 1.0)) - gv) <= 2e-16 * gv
+    # the minimum of silu: value -0.27846454276107..., where g = -1.27846454276107... (silu'(g) = 0 there
+    # means silu(g) = g + 1 ... i.e. the minimum value is g_min + 1)
+    gmin = -1.2784645427610738
+    assert abs(o.swiglu_f64(gmin, 1.0) - (gmin + 1.0)) < 1e-15
+    assert o.swiglu_f64(gmin - 1e-3, 1.0) > o.swiglu_f64(gmin, 1.0) < o.swiglu_f64(gmin + 1e-3, 1.0)
+    # limits: silu(0) = 0; silu(g) -> g for large g (exp(-g) below half an ulp of 1); silu(g) -> -0 far below
+    assert o.swiglu_f64(0.0, 7.0) == 0.0
+    for gv in (40.0, 86.0, 100.0, float(np.float32(3.0e38))):
+        assert o.swiglu_f64(gv, 1.0) == gv and float(o.swiglu_elem(gv, -0.5)) == -0.5 * gv
+    assert abs(o.swiglu_f64(-40.0, 1.0) + 40.0 * math.exp(-40.0)) < 1e-30
+    assert o.swiglu_f64(-800.0, 1.0) == 0.0 and float(o.swiglu_elem(-3.0e38, 2.0)) == 0.0
+    # u is a plain factor
     for gv in (-3.0, 0.7, 5.0):
-        assert float(o.swiglu_elem(gv, 4.0)) == 4.0 * float(o.swiglu_elem(gv, 1.0))
-    tail = float(o.swiglu_elem(-86.0, 1.0))
-    assert -5e-36 < tail < -3e-36
-    for gv in (-86.5, -100.0, -1.0e30, -3.0e38):
-        assert float(o.swiglu_elem(gv, 1.0)) == tail
+        assert o.swiglu_f64(gv, 4.0) == 4.0 * o.swiglu_f64(gv, 1.0)
+        assert o.swiglu_f64(gv, -1.0) == -o.swiglu_f64(gv, 1.0)
     # bf16 inputs are widened exactly: the same values given as bf16 bits or as fp32 agree
     gb, ub = _bf16_bits_torch(g[:4096]), _bf16_bits_torch(u[:4096])
     gw, uw = o.bf16_to_f32(gb), o.bf16_to_f32(ub)
     assert np.array_equal(o.swiglu(gb[None, :], ub[None, :]), o.swiglu(gw[None, :], uw[None, :]))
-    # bf16 output is the round-to-nearest-even of the fp32 output (torch's conversion)
-    h32 = o.swiglu(gw[None, :], uw[None, :])
-    assert np.array_equal(o.swiglu(gw[None, :], uw[None, :], out_bf16=True), _bf16_bits_torch(h32))
+    # bf16 output: ONE rounding of the fp64 value to nearest even.  Hand-worked double-rounding trap:
+    # 1 + 2^-8 + 2^-30 lies above the midpoint of 1 and 1 + 2^-7, so it rounds up (0x3F81); through fp32
+    # it would first become the midpoint itself and then tie down to 1 (0x3F80)
+    assert o.f64_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -30) == 0x3F81
+    assert o.f64_to_bf16(1.0 + 2.0 ** -8) == 0x3F80 and o.f64_to_bf16(1.0 + 3 * 2.0 ** -8) == 0x3F82      # ties to even
+    assert o.f64_to_bf16(-2.5) == 0xC020 and o.f64_to_bf16(0.0) == 0 and o.f64_to_bf16(-0.0) == 0x8000
+    assert o.f64_to_bf16(2.0 ** -133) == 1 and o.f64_to_bf16(2.0 ** -134) == 0 and o.f64_to_bf16(1.5 * 2.0 ** -133) == 2
+    # ... and it equals torch's conversion (which goes through fp32) wherever the fp32 value is not itself
+    # a bf16 midpoint, i.e. wherever rounding twice cannot differ from rounding once
+    x64 = rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 6, 20000)
+    got = np.array([o.f64_to_bf16(v) for v in x64], dtype=np.uint16)
+    t = torch.from_numpy(x64).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    safe = (x64.astype(np.float32).view(np.uint32) & np.uint32(0xFFFF)) != 0x8000
+    assert safe.mean() > 0.999 and np.array_equal(got[safe], t[safe])
+    hb = o.swiglu(gw[None, :], uw[None, :], out_bf16=True)[0]
+    ex = o.swiglu_exact(gw[None, :], uw[None, :])[0]
+    assert np.array_equal(hb, np.array([o.f64_to_bf16(v) for v in ex], dtype=np.uint16))
 
 
 def pin_swiglu_fused_is_the_composition(o):

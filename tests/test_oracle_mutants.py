@@ -47,17 +47,19 @@ MUTANTS = [
     ("signs_ignored", "if (signs && signs[b * B + i] < 0) e = -e;", ""),
     ("fused_drops_signs", "int rc = oracle_block_rotate_signed(x, xdt, M, K, ldx, B, signs, y, ORACLE_F32, K);",
      "int rc = oracle_block_rotate_signed(x, xdt, M, K, ldx, B, NULL, y, ORACLE_F32, K);"),
-    ("swiglu_exp_sign", "const float neg_log2e = -f32_from_bits(0x3FB8AA3Bu);", "const float neg_log2e = f32_from_bits(0x3FB8AA3Bu);"),
-    ("swiglu_forgets_up", "return s * u;", "return s;"),
-    ("swiglu_numerator_clamped_above", "float s = gn * y;", "float s = ge * y;"),
-    ("swiglu_two_newton_steps", "for (int it = 0; it < 3; ++it) {", "for (int it = 0; it < 2; ++it) {"),
-    ("swiglu_newton_sign", "float t = fmaf(-d, y, 1.0f);", "float t = fmaf(d, y, 1.0f);"),
-    ("swiglu_no_lower_clamp", "float gn = g > -86.0f ? g : -86.0f;", "float gn = g;"),
-    ("swiglu_poly_drops_top_term", "float p = c5;", "float p = 0.0f;"),
-    ("swiglu_poly_wrong_linear_term", "p = fmaf(p, r, c1);", "p = fmaf(p, r, 1.0f);"),
-    ("swiglu_denominator_without_one", "float d = 1.0f + e;", "float d = e;"),
-    ("swiglu_up_read_with_gate_pitch", "load_elem(up, dt, r * ldu + k)", "load_elem(up, dt, r * ldg + k)"),
-    ("swiglu_fused_skips_bf16", "if (rc == ORACLE_OK && hdt == ORACLE_BF16)", "if (0)"),
+    ("swiglu_exp_sign", "return g / (1.0 + exp(-g)) * u;", "return g / (1.0 + exp(g)) * u;"),
+    ("swiglu_forgets_up", "return g / (1.0 + exp(-g)) * u;", "return g / (1.0 + exp(-g));"),
+    ("swiglu_is_sigmoid_only", "return g / (1.0 + exp(-g)) * u;", "return 1.0 / (1.0 + exp(-g)) * u;"),
+    ("swiglu_denominator_without_one", "return g / (1.0 + exp(-g)) * u;", "return g / exp(-g) * u;"),
+    ("swiglu_gate_and_up_swapped", "return (float)oracle_swiglu_f64((double)g, (double)u);", "return (float)oracle_swiglu_f64((double)u, (double)g);"),
+    ("swiglu_bf16_through_fp32", "q = ldexp(rint(ldexp(a, -quantum)), quantum);", "q = ldexp(rint(ldexp((double)(float)a, -quantum)), quantum);"),
+    ("swiglu_bf16_seven_bits", "int quantum = ex - 8;", "int quantum = ex - 7;"),
+    ("swiglu_bf16_no_subnormal_quantum", "if (quantum < -133) quantum = -133;", ""),
+    ("swiglu_bf16_sign_lost", "(signbit(x) ? 0x8000u : 0u)", "0u"),
+    ("swiglu_up_read_with_gate_pitch", "(double)load_elem(up, dt, r * ldu + k));\n            if (hdt == ORACLE_BF16)",
+     "(double)load_elem(up, dt, r * ldg + k));\n            if (hdt == ORACLE_BF16)"),
+    ("swiglu_fused_skips_bf16", "        if (hdt == ORACLE_BF16) {\n            rc = oracle_swiglu(gate, up, dt, M, K, ldg, ldu, hb, ORACLE_BF16, K);",
+     "        if (0) {\n            rc = oracle_swiglu(gate, up, dt, M, K, ldg, ldu, hb, ORACLE_BF16, K);"),
     ("swiglu_fused_never_rotates", "        if (B == 1)\n            rc = signs ?", "        if (B >= 1)\n            rc = signs ?"),
     ("swiglu_fused_drops_signs", "rc = oracle_rotate_quantize_fused_signed(h, ORACLE_F32, M, K, K, B, signs, codes, scales);",
      "rc = oracle_rotate_quantize_fused_signed(h, ORACLE_F32, M, K, K, B, NULL, codes, scales);"),
