@@ -11,7 +11,10 @@
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers (HBM of the current HIP device).  The caller
- *     owns every buffer; the library allocates nothing and keeps no state.
+ *     owns every buffer; the library allocates nothing.  The only state it keeps is a per-device
+ *     set-up record (number of compute units; the declaration of the kernels that use more than
+ *     64 KB of LDS), made under a lock by brq_init() or by the first call on that device.  A caller
+ *     that captures calls into a HIP graph, or times the first call, calls brq_init() first.
  *   - Matrices are row-major with K contiguous.  X is [M][ldx] (ldx >= K, in elements),
  *     Y is [M][ldy].  Quantized operands come in one of two layouts (brq_layout):
  *       BRQ_LAYOUT_ROWMAJOR  codes [M][K/2] bytes, scales [M][K/32] bytes.
@@ -62,12 +65,19 @@ typedef enum {
     BRQ_ERR_ALIGN = 4,       /* pointer or pitch not 16-byte aligned */
     BRQ_ERR_DTYPE = 5,       /* dtype is not one of brq_dtype */
     BRQ_ERR_LAUNCH = 6,      /* hipLaunchKernel failed (hipGetLastError) */
-    BRQ_ERR_LAYOUT = 7       /* layout is not one of brq_layout */
+    BRQ_ERR_LAYOUT = 7,      /* layout is not one of brq_layout */
+    BRQ_ERR_DEVICE = 8       /* no current HIP device, or its one-time set-up failed */
 } brq_status;
 
 typedef enum { BRQ_F32 = 0, BRQ_BF16 = 1 } brq_dtype;
 
 typedef enum { BRQ_LAYOUT_ROWMAJOR = 0, BRQ_LAYOUT_TILED = 1 } brq_layout;
+
+/*
+ * One-time set-up for the CURRENT HIP device (see the conventions above): idempotent, thread-safe,
+ * launches nothing.  Optional: every call does the same on first use.
+ */
+brq_status brq_init(void);
 
 /*
  * Sizes in bytes of the codes and scales buffers of a quantized [rows][K] operand in `layout`
@@ -117,36 +127,33 @@ brq_status brq_rotate_quantize_fused(const void* x, brq_dtype xdt, int64_t M, in
                                      uint8_t* scales, brq_layout layout, void* stream);
 
 /*
- * The online step with its producer in front (Sec. 4.3: the online rotation R_4 sits before
+ * The gated activation that feeds the rotated layer (Sec. 4.3: the online rotation R_4 sits before
  * down_proj; in the LLaMA models the paper evaluates, down_proj reads h = silu(gate) * up):
- *     brq_rotate_quantize_fused(h, B, signs)  with  h[m][k] = silu(gate[m][k]) * up[m][k]
- * in one pass over gate and up; h never visits memory.  Bit-identical to that composition
- * with h computed as follows (the paper does not say how; since h feeds a quantizer, the
- * fp32 operation sequence is part of this interface; every step is one IEEE
- * round-to-nearest-even fp32 operation, fma = fused multiply-add):
- *     gn = max(g, -86);  ge = min(gn, 86);  z = ge * -log2(e)      (-log2(e) = -0x3FB8AA3B)
- *     n = z rounded to the nearest integer, ties to even;  r = z - n
- *     p = fma(fma(fma(fma(fma(c5, r, c4), r, c3), r, c2), r, c1), r, 1)
- *         c1..c5 = 0x3F317215, 0x3E75FCDE, 0x3D635BA9, 0x3C1E753D, 0x3AADDCFA   (2^r on [-1/2, 1/2])
- *     e = p * 2^n (exact);  d = 1 + e
- *     y = 1/d by Newton: y0 = the fp32 with bit pattern 0x7EF311C7 - bits(d), then three times
- *         t = fma(-d, y, 1), y = fma(y, t, y)
- *     s = gn * y;  h = s * u
- * |h - silu(g) u| <= (6 + 1.25 |g|) 2^-24 |silu(g) u| for |g| <= 86; below -86 silu is held at
- * silu(-86) ~ -4e-36.  hdt = BRQ_BF16 rounds h to bf16 (nearest even) before the rotation, which
- * reproduces a separate activation kernel that stores bf16; BRQ_F32 keeps the fp32 value.
- * gate [M][ldg], up [M][ldu], both of xdt (they may be two halves of one buffer).
- * B as in brq_rotate_quantize_fused, or 1 for no rotation (quantization alone; signs must
- * then be NULL).
- */
-/*
- * The activation alone: h = silu(gate) * up in the sequence above, stored as fp32 or as its
- * bf16 rounding.  Not on the fused path (that is its point); it is the unfused first half that
- * the fused call is measured and checked against.  h [M][ldh] of hdt may overlap neither input.
+ *     h[m][k] = silu(gate[m][k]) * up[m][k],   silu(g) = g / (1 + exp(-g)),
+ * stored as fp32 or as its bf16 rounding (nearest even).  Arithmetic: fp32 on the hardware's
+ * exponential and reciprocal; the result h' satisfies
+ *     |h' - h| <= (8 + 2 |g|) * 2^-24 * |h| + 2^-119 * |u|
+ * (the absolute term covers gates below -87, where the result may be flushed to zero).  The last
+ * bits are those of this kernel, not of a reference sequence.  The call exists as the unfused first
+ * half that the fused call below is measured and checked against.
+ * gate [M][ldg], up [M][ldu], both of xdt (they may be two halves of one buffer); h [M][ldh] of hdt
+ * may overlap neither input.
  */
 brq_status brq_swiglu(const void* gate, const void* up, brq_dtype xdt, int64_t M, int64_t K,
                       int64_t ldg, int64_t ldu, void* h, brq_dtype hdt, int64_t ldh, void* stream);
 
+/*
+ * The online step with its producer in front:
+ *     brq_rotate_quantize_fused(h, B, signs)   with h = brq_swiglu(gate, up) of type hdt,
+ * in one pass over gate and up; h never visits memory.  Bit-identical to that two-call sequence
+ * of THIS library (hdt = BRQ_BF16 rounds h to bf16 before the rotation, as a separate activation
+ * kernel storing bf16 would; BRQ_F32 keeps the fp32 value).  Against the exact activation the codes
+ * and scales are those of a value within the bound stated for brq_swiglu: equal to the codes of the
+ * exact h except where h (or its bf16 rounding, or the group maximum) lies within that bound of a
+ * rounding boundary.
+ * B as in brq_rotate_quantize_fused, or 1 for no rotation (quantization alone; signs must then be
+ * NULL).
+ */
 brq_status brq_swiglu_rotate_quantize_fused(const void* gate, const void* up, brq_dtype xdt,
                                             int64_t M, int64_t K, int64_t ldg, int64_t ldu,
                                             brq_dtype hdt, int64_t B, const int8_t* signs,
@@ -225,34 +232,6 @@ brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_lay
  */
 brq_status brq_to_rowmajor(const uint8_t* codes_tiled, const uint8_t* scales_tiled, int64_t rows,
                            int64_t K, uint8_t* codes_out, uint8_t* scales_out, void* stream);
-
-/*
- * Measurement aid, not part of the method: `workgroups` workgroups of 4 wavefronts each issue
- * iters x 16 block-scaled fp4 MFMAs (v_mfma_scale_f32_32x32x64, the instruction of the product
- * kernels) back to back from registers, 2 * 32*32*64 flops apiece, i.e. a launch does
- * workgroups * 4 * iters * 16 * 131072 flops.  Operand fragments are read once from
- * `operands` (2048 bytes: 16 bytes per lane for each of the two operands, e.g. the first bytes
- * of a quantized matrix, so that the arithmetic sees realistic bit patterns); `sink` receives
- * workgroups * 256 floats, of which sink[0] is the number of shader-clock cycles and sink[1] the
- * number of 100 MHz reference-clock ticks that workgroup 0's first wavefront spent in the loop
- * (10 * sink[0] / sink[1] = the clock in MHz that the chip held), the rest without meaning.
- * Timing a launch gives the rate the chip sustains on this
- * instruction alone, the ceiling against which a product kernel's own losses can be read.
- */
-brq_status brq_diag_mfma_ceiling(const uint8_t* operands, int64_t iters, int64_t workgroups,
-                                 float* sink, void* stream);
-
-/*
- * Measurement aid: brq_mxfp4_gemm on a shape that the persistent large-shape kernel takes (M > 128,
- * N % 256 == 0, K % 512 == 0 or both operands tiled; anything else: BRQ_ERR_SHAPE), which in
- * addition writes to clock2 (device, 2 x uint64): [0] the shader-clock cycles and [1] the 100 MHz
- * reference-clock ticks that the kernel's first workgroup ran for.  10 * [0] / [1] is the clock
- * in MHz that the chip held during the product; y receives the product as usual.
- */
-brq_status brq_diag_mxfp4_gemm_clock(const uint8_t* aq, const uint8_t* as, brq_layout a_layout,
-                                     const uint8_t* wq, const uint8_t* ws, brq_layout w_layout,
-                                     int64_t M, int64_t N, int64_t K, void* y, brq_dtype ydt,
-                                     int64_t ldy, uint64_t* clock2, void* stream);
 
 /* Static, human-readable text for a status code. */
 const char* brq_strerror(brq_status s);

@@ -1,0 +1,46 @@
+/*
+ * brq_diag.h -- measurement aids of the block-rotation MXFP4 library.  Not part of the method and not
+ * on the product path: bench.py uses them to read the ceiling of the block-scaled MFMA and the clock
+ * the chip holds, next to the product kernel's own time.  Same conventions as brq.h.
+ */
+#ifndef BRQ_DIAG_H
+#define BRQ_DIAG_H
+
+#include "brq.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * `workgroups` workgroups of 4 wavefronts each issue
+ * iters x 16 block-scaled fp4 MFMAs (v_mfma_scale_f32_32x32x64, the instruction of the product
+ * kernels) back to back from registers, 2 * 32*32*64 flops apiece, i.e. a launch does
+ * workgroups * 4 * iters * 16 * 131072 flops.  Operand fragments are read once from
+ * `operands` (2048 bytes: 16 bytes per lane for each of the two operands, e.g. the first bytes
+ * of a quantized matrix, so that the arithmetic sees realistic bit patterns); `sink` receives
+ * workgroups * 256 floats, of which sink[0] is the number of shader-clock cycles and sink[1] the
+ * number of 100 MHz reference-clock ticks that workgroup 0's first wavefront spent in the loop
+ * (10 * sink[0] / sink[1] = the clock in MHz that the chip held), the rest without meaning.
+ * Timing a launch gives the rate the chip sustains on this
+ * instruction alone, the ceiling against which a product kernel's own losses can be read.
+ */
+brq_status brq_diag_mfma_ceiling(const uint8_t* operands, int64_t iters, int64_t workgroups,
+                                 float* sink, void* stream);
+
+/*
+ * brq_mxfp4_gemm on a shape that the persistent large-shape kernel takes (M > 128,
+ * N % 256 == 0, K % 512 == 0 or both operands tiled; anything else: BRQ_ERR_SHAPE), which in
+ * addition writes to clock2 (device, 2 x uint64): [0] the shader-clock cycles and [1] the 100 MHz
+ * reference-clock ticks that the kernel's first workgroup ran for.  10 * [0] / [1] is the clock
+ * in MHz that the chip held during the product; y receives the product as usual.
+ */
+brq_status brq_diag_mxfp4_gemm_clock(const uint8_t* aq, const uint8_t* as, brq_layout a_layout,
+                                     const uint8_t* wq, const uint8_t* ws, brq_layout w_layout,
+                                     int64_t M, int64_t N, int64_t K, void* y, brq_dtype ydt,
+                                     int64_t ldy, uint64_t* clock2, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BRQ_DIAG_H */

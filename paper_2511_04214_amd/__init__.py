@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libbrq.so")
 
 BRQ_F32, BRQ_BF16 = 0, 1
 LAYOUTS = {"rowmajor": 0, "tiled": 1}
-EXPORTS = ["brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
+EXPORTS = ["brq_init", "brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
            "brq_swiglu", "brq_swiglu_rotate_quantize_fused", "brq_matrix_rotate",
            "brq_matrix_rotate_quantize_fused", "brq_block_stats", "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_diag_mxfp4_gemm_clock", "brq_strerror", "brq_version"]
 
@@ -64,11 +64,17 @@ def lib():
         L.brq_diag_mxfp4_gemm_clock.restype = i32
         L.brq_diag_mfma_ceiling.argtypes = [vp, i64, i64, vp, vp]
         L.brq_diag_mfma_ceiling.restype = i32
+        L.brq_init.restype = i32
         L.brq_strerror.argtypes = [i32]
         L.brq_strerror.restype = ctypes.c_char_p
         L.brq_version.restype = i32
         _lib = L
     return _lib
+
+
+def init():
+    """One-time set-up for the current device (brq_init); every call does the same on first use."""
+    _check(lib().brq_init())
 
 
 def _check(status):
@@ -171,7 +177,7 @@ def rotate_quantize_fused(x, B, codes=None, scales=None, stream=None, layout="ro
 
 
 def swiglu(gate, up, out_dtype=torch.float32, out=None, stream=None):
-    """h = silu(gate) * up in the library's fixed fp32 sequence (brq_swiglu)."""
+    """h = silu(gate) * up, within the error bound stated in brq.h (brq_swiglu)."""
     M, K, ldg = _rows(gate, "gate")
     M2, K2, ldu = _rows(up, "up")
     if (M, K) != (M2, K2) or gate.dtype != up.dtype:

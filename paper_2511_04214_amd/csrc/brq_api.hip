@@ -1,7 +1,40 @@
 // extern "C" boundary of the library: argument validation on the host, then a kernel launch
-// on the caller's stream.  No allocation, no state, no host synchronisation.
+// on the caller's stream.  No allocation, no host synchronisation; the only state is the per-device
+// set-up record below.
+#include <mutex>
+
 #include "../../include/brq.h"
+#include "../../include/brq_diag.h"
 #include "brq_launch.h"
+
+namespace brq {
+
+namespace {
+std::mutex g_device_mu;
+struct DeviceSlot { bool ready; int cus; } g_device[64];
+}  // namespace
+
+hipError_t device_cus(int* cus) {
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_device_mu);
+    DeviceSlot& slot = g_device[dev];
+    if (!slot.ready) {
+        int v = 0;
+        if (hipError_t e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev); e != hipSuccess) return e;
+        if (v <= 0) return hipErrorInvalidDevice;
+        if (hipError_t e = setup_gemm_tiled(); e != hipSuccess) return e;
+        if (hipError_t e = setup_gemm_smallm(); e != hipSuccess) return e;
+        if (hipError_t e = setup_matrix_rotate(); e != hipSuccess) return e;
+        slot.cus = v;
+        slot.ready = true;
+    }
+    *cus = slot.cus;
+    return hipSuccess;
+}
+
+}  // namespace brq
 
 namespace {
 
@@ -40,6 +73,11 @@ brq_status launched(hipError_t e) { return e == hipSuccess ? BRQ_OK : BRQ_ERR_LA
 }  // namespace
 
 extern "C" {
+
+brq_status brq_init(void) {
+    int cus = 0;
+    return brq::device_cus(&cus) == hipSuccess ? BRQ_OK : BRQ_ERR_DEVICE;
+}
 
 brq_status brq_block_rotate(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
                             const int8_t* signs, void* y, brq_dtype ydt, int64_t ldy, void* stream) {
@@ -255,10 +293,11 @@ const char* brq_strerror(brq_status s) {
         case BRQ_ERR_DTYPE: return "unknown dtype";
         case BRQ_ERR_LAUNCH: return "kernel launch failed";
         case BRQ_ERR_LAYOUT: return "unknown operand layout";
+        case BRQ_ERR_DEVICE: return "no usable HIP device, or its one-time set-up failed";
     }
     return "unknown status";
 }
 
-int brq_version(void) { return 350; }
+int brq_version(void) { return 400; }
 
 }  // extern "C"

@@ -5,6 +5,16 @@
 
 namespace brq {
 
+// Per-device facts and one-time set-up.  The launchers size their grids by the number of compute units
+// and three kernel families ask for more than the default 64 KB of LDS, which HIP wants declared per
+// function and device before the first launch.  device_cus() returns the CU count of the CURRENT device and
+// on its first call for that device (under a lock, keyed by the device id) runs the three set-up routines;
+// brq_init() is that call made ahead of time.  Nothing else in the library outlives a call.
+hipError_t device_cus(int* cus);
+hipError_t setup_gemm_tiled();     // mxfp4_gemm_tiled.hip
+hipError_t setup_gemm_smallm();    // mxfp4_gemm.hip
+hipError_t setup_matrix_rotate();  // matrix_rotate_quant.hip
+
 // mode: 0 rotate, 1 quantize, 2 fused rotate+quantize.  log2b: 0 for quantize, else 3..14.
 // tiled: codes and scales go out in the tiled operand layout instead of row-major.
 // signs: [K] sign bytes of a randomized rotation (element k negated where signs[k] < 0) or null.

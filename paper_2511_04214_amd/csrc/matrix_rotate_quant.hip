@@ -300,19 +300,24 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
 
 }  // namespace matrot
 
+// The kernels use 72 KB of LDS per workgroup: declared once per device.
+hipError_t setup_matrix_rotate() {
+    constexpr int NB = 4, LDS = 4 * matrot::wave_lds(NB);
+    const void* kernels[6] = {(const void*)matrot::k_matrot<true, 0, true, NB>, (const void*)matrot::k_matrot<true, 0, false, NB>,
+                              (const void*)matrot::k_matrot<false, 0, true, NB>, (const void*)matrot::k_matrot<false, 0, false, NB>,
+                              (const void*)matrot::k_matrot<true, 2, false, NB>, (const void*)matrot::k_matrot<false, 2, false, NB>};
+    for (const void* k : kernels)
+        if (hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, LDS); e != hipSuccess) return e;
+    return hipSuccess;
+}
+
 // mode 0: rotation alone into y; mode 2: fused with the quantizer into codes / scales.
 // K % 128 == 0 (checked by the caller), nR = 1 or K / 32.
 hipError_t launch_matrix_rotate(int mode, bool in_bf16, bool out_bf16, const void* x, int64_t M, int64_t K, int64_t ldx,
                                 const float* R, int64_t nR, void* y, int64_t ldy, uint8_t* codes, uint8_t* scales,
                                 bool tiled, hipStream_t s) {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        cus = 256;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-    }
+    int cus = 0;
+    if (hipError_t e = device_cus(&cus); e != hipSuccess) return e;
     matrot::Args a;
     a.x = x; a.ldx = ldx; a.R = R; a.shared = nR == 1 ? 1u : 0u;
     a.M = (uint32_t)M; a.K = (uint32_t)K; a.y = y; a.ldy = ldy; a.codes = codes; a.scales = scales;
@@ -332,18 +337,7 @@ hipError_t launch_matrix_rotate(int mode, bool in_bf16, bool out_bf16, const voi
         hipError_t e = launch_zero_kpad(codes, scales, M, K, s);
         if (e != hipSuccess) return e;
     }
-    constexpr int LDS = 4 * matrot::wave_lds(NB);          // 72 KB: above the default limit
-    static bool attr_set = false;
-    if (!attr_set) {
-        const void* kernels[6] = {(const void*)matrot::k_matrot<true, 0, true, NB>, (const void*)matrot::k_matrot<true, 0, false, NB>,
-                                  (const void*)matrot::k_matrot<false, 0, true, NB>, (const void*)matrot::k_matrot<false, 0, false, NB>,
-                                  (const void*)matrot::k_matrot<true, 2, false, NB>, (const void*)matrot::k_matrot<false, 2, false, NB>};
-        for (const void* k : kernels) {
-            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-            if (e != hipSuccess) return e;
-        }
-        attr_set = true;
-    }
+    constexpr int LDS = 4 * matrot::wave_lds(NB);          // 72 KB: above the default limit (setup_matrix_rotate)
     const dim3 grid((a.ncols * a.nsplits + 3u) / 4u), block(256);
     if (mode == 0) {
         if (in_bf16) {

@@ -363,28 +363,31 @@ hipError_t launch_mfma_ceiling(const uint8_t* operands, int iters, int workgroup
     return hipGetLastError();
 }
 
+using SmallmKern = void (*)(const uint8_t*, const uint8_t*, int, const uint8_t*, const uint8_t*, int, int, int, int, void*,
+                            int, int64_t);
+static const SmallmKern smallm_kern[4][4] = {
+    {k_gemm_smallm<1, 0>, k_gemm_smallm<1, 1>, k_gemm_smallm<1, 2>, k_gemm_smallm<1, 3 % SMALLM_SETS>},
+    {k_gemm_smallm<2, 0>, k_gemm_smallm<2, 1>, k_gemm_smallm<2, 2>, k_gemm_smallm<2, 3 % SMALLM_SETS>},
+    {k_gemm_smallm<3, 0>, k_gemm_smallm<3, 1>, k_gemm_smallm<3, 2>, k_gemm_smallm<3, 3 % SMALLM_SETS>},
+    {k_gemm_smallm<4, 0>, k_gemm_smallm<4, 1>, k_gemm_smallm<4, 2>, k_gemm_smallm<4, 3 % SMALLM_SETS>}};
+
+// The weight-streaming kernels use up to 108 KB of LDS per workgroup: declared once per device.
+hipError_t setup_gemm_smallm() {
+    for (int m = 0; m < 4; ++m)
+        for (int t = 0; t < 4; ++t)
+            if (hipError_t e = hipFuncSetAttribute((const void*)smallm_kern[m][t], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   smallm_lds_bytes(1 + m)); e != hipSuccess) return e;
+    return hipSuccess;
+}
+
 hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
                              bool out_bf16, int64_t ldy, hipStream_t s) {
     const int64_t Kp = (K + 511) / 512 * 512;
+    int cus = 0;
+    if (hipError_t e = device_cus(&cus); e != hipSuccess) return e;      // (also the per-device kernel set-up)
     if (M <= 128 && (K == Kp || (a.tiled && w.tiled)) && Kp < (int64_t(1) << 26)) {
         // decode batches: weight streaming with the activations shared through LDS
-        using Kern = void (*)(const uint8_t*, const uint8_t*, int, const uint8_t*, const uint8_t*, int, int, int, int, void*,
-                              int, int64_t);
-        static const Kern kern[4][4] = {
-            {k_gemm_smallm<1, 0>, k_gemm_smallm<1, 1>, k_gemm_smallm<1, 2>, k_gemm_smallm<1, 3 % SMALLM_SETS>},
-            {k_gemm_smallm<2, 0>, k_gemm_smallm<2, 1>, k_gemm_smallm<2, 2>, k_gemm_smallm<2, 3 % SMALLM_SETS>},
-            {k_gemm_smallm<3, 0>, k_gemm_smallm<3, 1>, k_gemm_smallm<3, 2>, k_gemm_smallm<3, 3 % SMALLM_SETS>},
-            {k_gemm_smallm<4, 0>, k_gemm_smallm<4, 1>, k_gemm_smallm<4, 2>, k_gemm_smallm<4, 3 % SMALLM_SETS>}};
-        static bool attr_set = false;
-        if (!attr_set) {
-            for (int m = 0; m < 4; ++m)
-                for (int t = 0; t < 4; ++t) {
-                    hipError_t e = hipFuncSetAttribute((const void*)kern[m][t], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                       smallm_lds_bytes(1 + m));
-                    if (e != hipSuccess) return e;
-                }
-            attr_set = true;
-        }
+        const auto& kern = smallm_kern;
         const int mi = (int)((M - 1) / 32), tail = (int)((Kp / 512) % SMALLM_SETS);
         const dim3 grid((uint32_t)((N + 127) / 128)), block(256);
         hipLaunchKernelGGL(kern[mi][tail], grid, block, smallm_lds_bytes(1 + mi), s, a.codes, a.scales, (int)a.tiled,

@@ -537,26 +537,16 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
 
 // ---- host side ---------------------------------------------------------------------
 
-static int g_rowwise_cus = 0;   // compute units of the device (0 = not yet asked)
-
 // Workgroups of a streaming launch.  Measured on X 16384 x 8192 (bf16, B = 32): one chunk in
 // flight per lane and many short-lived workgroups beat a persistent grid (8 per CU, two
 // chunks in flight: 63 us; 64 per CU, one chunk: 55 us): the dispatcher keeps every CU topped up
 // and the loads of a finished workgroup's successor overlap the arithmetic of its neighbours.
 // Each workgroup still makes about 4 passes so that small inputs do not pay for launching
 // thousands of workgroups.
-static int rowwise_grid(uint32_t nchunks, int U) {
-    if (g_rowwise_cus == 0) {
-        int dev = 0, cus = 256;
-        if (hipGetDevice(&dev) == hipSuccess) {
-            int v = 0;
-            if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-        }
-        g_rowwise_cus = cus;
-    }
+static int rowwise_grid(uint32_t nchunks, int U, int cus) {
     const uint32_t need = (nchunks + 256u * U - 1) / (256u * U);
     uint32_t grid = need / 4;
-    const uint32_t lo = (uint32_t)g_rowwise_cus * 8, hi = (uint32_t)g_rowwise_cus * 64;
+    const uint32_t lo = (uint32_t)cus * 8, hi = (uint32_t)cus * 64;
     if (grid < lo) grid = lo;
     if (grid > hi) grid = hi;
     return (int)(need < grid ? need : grid);
@@ -579,11 +569,13 @@ static uint32_t fix_columns(int& grid, uint32_t period, uint32_t per_wg) {
 
 template <int LOG2B, bool IN_BF16, int MODE, bool OUT_BF16, bool PROD = false>
 static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
+    int cus = 0;
+    if (hipError_t e = device_cus(&cus); e != hipSuccess) return e;
     if constexpr ((MODE == MODE_QUANT || MODE == MODE_FUSED) && LOG2B <= 7) {
         if (a.stages != 0 && (a.cpr & 15u) == 0 && a.ldx * (IN_BF16 ? 2 : 4) * 4 < (int64_t(1) << 32) &&
             (!PROD || a.ldx2 * (IN_BF16 ? 2 : 4) * 4 < (int64_t(1) << 32))) {
             const uint32_t rows = a.nchunks / a.cpr, nitems = ((rows + 3u) / 4u) * (a.cpr >> 4);
-            int grid = rowwise_grid(nitems * 64u, 1);
+            int grid = rowwise_grid(nitems * 64u, 1, cus);
             RowArgs b = a;
             b.sign_fixed = a.signs ? fix_columns(grid, a.cpr >> 4, 4) : 0;
             hipLaunchKernelGGL((k_rowwise_t4<LOG2B, IN_BF16, MODE, PROD>), dim3(grid), dim3(256), 0, s, b, rows, nitems);
@@ -591,9 +583,9 @@ static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
         }
     }
     constexpr int U = 1;
-    int grid = rowwise_grid(a.nchunks, U);
+    int grid = rowwise_grid(a.nchunks, U, cus);
     if constexpr (MODE == MODE_STATS) {   // fewer, longer-lived workgroups: each ends with atomics on the counters
-        const int cap = g_rowwise_cus * 8;
+        const int cap = cus * 8;
         if (grid > cap) grid = cap;
     }
     RowArgs b = a;
@@ -613,8 +605,9 @@ static hipError_t launch_lds(const RowArgs& a, int64_t M, int64_t K, hipStream_t
     const uint32_t nblocks = (uint32_t)(M * bpr);
     uint32_t grid = nblocks;
     if (MODE == MODE_STATS) {
-        rowwise_grid(1, 1);   // (fills g_rowwise_cus)
-        const uint32_t cap = (uint32_t)g_rowwise_cus * 8u;
+        int cus = 0;
+        if (hipError_t e = device_cus(&cus); e != hipSuccess) return e;
+        const uint32_t cap = (uint32_t)cus * 8u;
         if (grid > cap) grid = cap;
     }
     hipLaunchKernelGGL((k_rowwise_lds<LOG2B, IN_BF16, MODE, OUT_BF16, PROD>), dim3(grid), dim3(NT),

@@ -138,8 +138,9 @@ def test_tiny_config_end_to_end(brq, orc):
 
 @pytest.mark.parametrize("name", ["llama1b_up", "down_sweep", "mlp8b"])
 def test_gemm_full_size_sampled_rows(brq, orc, name):
-    """Benchmark shapes in the benchmark's launch configuration; the oracle computes a sample
-    of full output rows (first/last rows of tiles, and random ones)."""
+    """Benchmark shapes in the benchmark's launch configuration; the oracle computes a sample of full
+    output rows: the first and last row of every 128-row band (so of every row of output tiles, 256 or
+    128 rows high, wherever the tile walk puts it), rows next to the 32-row MFMA tile edges, and random ones."""
     from paper_2511_04214_amd import inputs
     cfg = inputs.CONFIGS[name]
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
@@ -147,7 +148,7 @@ def test_gemm_full_size_sampled_rows(brq, orc, name):
     aq, as_ = brq.rotate_quantize_fused(to_dev(x), 32)
     wq, ws = brq.rotate_quantize_fused(to_dev(w), 32)
     rng = np.random.default_rng(77)
-    rows = sorted(set([0, 1, 31, 32, 127, 128, 255, 256, M - 257, M - 256, M - 1] + rng.integers(0, M, 5).tolist()))
+    rows = sorted(set([r for t in range(0, M, 128) for r in (t, t + 127)] + [1, 31, 32, M - 257] + rng.integers(0, M, 8).tolist()))
     check_gemm(brq, orc, to_host(aq), to_host(as_), to_host(wq), to_host(ws), rows=rows)
 
 
@@ -163,6 +164,27 @@ def test_gemm_half_tiles_several_per_workgroup(brq, orc):
         rng = np.random.default_rng(43)
         rows = sorted(set([0, 63, 64, 127, 128, 255, 256, M - 129, M - 128, M - 1] + rng.integers(0, M, 12).tolist()))
         check_gemm(brq, orc, aq, as_, wq, ws, rows=rows)
+
+
+def test_gemm_full_tiles_ragged_last_row(brq, orc):
+    """4100 x 4096: 17 x 16 = 272 tiles of 256 x 256, enough for the full-height tile kernel, whose last
+    tile row has 4 live rows: clamped A loads (row-major and tiled operands take different paths there)
+    and masked stores.  Rows next to the ragged edge, of every tile row, and random ones."""
+    from paper_2511_04214_amd import inputs
+    from test_gpu_layout import to_tiled
+    M, N, K = 4100, 4096, 512
+    aq, as_ = inputs.random_mxfp4(M, K, seed=45)
+    wq, ws = inputs.random_mxfp4(N, K, seed=46)
+    rng = np.random.default_rng(47)
+    rows = sorted(set([r for t in range(0, 4096, 256) for r in (t, t + 255)] + [4096, 4097, 4098, 4099, 3840, 4095]
+                      + rng.integers(0, M, 8).tolist()))
+    y32 = check_gemm(brq, orc, aq, as_, wq, ws, rows=rows)
+    # the same product on tiled operands (slab-clamped A loads): same kernel, same summation order
+    at, wt = [to_dev(t) for t in to_tiled(aq, as_)], [to_dev(t) for t in to_tiled(wq, ws)]
+    buf = torch.full((M + 3, N), -7.0, dtype=torch.float32, device="cuda")
+    brq.mxfp4_gemm(at[0], at[1], wt[0], wt[1], out=buf[:M], a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)
+    assert np.array_equal(to_host(buf[:M]), y32)
+    assert (buf[M:] == -7.0).all(), "wrote below the last row"
 
 
 # 16 < M <= 128: the weight-streaming kernel that shares the activations through LDS (1 to 4 tiles of 32

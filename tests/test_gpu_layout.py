@@ -185,22 +185,25 @@ def test_fused_tiled_full_size_against_the_oracle(brq, orc, name):
     assert np.array_equal(to_host(st)[si], os_)
 
 
-@pytest.mark.parametrize("name", ["mlp8b", "down_sweep"])
-def test_product_tiled_full_size_sampled_rows(brq, orc, name):
-    """bench.py's step on its own inputs (tiled operands, bf16 and fp32 out); the oracle computes
-    a sample of full output rows from its own quantization of the same inputs."""
+@pytest.mark.parametrize("name,B", [("mlp8b", 32), ("down_sweep", 32), ("down_sweep", 64), ("down_sweep", 128),
+                                    ("down_sweep", 8192), ("llama1b_up", 32)])
+def test_product_tiled_full_size_sampled_rows(brq, orc, name, B):
+    """bench.py's step on its own inputs (tiled operands, bf16 and fp32 out), for the down-projection shape
+    at every rotation block of its sweep (Sec. 5.2; B = K is the global rotation); the oracle computes a
+    sample of full output rows from its own rotation and quantization of the same inputs: the first and
+    last row of every 128-row band (every row of output tiles), and random ones."""
     from paper_2511_04214_amd import inputs
     cfg = inputs.CONFIGS[name]
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
     x, w = inputs.make_x(cfg), inputs.make_w(cfg)
-    act, ast = brq.rotate_quantize_fused(to_dev(x), 32, layout="tiled")
-    wct, wst = brq.rotate_quantize_fused(to_dev(w), 32, layout="tiled")
+    act, ast = brq.rotate_quantize_fused(to_dev(x), B, layout="tiled")
+    wct, wst = brq.rotate_quantize_fused(to_dev(w), B, layout="tiled")
     y32 = brq.mxfp4_gemm(act, ast, wct, wst, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)
     y16 = brq.mxfp4_gemm(act, ast, wct, wst, out_dtype=torch.bfloat16, a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)
     rng = np.random.default_rng(78)
-    rows = sorted(set([0, 63, 64, 255, 256, M - 256, M - 1] + rng.integers(0, M, 5).tolist()))
-    oa, oas = orc.rotate_quantize_fused(x[rows], 32)
-    ow, ows = orc.rotate_quantize_fused(w, 32)
+    rows = sorted(set([r for t in range(0, M, 128) for r in (t, t + 127)] + [63, 64] + rng.integers(0, M, 6).tolist()))
+    oa, oas = orc.rotate_quantize_fused(x[rows], B)
+    ow, ows = orc.rotate_quantize_fused(w, B)
     ref, bound = orc.mxfp4_gemm(oa, oas, ow, ows)
     got = to_host(y32).astype(np.float64)[rows]
     assert (np.abs(got - ref) <= 1e-5 * bound + 2.0 ** -126).all()
@@ -209,6 +212,10 @@ def test_product_tiled_full_size_sampled_rows(brq, orc, name):
     u = to_host(y32).view(np.uint32)
     rne = ((u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) >> np.uint32(16)).astype(np.uint16)
     assert np.array_equal(to_host(y16), rne)
+    # the rotation leaves the product invariant before quantization (Sec. 2), so the quantized product stays
+    # near X W^T whatever B is (loose sanity bound on the sampled rows)
+    exact = orc.bf16_to_f32(x[rows]).astype(np.float64) @ orc.bf16_to_f32(w).astype(np.float64).T
+    assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.35
 
 
 @pytest.mark.parametrize("M", [1, 16, 24, 64, 128])

@@ -11,6 +11,7 @@ import pytest
 import torch
 
 from gpu_util import to_dev, to_host
+from interval_check import check_codes_within
 from paper_2511_04214_amd.inputs import f32_to_bf16_bits
 
 pytestmark = pytest.mark.gpu
@@ -45,46 +46,11 @@ def signed_permutation(seed):
     return P
 
 
-def outward32(lo, hi):
-    """float64 interval -> float32 interval that contains it."""
-    l32, h32 = lo.astype(np.float32), hi.astype(np.float32)
-    l32 = np.where(l32.astype(np.float64) > lo, np.nextafter(l32, np.float32(-np.inf)), l32)
-    h32 = np.where(h32.astype(np.float64) < hi, np.nextafter(h32, np.float32(np.inf)), h32)
-    return l32, h32
-
-
-def unpack(codes):
-    out = np.empty((codes.shape[0], codes.shape[1] * 2), dtype=np.uint8)
-    out[:, 0::2] = codes & 0xF
-    out[:, 1::2] = codes >> 4
-    return out
-
-
 def check_fused_within_bound(orc, x_np, R_np, codes, scales):
     """codes / scales (row-major, from the GPU) are reachable from a value within TOL * bound of the
     exact rotation; returns the fraction of code bytes equal to the oracle's nominal ones."""
-    M, K = x_np.shape
     y, bound = orc.matrix_rotate_f64(x_np, R_np, want_bound=True)
-    d = TOL * bound + 2.0 ** -140
-    lo32, hi32 = outward32(y - d, y + d)
-    # scale bytes: the group maximum lies between max(|y| - d) and max(|y| + d)
-    a_lo = np.maximum(np.abs(y) - d, 0).reshape(M, K // 32, 32).max(axis=2)
-    a_hi = (np.abs(y) + d).reshape(M, K // 32, 32).max(axis=2)
-    a_lo32, a_hi32 = outward32(a_lo, a_hi)
-    a_lo32 = np.maximum(a_lo32, 0)
-    s_lo = orc.mxfp4_quantize(np.repeat(a_lo32, 32, axis=1))[1]
-    s_hi = orc.mxfp4_quantize(np.repeat(a_hi32, 32, axis=1))[1]
-    assert ((s_lo <= scales) & (scales <= s_hi)).all(), "scale bytes outside the interval in %d groups" % int(
-        ((scales < s_lo) | (scales > s_hi)).sum())
-    # codes under the GPU's own scale bytes: between the codes of the interval's ends (the encoder is monotone)
-    val = np.array([orc.e2m1_value(c) for c in range(16)])
-    v_lo = val[unpack(orc.mxfp4_encode_with_scales(lo32, scales))]
-    v_hi = val[unpack(orc.mxfp4_encode_with_scales(hi32, scales))]
-    v = val[unpack(codes)]
-    bad = (v < v_lo) | (v > v_hi)
-    assert not bad.any(), "%d codes outside their interval, first at %s" % (int(bad.sum()), np.argwhere(bad)[0])
-    nz = unpack(codes)
-    assert not (nz == 8).any()        # a zero magnitude is code 0
+    check_codes_within(orc, y, TOL * bound + 2.0 ** -140, codes, scales)
     rc, rs = orc.matrix_rotate_quantize_fused(x_np, R_np)
     return float((rc == codes).mean()), float((rs == scales).mean())
 

@@ -1,13 +1,18 @@
 """GPU parity of the gated-activation producer (silu(gate) * up in front of the online
-rotation, Sec. 4.3) through the C ABI against the CPU oracle: the activation itself bit for
-bit in fp32 and bf16, and the fused producer + rotation + MXFP4 call bit for bit in codes and
-scales, in both operand layouts, with gate and up as separate matrices or as two halves of one
-buffer."""
+rotation, Sec. 4.3) through the C ABI against the CPU oracle, which is the definition in fp64.
+
+The library computes the activation in fp32 on the hardware's exponential and reciprocal, so the
+rule is the error bound its interface states: |h' - h| <= (8 + 2 |g|) 2^-24 |h| + 2^-119 |u|.  The
+activation alone is checked against that bound element by element; the fused producer + rotation +
+MXFP4 call by the interval rule (every scale byte and code reachable from a value within the bound,
+tests/interval_check.py), in both operand layouts, with gate and up as separate matrices or as two
+halves of one buffer; and the library's fused call must equal its own two-call sequence bit for bit."""
 import numpy as np
 import pytest
 import torch
 
 from gpu_util import to_dev, to_host
+from interval_check import check_swiglu_fused, swiglu_bound
 from paper_2511_04214_amd.inputs import f32_to_bf16_bits
 
 pytestmark = pytest.mark.gpu
@@ -38,48 +43,47 @@ def make_gu(M, K, seed, dtype):
     return g, u
 
 
-def same_bits(a, b):
-    return np.array_equal(a.view(np.uint32) if a.dtype == np.float32 else a, b.view(np.uint32) if b.dtype == np.float32 else b)
-
-
 # ------------------------------------------------------------------ the activation alone
 
+def check_activation(brq, orc, g, u):
+    """fp32 result within the stated bound of the fp64 definition; bf16 result = nearest-even rounding of
+    the library's own fp32 result.  Returns the largest error in units of the bound."""
+    exact = orc.swiglu_exact(g, u)
+    g64 = (orc.bf16_to_f32(g) if g.dtype == np.uint16 else g).astype(np.float64)
+    u64 = (orc.bf16_to_f32(u) if u.dtype == np.uint16 else u).astype(np.float64)
+    bound = swiglu_bound(g64, u64, exact)
+    got = to_host(brq.swiglu(to_dev(g), to_dev(u)))
+    err = np.abs(got.astype(np.float64) - exact)
+    bad = err > bound
+    assert not bad.any(), "%d of %d outside the bound, first at g=%r u=%r: got %r, exact %r" % (
+        int(bad.sum()), bad.size, g64[bad][0], u64[bad][0], got[bad][0], exact[bad][0])
+    got_b = to_host(brq.swiglu(to_dev(g), to_dev(u), out_dtype=torch.bfloat16))
+    assert np.array_equal(got_b, f32_to_bf16_bits(got))
+    return float((err / np.maximum(bound, 1e-300)).max())
+
+
 def test_swiglu_every_bf16_gate(brq, orc):
-    # every finite bf16 pattern as gate (zeros, subnormals, both signs, the clamps at +-86, the
-    # largest values), against a handful of up values: fp32 results must agree in every bit
+    # every finite bf16 pattern as gate (zeros, subnormals, both signs, gates far outside +-87, the
+    # largest values), against a handful of up values
     bits = finite_bf16(np.arange(1 << 16, dtype=np.uint16)).reshape(64, 1024)
+    worst = 0.0
     for uv in (1.0, -0.5, 3.140625, 1.0e-3, 0.0):
         up = np.full(bits.shape, f32_to_bf16_bits(np.float32([uv]))[0], dtype=np.uint16)
         if uv == 3.140625:   # keep the product finite for the largest gates
             up[(bits & 0x7F80) > 0x7E00] = 0x3F80
-        want = orc.swiglu(bits, up)
-        got = to_host(brq.swiglu(to_dev(bits), to_dev(up)))
-        bad = want.view(np.uint32) != got.view(np.uint32)
-        assert not bad.any(), "u=%g: %d of %d differ, first at gate bits %#x" % (
-            uv, int(bad.sum()), bad.size, int(bits[bad][0]))
-        want_b = orc.swiglu(bits, up, out_bf16=True)
-        got_b = to_host(brq.swiglu(to_dev(bits), to_dev(up), out_dtype=torch.bfloat16))
-        assert np.array_equal(want_b, got_b)
+        worst = max(worst, check_activation(brq, orc, bits, up))
+    # the bound is not slack by orders of magnitude: the measured worst case uses a fair part of it
+    assert 0.02 < worst <= 1.0, worst
 
 
 def test_swiglu_fp32_inputs_dense_sweep(brq, orc):
-    # fp32 gates: a dense sweep of the interesting range plus values whose z = g log2(e) lands on
-    # or next to a half integer (the tie rule of n), and random up
+    # fp32 gates: a dense sweep of the interesting range (incl. where exp(-g) overflows and where
+    # 1 + exp(-g) rounds to 1) plus random gates, random up
     rng = np.random.default_rng(201)
-    g = np.concatenate([np.linspace(-90, 90, 1 << 20), rng.standard_normal(1 << 20) * 3]).astype(np.float32)
-    half = (np.arange(-60, 60, dtype=np.float64) + 0.5) / -1.4426950216293335
-    for d in (-2, -1, 0, 1, 2):
-        h32 = half.astype(np.float32)
-        for _ in range(abs(d)):
-            h32 = np.nextafter(h32, np.float32(np.sign(d) * 1e9))
-        g[rng.choice(g.size, size=h32.size, replace=False)] = h32
+    g = np.concatenate([np.linspace(-95, 95, 1 << 20), rng.standard_normal(1 << 20) * 3]).astype(np.float32)
     g = g.reshape(2048, 1024)
     u = (rng.standard_normal(g.shape) * 2).astype(np.float32)
-    want = orc.swiglu(g, u)
-    got = to_host(brq.swiglu(to_dev(g), to_dev(u)))
-    bad = want.view(np.uint32) != got.view(np.uint32)
-    assert not bad.any(), "%d differ; first g=%r u=%r want=%r got=%r" % (
-        int(bad.sum()), g[bad][0], u[bad][0], want[bad][0], got[bad][0])
+    check_activation(brq, orc, g, u)
 
 
 def test_swiglu_strided_and_ragged(brq, orc):
@@ -90,9 +94,11 @@ def test_swiglu_strided_and_ragged(brq, orc):
     gate, up = buf[:, :K], buf[:, K:]
     out = torch.zeros((M, K + 64), dtype=torch.float32, device="cuda")
     brq.swiglu(gate, up, out=out[:, :K])
-    want = orc.swiglu(g[:, :K], g[:, K:])
     got = to_host(out)
-    assert same_bits(np.ascontiguousarray(got[:, :K]), want)
+    assert np.array_equal(got[:, :K], to_host(brq.swiglu(to_dev(g[:, :K]), to_dev(g[:, K:]))))
+    exact = orc.swiglu_exact(np.ascontiguousarray(g[:, :K]), np.ascontiguousarray(g[:, K:]))
+    bound = swiglu_bound(orc.bf16_to_f32(g[:, :K]).astype(np.float64), orc.bf16_to_f32(g[:, K:]).astype(np.float64), exact)
+    assert (np.abs(got[:, :K] - exact) <= bound).all()
     assert not got[:, K:].any()                      # nothing written past the row
 
 
@@ -102,14 +108,18 @@ def run_fused(brq, orc, g, u, B, h_bf16, layout, signs=None, views=None):
     M, K = g.shape
     gd, ud = (to_dev(g), to_dev(u)) if views is None else views
     sg = None if signs is None else torch.from_numpy(signs).cuda()
-    c, s = brq.swiglu_rotate_quantize_fused(gd, ud, B, h_dtype=torch.bfloat16 if h_bf16 else torch.float32,
-                                            layout=layout, signs=sg)
+    hdt = torch.bfloat16 if h_bf16 else torch.float32
+    c, s = brq.swiglu_rotate_quantize_fused(gd, ud, B, h_dtype=hdt, layout=layout, signs=sg)
+    # the library's own two-call sequence gives the same bytes
+    h = brq.swiglu(gd, ud, out_dtype=hdt)
+    c2, s2 = brq.mxfp4_quantize(h, layout=layout) if B == 1 else brq.rotate_quantize_fused(h, B, layout=layout, signs=sg)
     if layout == "tiled":
         c, s = brq.to_rowmajor(c, s, M, K)
-    rc, rs = orc.swiglu_rotate_quantize_fused(g, u, B, h_bf16=h_bf16, signs=signs)
-    c, s = to_host(c), to_host(s)
-    assert np.array_equal(s, rs), "scales differ in %d places" % int((s != rs).sum())
-    assert np.array_equal(c, rc), "codes differ in %d bytes" % int((c != rc).sum())
+        c2, s2 = brq.to_rowmajor(c2, s2, M, K)
+    assert torch.equal(c, c2) and torch.equal(s, s2), "fused call differs from the two-call sequence"
+    # against the definition: the interval rule
+    same_c, same_s = check_swiglu_fused(orc, g, u, B, h_bf16, signs, to_host(c), to_host(s))
+    assert same_c > 0.995 and same_s > 0.995, (same_c, same_s)      # nearly all are simply the oracle's
 
 
 @pytest.mark.parametrize("layout", ["rowmajor", "tiled"])
@@ -158,8 +168,8 @@ def test_fused_equals_unfused_two_kernel_path(brq):
 
 def test_fused_full_size_sampled_rows(brq, orc):
     # the down_proj input of the 8B MLP (intermediate size 14336) at 8192 tokens, in the launch
-    # configuration the benchmark times; the oracle checks a sample of rows, the rest through the
-    # unfused path's bit identity
+    # configuration the benchmark times; the oracle checks a sample of rows by the interval rule, the
+    # rest through the bit identity with the library's two-call sequence
     M, K = 8192, 14336
     rng = np.random.default_rng(330)
     gd = (torch.randn((M, 2 * K), device="cuda", generator=torch.Generator(device="cuda").manual_seed(330)) * 1.5
@@ -171,8 +181,8 @@ def test_fused_full_size_sampled_rows(brq, orc):
     rows[0], rows[-1] = 0, M - 1
     idx = torch.from_numpy(rows).cuda()
     gs, us = to_host(gate[idx].contiguous()), to_host(up[idx].contiguous())
-    rc, rs = orc.swiglu_rotate_quantize_fused(gs, us, 32, h_bf16=True)
-    assert np.array_equal(to_host(s[idx]), rs) and np.array_equal(to_host(c[idx]), rc)
+    same_c, same_s = check_swiglu_fused(orc, gs, us, 32, True, None, to_host(c[idx]), to_host(s[idx]))
+    assert same_c > 0.999 and same_s > 0.999, (same_c, same_s)
     h = brq.swiglu(gate, up, out_dtype=torch.bfloat16)
     c0, s0 = brq.rotate_quantize_fused(h, 32, layout="tiled")
     c0, s0 = brq.to_rowmajor(c0, s0, M, K)
