@@ -216,26 +216,32 @@ def main():
     gm_clock = {}
     if gemm_M > 128 and N % 256 == 0:
         with torch.cuda.stream(stream):
-            clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+            clk = torch.zeros(6, dtype=torch.int64, device="cuda")
+        split = {}
 
-        def clocked(a_c, a_s, w_c, w_s):
+        def clocked(a_c, a_s, w_c, w_s, key=None):
             vals = []
             for _ in range(3):      # the last launch of a train of back-to-back ones (every launch overwrites clk)
                 for i in range(20):
                     brq.mxfp4_gemm(a_c, a_s, w_c, w_s, out=ys[0], stream=stream, a_layout=LAY, w_layout=LAY, M=gemm_M, N=N,
                                    K=K, clock=clk)
                 stream.synchronize()
-                c, t = clk.tolist()
+                c, t, loop, epi, tiles, pro = clk.tolist()
                 vals.append(0.1 * c / max(t, 1))
+                if key:     # cycles of the kernel's first wavefront: per tile inside the K loop / the epilogue; prologue
+                    split[key] = {"tiles": tiles, "k_loop_cycles_per_tile": loop / max(tiles, 1),
+                                  "epilogue_cycles_per_tile": epi / max(tiles, 1), "prologue_cycles": pro, "total_cycles": c,
+                                  "mfma_cycles_per_tile_at_32": (K // 64) * 16 * 32 * (gemm_M > 0)}
             return float(np.mean(vals))
         for i in range(40):
             gemm(i)
         a_c, a_s = a_operand(codes[0], scales[0], gemm_M)
-        gm_clock["shader_clock_GHz"] = clocked(a_c, a_s, wqs[0], wss[0])
+        gm_clock["shader_clock_GHz"] = clocked(a_c, a_s, wqs[0], wss[0], "workload_operands")
         for i in range(40):
             gemm_const(0)
         a_c, a_s = a_operand(zc, zs, gemm_M)
-        gm_clock["constant_operands_shader_clock_GHz"] = clocked(a_c, a_s, zwc, zws)
+        gm_clock["constant_operands_shader_clock_GHz"] = clocked(a_c, a_s, zwc, zws, "constant_operands")
+        gm_clock["cycle_split_first_wavefront"] = split
     stream.synchronize()
     del zc, zs, zwc, zws
 

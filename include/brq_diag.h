@@ -29,16 +29,19 @@ brq_status brq_diag_mfma_ceiling(const uint8_t* operands, int64_t iters, int64_t
                                  float* sink, void* stream);
 
 /*
- * brq_mxfp4_gemm on a shape that the persistent large-shape kernel takes (M > 128,
- * N % 256 == 0, K % 512 == 0 or both operands tiled; anything else: BRQ_ERR_SHAPE), which in
- * addition writes to clock2 (device, 2 x uint64): [0] the shader-clock cycles and [1] the 100 MHz
- * reference-clock ticks that the kernel's first workgroup ran for.  10 * [0] / [1] is the clock
- * in MHz that the chip held during the product; y receives the product as usual.
+ * brq_mxfp4_gemm on a shape that the persistent large-shape kernel takes (M > 128, N % 256 == 0,
+ * K % 512 == 0 or both operands tiled; anything else: BRQ_ERR_SHAPE), which in addition writes to
+ * `clock` (device, 6 x uint64) what the first wavefront of the kernel's first workgroup measured:
+ *   [0] shader-clock cycles and [1] 100 MHz reference-clock ticks from start to end
+ *       (10 * [0] / [1] is the clock in MHz that the chip held during the product),
+ *   [2] cycles inside the K loops of its output tiles, [3] cycles inside their epilogues,
+ *   [4] the number of output tiles that workgroup processed, [5] cycles of the prologue.
+ * y receives the product as usual.
  */
 brq_status brq_diag_mxfp4_gemm_clock(const uint8_t* aq, const uint8_t* as, brq_layout a_layout,
                                      const uint8_t* wq, const uint8_t* ws, brq_layout w_layout,
                                      int64_t M, int64_t N, int64_t K, void* y, brq_dtype ydt,
-                                     int64_t ldy, uint64_t* clock2, void* stream);
+                                     int64_t ldy, uint64_t* clock, void* stream);
 
 #ifdef __cplusplus
 }

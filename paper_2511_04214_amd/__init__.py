@@ -294,9 +294,9 @@ def mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.float32, out=None, stream=None, 
     """Y[M, N] = deq(aq, as) @ deq(wq, ws)^T on the block-scaled MFMA (brq_mxfp4_gemm).
 
     Row-major operands are 2-D tensors that carry their shape; a tiled operand is a flat byte
-    buffer, so its rows (M or N) and K must be given.  `clock` (an int64 GPU tensor of 2 elements;
+    buffer, so its rows (M or N) and K must be given.  `clock` (an int64 GPU tensor of 6 elements;
     large shapes only, brq_diag_mxfp4_gemm_clock) receives the shader-clock cycles and the 100 MHz
-    ticks that the kernel's first workgroup ran for.
+    ticks that the kernel's first workgroup ran for, and their split over K loops and epilogues.
     """
     for t, n in ((aq, "aq"), (as_, "as"), (wq, "wq"), (ws, "ws")):
         if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.uint8):
@@ -321,8 +321,8 @@ def mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.float32, out=None, stream=None, 
     if y.shape[0] != M or y.shape[1] != N:
         raise ValueError("out must be [M, N]")
     if clock is not None:
-        if not (clock.is_cuda and clock.is_contiguous() and clock.dtype == torch.int64 and clock.numel() == 2):
-            raise ValueError("clock must be a contiguous int64 GPU tensor of 2 elements")
+        if not (clock.is_cuda and clock.is_contiguous() and clock.dtype == torch.int64 and clock.numel() == 6):
+            raise ValueError("clock must be a contiguous int64 GPU tensor of 6 elements")
         _check(lib().brq_diag_mxfp4_gemm_clock(aq.data_ptr(), as_.data_ptr(), la, wq.data_ptr(), ws.data_ptr(), lw, M, N, K,
                                                y.data_ptr(), _dtype_code(y), ldy, clock.data_ptr(), _stream(stream)))
         return y

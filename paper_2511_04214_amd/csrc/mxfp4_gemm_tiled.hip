@@ -59,14 +59,35 @@ template <int N>
 __device__ __forceinline__ void wait_vm_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier\n\t" ::"n"(N) : "memory");
 }
-// The same, but the wait for global memory is skipped when `skip_vm` (wave-uniform) is non-zero.
-template <int N>
-__device__ __forceinline__ void wait_vm_unless_and_barrier(int skip_vm) {
-    asm volatile("s_cmp_lg_u32 %1, 0\n\t"
-                 "s_cbranch_scc1 .Lbrq_novm%=\n\t"
-                 "s_waitcnt vmcnt(%0)\n"
-                 ".Lbrq_novm%=:\n\t"
-                 "s_waitcnt lgkmcnt(0)\n\ts_barrier\n\t" ::"n"(N), "s"(skip_vm) : "memory", "scc");
+// Elements O .. O + 7 of an accumulator, copied to vector registers by instructions that stay where they
+// are written (volatile, ordered with the MFMAs).
+template <int O>
+__device__ __forceinline__ void read_acc8(const v16f& a, IC<O>, float (&c)[16]) {
+    asm volatile("v_accvgpr_read_b32 %0, %8\n\tv_accvgpr_read_b32 %1, %9\n\tv_accvgpr_read_b32 %2, %10\n\t"
+                 "v_accvgpr_read_b32 %3, %11\n\tv_accvgpr_read_b32 %4, %12\n\tv_accvgpr_read_b32 %5, %13\n\t"
+                 "v_accvgpr_read_b32 %6, %14\n\tv_accvgpr_read_b32 %7, %15"
+                 : "=v"(c[O]), "=v"(c[O + 1]), "=v"(c[O + 2]), "=v"(c[O + 3]), "=v"(c[O + 4]), "=v"(c[O + 5]), "=v"(c[O + 6]), "=v"(c[O + 7])
+                 : "a"(a[O]), "a"(a[O + 1]), "a"(a[O + 2]), "a"(a[O + 3]), "a"(a[O + 4]), "a"(a[O + 5]), "a"(a[O + 6]), "a"(a[O + 7]));
+}
+
+// The same without a wait for global memory: the caller has already seen its loads land.
+__device__ __forceinline__ void lds_wait_and_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier\n\t" ::: "memory");
+}
+
+// Pair order of the NACC = 4 * MB accumulators of a wavefront (the order in which a tile's first stage
+// starts them and the output path takes them): index X -> W tile 2 * ((X / 2) / MB) + X % 2, A tile
+// (X / 2) % MB: the two W tiles of one 128-byte bf16 output block are neighbours.
+template <int X, int MB>
+struct PairA { static constexpr int value = 2 * ((X >> 1) / MB) + (X & 1); };
+template <int X, int MB>
+struct PairB { static constexpr int value = (X >> 1) % MB; };
+
+// f(IC<-1>), f(IC<0>), ..., f(IC<N>)
+template <class F, int N, int S = -1>
+__device__ __forceinline__ void static_for_drain(F& f, IC<N> n, IC<S> = {}) {
+    f(IC<S>{});
+    if constexpr (S < N) static_for_drain(f, n, IC<S + 1>{});
 }
 
 // Tiles of one workgroup.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its
@@ -97,6 +118,12 @@ __device__ __forceinline__ void mfma_fp4(v16f& acc, const v4i& wf, const v4i& af
     asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %4 op_sel:[1,1,0] op_sel_hi:[0,0,0] cbsz:4 blgp:4"
                  : "+a"(acc) : "v"(wf), "v"(af), "v"(sw), "v"(sa));
 }
+// The same with C = 0: the first MFMA of a tile on its accumulator (step 0 of the tile's first stage)
+// starts the sum, so the 256 accumulator registers are never cleared by separate instructions.
+__device__ __forceinline__ void mfma_fp4_init(v16f& acc, const v4i& wf, const v4i& af, int sw, int sa) {
+    asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, 0, %3, %4 op_sel_hi:[0,0,0] cbsz:4 blgp:4"
+                 : "+a"(acc) : "v"(wf), "v"(af), "v"(sw), "v"(sa));     // (tied like the others; the old value is not read)
+}
 #define BRQ_MFMA(ACC, WF, AF, SEL, SW, SA) mfma_fp4(ACC, WF, AF, IC<SEL>{}, SW, SA)
 #define BRQ_SLOT_END() __builtin_amdgcn_sched_barrier(0)
 // Refill load S/2 of the stage goes into the even slot S, for all four wavefronts alike.
@@ -113,7 +140,8 @@ struct ClockOut<true> { unsigned long long* p; };
 // MB = A tiles (32 rows) per wavefront: 4 -> 256 x 256 output tile, 2 -> 128 x 256 (for shapes
 // with too few 256 x 256 tiles to fill the chip; the stage is then 16 MFMA slots long).
 // TIMED = the measurement aid of brq_diag.h: workgroup 0 also reports the shader-clock cycles and the
-// 100 MHz ticks it ran for.  The product (TIMED = false) has no such code.
+// 100 MHz ticks it ran for, and how the cycles split into prologue, K loops and epilogues.  The product
+// (TIMED = false) has no such code.
 template <bool OUT_BF16, int MB, bool TIMED>
 __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
                                                        const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
@@ -122,7 +150,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    unsigned long long t_c0 = 0, t_r0 = 0;
+    unsigned long long t_c0 = 0, t_r0 = 0, t_loop = 0, t_epi = 0, t_pro = 0, t_mark = 0;
     if constexpr (TIMED) {
         if (blockIdx.x == 0) { t_c0 = __builtin_readcyclecounter(); t_r0 = __builtin_amdgcn_s_memrealtime(); }
     }
@@ -272,6 +300,112 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         return *reinterpret_cast<const v4i*>(ap[U >> 1][J] + (U & 1) * STAGE_BYTES + T * 2048);
     };
 
+    // ---- output path.  Lane (r, h) holds, for W tile a and A tile b, output row m = 32 b + r and
+    // columns n = 32 a + 8 q + 4 h + {0..3}, q = 0..3: neighbouring lanes hold different rows.
+    // The store path merges the 16-byte accesses of neighbouring lanes only, so storing from
+    // this layout costs one cycle per lane (64 per instruction, 8K per tile).  Each wavefront
+    // therefore turns its output round in a private 4 KB LDS block, 32 rows x 128 bytes at a
+    // time: written as 16-byte chunks from the accumulator layout, read back with 8
+    // consecutive lanes per row, stored as 8 rows x 128 contiguous bytes per instruction.
+    // Chunk c of row i sits at i * 128 + ((c ^ (i & 7)) << 4): 8 lanes that write (8 rows, one
+    // chunk) or read (one row, 8 chunks) then cover all 32 banks.  LDS operations of one
+    // wavefront execute in order, so write -> read -> next write need no waits.
+    //
+    // A block is 32 rows x 128 bytes: bf16 -> the accumulators of two neighbouring W tiles and one
+    // A tile; fp32 -> one accumulator.  Accumulators are taken in "pair order": index x ->
+    // W tile 2 * ((x / 2) / MB) + x % 2, A tile (x / 2) % MB, so that the two accumulators of a bf16
+    // block are consecutive.  Three steps per block: pack + write to LDS (per accumulator), read
+    // back, store.  They are spread over the MFMA slots of the NEXT tile's first stage (drain_slot
+    // below): the matrix cores start the next tile while the vector units move this one out, and
+    // only a workgroup's last tile pays for its output on its own.
+    constexpr int ES = OUT_BF16 ? 2 : 4;
+    constexpr int NACC = 4 * MB, XPB = OUT_BF16 ? 2 : 1;     // accumulators per wavefront, per block
+    const int64_t pitch = ldy * ES;
+    uint8_t* const ybytes = reinterpret_cast<uint8_t*>(y);
+    uint8_t* const ebuf = lds + EPI_BASE + wave * 4096;
+    uint8_t* ytile = ybytes;        // the finished tile's corner for this wavefront
+    int mrem = 0;                   // this lane stores rows row + 8 j < mrem
+    uint32_t st_off = 0, wsw = 0;
+    uint8_t* ewr = ebuf;
+    const uint8_t* erd = ebuf;
+    uint4 ob[2][4];                 // two blocks read back: rows (lane >> 3) + 8 j, j = 0..3
+    auto out_begin = [&](int ti_done) __attribute__((always_inline)) {
+        int ti_e = ti_done;
+        asm volatile("" : "+s"(ti_e));    // keeps the address arithmetic below out of the K loop
+        int tm, tn;
+        tw.tile(ti_e, tm, tn);
+        ytile = ybytes + ((int64_t)tm * TMv + wm * 32 * MB) * pitch + ((int64_t)tn * TN + wn * 128) * ES;
+        // The per-lane offsets do not depend on the tile; passing the lane through an empty asm
+        // statement makes them be recomputed here (a dozen instructions per tile) instead of living in
+        // registers across the K loop.
+        int le = lane;
+        asm volatile("" : "+v"(le));
+        const int re = le & 31, he = le >> 5;
+        st_off = (uint32_t)(le >> 3) * (uint32_t)pitch + (le & 7) * 16;
+        ewr = ebuf + re * 128;                                   // this lane's row for writing
+        wsw = (uint32_t)((re & 7) ^ he) << 4;                    // its chunk swizzle, h folded in
+        erd = ebuf + (le >> 3) * 128 + (((le & 7) ^ ((le >> 3) & 7)) << 4);
+        mrem = M - (tm * TMv + wm * 32 * MB) - (le >> 3);
+    };
+    auto out_pack_write = [&](auto Xc) __attribute__((always_inline)) {
+        constexpr int X = decltype(Xc)::value;
+        const v16f& cacc = acc[PairA<X, MB>::value][PairB<X, MB>::value];
+        if constexpr (OUT_BF16) {
+            // The accumulator is read HERE, by instructions the compiler cannot move: left to itself it copies
+            // every accumulator that a stage will move out into vector registers at the top of the stage
+            // (the copies depend on nothing), which takes more registers than there are.
+            float c[16];
+            read_acc8(cacc, IC<0>{}, c);
+            read_acc8(cacc, IC<8>{}, c);
+            // v_permlane32_swap trades q between the lane halves: a lane then holds columns
+            // 32 a + 16 p + 8 h + {0..7}, p = 0, 1, as one chunk, index (a & 1) * 4 + 2 p + h within the row
+            constexpr int a1 = X & 1;
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                uint32_t x0 = pack_bf16x2(c[8 * p + 0], c[8 * p + 1]), x1 = pack_bf16x2(c[8 * p + 2], c[8 * p + 3]);
+                uint32_t y0 = pack_bf16x2(c[8 * p + 4], c[8 * p + 5]), y1 = pack_bf16x2(c[8 * p + 6], c[8 * p + 7]);
+                auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+                auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+                *reinterpret_cast<uint4*>(ewr + (wsw ^ (uint32_t)((a1 * 4 + 2 * p) << 4))) = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+            }
+        } else {
+            // chunk index 2 q + h
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4*>(ewr + (wsw ^ (uint32_t)(q << 5))) = make_float4(cacc[4 * q], cacc[4 * q + 1], cacc[4 * q + 2], cacc[4 * q + 3]);
+        }
+    };
+    auto out_read = [&](auto Kc) __attribute__((always_inline)) {
+        constexpr int Kb = decltype(Kc)::value & 1;
+        ob[Kb][0] = *reinterpret_cast<const uint4*>(erd);
+        ob[Kb][1] = *reinterpret_cast<const uint4*>(erd + 1024);
+        ob[Kb][2] = *reinterpret_cast<const uint4*>(erd + 2048);
+        ob[Kb][3] = *reinterpret_cast<const uint4*>(erd + 3072);
+    };
+    auto out_store = [&](auto Kc) __attribute__((always_inline)) {
+        constexpr int Kk = decltype(Kc)::value, Kb = Kk & 1, X = Kk * XPB;
+        constexpr int row = PairB<X, MB>::value * 32;
+        constexpr int colbytes = (OUT_BF16 ? PairA<X, MB>::value / 2 : PairA<X, MB>::value) * 128;
+        uint8_t* dst = ytile + row * pitch + colbytes + st_off;
+        // whole 128-byte lines that this kernel never reads back: with the streaming hint the output does not
+        // displace the operand panels that the other XCDs are about to fetch from the memory-side cache
+        typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (row + 8 * j < mrem)
+                __builtin_nontemporal_store(u4{ob[Kb][j].x, ob[Kb][j].y, ob[Kb][j].z, ob[Kb][j].w}, reinterpret_cast<u4*>(dst + 8 * j * pitch));
+    };
+    // What the output path does after MFMA slot S of the next tile's first stage (S = -1: before slot 0;
+    // S = NACC: the first slot of that stage's second step): accumulator S + 1 is packed and written (the
+    // MFMA of slot S + 1 overwrites it), a completed block is read back, and the block read two slots
+    // earlier is stored.
+    auto drain_slot = [&](auto Sc) __attribute__((always_inline)) {
+        constexpr int X = decltype(Sc)::value + 1, XR = X - 2;
+        if constexpr (X < NACC) out_pack_write(IC<X>{});
+        if constexpr (XR >= 0 && XR < NACC && XR % XPB == XPB - 1) out_store(IC<XR / XPB>{});
+        if constexpr (X < NACC && X % XPB == XPB - 1) out_read(IC<X / XPB>{});
+    };
+
     // One stage (U = stage & 3).  Slots m0..m31 = MFMAs in (W tile a, A tile b) order, step 0
     // then step 1.  F1 = step-1 fragments of this stage, N0 = step-0 fragments of the next.
     //   m0..m7    one F1 read each (this stage landed before the previous barrier)
@@ -280,9 +414,15 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     //   m16..m20  N0 W-fragment 3 and the A-fragments (registers free after m15)
     //   m12..m31  the loads that refill this stage's buffer with stage + 4, every other slot
     //   m26..m29  next stage's scale registers
-    int fresh = 1;    // 1 during the first superstage of a tile
-    auto stage = [&](auto Uc) {
+    // MODE 0: any stage but a tile's first.  MODE 1, 2: a tile's first stage (U = 0): its step-0 MFMAs take
+    // C = 0 (nothing ever clears the accumulators) and run in pair order; MODE 2 also moves the previous
+    // tile out (drain_slot after every step-0 MFMA).  The order of MFMAs on different accumulators does not
+    // change any sum; the read schedule above still holds in pair order (W fragments 0, 1 are last used by
+    // m6, m7, fragment 2 by m14, fragment 3 and the A fragments by m12..m15).
+    auto stage = [&](auto Uc, auto Modec) __attribute__((always_inline)) {
         constexpr int U = decltype(Uc)::value, P = U & 1, NU = (U + 1) & 3;
+        constexpr int MODE = decltype(Modec)::value;
+        static_assert(MODE == 0 || U == 0, "a tile starts with stage 0");
         using N_ = IC<NU>;
         using J0 = IC<0>;
         using J1 = IC<1>;
@@ -292,39 +432,62 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         int (&nsa)[MB] = sca[P ^ 1];
         const uint32_t nbuf = (U == 3) ? (c_buf ^ SCALE_BUF) : c_buf;   // scale buffer of the next stage
         uint32_t rw[4], ra[MB];
+        // step-0 MFMA of slot S: plain order + accumulate, or pair order + C = 0 (+ the output path's share)
+#define BRQ_STEP0(S, A, B_)                                                                                          \
+        do {                                                                                                         \
+            if constexpr (MODE == 0) BRQ_MFMA(acc[A][B_], w0[A], a0[B_], 0, csw[A], csa[B_]);                        \
+            else {                                                                                                   \
+                mfma_fp4_init(acc[PairA<S, MB>::value][PairB<S, MB>::value], w0[PairA<S, MB>::value],               \
+                              a0[PairB<S, MB>::value], csw[PairA<S, MB>::value], csa[PairB<S, MB>::value]);          \
+                if constexpr (MODE == 2) drain_slot(IC<S>{});                                                        \
+            }                                                                                                        \
+        } while (0)
+        if constexpr (MODE == 2) {
+            // The next stage's loads are waited for HERE, before the output path issues its first store: from
+            // now on stores and loads are mixed in the counter, and a count is only safe against loads.  (Its
+            // younger loads are the 2 stages after it; nothing older than a tile ago is still outstanding.)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MB == 4 ? 16 : 12) : "memory");
+            drain_slot(IC<-1>{});
+            BRQ_SLOT_END();
+        }
 
         if constexpr (MB == 4) {
-            BRQ_MFMA(acc[0][0], w0[0], a0[0], 0, csw[0], csa[0]); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][1], w0[0], a0[1], 0, csw[0], csa[1]); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][2], w0[0], a0[2], 0, csw[0], csa[2]); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][3], w0[0], a0[3], 0, csw[0], csa[3]); a1[2] = ld_a(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][0], w0[1], a0[0], 0, csw[1], csa[0]); a1[3] = ld_a(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][1], w0[1], a0[1], 0, csw[1], csa[1]); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][2], w0[1], a0[2], 0, csw[1], csa[2]); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][3], w0[1], a0[3], 0, csw[1], csa[3]); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][0], w0[2], a0[0], 0, csw[2], csa[0]); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][1], w0[2], a0[1], 0, csw[2], csa[1]); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][2], w0[2], a0[2], 0, csw[2], csa[2]); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][3], w0[2], a0[3], 0, csw[2], csa[3]); BRQ_SLOT_END();
-            // Younger than the next stage's loads: the two stages after it, 8 code loads each.  The
-            // first three stages of a tile find their data landed (everything in flight was waited
-            // for before the previous epilogue) and must not wait: the counter still holds that
-            // epilogue's stores, which drain behind these stages.  From the fourth stage on the stores
-            // are older than every load that is waited for, so counting stays safe.
-            if constexpr (U == 3) wait_vm_and_barrier<16>();
-            else wait_vm_unless_and_barrier<16>(fresh);
-            BRQ_MFMA(acc[3][0], w0[3], a0[0], 0, csw[3], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(0); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][1], w0[3], a0[1], 0, csw[3], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(1); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][2], w0[3], a0[2], 0, csw[3], csa[2]); w0[2] = ld_w(N_{}, J0{}, IC<2>{});
+            BRQ_STEP0(0, 0, 0); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(1, 0, 1); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(2, 0, 2); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+            BRQ_STEP0(3, 0, 3); a1[2] = ld_a(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
+            BRQ_STEP0(4, 1, 0); a1[3] = ld_a(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_STEP0(5, 1, 1); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+            BRQ_STEP0(6, 1, 2); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
+            BRQ_STEP0(7, 1, 3); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_STEP0(8, 2, 0); BRQ_SLOT_END();
+            BRQ_STEP0(9, 2, 1); BRQ_SLOT_END();
+            BRQ_STEP0(10, 2, 2); BRQ_SLOT_END();
+            BRQ_STEP0(11, 2, 3); BRQ_SLOT_END();
+            // The next stage's loads have landed once at most 16 vector-memory operations are outstanding:
+            // the LOADS younger than them are the two stages after it, 8 code loads each (18 when one of
+            // those is a stage 0 with its two scale loads).  The output path's stores share the counter and
+            // complete out of order with the loads, but loads complete in order among themselves: if a
+            // load of the next stage were still outstanding, so would be its 16 younger ones, 17 in all.
+            // The count is therefore safe whatever the stores do; stores still in flight only make the
+            // wait stricter, which is why MODE 2 has waited before its first store and only meets the
+            // others here.
+            if constexpr (MODE == 2) lds_wait_and_barrier();
+            else wait_vm_and_barrier<16>();
+            BRQ_STEP0(12, 3, 0); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(0); BRQ_SLOT_END();
+            BRQ_STEP0(13, 3, 1); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(1); BRQ_SLOT_END();
+            BRQ_STEP0(14, 3, 2); w0[2] = ld_w(N_{}, J0{}, IC<2>{});
     #pragma unroll
             for (int t = 0; t < 4; ++t) rw[t] = *reinterpret_cast<const uint32_t*>(wsp + nbuf + NU * 4 + t * 512);
             BRQ_DMA_SLOT(2); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][3], w0[3], a0[3], 0, csw[3], csa[3]);
+            BRQ_STEP0(15, 3, 3);
     #pragma unroll
             for (int t = 0; t < 4; ++t) ra[t] = *reinterpret_cast<const uint32_t*>(asp + nbuf + NU * 4 + t * 512);
             BRQ_DMA_SLOT(3); BRQ_SLOT_END();
 
-            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(4); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(4);
+            if constexpr (MODE == 2) drain_slot(IC<NACC>{});
+            BRQ_SLOT_END();
             BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(5); BRQ_SLOT_END();
             BRQ_MFMA(acc[0][2], w1[0], a1[2], 1, csw[0], csa[2]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(6); BRQ_SLOT_END();
             BRQ_MFMA(acc[0][3], w1[0], a1[3], 1, csw[0], csa[3]); a0[2] = ld_a(N_{}, J0{}, IC<2>{}); BRQ_DMA_SLOT(7); BRQ_SLOT_END();
@@ -344,17 +507,19 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             // 128 x 256 tile: 16 slots.  m0..m5 F1 reads, m7|m8 wait + barrier, m8..m13 N0 reads,
             // m8..m15 refill loads (6 code loads, and the 2 scale loads in stage 0), m13..m15 scales.
             // Two windows of 6 code loads may stay in flight.
-            BRQ_MFMA(acc[0][0], w0[0], a0[0], 0, csw[0], csa[0]); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][1], w0[0], a0[1], 0, csw[0], csa[1]); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][0], w0[1], a0[0], 0, csw[1], csa[0]); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][1], w0[1], a0[1], 0, csw[1], csa[1]); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][0], w0[2], a0[0], 0, csw[2], csa[0]); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][1], w0[2], a0[1], 0, csw[2], csa[1]); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][0], w0[3], a0[0], 0, csw[3], csa[0]); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][1], w0[3], a0[1], 0, csw[3], csa[1]); BRQ_SLOT_END();
-            if constexpr (U == 3) wait_vm_and_barrier<12>();
-            else wait_vm_unless_and_barrier<12>(fresh);
-            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); dma_step(Uc, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(0, 0, 0); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(1, 0, 1); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(2, 1, 0); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+            BRQ_STEP0(3, 1, 1); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
+            BRQ_STEP0(4, 2, 0); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
+            BRQ_STEP0(5, 2, 1); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_STEP0(6, 3, 0); BRQ_SLOT_END();
+            BRQ_STEP0(7, 3, 1); BRQ_SLOT_END();
+            if constexpr (MODE == 2) lds_wait_and_barrier();
+            else wait_vm_and_barrier<12>();      // as above, 6 code loads per stage
+            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); dma_step(Uc, IC<0>{});
+            if constexpr (MODE == 2) drain_slot(IC<NACC>{});
+            BRQ_SLOT_END();
             BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); dma_step(Uc, IC<1>{}); BRQ_SLOT_END();
             BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); dma_step(Uc, IC<2>{}); BRQ_SLOT_END();
             BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{});
@@ -370,6 +535,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsw[2] = (int)(rw[2] >> hshift); nsw[3] = (int)(rw[3] >> hshift);
             nsa[0] = (int)(ra[0] >> hshift); nsa[1] = (int)(ra[1] >> hshift); dma_step(Uc, IC<8>{}); BRQ_SLOT_END();
         }
+#undef BRQ_STEP0
     };
 
     // ---- prologue: superstage 0 in flight, its first fragments in registers
@@ -390,126 +556,50 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 #pragma unroll
     for (int t = 0; t < MB; ++t) sca[0][t] = (int)(*reinterpret_cast<const uint32_t*>(asp + t * ASC_TILE) >> hshift);
 
-    uint8_t* const ybytes = reinterpret_cast<uint8_t*>(y);
-    uint8_t* const ebuf = lds + EPI_BASE + wave * 4096;
-    for (int ti = 0; ti < ntiles; ++ti) {
+    // One superstage = 4 stages of MFMAs on the consumer side, and the loads of the producer's
+    // superstage (the next one of the stream) on the other.
+    auto superstage = [&](auto Modec) __attribute__((always_inline)) {
+        stage(IC<0>{}, Modec);
+        stage(IC<1>{}, IC<0>{});
+        stage(IC<2>{}, IC<0>{});
+        stage(IC<3>{}, IC<0>{});
+        producer_next();
+        p_buf ^= SCALE_BUF;
+        c_buf ^= SCALE_BUF;
+    };
+    // The accumulators are one read-modify-write chain from here to the end (no instruction: each tile's
+    // first MFMAs take C = 0).
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-            for (int b = 0; b < MB; ++b) acc[a][b] = v16f{};
-
-        for (int kq = 0; kq < KQ; ++kq) {
-            // the four stages below also load the producer's superstage, the next one of the stream
-            stage(IC<0>{});
-            stage(IC<1>{});
-            stage(IC<2>{});
-            stage(IC<3>{});
-            producer_next();
-            p_buf ^= SCALE_BUF;
-            c_buf ^= SCALE_BUF;
-            fresh = 0;
-        }
-        fresh = 1;
-        // Let the four stages in flight land now.  The epilogue's stores count in the same vmcnt
-        // as the loads and complete out of order with them, so no load that is older than a
-        // store may be waited for by count.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-
-        // ---- epilogue.  Lane (r, h) holds, for W tile a and A tile b, output row m = 32 b + r and
-        // columns n = 32 a + 8 q + 4 h + {0..3}, q = 0..3: neighbouring lanes hold different rows.
-        // The store path merges the 16-byte accesses of neighbouring lanes only, so storing from
-        // this layout costs one cycle per lane (64 per instruction, 8K per tile).  Each wavefront
-        // therefore turns its output round in a private 4 KB LDS block, 32 rows x 128 bytes at a
-        // time: written as 16-byte chunks from the accumulator layout, read back with 8
-        // consecutive lanes per row, stored as 8 rows x 128 contiguous bytes per instruction.
-        // Chunk c of row i sits at i * 128 + ((c ^ (i & 7)) << 4): 8 lanes that write (8 rows, one
-        // chunk) or read (one row, 8 chunks) then cover all 32 banks.  LDS operations of one
-        // wavefront execute in order, so write -> read -> next write need no waits.
-        // The accumulators were last written by MFMAs hidden in inline assembly: the compiler does
-        // not know to keep the 18 wait states between a 16-pass MFMA and a read of its result.
-        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-        int ti_e = ti;
-        asm volatile("" : "+s"(ti_e));    // keeps the address arithmetic below out of the K loop
-        int tm, tn;
-        tw.tile(ti_e, tm, tn);
-        constexpr int ES = OUT_BF16 ? 2 : 4;
-        const int64_t pitch = ldy * ES;
-        uint8_t* const ytile = ybytes + ((int64_t)tm * TMv + wm * 32 * MB) * pitch + ((int64_t)tn * TN + wn * 128) * ES;
-        const uint32_t st_off = (uint32_t)(lane >> 3) * (uint32_t)pitch + (lane & 7) * 16;
-        uint8_t* const ewr = ebuf + r * 128;                     // this lane's row for writing
-        const uint32_t wsw = (uint32_t)((r & 7) ^ h) << 4;        // its chunk swizzle, h folded in
-        const uint8_t* const erd = ebuf + (lane >> 3) * 128 + (((lane & 7) ^ ((lane >> 3) & 7)) << 4);
-        uint4 o0, o1, o2, o3;    // the block read back: rows (lane >> 3) + 8 j, j = 0..3
-        auto read_block = [&]() {
-            o0 = *reinterpret_cast<const uint4*>(erd);
-            o1 = *reinterpret_cast<const uint4*>(erd + 1024);
-            o2 = *reinterpret_cast<const uint4*>(erd + 2048);
-            o3 = *reinterpret_cast<const uint4*>(erd + 3072);
-        };
-        const int mrem = M - (tm * TMv + wm * 32 * MB) - (lane >> 3);   // this lane stores rows row + 8 j < mrem
-        auto store_block = [&](int row, int colbytes) {
-            uint8_t* dst = ytile + row * pitch + colbytes;
-            // whole 128-byte lines that this kernel never reads back: the streaming hint is worth 2 % of the
-            // kernel on the 8192 x 14336 x 4096 shape (224 -> 220 us)
-            typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-            if (row < mrem) __builtin_nontemporal_store(u4{o0.x, o0.y, o0.z, o0.w}, reinterpret_cast<u4*>(dst + st_off));
-            if (row + 8 < mrem) __builtin_nontemporal_store(u4{o1.x, o1.y, o1.z, o1.w}, reinterpret_cast<u4*>(dst + st_off + 8 * pitch));
-            if (row + 16 < mrem) __builtin_nontemporal_store(u4{o2.x, o2.y, o2.z, o2.w}, reinterpret_cast<u4*>(dst + st_off + 16 * pitch));
-            if (row + 24 < mrem) __builtin_nontemporal_store(u4{o3.x, o3.y, o3.z, o3.w}, reinterpret_cast<u4*>(dst + st_off + 24 * pitch));
-        };
-        if constexpr (OUT_BF16) {
-            // block = (b, pair of W tiles): 32 rows x 64 columns.  v_permlane32_swap trades q
-            // between the lane halves: a lane then holds columns 32 a + 16 p + 8 h + {0..7},
-            // p = 0, 1, as one chunk, index (a & 1) * 4 + 2 p + h within the block's row
-#pragma unroll
-            for (int blk = 0; blk < 2 * MB; ++blk) {
-                const int b = blk >> 1, ap = blk & 1;
-                uint4 ch[2][2];
-#pragma unroll
-                for (int a1 = 0; a1 < 2; ++a1) {
-                    const v16f& c = acc[2 * ap + a1][b];
-#pragma unroll
-                    for (int p = 0; p < 2; ++p) {
-                        uint32_t x0 = pack_bf16x2(c[8 * p + 0], c[8 * p + 1]), x1 = pack_bf16x2(c[8 * p + 2], c[8 * p + 3]);
-                        uint32_t y0 = pack_bf16x2(c[8 * p + 4], c[8 * p + 5]), y1 = pack_bf16x2(c[8 * p + 6], c[8 * p + 7]);
-                        auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
-                        auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
-                        ch[a1][p] = make_uint4(s0[0], s1[0], s0[1], s1[1]);
-                    }
-                }
-                BRQ_SLOT_END();
-#pragma unroll
-                for (int a1 = 0; a1 < 2; ++a1)
-#pragma unroll
-                    for (int p = 0; p < 2; ++p)
-                        *reinterpret_cast<uint4*>(ewr + (wsw ^ (uint32_t)((a1 * 4 + 2 * p) << 4))) = ch[a1][p];
-                if (blk > 0) store_block(((blk - 1) >> 1) * 32, ((blk - 1) & 1) * 128);   // the block read before
-                read_block();
-                BRQ_SLOT_END();    // one block at a time keeps the register pressure flat
-            }
-            store_block((MB - 1) * 32, 128);
-        } else {
-            // block = one accumulator: 32 rows x 32 columns; chunk index 2 q + h
-#pragma unroll
-            for (int blk = 0; blk < 4 * MB; ++blk) {
-                const int b = blk >> 2, a = blk & 3;
-                const v16f& c = acc[a][b];
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    *reinterpret_cast<float4*>(ewr + (wsw ^ (uint32_t)(q << 5))) = make_float4(c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]);
-                if (blk > 0) store_block(((blk - 1) >> 2) * 32, ((blk - 1) & 3) * 128);
-                read_block();
-                BRQ_SLOT_END();
-            }
-            store_block((MB - 1) * 32, 3 * 128);
-        }
+        for (int b = 0; b < MB; ++b) asm volatile("" : "=a"(acc[a][b]));
+    if constexpr (TIMED) { t_mark = __builtin_readcyclecounter(); t_pro = t_mark - t_c0; }
+    // The workgroup's first tile has no predecessor to move out; every later tile's first stage carries the
+    // output of the tile before it.
+    superstage(IC<1>{});
+    for (int kq = 1; kq < KQ; ++kq) superstage(IC<0>{});
+    for (int ti = 1; ti < ntiles; ++ti) {
+        out_begin(ti - 1);
+        superstage(IC<2>{});
+        for (int kq = 1; kq < KQ; ++kq) superstage(IC<0>{});
     }
+    if constexpr (TIMED) { const unsigned long long t = __builtin_readcyclecounter(); t_loop += t - t_mark; t_mark = t; }
+    // ---- the last tile's output, with nothing to overlap it.  Its accumulators were last written by MFMAs
+    // hidden in inline assembly: the compiler does not know to keep the 18 wait states between a 16-pass
+    // MFMA and a read of its result.
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    out_begin(ntiles - 1);
+    static_for_drain(drain_slot, IC<NACC>{});
+    if constexpr (TIMED) { const unsigned long long t = __builtin_readcyclecounter(); t_epi += t - t_mark; t_mark = t; }
     // the throw-away superstage is still in flight: let it land before the LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if constexpr (TIMED) {
         if (blockIdx.x == 0) {
             const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
-            if (tid == 0) { clk.p[0] = c1 - t_c0; clk.p[1] = r1 - t_r0; }
+            if (tid == 0) {
+                clk.p[0] = c1 - t_c0; clk.p[1] = r1 - t_r0; clk.p[2] = t_loop; clk.p[3] = t_epi;
+                clk.p[4] = (unsigned long long)ntiles; clk.p[5] = t_pro;
+            }
         }
     }
 }

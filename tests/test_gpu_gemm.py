@@ -234,14 +234,15 @@ def test_product_reports_its_clock(brq):
     aq, as_ = inputs.random_mxfp4(M, K, seed=71)
     wq, ws = inputs.random_mxfp4(N, K, seed=72)
     ops = [to_dev(t) for t in (aq, as_, wq, ws)]
-    clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+    clk = torch.zeros(6, dtype=torch.int64, device="cuda")
     y0 = brq.mxfp4_gemm(*ops, out_dtype=torch.bfloat16)
     y1 = brq.mxfp4_gemm(*ops, out_dtype=torch.bfloat16, clock=clk)
     torch.cuda.synchronize()
     assert torch.equal(y0, y1)
-    cycles, ticks = clk.tolist()
+    cycles, ticks, loop, epi, tiles, pro = clk.tolist()
     assert cycles >= 16 * 32 * 32 and ticks > 0           # at least the MFMAs of one tile's K loop
     assert 0.2 < 0.1 * cycles / ticks < 3.0               # GHz
+    assert tiles >= 1 and loop >= tiles * 16 * 16 * 32 and epi > 0 and pro > 0 and loop + epi + pro <= cycles
     with pytest.raises(brq.BrqError) as e:                # a shape that another kernel takes
         brq.mxfp4_gemm(ops[0][:64], ops[1][:64], ops[2], ops[3], clock=clk)
     assert e.value.status == 2
