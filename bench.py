@@ -438,8 +438,36 @@ def main():
                         what="block-wise scale + MXFP4 loss per block + counts above 1.5 and 3.0, B = 32",
                         traffic=PROFILED_TRAFFIC["block_stats_16384x8192"], traffic_source=TRAFFIC_SOURCE,
                         with_fp16_scale_loss_ms=float(bms.mean()))
+        # the paper's comparison from those outputs (Sec. 4.2, Appendix "Rotation Comparison"): scales and losses
+        # after no / block / global rotation, blocks classified by their untransformed scale
+        with torch.cuda.stream(stream):
+            ref_a = torch.empty_like(st_a)
+        brq.block_stats(axs[0], 1, (), amax=ref_a, sqerr=st_q, stream=stream)
+        cmp_res = {}
+        with torch.cuda.stream(stream):
+            h_ = torch.zeros(8, dtype=torch.int64, device="cuda")
+            c_ = torch.zeros(4, dtype=torch.int64, device="cuda")
+            s_ = torch.zeros(4, dtype=torch.float64, device="cuda")
+
+        def summarize(i=0):
+            brq.block_stats_summary(st_a.view(-1), st_q.view(-1), ref_a.view(-1), outlier_threshold=60.0,
+                                    edges=(1.0, 2.0, 4.0, 8.0, 16.0, 32.0, 64.0), hist=h_, counts=c_, sums=s_, stream=stream)
+        for name, blk in (("none", 1), ("block_%d" % B, B), ("global_%d" % aK, aK)):
+            brq.block_stats(axs[0], blk, (), amax=st_a, sqerr=st_q, stream=stream)
+            with torch.cuda.stream(stream):
+                h_.zero_(), c_.zero_(), s_.zero_()
+            summarize()
+            stream.synchronize()
+            c_l, s_l = c_.tolist(), s_.tolist()
+            cmp_res[name] = {"scale_histogram": h_.tolist(), "regular_blocks": c_l[0], "outlier_blocks": c_l[1],
+                             "regular_blocks_whose_scale_grew": c_l[2] / max(c_l[0], 1),
+                             "mean_scale_regular": s_l[2] / max(c_l[0], 1), "mean_scale_outlier": s_l[3] / max(c_l[1], 1),
+                             "mean_loss_regular": s_l[0] / max(c_l[0], 1), "mean_loss_outlier": s_l[1] / max(c_l[1], 1)}
+        sum_ms = train(summarize, reps=3)
+        aux_s["rotation_comparison"] = {"what": "blocks of 32 classified by untransformed scale > 60; scale histogram edges "
+                                                "1, 2, 4, ..., 64", "summary_kernel_ms": float(sum_ms.mean()), **cmp_res}
         stream.synchronize()
-        del axs, ac, asc, Rb, st_a, st_q, st_b
+        del axs, ac, asc, Rb, st_a, st_q, st_b, ref_a
         torch.cuda.empty_cache()
 
     # ---- the online step with its producer fused in: silu(gate) * up -> rotation -> MXFP4 on the

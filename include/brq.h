@@ -214,6 +214,29 @@ brq_status brq_block_stats(const void* x, brq_dtype xdt, int64_t M, int64_t K, i
                            void* stream);
 
 /*
+ * What the paper's analysis reports from those per-block arrays (Sec. 4.1: loss of regular against
+ * outlier blocks; Sec. 4.2 and the Appendix "Rotation Comparison": the distribution of the block-wise
+ * scales before and after a rotation, and how many regular blocks' scales a rotation inflates).  Over
+ * nblocks blocks, with amax / sqerr the outputs of brq_block_stats for the transformation under study and
+ * amax_ref (optional) the block-wise scales of the reference, normally the untransformed activations
+ * (B = 1); where amax_ref is NULL the block's own scale stands in for it:
+ *     class(i)   = outlier if ref[i] > outlier_threshold, else regular        (strictly greater)
+ *     hist[j]   += #{ i : amax[i] exceeds exactly j of the nedges <= 32 edges }  (strictly; nedges + 1 bins)
+ *     counts[0] += #regular, counts[1] += #outlier,
+ *     counts[2] += #{ regular i : amax[i] > ref[i] }, counts[3] += the same over outlier blocks
+ *     sums[0]   += sum of sqerr over regular blocks, sums[1] += over outlier blocks   (0 where sqerr is NULL)
+ *     sums[2]   += sum of amax over regular blocks,  sums[3] += over outlier blocks
+ * Every output is ADDED to (the caller zeroes it) and may be NULL.  Counts are exact; the fp64 sums are
+ * accumulated in an order the schedule decides and agree with a sequential fp64 sum to 1e-12 relative.
+ * edges is a HOST pointer read during the call; everything else is device memory: amax, sqerr, amax_ref
+ * [nblocks] fp32; hist [nedges + 1] and counts [4] uint64; sums [4] double.
+ */
+brq_status brq_block_stats_summary(const float* amax, const float* sqerr, const float* amax_ref,
+                                   int64_t nblocks, float outlier_threshold, const float* edges,
+                                   int64_t nedges, uint64_t* hist, uint64_t* counts, double* sums,
+                                   void* stream);
+
+/*
  * W4A4 product on MXFP4 operands (Sec. 2; Sec. 4.1 "scaling factor integrated into
  * hardware"):   y[m][n] = sum_g 2^(as[m][g]-127 + ws[n][g]-127) *
  *                          sum_{j<32} val(aq[m][32g+j]) * val(wq[n][32g+j]),  fp32 accumulate.

@@ -71,6 +71,7 @@ def _bind(path):
     L.oracle_matrix_rotate_quantize_fused.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
     L.oracle_mxfp4_encode_with_scales.argtypes = [vp, vp, i64, i64, vp]
     L.oracle_block_stats.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i32, vp, vp, vp, vp]
+    L.oracle_block_stats_summary.argtypes = [vp, vp, vp, i64, ctypes.c_float, vp, i32, vp, vp, vp]
     L.oracle_round_to_f16.argtypes = [ctypes.c_float]
     L.oracle_round_to_f16.restype = ctypes.c_float
     L.oracle_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, vp]
@@ -292,6 +293,20 @@ class Oracle:
                                          _p(th) if th.size else None, th.size, _p(amax), _p(count), _p(sqerr),
                                          None if bfp4 is None else _p(bfp4)), "block_stats")
         return (amax, count, sqerr, bfp4) if want_bfp4 else (amax, count, sqerr)
+
+    def block_stats_summary(self, amax, sqerr=None, ref=None, outlier=0.0, edges=()):
+        """(hist [len(edges) + 1] u64, counts [4] u64, sums [4] f64) over per-block statistics."""
+        amax = np.ascontiguousarray(amax, dtype=np.float32).ravel()
+        sq = None if sqerr is None else np.ascontiguousarray(sqerr, dtype=np.float32).ravel()
+        rf = None if ref is None else np.ascontiguousarray(ref, dtype=np.float32).ravel()
+        ed = np.ascontiguousarray(edges, dtype=np.float32)
+        hist = np.zeros(ed.size + 1, dtype=np.uint64)
+        counts = np.zeros(4, dtype=np.uint64)
+        sums = np.zeros(4, dtype=np.float64)
+        _check(self.L.oracle_block_stats_summary(_p(amax), None if sq is None else _p(sq), None if rf is None else _p(rf),
+                                                 amax.size, float(outlier), _p(ed) if ed.size else None, ed.size,
+                                                 _p(hist), _p(counts), _p(sums)), "block_stats_summary")
+        return hist, counts, sums
 
     def mxfp4_dequantize(self, codes, scales):
         codes = np.ascontiguousarray(codes, dtype=np.uint8)

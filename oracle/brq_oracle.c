@@ -566,6 +566,41 @@ int oracle_block_stats(const void *x, int xdt, int64_t M, int64_t K, int64_t ldx
     return rc;
 }
 
+/* What the paper's analysis reports from the per-block statistics (Sec. 4.1: loss of regular against
+ * outlier blocks; Sec. 4.2 and Appendix "Rotation Comparison": distribution of the block-wise scales,
+ * share of regular blocks whose scale a rotation inflates).  amax / sqerr: per-block outputs for the
+ * transformation under study; ref (optional): block-wise scales of the reference (the untransformed
+ * activations); a block is an outlier block when its reference scale exceeds `outlier` (strictly), and
+ * without ref its own scale is the reference.
+ *   hist[j]   += number of blocks whose amax exceeds (strictly) exactly j of the nedges edges
+ *   counts[0] += regular blocks, counts[1] += outlier blocks,
+ *   counts[2] += regular blocks with amax > ref, counts[3] += outlier blocks with amax > ref
+ *   sums[0]   += sqerr over regular blocks, sums[1] += over outlier blocks (sqerr may be NULL),
+ *   sums[2]   += amax over regular blocks,  sums[3] += over outlier blocks            (fp64) */
+int oracle_block_stats_summary(const float *amax, const float *sqerr, const float *ref, int64_t n, float outlier,
+                               const float *edges, int nedges, uint64_t *hist, uint64_t *counts, double *sums) {
+    if (!amax || nedges < 0 || (nedges > 0 && !edges)) return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        float r = ref ? ref[i] : amax[i];
+        int outl = r > outlier;
+        if (counts) {
+            counts[outl] += 1;
+            if (ref && amax[i] > r) counts[2 + outl] += 1;
+        }
+        if (sums) {
+            if (sqerr) sums[outl] += (double)sqerr[i];
+            sums[2 + outl] += (double)amax[i];
+        }
+        if (hist) {
+            int bin = 0;
+            for (int e = 0; e < nedges; ++e)
+                if (amax[i] > edges[e]) bin += 1;
+            hist[bin] += 1;
+        }
+    }
+    return ORACLE_OK;
+}
+
 /* deq[r][k] = value(code) * 2^(scale - 127), fp64 (exact). */
 int oracle_mxfp4_dequantize(const uint8_t *codes, const uint8_t *scales, int64_t M, int64_t K,
                             double *out) {

@@ -18,7 +18,7 @@ BRQ_F32, BRQ_BF16 = 0, 1
 LAYOUTS = {"rowmajor": 0, "tiled": 1}
 EXPORTS = ["brq_init", "brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
            "brq_swiglu", "brq_swiglu_rotate_quantize_fused", "brq_matrix_rotate",
-           "brq_matrix_rotate_quantize_fused", "brq_block_stats", "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_diag_mxfp4_gemm_clock", "brq_strerror", "brq_version"]
+           "brq_matrix_rotate_quantize_fused", "brq_block_stats", "brq_block_stats_summary", "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_diag_mxfp4_gemm_clock", "brq_strerror", "brq_version"]
 
 _lib = None
 
@@ -56,6 +56,8 @@ def lib():
         L.brq_matrix_rotate_quantize_fused.restype = i32
         L.brq_block_stats.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i64, vp, vp, vp, vp, vp]
         L.brq_block_stats.restype = i32
+        L.brq_block_stats_summary.argtypes = [vp, vp, vp, i64, ctypes.c_float, vp, i64, vp, vp, vp, vp]
+        L.brq_block_stats_summary.restype = i32
         L.brq_mxfp4_gemm.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp]
         L.brq_mxfp4_gemm.restype = i32
         L.brq_to_rowmajor.argtypes = [vp, vp, i64, i64, vp, vp, vp]
@@ -274,6 +276,30 @@ def block_stats(x, B, thresholds=(), signs=None, counts=None, want_amax=True, wa
                                  None if sqerr is None else sqerr.data_ptr(),
                                  None if sqerr_bfp4 is None else sqerr_bfp4.data_ptr(), _stream(stream)))
     return (amax, counts, sqerr, sqerr_bfp4) if four else (amax, counts, sqerr)
+
+
+def block_stats_summary(amax, sqerr=None, amax_ref=None, outlier_threshold=0.0, edges=(), hist=None, counts=None,
+                        sums=None, stream=None):
+    """(hist [len(edges) + 1] int64, counts [4] int64, sums [4] float64) over the per-block arrays of block_stats
+    (brq_block_stats_summary).  Outputs given by the caller are added to."""
+    n = amax.numel()
+    for t, nm in ((amax, "amax"), (sqerr, "sqerr"), (amax_ref, "amax_ref")):
+        if t is not None and not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and t.numel() == n):
+            raise ValueError("%s must be a contiguous float32 GPU tensor with one element per block" % nm)
+    ed = (ctypes.c_float * max(1, len(edges)))(*[float(e) for e in edges])
+    if hist is None:
+        hist = torch.zeros((len(edges) + 1,), dtype=torch.int64, device=amax.device)
+    if counts is None:
+        counts = torch.zeros((4,), dtype=torch.int64, device=amax.device)
+    if sums is None:
+        sums = torch.zeros((4,), dtype=torch.float64, device=amax.device)
+    for t, nm, dt, ne in ((hist, "hist", torch.int64, len(edges) + 1), (counts, "counts", torch.int64, 4), (sums, "sums", torch.float64, 4)):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and t.numel() == ne):
+            raise ValueError("%s must be a contiguous GPU tensor of %d elements of %s" % (nm, ne, dt))
+    _check(lib().brq_block_stats_summary(amax.data_ptr(), None if sqerr is None else sqerr.data_ptr(),
+                                         None if amax_ref is None else amax_ref.data_ptr(), n, float(outlier_threshold), ed,
+                                         len(edges), hist.data_ptr(), counts.data_ptr(), sums.data_ptr(), _stream(stream)))
+    return hist, counts, sums
 
 
 def to_rowmajor(codes_tiled, scales_tiled, rows, K, stream=None):

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbrq.so")
-SOURCES = ["brq_api.hip", "rotate_quant.hip", "matrix_rotate_quant.hip", "mxfp4_gemm.hip", "mxfp4_gemm_tiled.hip"]
+SOURCES = ["brq_api.hip", "rotate_quant.hip", "matrix_rotate_quant.hip", "block_summary.hip", "mxfp4_gemm.hip", "mxfp4_gemm_tiled.hip"]
 # -ffp-contract=off: the rotation's add/sub/mul sequence is part of the result's definition.
 # packed fp32 instructions are kept out of the generated code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

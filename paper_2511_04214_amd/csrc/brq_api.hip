@@ -187,6 +187,22 @@ brq_status brq_block_stats(const void* x, brq_dtype xdt, int64_t M, int64_t K, i
                                         signs, nullptr, static_cast<hipStream_t>(stream), &so));
 }
 
+brq_status brq_block_stats_summary(const float* amax, const float* sqerr, const float* amax_ref, int64_t nblocks,
+                                   float outlier_threshold, const float* edges, int64_t nedges, uint64_t* hist,
+                                   uint64_t* counts, double* sums, void* stream) {
+    if (nblocks < 0 || nedges < 0 || nedges > 32) return BRQ_ERR_SHAPE;
+    if (nblocks > 0 && !amax) return BRQ_ERR_NULL;
+    if (nedges > 0 && hist && !edges) return BRQ_ERR_NULL;
+    const uintptr_t a4 = reinterpret_cast<uintptr_t>(amax) | reinterpret_cast<uintptr_t>(sqerr) | reinterpret_cast<uintptr_t>(amax_ref);
+    const uintptr_t a8 = reinterpret_cast<uintptr_t>(hist) | reinterpret_cast<uintptr_t>(counts) | reinterpret_cast<uintptr_t>(sums);
+    if ((a4 & 3u) || (a8 & 7u)) return BRQ_ERR_ALIGN;
+    if (nblocks == 0 || (!hist && !counts && !sums)) return BRQ_OK;
+    return launched(brq::launch_block_summary(amax, sqerr, amax_ref, nblocks, outlier_threshold, edges, (int)nedges,
+                                              reinterpret_cast<unsigned long long*>(hist),
+                                              reinterpret_cast<unsigned long long*>(counts), sums,
+                                              static_cast<hipStream_t>(stream)));
+}
+
 static brq_status check_blocks(const float* R, int64_t nR, int64_t K, int64_t ld_bytes) {
     if (K % 128 != 0 || ld_bytes * 32 >= (int64_t(1) << 32)) return BRQ_ERR_SHAPE;   // 32 rows of pitch: 32-bit offsets
     if (nR != 1 && nR != K / 32) return BRQ_ERR_BLOCK;

@@ -165,6 +165,19 @@ __device__ __forceinline__ float quad_max(float m) {
     return as_f32(u);
 }
 
+// Sum over the 4 lanes of a quad, every lane receiving it: two adds with the lane permute folded in
+// (((v0 + v1) + (v2 + v3)) in lanes 0, 1 and the mirror image in lanes 2, 3: the same value, since fp32
+// addition is commutative).  Same DPP read-after-write spacing rule as above.
+__device__ __forceinline__ float quad_sum(float v) {
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        : "+v"(v));
+    return v;
+}
+
 // E8M0 byte of a group from its maximum magnitude: max(exponent field - 2, 0).
 // (2 = exponent of the largest E2M1 value, 6 = 1.5 * 2^2.)
 __device__ __forceinline__ uint32_t e8m0_from_amax(float amax) {
@@ -177,13 +190,19 @@ __device__ __forceinline__ uint32_t e8m0_from_amax(float amax) {
 // its scale operand, field 0 meaning 2^-127), rounds to nearest with ties to the even
 // code and saturates at 6.  It keeps the sign of results that round to zero; those
 // nibbles are cleared afterwards so that a zero magnitude is always code 0.
-__device__ __forceinline__ uint32_t encode8_e2m1(const float (&y)[8], uint32_t sb) {
+// encode8_e2m1_signed_zero is the instruction's own result (a zero magnitude may carry a sign bit): enough
+// where the codes are only decoded again.
+__device__ __forceinline__ uint32_t encode8_e2m1_signed_zero(const float (&y)[8], uint32_t sb) {
     float scale = as_f32(sb << 23);
     uint32_t w = 0;
     w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, y[0], y[1], scale, 0);
     w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, y[2], y[3], scale, 1);
     w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, y[4], y[5], scale, 2);
     w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, y[6], y[7], scale, 3);
+    return w;
+}
+__device__ __forceinline__ uint32_t encode8_e2m1(const float (&y)[8], uint32_t sb) {
+    const uint32_t w = encode8_e2m1_signed_zero(y, sb);
     uint32_t mag = w & 0x77777777u;
     uint32_t nz = mag + 0x77777777u;            // bit 3 of a nibble set <=> magnitude != 0
     return w & (nz | 0x77777777u);

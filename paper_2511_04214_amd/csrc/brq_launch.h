@@ -40,6 +40,12 @@ hipError_t launch_rowwise(int mode, int log2b, bool in_bf16, bool out_bf16, cons
                           bool tiled, const int8_t* signs, const Producer* prod, hipStream_t s,
                           const StatsOut* stats = nullptr);
 
+// Reduction of per-block statistics (block_summary.hip): histogram of the block scales over `nedges` <= 32
+// host-side edges, class counts and fp64 sums split by reference scale > outlier.  Outputs are added to.
+hipError_t launch_block_summary(const float* amax, const float* sqerr, const float* ref, int64_t n, float outlier,
+                                const float* edges, int nedges, unsigned long long* hist, unsigned long long* counts,
+                                double* sums, hipStream_t s);
+
 // Tiled operand whose K is not a multiple of 512: writes the K padding of rows 0..M-1 as zeros.
 hipError_t launch_zero_kpad(uint8_t* codes, uint8_t* scales, int64_t M, int64_t K, hipStream_t s);
 

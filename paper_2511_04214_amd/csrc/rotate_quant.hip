@@ -213,14 +213,26 @@ __device__ __forceinline__ void quant_store(const float (&y)[8], uint32_t row, u
 // ---- block statistics (Sec. 4.1, 4.2, Appendix "Rotation Comparison") ----------------------
 // For the lane's 8 (rotated) values, quad = one 32-element block: the block-wise scale max|y|, the
 // block's MXFP4 quantization loss sum (y - deq(q(y)))^2 (fp32; each difference is exact, the
-// squares and the 32-term sum round), and per threshold the number of values with |y| above it,
-// counted per lane (a lane's counter cannot overflow: fewer than 2^31 chunks per launch).
-__device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, bool live, uint32_t lane,
+// squares and the 32-term sum round), and per threshold the number of values with |y| above it.
+//
+// Counting costs one vector instruction per value and threshold: the comparison writes a lane mask to
+// scalar registers, and the scalar unit, which has nothing else to do in this kernel, counts its bits
+// and keeps the wavefront's running sums (`cnt`, wavefront-uniform; a wavefront meets fewer than 2^32
+// values per launch).  Per-lane counters cost a second vector instruction per value and threshold on a
+// kernel whose vector units are the busiest part.
+//
+// The per-block outputs of a wavefront's 16 blocks sit in lanes 0, 4, 8, ...; stored from there they are
+// 16 separate 4-byte accesses.  One lane permute brings them to lanes 0..15, which store 64 contiguous
+// bytes.  gidx0 = block index of the wavefront's first chunk; `live` = this lane's chunk exists.
+__device__ __forceinline__ float gather_quads(float v, uint32_t lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((int)((lane & 15u) << 4), __builtin_bit_cast(int, v)));
+}
+__device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx0, bool live, uint32_t lane,
                                             const RowArgs& a, uint32_t (&cnt)[8]) {
     typedef float f2 __attribute__((ext_vector_type(2)));
     const float am = quad_max(absmax8(y));
     const uint32_t sb = e8m0_from_amax(am);
-    const uint32_t w = encode8_e2m1(y, sb);
+    const uint32_t w = encode8_e2m1_signed_zero(y, sb);      // decoded again below: the sign of a zero does not matter
     const float sc = as_f32(sb ? sb << 23 : 0x00400000u);   // 2^(sb - 127); scale byte 0 is the subnormal 2^-127
     float e2 = 0.0f;
 #pragma unroll
@@ -234,11 +246,17 @@ __device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, 
         e2 = __builtin_fmaf(e0, e0, e2);
         e2 = __builtin_fmaf(e1, e1, e2);
     }
-    e2 += lane_xor<1>(e2);
-    e2 += lane_xor<2>(e2);
-    if (live && (lane & 3) == 0) {
-        if (a.amax) a.amax[gidx] = am;
-        if (a.sqerr) a.sqerr[gidx] = e2;
+    e2 = quad_sum(e2);
+    // lane j < 16 takes over block j of the wavefront (held by lanes 4 j .. 4 j + 3) and stores it
+    const bool blive = __builtin_amdgcn_ds_bpermute((int)((lane & 15u) << 4), (int)live) != 0;
+    const bool st = lane < 16u && blive;
+    if (a.amax) {   // uniform
+        const float g = gather_quads(am, lane);
+        if (st) a.amax[gidx0 + lane] = g;
+    }
+    if (a.sqerr) {
+        const float g = gather_quads(e2, lane);
+        if (st) a.sqerr[gidx0 + lane] = g;
     }
     if (a.sqerr_bfp4) {   // uniform
         // The FP16-scale counterpart (Sec. 3, 4.1): scale s = half(max / 6), codes = E2M1 rounding of
@@ -247,7 +265,7 @@ __device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, 
         float r[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) r[i] = (s > 0.0f) ? y[i] / s : 0.0f;
-        const uint32_t wb = encode8_e2m1(r, 127u);
+        const uint32_t wb = encode8_e2m1_signed_zero(r, 127u);
         float eb = 0.0f;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
@@ -260,26 +278,31 @@ __device__ __forceinline__ void stats_chunk(const float (&y)[8], uint32_t gidx, 
             eb = __builtin_fmaf(e0, e0, eb);
             eb = __builtin_fmaf(e1, e1, eb);
         }
-        eb += lane_xor<1>(eb);
-        eb += lane_xor<2>(eb);
-        if (live && (lane & 3) == 0) a.sqerr_bfp4[gidx] = eb;
+        eb = quad_sum(eb);
+        const float g = gather_quads(eb, lane);
+        if (st) a.sqerr_bfp4[gidx0 + lane] = g;
     }
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         if (t < (int)a.nt) {   // uniform
             const float th = a.th[t];
+            // a lane without a chunk carries a copy of the last one: its comparisons are masked out
+            const float lim = live ? th : __builtin_inff();
 #pragma unroll
-            for (int i = 0; i < 8; ++i) cnt[t] += (live && fabsf(y[i]) > th) ? 1u : 0u;   // compare + add-with-carry
+            for (int i = 0; i < 8; ++i)
+                cnt[t] += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(fabsf(y[i]) > lim));
         }
     }
 }
 
-// Every lane adds its counters in LDS (`red`: 8 words, zeroed by the caller before a barrier), then
-// one lane per threshold adds the workgroup's sum to the global counter.
+// The wavefront's sums go to LDS (`red`: 8 words, zeroed by the caller before a barrier) through one lane,
+// then one lane per threshold adds the workgroup's sum to the global counter.
 __device__ __forceinline__ void stats_flush(const uint32_t (&cnt)[8], uint32_t* red, const RowArgs& a) {
+    if ((threadIdx.x & 63u) == 0) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
-        if (t < (int)a.nt && cnt[t]) atomicAdd(&red[t], cnt[t]);
+        for (int t = 0; t < 8; ++t)
+            if (t < (int)a.nt && cnt[t]) atomicAdd(&red[t], cnt[t]);
+    }
     __syncthreads();
     if (threadIdx.x < a.nt && red[threadIdx.x]) atomicAdd(&a.counts[threadIdx.x], (unsigned long long)red[threadIdx.x]);
 }
@@ -350,7 +373,7 @@ __global__ void __launch_bounds__(256) k_rowwise(RowArgs a) {
                     else store_chunk_f32_quad(p, v[u], lane);
                 }
             } else if constexpr (MODE == MODE_STATS) {
-                stats_chunk(v[u], c >> 2, live, lane, a, cnt);
+                stats_chunk(v[u], (c - lane) >> 2, live, lane, a, cnt);
             } else {
                 uint32_t sb = e8m0_from_amax(quad_max(absmax8(v[u])));
                 uint32_t w = encode8_e2m1(v[u], sb);
@@ -523,7 +546,7 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
                 if constexpr (OUT_BF16) store_chunk<true>((char*)a.y + yoff * 2, y);
                 else store_chunk_f32_quad((char*)a.y + yoff * 4, y, lane);
             } else if constexpr (MODE == MODE_STATS) {
-                stats_chunk(y, (row * a.cpr + blk * (B / 8) + q) >> 2, true, lane, a, cnt);
+                stats_chunk(y, (row * a.cpr + blk * (B / 8) + q - lane) >> 2, true, lane, a, cnt);
             } else {
                 quant_store(y, row, blk * (B / 8) + q, lane, a);
             }
@@ -536,6 +559,11 @@ __global__ void __launch_bounds__(256) k_rowwise_lds(RowArgs a, uint32_t blocks_
 }
 
 // ---- host side ---------------------------------------------------------------------
+
+// Workgroups per compute unit of a statistics launch: each ends with up to 8 atomics on the caller's counters.
+#ifndef BRQ_STATS_WGS_PER_CU
+#define BRQ_STATS_WGS_PER_CU 8
+#endif
 
 // Workgroups of a streaming launch.  Measured on X 16384 x 8192 (bf16, B = 32): one chunk in
 // flight per lane and many short-lived workgroups beat a persistent grid (8 per CU, two
@@ -585,7 +613,7 @@ static hipError_t launch_inwave(const RowArgs& a, bool contig, hipStream_t s) {
     constexpr int U = 1;
     int grid = rowwise_grid(a.nchunks, U, cus);
     if constexpr (MODE == MODE_STATS) {   // fewer, longer-lived workgroups: each ends with atomics on the counters
-        const int cap = cus * 8;
+        const int cap = cus * BRQ_STATS_WGS_PER_CU;
         if (grid > cap) grid = cap;
     }
     RowArgs b = a;
@@ -607,7 +635,7 @@ static hipError_t launch_lds(const RowArgs& a, int64_t M, int64_t K, hipStream_t
     if (MODE == MODE_STATS) {
         int cus = 0;
         if (hipError_t e = device_cus(&cus); e != hipSuccess) return e;
-        const uint32_t cap = (uint32_t)cus * 8u;
+        const uint32_t cap = (uint32_t)cus * (uint32_t)BRQ_STATS_WGS_PER_CU;
         if (grid > cap) grid = cap;
     }
     hipLaunchKernelGGL((k_rowwise_lds<LOG2B, IN_BF16, MODE, OUT_BF16, PROD>), dim3(grid), dim3(NT),

@@ -590,6 +590,58 @@ def pin_block_stats(o):
     assert np.median(a_blk[:, regular] / a_none[:, regular]) < 1.2 < np.median(a_glob[:, regular] / a_none[:, regular])
 
 
+def pin_block_stats_summary(o):
+    # The reductions of the paper's analysis over per-block statistics, against numpy (searchsorted and masked
+    # sums, which the oracle does not call) and a hand-worked case.
+    rng = np.random.default_rng(55)
+    n = 5000
+    amax = np.abs(rng.standard_t(3, size=n)).astype(np.float32) * 2
+    ref = np.abs(rng.standard_t(3, size=n)).astype(np.float32) * 2
+    sq = rng.random(n).astype(np.float32)
+    edges = np.array([0.5, 1.0, 2.0, 4.0, 8.0], dtype=np.float32)
+    amax[:6] = [0.5, 1.0, 2.0, 4.0, 8.0, 8.5]                 # values on the edges: strictly greater decides
+    ref[:6] = [3.0, 1.0, 2.0, 5.0, 8.0, 9.0]                  # ... and on the outlier threshold / equal to amax
+    hist, counts, sums = o.block_stats_summary(amax, sq, ref, outlier=3.0, edges=edges)
+    want_hist = np.bincount(np.searchsorted(edges, amax, side="left"), minlength=6)       # number of edges < amax
+    assert np.array_equal(hist, want_hist) and hist.sum() == n
+    outl = ref > np.float32(3.0)
+    grew = amax > ref
+    assert list(counts) == [int((~outl).sum()), int(outl.sum()), int((grew & ~outl).sum()), int((grew & outl).sum())]
+    want = [np.float64(sq)[~outl].sum(), np.float64(sq)[outl].sum(), np.float64(amax)[~outl].sum(), np.float64(amax)[outl].sum()]
+    assert np.allclose(sums, want, rtol=1e-12, atol=0)
+    # the first six by hand: amax on an edge falls into the bin below it; ref = 3.0 is regular (not > 3); equal scales did not grow
+    h6, c6, s6 = o.block_stats_summary(amax[:6], sq[:6], ref[:6], outlier=3.0, edges=edges)
+    assert list(h6) == [1, 1, 1, 1, 1, 1]
+    assert list(c6) == [3, 3, 0, 0]
+    # without a reference the block's own scale classifies it and nothing "grew"; without sqerr no loss sums
+    h0, c0, s0 = o.block_stats_summary(amax, None, None, outlier=3.0, edges=edges)
+    own = amax > np.float32(3.0)
+    assert list(c0) == [int((~own).sum()), int(own.sum()), 0, 0] and s0[0] == 0.0 and s0[1] == 0.0
+    assert np.array_equal(h0, want_hist)
+    # no edges: one bin with everything
+    h1, _, _ = o.block_stats_summary(amax, sq, ref, outlier=3.0)
+    assert list(h1) == [n]
+    # the paper's comparison on activations with outlier channels (Appendix): classify blocks by the
+    # untransformed scale; a global rotation inflates the scale of most regular blocks, a block rotation of
+    # few, and removes the bulk of that inflation in the mean regular-block scale
+    X = (rng.standard_t(4, size=(64, 1024))).astype(np.float32)
+    X[:, [5, 700]] *= 40.0
+    a_none, _, q_none = o.block_stats(X, 1)
+    thr = float(np.quantile(np.abs(X), 0.999))                # top 0.1 % of magnitudes (Sec. 4.1)
+    res = {}
+    for B in (32, 1024):
+        a, _, q = o.block_stats(X, B)
+        _, c, s_ = o.block_stats_summary(a, q.astype(np.float32), a_none, outlier=thr)
+        res[B] = (c, s_)
+    _, c_n, s_n = o.block_stats_summary(a_none, q_none.astype(np.float32), a_none, outlier=thr)
+    assert c_n[1] > 0 and c_n[0] > 10 * c_n[1] and c_n[2] == 0 and c_n[3] == 0
+    assert res[1024][0][2] > 0.6 * res[1024][0][0]            # most regular blocks' scales grow under the global rotation (the paper: > 70 %)
+    assert res[32][0][2] < 0.5 * res[1024][0][2]              # ... far fewer under the block rotation
+    infl_glob = res[1024][1][2] - s_n[2]
+    infl_blk = res[32][1][2] - s_n[2]
+    assert infl_glob > 0 and infl_blk < 0.2 * infl_glob        # block rotation removes > 80 % of that inflation
+
+
 def pin_bfp4_loss(o):
     # The FP16-scale counterpart (Sec. 3, 4.1): half-precision rounding against numpy's float16 (a
     # conversion the oracle does not call), the loss against a composition of separately pinned

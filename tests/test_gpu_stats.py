@@ -138,3 +138,91 @@ def test_argument_errors(brq):
     assert e.value.status == 2
     a, c, s = brq.block_stats(x[:0], 32, TH)
     assert a.numel() == 0 and int(c.sum().item()) == 0
+
+
+# ------------------------------------------------------------------ the reductions of the paper's analysis
+
+EDGES = [0.5, 1.0, 2.0, 4.0, 8.0, 16.0, 64.0]
+
+
+def check_summary(brq, orc, amax, sqerr, ref, outlier, edges):
+    d = lambda t: None if t is None else to_dev(t)
+    hist, counts, sums = brq.block_stats_summary(d(amax), d(sqerr), d(ref), outlier_threshold=outlier, edges=edges)
+    rh, rc, rs = orc.block_stats_summary(amax, sqerr, ref, outlier=outlier, edges=edges)
+    assert np.array_equal(to_host(hist).astype(np.uint64), rh), (to_host(hist), rh)
+    assert np.array_equal(to_host(counts).astype(np.uint64), rc), (to_host(counts), rc)
+    assert np.allclose(to_host(sums), rs, rtol=1e-12, atol=0), (to_host(sums), rs)
+    return rh, rc, rs
+
+
+@pytest.mark.parametrize("n", [1, 255, 256, 4097, 300000])
+def test_summary_matches_oracle(brq, orc, n):
+    rng = np.random.default_rng(700 + n)
+    amax = (np.abs(rng.standard_t(3, size=n)) * 2).astype(np.float32)
+    ref = (np.abs(rng.standard_t(3, size=n)) * 2).astype(np.float32)
+    sq = rng.random(n).astype(np.float32)
+    k = min(n, len(EDGES))
+    amax[:k] = EDGES[:k]                                   # values on the edges and on the threshold
+    ref[:k] = amax[:k]
+    check_summary(brq, orc, amax, sq, ref, 4.0, EDGES)
+    check_summary(brq, orc, amax, None, None, 4.0, EDGES[:3])
+    check_summary(brq, orc, amax, sq, ref, 0.0, [])         # no edges: one bin
+    check_summary(brq, orc, amax, sq, ref, 1.0e30, [float(i) for i in range(32)])   # the most edges
+
+
+def test_summary_adds_to_its_outputs_and_takes_nothing(brq):
+    amax = torch.full((1000,), 3.0, dtype=torch.float32, device="cuda")
+    hist = torch.tensor([5, 0, 0], dtype=torch.int64, device="cuda")
+    counts = torch.tensor([1, 2, 3, 4], dtype=torch.int64, device="cuda")
+    sums = torch.tensor([1.0, 2.0, 3.0, 4.0], dtype=torch.float64, device="cuda")
+    for _ in range(2):
+        brq.block_stats_summary(amax, outlier_threshold=2.0, edges=[1.0, 3.0], hist=hist, counts=counts, sums=sums)
+    assert hist.tolist() == [5, 2000, 0]                    # 3.0 exceeds the edge 1.0 only
+    assert counts.tolist() == [1, 2002, 3, 4] and sums.tolist() == [1.0, 2.0, 3.0, 4.0 + 6000.0]
+    e = torch.empty((0,), dtype=torch.float32, device="cuda")
+    h, c, s_ = brq.block_stats_summary(e)                   # no blocks: nothing launched
+    assert h.tolist() == [0] and c.tolist() == [0, 0, 0, 0]
+    with pytest.raises(brq.BrqError) as err:
+        brq.block_stats_summary(amax, edges=[float(i) for i in range(33)])
+    assert err.value.status == 2
+
+
+def test_rotation_comparison_full_size(brq, orc):
+    """The paper's comparison (Sec. 4.2, Appendix "Rotation Comparison") on the benchmark's activations
+    X 16384 x 8192: block-wise scales and losses after no, block and global rotation, classified into
+    regular and outlier blocks by the untransformed scale.  The GPU's per-block arrays and their reductions
+    against the oracle on a sample of rows (arrays bit for bit / 4e-6, reductions exact / 1e-12), and the
+    paper's observations on the whole matrix: a global rotation inflates the scale of most regular blocks, a
+    block rotation of few."""
+    from paper_2511_04214_amd import inputs
+    cfg = inputs.CONFIGS["decode"]
+    x = inputs.make_x(cfg)
+    M, K = x.shape
+    xd = to_dev(x)
+    thr = 60.0                                              # above the bulk, below the x20 outlier channels' tails
+    per = {}
+    for B in (1, 32, K):
+        amax, _, sqerr = brq.block_stats(xd, B)
+        per[B] = (amax, sqerr)
+    rows = np.sort(np.random.default_rng(710).choice(M, size=8, replace=False))
+    idx = torch.from_numpy(rows).cuda()
+    ref_rows = None
+    for B in (1, 32, K):
+        ra, _, rs = orc.block_stats(x[rows], B)
+        ga, gs = to_host(per[B][0][idx]), to_host(per[B][1][idx]).astype(np.float64)
+        assert np.array_equal(ga.view(np.uint32), ra.view(np.uint32))
+        assert (np.abs(gs - rs) <= 4e-6 * rs + 1e-44).all()
+        if B == 1:
+            ref_rows = ra
+        check_summary(brq, orc, ga, to_host(per[B][1][idx]), ref_rows, thr, EDGES)
+    res = {B: brq.block_stats_summary(per[B][0].view(-1), per[B][1].view(-1), per[1][0].view(-1), outlier_threshold=thr, edges=EDGES)
+           for B in (1, 32, K)}
+    c1, cb, cg = (to_host(res[B][1]) for B in (1, 32, K))
+    s1, sb_, sg = (to_host(res[B][2]) for B in (1, 32, K))
+    assert c1[0] + c1[1] == M * K // 32 and c1[2] == 0 and c1[3] == 0 and 0 < c1[1] < 0.1 * c1[0]
+    assert cg[2] > 0.6 * cg[0] and cb[2] < 0.5 * cg[2]
+    # (these activations have an outlier channel in about a quarter of their blocks, most of them below the
+    # threshold: the MEAN regular-block scale need not grow under the global rotation, and is not asserted)
+    assert sb_[2] < s1[2] and sb_[2] < sg[2]               # the block rotation gives the smallest regular-block scales
+    for B in (1, 32, K):
+        assert int(to_host(res[B][0]).sum()) == M * K // 32

@@ -77,6 +77,12 @@ MUTANTS = [
     ("stats_loss_not_squared", "loss += d * d;", "loss += fabs(d);"),
     ("stats_never_rotates", "    if (B == 1) {\n        for (int64_t r = 0; r < M; ++r)\n            for (int64_t k = 0; k < K; ++k) y[r * K + k]", "    if (B >= 1) {\n        for (int64_t r = 0; r < M; ++r)\n            for (int64_t k = 0; k < K; ++k) y[r * K + k]"),
     ("stats_nibbles_swapped", "int code = (j & 1) ? (codes16[j / 2] >> 4) : (codes16[j / 2] & 0xF);", "int code = (j & 1) ? (codes16[j / 2] & 0xF) : (codes16[j / 2] >> 4);"),
+    ("summary_bin_not_strict", "if (amax[i] > edges[e]) bin += 1;", "if (amax[i] >= edges[e]) bin += 1;"),
+    ("summary_outlier_not_strict", "int outl = r > outlier;", "int outl = r >= outlier;"),
+    ("summary_classifies_by_own_scale", "float r = ref ? ref[i] : amax[i];\n        int outl", "float r = amax[i];\n        int outl"),
+    ("summary_grew_not_strict", "if (ref && amax[i] > r) counts[2 + outl] += 1;", "if (ref && amax[i] >= r) counts[2 + outl] += 1;"),
+    ("summary_loss_classes_swapped", "if (sqerr) sums[outl] += (double)sqerr[i];", "if (sqerr) sums[1 - outl] += (double)sqerr[i];"),
+    ("summary_scale_sum_unsplit", "sums[2 + outl] += (double)amax[i];", "sums[2] += (double)amax[i];"),
     ("bfp4_scale_max_4", "const float s = oracle_round_to_f16(am / 6.0f);", "const float s = oracle_round_to_f16(am / 4.0f);"),
     ("bfp4_scale_not_rounded", "const float s = oracle_round_to_f16(am / 6.0f);", "const float s = am / 6.0f;"),
     ("bfp4_dequant_without_scale", "oracle_e2m1_value(code) * (double)s;", "oracle_e2m1_value(code);"),
