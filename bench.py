@@ -529,6 +529,21 @@ def main():
             t = float(train(dgemm, reps=3).mean())
             by = (dN + dM) * dK * 0.53125 + dM * dN * 2
             aux3["batches"][str(dM)] = {"avg_ms": t, "achieved": by / t / 1e6, "frac": by / t / 1e6 / HBM_PEAK_GBS}
+            if dM <= 16:
+                # the whole online path of a decode step (Sec. 4.3): rotate + quantize the bf16 activations, then the
+                # product - as two launches, and as the one launch that carries the online step in its prologue
+                dxm = dx[:dM].contiguous()
+                dqc, dqs = q_buffers(dM, dK, 1)
+
+                def two_launches(i):
+                    brq.rotate_quantize_fused(dxm, B, codes=dqc[0], scales=dqs[0], stream=stream, layout=LAY)
+                    brq.mxfp4_gemm(dqc[0], dqs[0], dws[i % 2][0], dws[i % 2][1], out=dy, stream=stream, a_layout=LAY,
+                                   w_layout=LAY, M=dM, N=dN, K=dK)
+
+                def one_launch(i):
+                    brq.rotate_quantize_gemm_fused(dxm, B, dws[i % 2][0], dws[i % 2][1], dN, out=dy, stream=stream, w_layout=LAY)
+                aux3["batches"][str(dM)]["online_step_plus_product_two_launches_ms"] = float(train(two_launches, reps=3).mean())
+                aux3["batches"][str(dM)]["online_step_inside_the_product_ms"] = float(train(one_launch, reps=3).mean())
         stream.synchronize()
         del dws, dx
         torch.cuda.empty_cache()

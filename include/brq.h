@@ -66,12 +66,18 @@ typedef enum {
     BRQ_ERR_DTYPE = 5,       /* dtype is not one of brq_dtype */
     BRQ_ERR_LAUNCH = 6,      /* hipLaunchKernel failed (hipGetLastError) */
     BRQ_ERR_LAYOUT = 7,      /* layout is not one of brq_layout */
-    BRQ_ERR_DEVICE = 8       /* no current HIP device, or its one-time set-up failed */
+    BRQ_ERR_DEVICE = 8,      /* no current HIP device, or its one-time set-up failed */
+    BRQ_STATUS_INT_RANGE_ = 0x7fffffff   /* (gives the type the range of int: see below) */
 } brq_status;
 
-typedef enum { BRQ_F32 = 0, BRQ_BF16 = 1 } brq_dtype;
+/*
+ * Callers reach these enums through foreign-function interfaces that pass plain ints, and the calls answer
+ * an unknown value with BRQ_ERR_DTYPE / BRQ_ERR_LAYOUT.  The last enumerator of each type widens its value
+ * range to that of int, so that reading such a value is defined behaviour on the library's side.
+ */
+typedef enum { BRQ_F32 = 0, BRQ_BF16 = 1, BRQ_DTYPE_INT_RANGE_ = 0x7fffffff } brq_dtype;
 
-typedef enum { BRQ_LAYOUT_ROWMAJOR = 0, BRQ_LAYOUT_TILED = 1 } brq_layout;
+typedef enum { BRQ_LAYOUT_ROWMAJOR = 0, BRQ_LAYOUT_TILED = 1, BRQ_LAYOUT_INT_RANGE_ = 0x7fffffff } brq_layout;
 
 /*
  * One-time set-up for the CURRENT HIP device (see the conventions above): idempotent, thread-safe,
@@ -248,6 +254,21 @@ brq_status brq_block_stats_summary(const float* amax, const float* sqerr, const 
 brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout,
                           const uint8_t* wq, const uint8_t* ws, brq_layout w_layout, int64_t M,
                           int64_t N, int64_t K, void* y, brq_dtype ydt, int64_t ldy, void* stream);
+
+/*
+ * The whole online path of a decode step in one launch (Sec. 4.3: the online rotation and the quantizer in
+ * front of the quantized layer, folded into the product):
+ *     y = brq_mxfp4_gemm(brq_rotate_quantize_fused(x, B, signs), (wq, ws)),
+ * bit for bit that two-call sequence, for M <= 16 rows of activations.  Every workgroup quantizes all of x
+ * into LDS before it streams its weight rows, so the call pays for itself only where that prologue is
+ * shorter than a kernel launch (a few rows); the two-call sequence remains the general path.
+ * x [M][ldx] of xdt, M <= 16; K % 512 == 0, K <= 16384; B = 32 (anything else: BRQ_ERR_BLOCK); (wq, ws) the
+ * quantized [N][K] weights in w_layout; y [M][ldy] of ydt.
+ */
+brq_status brq_rotate_quantize_gemm_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx,
+                                          int64_t B, const int8_t* signs, const uint8_t* wq,
+                                          const uint8_t* ws, brq_layout w_layout, int64_t N, void* y,
+                                          brq_dtype ydt, int64_t ldy, void* stream);
 
 /*
  * Tiled -> row-major copy of a quantized [rows][K] operand (for inspection and parity checks;

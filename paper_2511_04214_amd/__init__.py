@@ -18,7 +18,7 @@ BRQ_F32, BRQ_BF16 = 0, 1
 LAYOUTS = {"rowmajor": 0, "tiled": 1}
 EXPORTS = ["brq_init", "brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
            "brq_swiglu", "brq_swiglu_rotate_quantize_fused", "brq_matrix_rotate",
-           "brq_matrix_rotate_quantize_fused", "brq_block_stats", "brq_block_stats_summary", "brq_mxfp4_gemm", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_diag_mxfp4_gemm_clock", "brq_strerror", "brq_version"]
+           "brq_matrix_rotate_quantize_fused", "brq_block_stats", "brq_block_stats_summary", "brq_mxfp4_gemm", "brq_rotate_quantize_gemm_fused", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_diag_mxfp4_gemm_clock", "brq_strerror", "brq_version"]
 
 _lib = None
 
@@ -60,6 +60,8 @@ def lib():
         L.brq_block_stats_summary.restype = i32
         L.brq_mxfp4_gemm.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp]
         L.brq_mxfp4_gemm.restype = i32
+        L.brq_rotate_quantize_gemm_fused.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp, i32, i64, vp, i32, i64, vp]
+        L.brq_rotate_quantize_gemm_fused.restype = i32
         L.brq_to_rowmajor.argtypes = [vp, vp, i64, i64, vp, vp, vp]
         L.brq_to_rowmajor.restype = i32
         L.brq_diag_mxfp4_gemm_clock.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp, vp]
@@ -354,6 +356,26 @@ def mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.float32, out=None, stream=None, 
         return y
     _check(lib().brq_mxfp4_gemm(aq.data_ptr(), as_.data_ptr(), la, wq.data_ptr(), ws.data_ptr(), lw, M, N, K,
                                 y.data_ptr(), _dtype_code(y), ldy, _stream(stream)))
+    return y
+
+
+def rotate_quantize_gemm_fused(x, B, wq, ws, N, out_dtype=torch.float32, out=None, stream=None, w_layout="rowmajor",
+                               signs=None):
+    """Y = mxfp4_gemm(rotate_quantize_fused(x, B), (wq, ws)) in one launch, M <= 16 (brq_rotate_quantize_gemm_fused)."""
+    M, K, ldx = _rows(x, "x")
+    for t, n in ((wq, "wq"), (ws, "ws")):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.uint8):
+            raise ValueError("%s must be a contiguous uint8 GPU tensor" % n)
+    cb, sb = operand_bytes(N, K, w_layout)
+    if wq.numel() < cb or ws.numel() < sb:
+        raise ValueError("weight buffers do not match N, K and the layout")
+    y = torch.empty((M, N), dtype=out_dtype, device=x.device) if out is None else out
+    _, _, ldy = _rows(y, "out")
+    if y.shape[0] != M or y.shape[1] != N:
+        raise ValueError("out must be [M, N]")
+    _check(lib().brq_rotate_quantize_gemm_fused(x.data_ptr(), _dtype_code(x), M, K, ldx, B, _signs_ptr(signs, K),
+                                                wq.data_ptr(), ws.data_ptr(), _layout_code(w_layout), N, y.data_ptr(),
+                                                _dtype_code(y), ldy, _stream(stream)))
     return y
 
 

@@ -27,6 +27,7 @@ hipError_t device_cus(int* cus) {
         if (hipError_t e = setup_gemm_tiled(); e != hipSuccess) return e;
         if (hipError_t e = setup_gemm_smallm(); e != hipSuccess) return e;
         if (hipError_t e = setup_matrix_rotate(); e != hipSuccess) return e;
+        if (hipError_t e = setup_gemm_decode_fused(); e != hipSuccess) return e;
         slot.cus = v;
         slot.ready = true;
     }
@@ -277,6 +278,23 @@ brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_lay
     return launched(brq::launch_mxfp4_gemm(a, w, M, N, K, y, ydt == BRQ_BF16, ldy, static_cast<hipStream_t>(stream)));
 }
 
+brq_status brq_rotate_quantize_gemm_fused(const void* x, brq_dtype xdt, int64_t M, int64_t K, int64_t ldx, int64_t B,
+                                          const int8_t* signs, const uint8_t* wq, const uint8_t* ws, brq_layout w_layout,
+                                          int64_t N, void* y, brq_dtype ydt, int64_t ldy, void* stream) {
+    brq_status st = check_rows(x, xdt, M, K, ldx);
+    if (st != BRQ_OK) return st;
+    if (dtype_size(ydt) == 0) return BRQ_ERR_DTYPE;
+    if (!layout_ok(w_layout)) return BRQ_ERR_LAYOUT;
+    if (M > 16 || N < 0 || N >= (int64_t(1) << 31) || K % 512 != 0 || K > brq::DECODE_FUSED_MAX_K || ldy < N) return BRQ_ERR_SHAPE;
+    if (B != 32) return BRQ_ERR_BLOCK;
+    if (M > 0 && N > 0 && (!wq || !ws || !y)) return BRQ_ERR_NULL;
+    if (!aligned16(signs) || !aligned16(wq) || !aligned16(ws) || !aligned16(y)) return BRQ_ERR_ALIGN;
+    if (M == 0 || N == 0) return BRQ_OK;
+    const brq::Operand w{wq, ws, w_layout == BRQ_LAYOUT_TILED};
+    return launched(brq::launch_gemm_decode_fused(x, xdt == BRQ_BF16, M, K, ldx, signs, w, N, y, ydt == BRQ_BF16, ldy,
+                                                  static_cast<hipStream_t>(stream)));
+}
+
 brq_status brq_to_rowmajor(const uint8_t* codes_tiled, const uint8_t* scales_tiled, int64_t rows, int64_t K,
                            uint8_t* codes_out, uint8_t* scales_out, void* stream) {
     if (rows < 0 || K <= 0 || K % 32 != 0) return BRQ_ERR_SHAPE;
@@ -310,6 +328,7 @@ const char* brq_strerror(brq_status s) {
         case BRQ_ERR_LAUNCH: return "kernel launch failed";
         case BRQ_ERR_LAYOUT: return "unknown operand layout";
         case BRQ_ERR_DEVICE: return "no usable HIP device, or its one-time set-up failed";
+        case BRQ_STATUS_INT_RANGE_: break;
     }
     return "unknown status";
 }

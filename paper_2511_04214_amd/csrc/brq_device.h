@@ -107,6 +107,46 @@ __device__ __forceinline__ void wht_cross_quad(float (&v)[8], float s1, float s2
 }
 #undef BRQ_FMAC_DPP
 
+// A lane's chunk of 8 consecutive elements, read once with the streaming hint (16 bytes of bf16, 32 of fp32).
+template <bool BF16>
+__device__ __forceinline__ void load_chunk(const void* p, float (&v)[8]) {
+    if constexpr (BF16) {
+        v4i w = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
+        v[0] = bf16_lo((uint32_t)w.x); v[1] = bf16_hi((uint32_t)w.x); v[2] = bf16_lo((uint32_t)w.y); v[3] = bf16_hi((uint32_t)w.y);
+        v[4] = bf16_lo((uint32_t)w.z); v[5] = bf16_hi((uint32_t)w.z); v[6] = bf16_lo((uint32_t)w.w); v[7] = bf16_hi((uint32_t)w.w);
+    } else {
+        v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+        v4f b = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p) + 1);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+}
+
+// The random sign diagonal of a randomized Hadamard rotation, applied on load: `signs` points at the 8 sign
+// bytes of this chunk (8-byte aligned); element i is negated where its byte is negative.
+__device__ __forceinline__ void apply_signs(float (&v)[8], const int8_t* signs) {
+    const uint2 sg = *reinterpret_cast<const uint2*>(signs);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t word = (i < 4) ? sg.x : sg.y;
+        v[i] = as_f32(as_u32(v[i]) ^ ((word << (24 - 8 * (i & 3))) & 0x80000000u));
+    }
+}
+
+// Stages of the order-2^LOG2B transform for the chunk in `v`; returns the value through
+// sign-tracked cross-lane stages: afterwards v holds sigma * (x H), with sigma = -1 for
+// lanes with an odd number of set bits among the lane bits that took part.
+template <int LOG2B>
+__device__ __forceinline__ void wht_inwave(float (&v)[8], uint32_t lane) {
+    static_assert(LOG2B >= 3, "a lane holds 8 elements");
+    wht8(v);
+    if constexpr (LOG2B == 4) wht_cross<1>(v, (lane & 1) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 5) wht_cross_quad(v, (lane & 1) ? -1.0f : 1.0f, (lane & 2) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 6) wht_cross<4>(v, (lane & 4) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 7) wht_cross<8>(v, (lane & 8) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 8) wht_cross<16>(v, (lane & 16) ? -1.0f : 1.0f);
+    if constexpr (LOG2B >= 9) wht_cross<32>(v, (lane & 32) ? -1.0f : 1.0f);
+}
+
 // silu(g) * u = g / (1 + exp(-g)) * u, the gated activation that produces the input of the rotated
 // layer (Sec. 4.3: the online rotation sits in front of down_proj).  The paper fixes no arithmetic
 // for it, so the kernel takes the cheapest one that stays within a stated bound of the definition:

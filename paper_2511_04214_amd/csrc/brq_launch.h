@@ -14,6 +14,7 @@ hipError_t device_cus(int* cus);
 hipError_t setup_gemm_tiled();     // mxfp4_gemm_tiled.hip
 hipError_t setup_gemm_smallm();    // mxfp4_gemm.hip
 hipError_t setup_matrix_rotate();  // matrix_rotate_quant.hip
+hipError_t setup_gemm_decode_fused();   // mxfp4_gemm.hip
 
 // mode: 0 rotate, 1 quantize, 2 fused rotate+quantize.  log2b: 0 for quantize, else 3..14.
 // tiled: codes and scales go out in the tiled operand layout instead of row-major.
@@ -64,6 +65,13 @@ struct Operand {
 
 hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
                              bool out_bf16, int64_t ldy, hipStream_t s);
+
+// The decode-size product with the online step (B = 32 rotation + quantizer) of its activations in its own
+// prologue: x [M <= 16][ldx] bf16 or fp32, K % 512 == 0, K <= DECODE_FUSED_MAX_K (the quantized activations of
+// all of K stay in LDS).
+constexpr int64_t DECODE_FUSED_MAX_K = 16384;
+hipError_t launch_gemm_decode_fused(const void* x, bool in_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* signs,
+                                    const Operand& w, int64_t N, void* y, bool out_bf16, int64_t ldy, hipStream_t s);
 
 // Persistent LDS-staged kernel for large shapes (N a multiple of 256, any M; K a multiple of 512,
 // or any K when both operands are tiled, whose K padding is zero).

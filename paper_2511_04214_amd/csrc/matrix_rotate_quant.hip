@@ -216,7 +216,10 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
                 const uint32_t U = encode8_e2m1(lo8, sb), V = encode8_e2m1(hi8, sb);
                 const auto sw = __builtin_amdgcn_permlane32_swap(U, V, false, false);
                 const uint2 o = make_uint2((sw[0] & 0xffffu) | (sw[1] << 16), (sw[0] >> 16) | (sw[1] & 0xffff0000u));
-                *reinterpret_cast<uint2*>(ep + m * (16u * NB) + (uint32_t)bb * 16u + 8u * h) = o;   // row m, block bb, half h
+                // row m, block bb, half h.  A row of the code block is 16 NB bytes: rows 4 apart would meet in
+                // the same banks (8 of a wavefront's 32 rows per bank group), so the 16-byte piece of block bb
+                // sits in slot bb ^ (m >> 2) of its row
+                *reinterpret_cast<uint2*>(ep + m * (16u * NB) + (((uint32_t)bb ^ ((m >> 2) & (NB - 1u))) << 4) + 8u * h) = o;
             }
         }
         if constexpr (MODE == 0) {
@@ -270,7 +273,10 @@ __global__ void __launch_bounds__(256) k_matrot(Args a) {
             // 16-byte piece L of the code block is row L / NB, block L % NB: lane l takes pieces l, l + 64, ...
             v4i wv[NB / 2];
 #pragma unroll
-            for (int k = 0; k < NB / 2; ++k) wv[k] = *reinterpret_cast<const v4i*>(ep + (lane + 64u * k) * 16u);
+            for (int k = 0; k < NB / 2; ++k) {      // (the reader undoes the slot swizzle: NB lanes read one whole row)
+                const uint32_t piece = lane + 64u * k, prow = piece / NB, pb = piece % NB;
+                wv[k] = *reinterpret_cast<const v4i*>(ep + prow * (16u * NB) + ((pb ^ ((prow >> 2) & (NB - 1u))) << 4));
+            }
             if constexpr (IN_BF16) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // next tile landed, earlier stores done
             const uint32_t g0 = col0 / 32u;
 #pragma unroll

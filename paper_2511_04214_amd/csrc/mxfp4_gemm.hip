@@ -320,6 +320,129 @@ __global__ void __launch_bounds__(256) k_gemm_smallm(const uint8_t* __restrict__
             }
 }
 
+// ---- M <= 16 with the online step inside (Sec. 4.3: the rotation R_4 and the quantizer in front of the
+// quantized layer, here folded into the product's own prologue) ---------------------------------------
+// Every workgroup first rotates (B = 32) and quantizes ALL of the activations, M <= 16 rows x K, into LDS -
+// the same arithmetic as the row-wise kernels, a quad of lanes per 32-element group - in the layout the
+// weight-streaming loop reads: codes [stage][16 rows][64 bytes] with the 16-byte chunks of row i XOR-swizzled
+// by (i >> 2) & 3, scales [superstage][16 rows][16 bytes].  Then it streams its 128 weight rows exactly like
+// k_gemm_smallm with one tile, without any barrier (the activations never change), so the result is bit
+// for bit that of brq_mxfp4_gemm on the output of brq_rotate_quantize_fused.  The first superstages of
+// weights are requested before the prologue and arrive under it.  What this saves is one small launch; what
+// it costs is that every one of the N / 128 workgroups repeats the quantization of the same activations.
+constexpr int decode_fused_lds_bytes(int64_t K) { return (int)(K / 128 * 1024 + K / 512 * 256); }
+
+template <bool IN_BF16, int TAIL>
+__global__ void __launch_bounds__(256) k_gemm_decode_fused(const void* __restrict__ x, int64_t ldx, const int8_t* __restrict__ signs,
+                                                           const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
+                                                           int w_tiled, int M, int N, int K, void* __restrict__ y, int out_bf16,
+                                                           int64_t ldy) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, h = lane >> 5;
+    const int n0 = blockIdx.x * 128 + wave * 32;
+    const int nss = K / 512;
+    uint8_t* const scl = lds + (K / 128) * 1024;          // scales behind the codes
+    const RowView vw(wq, ws, w_tiled != 0, min(n0 + r, N - 1), K);
+    auto load_w = [&](int ss, v4i (&c)[8], v4i& sc) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                c[2 * t + j] = *reinterpret_cast<const v4i*>(vw.codes + (int64_t)(4 * ss + t) * vw.cstep + h * 32 + j * 16);
+        sc = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(vw.scales + (int64_t)ss * vw.sstep));
+    };
+    constexpr int SETS = SMALLM_SETS, D = SETS - 1;
+    v4i c[SETS][8], s4[SETS];
+#pragma unroll
+    for (int i = 0; i < D; ++i) load_w(min(i, nss - 1), c[i], s4[i]);
+
+    // ---- prologue: the online step on all M rows.  A wavefront takes 64 chunks (512 elements: one
+    // superstage of one row) at a time; chunk kc of a row lies in stage kc / 16, 16-byte chunk (kc % 16) / 4.
+    {
+        const uint32_t cpr = (uint32_t)K / 8u, nchunks = (uint32_t)M * cpr;
+        const float sigma = (__builtin_popcount(lane & 3) & 1) ? -1.0f : 1.0f;
+        const float cs = as_f32(0x3E3504F3u) * sigma;      // fl(1 / sqrt(32)), sign of the cross-lane stages folded in
+        // four passes' loads are issued before the first is used: a wavefront is alone on its SIMD, and nothing
+        // else would hide their latency
+        constexpr uint32_t U = 4;
+        for (uint32_t cb0 = (uint32_t)wave * 64u; cb0 < nchunks; cb0 += 256u * U) {
+            float v[U][8];
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                const uint32_t cb = min(cb0 + 256u * u, nchunks - 64u);      // past the end: the last pass again, not written
+                const uint32_t row = cb / cpr, kc = cb - row * cpr + (uint32_t)lane;
+                load_chunk<IN_BF16>((const char*)x + ((int64_t)row * ldx + (int64_t)kc * 8) * (IN_BF16 ? 2 : 4), v[u]);
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                const uint32_t cb = cb0 + 256u * u;
+                if (cb >= nchunks) break;                                     // uniform
+                const uint32_t row = cb / cpr, kc = cb - row * cpr + (uint32_t)lane;
+                if (signs) apply_signs(v[u], signs + (size_t)kc * 8);   // uniform
+                wht_inwave<5>(v[u], (uint32_t)lane);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[u][i] *= cs;
+                const uint32_t sb = e8m0_from_amax(quad_max(absmax8(v[u])));
+                const uint32_t w = encode8_e2m1(v[u], sb);
+                const uint32_t st = kc >> 4, q16 = (kc >> 2) & 3u;
+                *reinterpret_cast<uint32_t*>(lds + st * 1024u + row * 64u + ((q16 ^ ((row >> 2) & 3u)) << 4) + (kc & 3u) * 4u) = w;
+                if ((lane & 3) == 0) scl[(kc >> 6) * 256u + row * 16u + ((kc >> 2) & 15u)] = (uint8_t)sb;
+            }
+        }
+    }
+    __syncthreads();
+
+    v16f acc = {};
+    const uint32_t ra = (uint32_t)(r & 15);               // lanes 16..31 of a half repeat rows 0..15: never stored
+    const uint32_t sw = (ra >> 2) & 3u;
+    auto superstage = [&](int ss, const v4i (&cw)[8], const v4i& sc) {
+        const uint8_t* cbase = lds + (uint32_t)ss * 4096u + ra * 64u;
+        const v4i asc = *reinterpret_cast<const v4i*>(scl + (uint32_t)ss * 256u + ra * 16u);
+        v4i af[2];
+        af[0] = *reinterpret_cast<const v4i*>(cbase + (((uint32_t)(2 * h) ^ sw) << 4));
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+            const int t = st >> 1, j = st & 1;
+            if (st + 1 < 8) af[(st + 1) & 1] = *reinterpret_cast<const v4i*>(cbase + ((st + 1) >> 1) * 1024 + (((uint32_t)(2 * h + ((st + 1) & 1)) ^ sw) << 4));
+            __builtin_amdgcn_sched_barrier(0);
+            const int scb = (int)(((uint32_t)sc[t] >> (16 * h + 8 * j)) & 0xffu);
+            const int sca = (int)(((uint32_t)asc[t] >> (16 * h + 8 * j)) & 0xffu);
+            v8i a = {}, b = {};
+            b[0] = cw[st][0]; b[1] = cw[st][1]; b[2] = cw[st][2]; b[3] = cw[st][3];
+            a[0] = af[st & 1][0]; a[1] = af[st & 1][1]; a[2] = af[st & 1][2]; a[3] = af[st & 1][3];
+            acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc, 4, 4, 0, sca, 0, scb);
+        }
+    };
+    // Register sets in rotation, SETS - 1 superstages of weights in flight; the loop body is one basic block of
+    // SETS turns and every load is visible to the compiler, whose wait counts are then exact.
+    auto turn = [&](auto Kc, auto Issue, int ss) {
+        constexpr int k = decltype(Kc)::value, kn = (k + D) % SETS;
+        if constexpr (decltype(Issue)::value) load_w(min(ss + D, nss - 1), c[kn], s4[kn]);
+        __builtin_amdgcn_sched_barrier(0);
+        superstage(ss, c[k], s4[k]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using Yes = std::true_type;
+    using No = std::false_type;
+    int ss = 0;
+    for (; ss + SETS <= nss; ss += SETS) {
+        turn(IC<0>{}, Yes{}, ss);
+        turn(IC<1>{}, Yes{}, ss + 1);
+        turn(IC<2>{}, Yes{}, ss + 2);
+    }
+    if constexpr (TAIL >= 1) turn(IC<0>{}, No{}, ss);
+    if constexpr (TAIL >= 2) turn(IC<1>{}, No{}, ss + 1);
+    const int col = n0 + r;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 8 * q + 4 * h + i;
+            if (row < M && col < N) store_out(y, out_bf16, (int64_t)row * ldy + col, acc[4 * q + i]);
+        }
+}
+
 // ---- measurement aid: the block-scaled fp4 MFMA back to back from registers ------------------
 // 4 wavefronts per workgroup, one per SIMD, 16 independent 32x32 accumulators each; operands are
 // 16 bytes per lane from `operands` (W fragment from bytes [0, 1024), A fragment from [1024, 2048)),
@@ -378,6 +501,33 @@ hipError_t setup_gemm_smallm() {
             if (hipError_t e = hipFuncSetAttribute((const void*)smallm_kern[m][t], hipFuncAttributeMaxDynamicSharedMemorySize,
                                                    smallm_lds_bytes(1 + m)); e != hipSuccess) return e;
     return hipSuccess;
+}
+
+static_assert(SMALLM_SETS == 3, "k_gemm_decode_fused writes its turns out for three register sets");
+
+hipError_t setup_gemm_decode_fused() {
+    const void* kernels[6] = {(const void*)k_gemm_decode_fused<true, 0>, (const void*)k_gemm_decode_fused<true, 1>,
+                              (const void*)k_gemm_decode_fused<true, 2>, (const void*)k_gemm_decode_fused<false, 0>,
+                              (const void*)k_gemm_decode_fused<false, 1>, (const void*)k_gemm_decode_fused<false, 2>};
+    for (const void* k : kernels)
+        if (hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, decode_fused_lds_bytes(DECODE_FUSED_MAX_K));
+            e != hipSuccess) return e;
+    return hipSuccess;
+}
+
+hipError_t launch_gemm_decode_fused(const void* x, bool in_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* signs,
+                                    const Operand& w, int64_t N, void* y, bool out_bf16, int64_t ldy, hipStream_t s) {
+    int cus = 0;
+    if (hipError_t e = device_cus(&cus); e != hipSuccess) return e;
+    const int tail = (int)((K / 512) % SMALLM_SETS);
+    const dim3 grid((uint32_t)((N + 127) / 128)), block(256);
+    const int ldsb = decode_fused_lds_bytes(K);
+#define BRQ_LAUNCH_DF(BF, T) hipLaunchKernelGGL((k_gemm_decode_fused<BF, T>), grid, block, ldsb, s, x, ldx, signs, w.codes, w.scales, \
+                                                (int)w.tiled, (int)M, (int)N, (int)K, y, (int)out_bf16, ldy)
+    if (in_bf16) { if (tail == 0) BRQ_LAUNCH_DF(true, 0); else if (tail == 1) BRQ_LAUNCH_DF(true, 1); else BRQ_LAUNCH_DF(true, 2); }
+    else { if (tail == 0) BRQ_LAUNCH_DF(false, 0); else if (tail == 1) BRQ_LAUNCH_DF(false, 1); else BRQ_LAUNCH_DF(false, 2); }
+#undef BRQ_LAUNCH_DF
+    return hipGetLastError();
 }
 
 hipError_t launch_mxfp4_gemm(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,

@@ -55,15 +55,6 @@ __device__ __forceinline__ void flip(float (&v)[8], const uint32_t (&m)[8]) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] = as_f32(as_u32(v[i]) ^ m[i]);
 }
-__device__ __forceinline__ void apply_signs(float (&v)[8], const int8_t* signs) {
-    const uint2 sg = *reinterpret_cast<const uint2*>(signs);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint32_t word = (i < 4) ? sg.x : sg.y;
-        v[i] = as_f32(as_u32(v[i]) ^ ((word << (24 - 8 * (i & 3))) & 0x80000000u));
-    }
-}
-
 // Byte offsets of chunk kc (8 elements = 4 code bytes) of row `row` in the tiled layout.
 __device__ __forceinline__ uint64_t tiled_code_offset(uint32_t row, uint32_t kc, uint32_t stages) {
     return ((uint64_t)(row >> 6) * stages + (kc >> 4)) * 4096u + (row & 63u) * 64u + (kc & 15u) * 4u;
@@ -79,19 +70,6 @@ __device__ __forceinline__ uint64_t tiled_scale_offset(uint32_t row, uint32_t kc
 // displace what the caches hold (on a 16 B in / 4 B out stream this alone is worth about 10% of
 // HBM throughput).  The scale bytes are stored plainly: a cache line of scales is completed by
 // several wavefronts, and the L2 merges their pieces before the line goes to memory.
-template <bool BF16>
-__device__ __forceinline__ void load_chunk(const void* p, float (&v)[8]) {
-    if constexpr (BF16) {
-        v4i w = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
-        v[0] = bf16_lo((uint32_t)w.x); v[1] = bf16_hi((uint32_t)w.x); v[2] = bf16_lo((uint32_t)w.y); v[3] = bf16_hi((uint32_t)w.y);
-        v[4] = bf16_lo((uint32_t)w.z); v[5] = bf16_hi((uint32_t)w.z); v[6] = bf16_lo((uint32_t)w.w); v[7] = bf16_hi((uint32_t)w.w);
-    } else {
-        v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
-        v4f b = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p) + 1);
-        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-    }
-}
-
 template <bool BF16>
 __device__ __forceinline__ void store_chunk(void* p, const float (&v)[8]) {
     if constexpr (BF16) {
@@ -171,21 +149,6 @@ __device__ __forceinline__ int64_t chunk_offset(uint32_t c, uint32_t cpr, int64_
 }
 
 // ---- in-wavefront rotation, 32 <= B <= 512 ------------------------------------------
-
-// Stages of the order-2^LOG2B transform for the chunk in `v`; returns the value through
-// sign-tracked cross-lane stages: afterwards v holds sigma * (x H), with sigma = -1 for
-// lanes with an odd number of set bits among the lane bits that took part.
-template <int LOG2B>
-__device__ __forceinline__ void wht_inwave(float (&v)[8], uint32_t lane) {
-    static_assert(LOG2B >= 3, "a lane holds 8 elements");
-    wht8(v);
-    if constexpr (LOG2B == 4) wht_cross<1>(v, (lane & 1) ? -1.0f : 1.0f);
-    if constexpr (LOG2B >= 5) wht_cross_quad(v, (lane & 1) ? -1.0f : 1.0f, (lane & 2) ? -1.0f : 1.0f);
-    if constexpr (LOG2B >= 6) wht_cross<4>(v, (lane & 4) ? -1.0f : 1.0f);
-    if constexpr (LOG2B >= 7) wht_cross<8>(v, (lane & 8) ? -1.0f : 1.0f);
-    if constexpr (LOG2B >= 8) wht_cross<16>(v, (lane & 16) ? -1.0f : 1.0f);
-    if constexpr (LOG2B >= 9) wht_cross<32>(v, (lane & 32) ? -1.0f : 1.0f);
-}
 
 // fl(1/sqrt(2^LOG2B)) as fp32 bits: sqrt(2)/2 = 0x3F3504F3 scaled by a power of two.
 __host__ __device__ constexpr uint32_t norm_bits(int log2b) {

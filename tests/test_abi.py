@@ -124,6 +124,21 @@ def test_argument_errors_before_any_launch(L):
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 200, 512, q(p), 0, 200, q(p), None) == SHAPE
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 256, 544, q(p), 0, 256, q(p), None) == SHAPE
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 0, 256, 512, q(p), 0, 256, q(p), None) == SHAPE
+    # decode product with the online step inside: (x, xdt, M, K, ldx, B, signs, wq, ws, w_layout, N, y, ydt, ldy, stream)
+    assert L.brq_rotate_quantize_gemm_fused(q(p), 1, 17, 512, 512, 32, None, q(p), q(p), 0, 64, q(p), 0, 64, None) == SHAPE   # M > 16
+    assert L.brq_rotate_quantize_gemm_fused(q(p), 1, 4, 544, 544, 32, None, q(p), q(p), 0, 64, q(p), 0, 64, None) == SHAPE    # K % 512
+    assert L.brq_rotate_quantize_gemm_fused(q(p), 1, 4, 32768, 32768, 32, None, q(p), q(p), 0, 64, q(p), 0, 64, None) == SHAPE # K too large
+    assert L.brq_rotate_quantize_gemm_fused(q(p), 1, 4, 512, 512, 64, None, q(p), q(p), 0, 64, q(p), 0, 64, None) == BLOCK
+    assert L.brq_rotate_quantize_gemm_fused(q(p), 1, 4, 512, 512, 32, None, None, q(p), 0, 64, q(p), 0, 64, None) == NULL
+    assert L.brq_rotate_quantize_gemm_fused(q(p), 1, 4, 512, 512, 32, None, q(p), q(p), 3, 64, q(p), 0, 64, None) == LAYOUT
+    assert L.brq_rotate_quantize_gemm_fused(q(p), 1, 4, 512, 512, 32, None, q(p), q(p), 0, 64, q(p), 0, 32, None) == SHAPE     # ldy < N
+    assert L.brq_rotate_quantize_gemm_fused(None, 1, 0, 512, 512, 32, None, None, None, 0, 64, None, 0, 64, None) == OK
+    # the reductions of the block statistics
+    assert L.brq_block_stats_summary(None, None, None, 5, ctypes.c_float(1.0), None, 0, q(p), q(p), q(p), None) == NULL
+    assert L.brq_block_stats_summary(q(p), None, None, 5, ctypes.c_float(1.0), None, 33, q(p), q(p), q(p), None) == SHAPE
+    assert L.brq_block_stats_summary(q(p), None, None, 5, ctypes.c_float(1.0), None, 3, q(p), q(p), q(p), None) == NULL       # edges
+    assert L.brq_block_stats_summary(q(p), None, None, 5, ctypes.c_float(1.0), None, 0, q(p + 4), q(p), q(p), None) == ALIGN
+    assert L.brq_block_stats_summary(None, None, None, 0, ctypes.c_float(1.0), None, 0, None, None, None, None) == OK
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 0, 8, 64, q(p), 0, 8, None) == OK
     assert L.brq_mxfp4_gemm(q(p), q(p), 0, q(p), q(p), 0, 8, 0, 64, q(p), 0, 0, None) == OK
 
