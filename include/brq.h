@@ -227,7 +227,8 @@ brq_status brq_block_stats(const void* x, brq_dtype xdt, int64_t M, int64_t K, i
  * amax_ref (optional) the block-wise scales of the reference, normally the untransformed activations
  * (B = 1); where amax_ref is NULL the block's own scale stands in for it:
  *     class(i)   = outlier if ref[i] > outlier_threshold, else regular        (strictly greater)
- *     hist[j]   += #{ i : amax[i] exceeds exactly j of the nedges <= 32 edges }  (strictly; nedges + 1 bins)
+ *     hist[j]   += #{ i : amax[i] exceeds exactly j of the nedges <= 32 edges }  (strictly; nedges + 1 bins;
+ *                  the edges must ascend: edges[0] <= edges[1] <= ..., else BRQ_ERR_SHAPE)
  *     counts[0] += #regular, counts[1] += #outlier,
  *     counts[2] += #{ regular i : amax[i] > ref[i] }, counts[3] += the same over outlier blocks
  *     sums[0]   += sum of sqerr over regular blocks, sums[1] += over outlier blocks   (0 where sqerr is NULL)

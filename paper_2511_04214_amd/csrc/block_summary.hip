@@ -20,27 +20,29 @@ struct SummaryArgs {
     double* sums;                   // [4] or null, added to
 };
 
-// One block per lane and pass.  Histogram: a lane's bin is the number of edges its scale exceeds; for every
-// bin the wavefront counts its lanes in that bin with one comparison and the scalar unit's bit count (an LDS
-// atomic per block would have every lane of the chip queueing for the same few words).  Every lane keeps its
-// own class counts and fp64 sums; one LDS atomic per wavefront and one global atomic per workgroup and output
-// word (a workgroup has 16 wavefronts, and a launch at most one workgroup per compute unit).  The fp64 sums are added in an order that depends
-// on the schedule: they agree with a sequential sum to a few units of 2^-53 times the number of workgroups.
+// One block per lane and pass, four passes' loads in flight (a lane's loads are 4 bytes; every load is
+// unconditional - an absent array is replaced by the scales themselves - because a load behind a branch makes
+// the compiler wait for all earlier ones).  Histogram: the edges ascend, so a scale that exceeds edge e exceeds
+// every edge below it; per edge the wavefront counts its lanes above it with one comparison and the scalar
+// unit's bit count, and bin j follows as (count above edge j - 1) - (count above edge j).  Class counts the same
+// way.  The fp64 sums are added across a wavefront's lanes in a fixed butterfly, across the workgroup's
+// wavefronts in index order, and across workgroups by the hardware's fp64 atomic add (the generic atomicAdd on a
+// double is a compare-and-swap loop): the result depends on the order in which workgroups finish, to a few units
+// of 2^-53 times their number.
 __global__ void __launch_bounds__(1024) k_block_summary(SummaryArgs a) {
-    __shared__ unsigned int s_hist[33];
+    __shared__ unsigned int s_gt[33];        // [e]: blocks above edge e; [32]: all blocks of the workgroup
     __shared__ unsigned int s_cnt[4];
-    __shared__ double s_sum[4];
-    if (threadIdx.x < 33) s_hist[threadIdx.x] = 0;
-    if (threadIdx.x < 4) { s_cnt[threadIdx.x] = 0; s_sum[threadIdx.x] = 0.0; }
+    __shared__ double s_wsum[16][4];
+    if (threadIdx.x < 33) s_gt[threadIdx.x] = 0;
+    if (threadIdx.x < 4) s_cnt[threadIdx.x] = 0;
     __syncthreads();
-    unsigned int cnt[4] = {0, 0, 0, 0};
-    double sum[4] = {0.0, 0.0, 0.0, 0.0};
-    unsigned int hcnt[33];          // wavefront-uniform: blocks of this wavefront in bin j
+    const float* const refp = a.ref ? a.ref : a.amax;
+    const float* const sqp = a.sqerr ? a.sqerr : a.amax;
+    const bool has_sq = a.sqerr != nullptr, has_ref = a.ref != nullptr, lane0 = (threadIdx.x & 63u) == 0;
+    unsigned int cnt[4] = {0, 0, 0, 0}, nlive = 0, gt[32];     // wavefront-uniform, held by the scalar unit
 #pragma unroll
-    for (int j = 0; j < 33; ++j) hcnt[j] = 0;
-    // Four passes' worth of loads are issued before any of them is used (a lane's loads are 4 bytes: without
-    // this the kernel waits for memory most of the time).  Uniform trip count: lanes past the end carry a
-    // scale that falls into no bin and into no class.
+    for (int e = 0; e < 32; ++e) gt[e] = 0;
+    double sum[4] = {0.0, 0.0, 0.0, 0.0};
     constexpr int U = 4;
     const unsigned long long step = (unsigned long long)gridDim.x * 1024 * U;
     for (unsigned long long i0 = (unsigned long long)blockIdx.x * 1024 * U; i0 < a.n; i0 += step) {
@@ -50,47 +52,66 @@ __global__ void __launch_bounds__(1024) k_block_summary(SummaryArgs a) {
         for (int u = 0; u < U; ++u) {
             const unsigned long long i = i0 + (unsigned long long)u * 1024 + threadIdx.x;
             live[u] = i < a.n;
-            const unsigned long long ic = live[u] ? i : a.n - 1;
+            const unsigned long long ic = live[u] ? i : a.n - 1;       // past the end: the last block again, masked below
             am[u] = a.amax[ic];
-            rf[u] = a.ref ? a.ref[ic] : am[u];
-            sq[u] = a.sqerr ? a.sqerr[ic] : 0.0f;
+            rf[u] = refp[ic];
+            sq[u] = sqp[ic];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bool outl = rf[u] > a.outlier, grew = a.ref && am[u] > rf[u];
-            const bool l = live[u];
-            cnt[0] += (l && !outl) ? 1u : 0u;
-            cnt[1] += (l && outl) ? 1u : 0u;
-            cnt[2] += (l && !outl && grew) ? 1u : 0u;
-            cnt[3] += (l && outl && grew) ? 1u : 0u;
-            sum[0] += (l && !outl) ? (double)sq[u] : 0.0;
-            sum[1] += (l && outl) ? (double)sq[u] : 0.0;
-            sum[2] += (l && !outl) ? (double)am[u] : 0.0;
-            sum[3] += (l && outl) ? (double)am[u] : 0.0;
-            if (a.hist) {   // uniform
-                int bin = l ? 0 : -1;
-                for (int e = 0; e < a.nedges; ++e) bin += (l && am[u] > a.edges[e]) ? 1 : 0;
+            const unsigned long long lm = __builtin_amdgcn_ballot_w64(live[u]);
+            const unsigned long long mo = __builtin_amdgcn_ballot_w64(rf[u] > a.outlier) & lm;
+            const unsigned long long mr = lm & ~mo;
+            const unsigned long long mg = has_ref ? __builtin_amdgcn_ballot_w64(am[u] > rf[u]) : 0ull;
+            cnt[0] += (unsigned int)__builtin_popcountll(mr);
+            cnt[1] += (unsigned int)__builtin_popcountll(mo);
+            cnt[2] += (unsigned int)__builtin_popcountll(mr & mg);
+            cnt[3] += (unsigned int)__builtin_popcountll(mo & mg);
+            const bool isr = (mr >> (threadIdx.x & 63u)) & 1ull, iso = (mo >> (threadIdx.x & 63u)) & 1ull;
+            sum[0] += (double)((isr && has_sq) ? sq[u] : 0.0f);
+            sum[1] += (double)((iso && has_sq) ? sq[u] : 0.0f);
+            sum[2] += (double)(isr ? am[u] : 0.0f);
+            sum[3] += (double)(iso ? am[u] : 0.0f);
+            if (a.hist) {   // uniform; the edges beyond nedges are +inf, eight at a time behind a uniform test
+                nlive += (unsigned int)__builtin_popcountll(lm);
 #pragma unroll
-                for (int j = 0; j < 33; ++j)
-                    if (j <= a.nedges) hcnt[j] += (unsigned int)__builtin_popcountll(__builtin_amdgcn_ballot_w64(bin == j));
+                for (int e0 = 0; e0 < 32; e0 += 8)
+                    if (e0 < a.nedges) {
+#pragma unroll
+                        for (int e = e0; e < e0 + 8; ++e)
+                            gt[e] += (unsigned int)__builtin_popcountll(__builtin_amdgcn_ballot_w64(am[u] > a.edges[e]) & lm);
+                    }
             }
         }
     }
+    const unsigned int wave = threadIdx.x >> 6;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        if (cnt[k]) atomicAdd(&s_cnt[k], cnt[k]);
-        if (sum[k] != 0.0) atomicAdd(&s_sum[k], sum[k]);
-    }
-    if ((threadIdx.x & 63u) == 0) {
+        double v = sum[k];
 #pragma unroll
-        for (int j = 0; j < 33; ++j)
-            if (j <= a.nedges && hcnt[j]) atomicAdd(&s_hist[j], hcnt[j]);
+        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        if (lane0) {
+            s_wsum[wave][k] = v;
+            if (cnt[k]) atomicAdd(&s_cnt[k], cnt[k]);
+        }
+    }
+    if (lane0 && a.hist) {
+        atomicAdd(&s_gt[32], nlive);
+#pragma unroll
+        for (int e = 0; e < 32; ++e)
+            if (gt[e]) atomicAdd(&s_gt[e], gt[e]);
     }
     __syncthreads();
-    if (a.hist && threadIdx.x <= (unsigned)a.nedges && s_hist[threadIdx.x]) atomicAdd(&a.hist[threadIdx.x], (unsigned long long)s_hist[threadIdx.x]);
+    if (a.hist && threadIdx.x <= (unsigned)a.nedges) {
+        const unsigned int above_prev = threadIdx.x == 0 ? s_gt[32] : s_gt[threadIdx.x - 1];
+        const unsigned int above_this = threadIdx.x == (unsigned)a.nedges ? 0u : s_gt[threadIdx.x];
+        if (above_prev != above_this) atomicAdd(&a.hist[threadIdx.x], (unsigned long long)(above_prev - above_this));
+    }
     if (threadIdx.x < 4) {
         if (a.counts && s_cnt[threadIdx.x]) atomicAdd(&a.counts[threadIdx.x], (unsigned long long)s_cnt[threadIdx.x]);
-        if (a.sums && s_sum[threadIdx.x] != 0.0) atomicAdd(&a.sums[threadIdx.x], s_sum[threadIdx.x]);
+        double t = 0.0;
+        for (unsigned int w = 0; w < blockDim.x / 64u; ++w) t += s_wsum[w][threadIdx.x];
+        if (a.sums && t != 0.0) __builtin_amdgcn_global_atomic_fadd_f64(&a.sums[threadIdx.x], t);
     }
 }
 
@@ -101,7 +122,7 @@ hipError_t launch_block_summary(const float* amax, const float* sqerr, const flo
     if (hipError_t e = device_cus(&cus); e != hipSuccess) return e;
     SummaryArgs a;
     a.amax = amax; a.sqerr = sqerr; a.ref = ref; a.n = (unsigned long long)n; a.outlier = outlier; a.nedges = nedges;
-    for (int e = 0; e < 32; ++e) a.edges[e] = e < nedges ? edges[e] : 0.0f;
+    for (int e = 0; e < 32; ++e) a.edges[e] = e < nedges ? edges[e] : __builtin_inff();   // beyond nedges: exceeded by nothing
     a.hist = hist; a.counts = counts; a.sums = sums;
     // One workgroup of 16 wavefronts per compute unit at most: every workgroup ends with an atomic per output
     // word, and atomics on the same few words from thousands of workgroups would take longer than the pass

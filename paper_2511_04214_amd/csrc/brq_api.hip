@@ -194,6 +194,9 @@ brq_status brq_block_stats_summary(const float* amax, const float* sqerr, const 
     if (nblocks < 0 || nedges < 0 || nedges > 32) return BRQ_ERR_SHAPE;
     if (nblocks > 0 && !amax) return BRQ_ERR_NULL;
     if (nedges > 0 && hist && !edges) return BRQ_ERR_NULL;
+    if (hist)
+        for (int64_t e = 1; e < nedges; ++e)
+            if (!(edges[e - 1] <= edges[e])) return BRQ_ERR_SHAPE;      // edges ascend (and are not NaN)
     const uintptr_t a4 = reinterpret_cast<uintptr_t>(amax) | reinterpret_cast<uintptr_t>(sqerr) | reinterpret_cast<uintptr_t>(amax_ref);
     const uintptr_t a8 = reinterpret_cast<uintptr_t>(hist) | reinterpret_cast<uintptr_t>(counts) | reinterpret_cast<uintptr_t>(sums);
     if ((a4 & 3u) || (a8 & 7u)) return BRQ_ERR_ALIGN;

@@ -185,6 +185,9 @@ def test_summary_adds_to_its_outputs_and_takes_nothing(brq):
     with pytest.raises(brq.BrqError) as err:
         brq.block_stats_summary(amax, edges=[float(i) for i in range(33)])
     assert err.value.status == 2
+    with pytest.raises(brq.BrqError) as err:
+        brq.block_stats_summary(amax, edges=[1.0, 3.0, 2.0])       # edges must ascend
+    assert err.value.status == 2
 
 
 def test_rotation_comparison_full_size(brq, orc):
