@@ -289,6 +289,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 
     v4i w0[4], a0[MB], w1[4], a1[MB];    // step-0 / step-1 operand fragments
     int scw[2][4], sca[2][MB];           // scale registers, [stage parity][MFMA tile]
+    v4i srw[4], sra[MB];                 // a superstage's 16 scale bytes of this lane's row in each MFMA tile
     v16f acc[4][MB];                     // [W tile][A tile]
 
     auto ld_w = [&](auto Uc, auto Jc, auto Tc) -> v4i {
@@ -409,8 +410,9 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     // One stage (U = stage & 3).  Slots m0..m31 = MFMAs in (W tile a, A tile b) order, step 0
     // then step 1.  F1 = step-1 fragments of this stage, N0 = step-0 fragments of the next.
     //   m0..m7    one F1 read each (this stage landed before the previous barrier)
+    //   m8..m11   stage 3 only: the next superstage's scale rows (ld_scales)
     //   m11|m12   wait (next stage landed) + barrier (everyone is done reading this stage)
-    //   m12..m15  N0 W-fragments 0..2 (registers last used by m3, m7, m11); raw scale dwords
+    //   m12..m15  N0 W-fragments 0..2 (registers last used by m3, m7, m11)
     //   m16..m20  N0 W-fragment 3 and the A-fragments (registers free after m15)
     //   m12..m31  the loads that refill this stage's buffer with stage + 4, every other slot
     //   m26..m29  next stage's scale registers
@@ -419,6 +421,29 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     // tile out (drain_slot after every step-0 MFMA).  The order of MFMAs on different accumulators does not
     // change any sum; the read schedule above still holds in pair order (W fragments 0, 1 are last used by
     // m6, m7, fragment 2 by m14, fragment 3 and the A fragments by m12..m15).
+    // Scales.  A row's 16 scale bytes of a superstage are read ONCE, as one 16-byte access per MFMA tile
+    // (32 rows x 16 bytes: every bank once), in the last stage of the superstage before, slots 8..11 (MB = 2:
+    // 4..7), which carry no other LDS read: the buffer landed two barriers earlier, and the registers' old
+    // contents were last used when this stage's scale registers were made during the stage before.  Reading
+    // the dword of one stage at a time instead costs four accesses per tile and superstage, each of them a
+    // 4-way bank conflict (32 rows, 16 bytes apart, 4 bytes wide).  Dword NU of the row holds stage NU's four
+    // groups; lane half h takes bytes 2h, 2h + 1 of it.
+    auto ld_scales = [&](auto Uc, auto Ic) __attribute__((always_inline)) {
+        constexpr int U = decltype(Uc)::value, I = decltype(Ic)::value;
+        if constexpr (U == 3) {
+            const uint32_t nb = c_buf ^ SCALE_BUF;
+            if constexpr (MB == 4) {
+                srw[I] = *reinterpret_cast<const v4i*>(wsp + nb + I * 512);
+                sra[I] = *reinterpret_cast<const v4i*>(asp + nb + I * ASC_TILE);
+            } else {
+                srw[I] = *reinterpret_cast<const v4i*>(wsp + nb + I * 512);
+                if constexpr (I < MB) sra[I] = *reinterpret_cast<const v4i*>(asp + nb + I * ASC_TILE);
+            }
+        }
+    };
+    auto next_scale = [&](const v4i& row, auto Nc) __attribute__((always_inline)) -> int {
+        return (int)((uint32_t)row[decltype(Nc)::value] >> hshift);
+    };
     auto stage = [&](auto Uc, auto Modec) __attribute__((always_inline)) {
         constexpr int U = decltype(Uc)::value, P = U & 1, NU = (U + 1) & 3;
         constexpr int MODE = decltype(Modec)::value;
@@ -430,8 +455,6 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         int (&csa)[MB] = sca[P];
         int (&nsw)[4] = scw[P ^ 1];
         int (&nsa)[MB] = sca[P ^ 1];
-        const uint32_t nbuf = (U == 3) ? (c_buf ^ SCALE_BUF) : c_buf;   // scale buffer of the next stage
-        uint32_t rw[4], ra[MB];
         // step-0 MFMA of slot S: plain order + accumulate, or pair order + C = 0 (+ the output path's share)
 #define BRQ_STEP0(S, A, B_)                                                                                          \
         do {                                                                                                         \
@@ -460,10 +483,10 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             BRQ_STEP0(5, 1, 1); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
             BRQ_STEP0(6, 1, 2); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
             BRQ_STEP0(7, 1, 3); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
-            BRQ_STEP0(8, 2, 0); BRQ_SLOT_END();
-            BRQ_STEP0(9, 2, 1); BRQ_SLOT_END();
-            BRQ_STEP0(10, 2, 2); BRQ_SLOT_END();
-            BRQ_STEP0(11, 2, 3); BRQ_SLOT_END();
+            BRQ_STEP0(8, 2, 0); ld_scales(Uc, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(9, 2, 1); ld_scales(Uc, IC<1>{}); BRQ_SLOT_END();
+            BRQ_STEP0(10, 2, 2); ld_scales(Uc, IC<2>{}); BRQ_SLOT_END();
+            BRQ_STEP0(11, 2, 3); ld_scales(Uc, IC<3>{}); BRQ_SLOT_END();
             // The next stage's loads have landed once at most 16 vector-memory operations are outstanding:
             // the LOADS younger than them are the two stages after it, 8 code loads each (18 when one of
             // those is a stage 0 with its two scale loads).  The output path's stores share the counter and
@@ -476,14 +499,8 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             else wait_vm_and_barrier<16>();
             BRQ_STEP0(12, 3, 0); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(0); BRQ_SLOT_END();
             BRQ_STEP0(13, 3, 1); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(1); BRQ_SLOT_END();
-            BRQ_STEP0(14, 3, 2); w0[2] = ld_w(N_{}, J0{}, IC<2>{});
-    #pragma unroll
-            for (int t = 0; t < 4; ++t) rw[t] = *reinterpret_cast<const uint32_t*>(wsp + nbuf + NU * 4 + t * 512);
-            BRQ_DMA_SLOT(2); BRQ_SLOT_END();
-            BRQ_STEP0(15, 3, 3);
-    #pragma unroll
-            for (int t = 0; t < 4; ++t) ra[t] = *reinterpret_cast<const uint32_t*>(asp + nbuf + NU * 4 + t * 512);
-            BRQ_DMA_SLOT(3); BRQ_SLOT_END();
+            BRQ_STEP0(14, 3, 2); w0[2] = ld_w(N_{}, J0{}, IC<2>{}); BRQ_DMA_SLOT(2); BRQ_SLOT_END();
+            BRQ_STEP0(15, 3, 3); BRQ_DMA_SLOT(3); BRQ_SLOT_END();
 
             BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(4);
             if constexpr (MODE == 2) drain_slot(IC<NACC>{});
@@ -497,10 +514,10 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             BRQ_MFMA(acc[1][3], w1[1], a1[3], 1, csw[1], csa[3]); BRQ_DMA_SLOT(11); BRQ_SLOT_END();
             BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); BRQ_DMA_SLOT(12); BRQ_SLOT_END();
             BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); BRQ_DMA_SLOT(13); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][2], w1[2], a1[2], 1, csw[2], csa[2]); nsw[0] = (int)(rw[0] >> hshift); nsw[1] = (int)(rw[1] >> hshift); BRQ_DMA_SLOT(14); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][3], w1[2], a1[3], 1, csw[2], csa[3]); nsw[2] = (int)(rw[2] >> hshift); nsw[3] = (int)(rw[3] >> hshift); BRQ_DMA_SLOT(15); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsa[0] = (int)(ra[0] >> hshift); nsa[1] = (int)(ra[1] >> hshift); BRQ_DMA_SLOT(16); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsa[2] = (int)(ra[2] >> hshift); nsa[3] = (int)(ra[3] >> hshift); BRQ_DMA_SLOT(17); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][2], w1[2], a1[2], 1, csw[2], csa[2]); nsw[0] = next_scale(srw[0], N_{}); nsw[1] = next_scale(srw[1], N_{}); BRQ_DMA_SLOT(14); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][3], w1[2], a1[3], 1, csw[2], csa[3]); nsw[2] = next_scale(srw[2], N_{}); nsw[3] = next_scale(srw[3], N_{}); BRQ_DMA_SLOT(15); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsa[0] = next_scale(sra[0], N_{}); nsa[1] = next_scale(sra[1], N_{}); BRQ_DMA_SLOT(16); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsa[2] = next_scale(sra[2], N_{}); nsa[3] = next_scale(sra[3], N_{}); BRQ_DMA_SLOT(17); BRQ_SLOT_END();
             BRQ_MFMA(acc[3][2], w1[3], a1[2], 1, csw[3], csa[2]); BRQ_DMA_SLOT(18); BRQ_SLOT_END();
             BRQ_MFMA(acc[3][3], w1[3], a1[3], 1, csw[3], csa[3]); BRQ_DMA_SLOT(19); BRQ_SLOT_END();
         } else {
@@ -511,10 +528,10 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             BRQ_STEP0(1, 0, 1); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
             BRQ_STEP0(2, 1, 0); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
             BRQ_STEP0(3, 1, 1); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
-            BRQ_STEP0(4, 2, 0); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
-            BRQ_STEP0(5, 2, 1); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
-            BRQ_STEP0(6, 3, 0); BRQ_SLOT_END();
-            BRQ_STEP0(7, 3, 1); BRQ_SLOT_END();
+            BRQ_STEP0(4, 2, 0); w1[2] = ld_w(Uc, J1{}, IC<2>{}); ld_scales(Uc, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(5, 2, 1); w1[3] = ld_w(Uc, J1{}, IC<3>{}); ld_scales(Uc, IC<1>{}); BRQ_SLOT_END();
+            BRQ_STEP0(6, 3, 0); ld_scales(Uc, IC<2>{}); BRQ_SLOT_END();
+            BRQ_STEP0(7, 3, 1); ld_scales(Uc, IC<3>{}); BRQ_SLOT_END();
             if constexpr (MODE == 2) lds_wait_and_barrier();
             else wait_vm_and_barrier<12>();      // as above, 6 code loads per stage
             BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); dma_step(Uc, IC<0>{});
@@ -522,18 +539,12 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             BRQ_SLOT_END();
             BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); dma_step(Uc, IC<1>{}); BRQ_SLOT_END();
             BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); dma_step(Uc, IC<2>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{});
-#pragma unroll
-            for (int t = 0; t < 4; ++t) rw[t] = *reinterpret_cast<const uint32_t*>(wsp + nbuf + NU * 4 + t * 512);
-            dma_step(Uc, IC<3>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); w0[2] = ld_w(N_{}, J0{}, IC<2>{});
-#pragma unroll
-            for (int t = 0; t < MB; ++t) ra[t] = *reinterpret_cast<const uint32_t*>(asp + nbuf + NU * 4 + t * ASC_TILE);
-            dma_step(Uc, IC<4>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); dma_step(Uc, IC<3>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); w0[2] = ld_w(N_{}, J0{}, IC<2>{}); dma_step(Uc, IC<4>{}); BRQ_SLOT_END();
             BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); dma_step(Uc, IC<5>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsw[0] = (int)(rw[0] >> hshift); nsw[1] = (int)(rw[1] >> hshift); dma_step(Uc, IC<6>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsw[2] = (int)(rw[2] >> hshift); nsw[3] = (int)(rw[3] >> hshift);
-            nsa[0] = (int)(ra[0] >> hshift); nsa[1] = (int)(ra[1] >> hshift); dma_step(Uc, IC<8>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsw[0] = next_scale(srw[0], N_{}); nsw[1] = next_scale(srw[1], N_{}); dma_step(Uc, IC<6>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsw[2] = next_scale(srw[2], N_{}); nsw[3] = next_scale(srw[3], N_{});
+            nsa[0] = next_scale(sra[0], N_{}); nsa[1] = next_scale(sra[1], N_{}); dma_step(Uc, IC<8>{}); BRQ_SLOT_END();
         }
 #undef BRQ_STEP0
     };
@@ -552,9 +563,9 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     a0[0] = ld_a(IC<0>{}, IC<0>{}, IC<0>{}); a0[1] = ld_a(IC<0>{}, IC<0>{}, IC<1>{});
     if constexpr (MB == 4) { a0[2] = ld_a(IC<0>{}, IC<0>{}, IC<2>{}); a0[3] = ld_a(IC<0>{}, IC<0>{}, IC<3>{}); }
 #pragma unroll
-    for (int t = 0; t < 4; ++t) scw[0][t] = (int)(*reinterpret_cast<const uint32_t*>(wsp + t * 512) >> hshift);
+    for (int t = 0; t < 4; ++t) { srw[t] = *reinterpret_cast<const v4i*>(wsp + t * 512); scw[0][t] = (int)((uint32_t)srw[t][0] >> hshift); }
 #pragma unroll
-    for (int t = 0; t < MB; ++t) sca[0][t] = (int)(*reinterpret_cast<const uint32_t*>(asp + t * ASC_TILE) >> hshift);
+    for (int t = 0; t < MB; ++t) { sra[t] = *reinterpret_cast<const v4i*>(asp + t * ASC_TILE); sca[0][t] = (int)((uint32_t)sra[t][0] >> hshift); }
 
     // One superstage = 4 stages of MFMAs on the consumer side, and the loads of the producer's
     // superstage (the next one of the stream) on the other.
