@@ -126,10 +126,12 @@ __device__ __forceinline__ void mfma_fp4_init(v16f& acc, const v4i& wf, const v4
 }
 #define BRQ_MFMA(ACC, WF, AF, SEL, SW, SA) mfma_fp4(ACC, WF, AF, IC<SEL>{}, SW, SA)
 #define BRQ_SLOT_END() __builtin_amdgcn_sched_barrier(0)
-// Refill load S/2 of the stage goes into the even slot S, for all four wavefronts alike.
-// Staggering the wavefronts over the slots needs a branch per slot, and the taken branches cost
-// more (5% of the kernel) than the short queue of four loads at the texture-address unit does.
-#define BRQ_DMA_SLOT(S) do { if constexpr (((S) & 1) == 0) dma_step(Uc, IC<(S) / 2>{}); } while (0)
+// Refill loads are spread over the whole stage, one every fourth slot, for all four wavefronts alike: the
+// texture-address unit takes ~27 cycles per load and the workgroup's four wavefronts issue theirs in the same
+// slot, so four loads keep it busy for most of four slots.  (Staggering the wavefronts over the slots instead
+// needs a branch per slot, and the taken branches cost more - 5% of the kernel - than the short queue does.)
+#define BRQ_DMA_TAIL(I) dma_step(Uc, IC<(I)>{})
+#define BRQ_DMA_HEAD(I) do { if constexpr (MODE != 1) dma_step(IC<PU>{}, IC<(I)>{}); } while (0)
 
 // Where the measurement instantiation reports its clock; the product instantiation's is empty.
 template <bool TIMED>
@@ -445,7 +447,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         return (int)((uint32_t)row[decltype(Nc)::value] >> hshift);
     };
     auto stage = [&](auto Uc, auto Modec) __attribute__((always_inline)) {
-        constexpr int U = decltype(Uc)::value, P = U & 1, NU = (U + 1) & 3;
+        constexpr int U = decltype(Uc)::value, P = U & 1, NU = (U + 1) & 3, PU = (U + 3) & 3;
         constexpr int MODE = decltype(Modec)::value;
         static_assert(MODE == 0 || U == 0, "a tile starts with stage 0");
         using N_ = IC<NU>;
@@ -469,82 +471,91 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             // The next stage's loads are waited for HERE, before the output path issues its first store: from
             // now on stores and loads are mixed in the counter, and a count is only safe against loads.  (Its
             // younger loads are the 2 stages after it; nothing older than a tile ago is still outstanding.)
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MB == 4 ? 16 : 12) : "memory");
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MB == 4 ? 13 : 10) : "memory");
             drain_slot(IC<-1>{});
             BRQ_SLOT_END();
         }
 
         if constexpr (MB == 4) {
-            BRQ_STEP0(0, 0, 0); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(0, 0, 0); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_DMA_HEAD(7); BRQ_SLOT_END();
             BRQ_STEP0(1, 0, 1); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
             BRQ_STEP0(2, 0, 2); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
             BRQ_STEP0(3, 0, 3); a1[2] = ld_a(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
-            BRQ_STEP0(4, 1, 0); a1[3] = ld_a(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_STEP0(4, 1, 0); a1[3] = ld_a(Uc, J1{}, IC<3>{}); BRQ_DMA_HEAD(8); BRQ_SLOT_END();
             BRQ_STEP0(5, 1, 1); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
             BRQ_STEP0(6, 1, 2); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
             BRQ_STEP0(7, 1, 3); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
-            BRQ_STEP0(8, 2, 0); ld_scales(Uc, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(8, 2, 0); ld_scales(Uc, IC<0>{}); BRQ_DMA_HEAD(9);
+            if constexpr (U == 0) { producer_next(); p_buf ^= SCALE_BUF; }      // the previous superstage's loads are all issued
+            BRQ_SLOT_END();
             BRQ_STEP0(9, 2, 1); ld_scales(Uc, IC<1>{}); BRQ_SLOT_END();
             BRQ_STEP0(10, 2, 2); ld_scales(Uc, IC<2>{}); BRQ_SLOT_END();
             BRQ_STEP0(11, 2, 3); ld_scales(Uc, IC<3>{}); BRQ_SLOT_END();
             // The next stage's loads have landed once at most 16 vector-memory operations are outstanding:
-            // the LOADS younger than them are the two stages after it, 8 code loads each (18 when one of
-            // those is a stage 0 with its two scale loads).  The output path's stores share the counter and
-            // complete out of order with the loads, but loads complete in order among themselves: if a
-            // load of the next stage were still outstanding, so would be its 16 younger ones, 17 in all.
-            // The count is therefore safe whatever the stores do; stores still in flight only make the
-            // wait stricter, which is why MODE 2 has waited before its first store and only meets the
-            // others here.
+            // the LOADS younger than them are two stages' worth, 8 code loads each (this stage's buffer
+            // was refilled by slots 12..31 of the stage three back and slots 0..8 of the one after it; since
+            // then came that stage's slots 12..31, all of the stage before this one, and this stage's slots
+            // 0..8: 5 + 3 + 5 + 3, and 2 more when a stage 0 with its scale loads is among them).  The output
+            // path's stores share the counter and complete out of order with the loads, but loads complete in
+            // order among themselves: if a load of the next stage were still outstanding, so would be its 16
+            // younger ones, 17 in all.  The count is therefore safe whatever the stores do; stores still in
+            // flight only make the wait stricter, which is why MODE 2 has waited before its first store (there
+            // with this stage's own 3 loads not yet issued: 13) and only meets the others here.
             if constexpr (MODE == 2) lds_wait_and_barrier();
             else wait_vm_and_barrier<16>();
-            BRQ_STEP0(12, 3, 0); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(0); BRQ_SLOT_END();
-            BRQ_STEP0(13, 3, 1); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(1); BRQ_SLOT_END();
-            BRQ_STEP0(14, 3, 2); w0[2] = ld_w(N_{}, J0{}, IC<2>{}); BRQ_DMA_SLOT(2); BRQ_SLOT_END();
-            BRQ_STEP0(15, 3, 3); BRQ_DMA_SLOT(3); BRQ_SLOT_END();
+            // refill of this stage's buffer: the scale rows first (stage 0; the wait two stages on then covers
+            // them: 5 + 8 + 3 younger loads), a code load every fourth slot, the last three in the next stage
+            BRQ_STEP0(12, 3, 0); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_TAIL(0); BRQ_SLOT_END();
+            BRQ_STEP0(13, 3, 1); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_TAIL(1); BRQ_SLOT_END();
+            BRQ_STEP0(14, 3, 2); w0[2] = ld_w(N_{}, J0{}, IC<2>{}); BRQ_DMA_TAIL(2); BRQ_SLOT_END();
+            BRQ_STEP0(15, 3, 3); BRQ_SLOT_END();
 
-            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(4);
+            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[3] = ld_w(N_{}, J0{}, IC<3>{});
             if constexpr (MODE == 2) drain_slot(IC<NACC>{});
             BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); BRQ_DMA_SLOT(5); BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][2], w1[0], a1[2], 1, csw[0], csa[2]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); BRQ_DMA_SLOT(6); BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][3], w1[0], a1[3], 1, csw[0], csa[3]); a0[2] = ld_a(N_{}, J0{}, IC<2>{}); BRQ_DMA_SLOT(7); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[3] = ld_a(N_{}, J0{}, IC<3>{}); BRQ_DMA_SLOT(8); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); BRQ_DMA_SLOT(9); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][2], w1[1], a1[2], 1, csw[1], csa[2]); BRQ_DMA_SLOT(10); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][3], w1[1], a1[3], 1, csw[1], csa[3]); BRQ_DMA_SLOT(11); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); BRQ_DMA_SLOT(12); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); BRQ_DMA_SLOT(13); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][2], w1[2], a1[2], 1, csw[2], csa[2]); nsw[0] = next_scale(srw[0], N_{}); nsw[1] = next_scale(srw[1], N_{}); BRQ_DMA_SLOT(14); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][3], w1[2], a1[3], 1, csw[2], csa[3]); nsw[2] = next_scale(srw[2], N_{}); nsw[3] = next_scale(srw[3], N_{}); BRQ_DMA_SLOT(15); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsa[0] = next_scale(sra[0], N_{}); nsa[1] = next_scale(sra[1], N_{}); BRQ_DMA_SLOT(16); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsa[2] = next_scale(sra[2], N_{}); nsa[3] = next_scale(sra[3], N_{}); BRQ_DMA_SLOT(17); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][2], w1[3], a1[2], 1, csw[3], csa[2]); BRQ_DMA_SLOT(18); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][3], w1[3], a1[3], 1, csw[3], csa[3]); BRQ_DMA_SLOT(19); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][2], w1[0], a1[2], 1, csw[0], csa[2]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); BRQ_DMA_TAIL(3); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][3], w1[0], a1[3], 1, csw[0], csa[3]); a0[2] = ld_a(N_{}, J0{}, IC<2>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[3] = ld_a(N_{}, J0{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][2], w1[1], a1[2], 1, csw[1], csa[2]); BRQ_DMA_TAIL(4); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][3], w1[1], a1[3], 1, csw[1], csa[3]); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][2], w1[2], a1[2], 1, csw[2], csa[2]); nsw[0] = next_scale(srw[0], N_{}); nsw[1] = next_scale(srw[1], N_{}); BRQ_DMA_TAIL(5); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][3], w1[2], a1[3], 1, csw[2], csa[3]); nsw[2] = next_scale(srw[2], N_{}); nsw[3] = next_scale(srw[3], N_{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsa[0] = next_scale(sra[0], N_{}); nsa[1] = next_scale(sra[1], N_{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsa[2] = next_scale(sra[2], N_{}); nsa[3] = next_scale(sra[3], N_{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][2], w1[3], a1[2], 1, csw[3], csa[2]); BRQ_DMA_TAIL(6); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][3], w1[3], a1[3], 1, csw[3], csa[3]); BRQ_SLOT_END();
         } else {
-            // 128 x 256 tile: 16 slots.  m0..m5 F1 reads, m7|m8 wait + barrier, m8..m13 N0 reads,
-            // m8..m15 refill loads (6 code loads, and the 2 scale loads in stage 0), m13..m15 scales.
-            // Two windows of 6 code loads may stay in flight.
+            // 128 x 256 tile: 16 slots.  m0..m5 F1 reads, m4..m7 scale rows (stage 3), m7|m8 wait + barrier,
+            // m8..m13 N0 reads, m13..m15 scale registers.  Refill: 6 code loads per stage, 4 of them in
+            // m10..m15 and 2 in the next stage's m1, m5; the scale loads of stage 0 in m8, m9.  Two stages'
+            // worth of loads, 12, are younger than the stage the wait is for (10 before MODE 2's first store).
             BRQ_STEP0(0, 0, 0); w1[0] = ld_w(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
-            BRQ_STEP0(1, 0, 1); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_SLOT_END();
+            BRQ_STEP0(1, 0, 1); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_DMA_HEAD(6); BRQ_SLOT_END();
             BRQ_STEP0(2, 1, 0); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
             BRQ_STEP0(3, 1, 1); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
             BRQ_STEP0(4, 2, 0); w1[2] = ld_w(Uc, J1{}, IC<2>{}); ld_scales(Uc, IC<0>{}); BRQ_SLOT_END();
-            BRQ_STEP0(5, 2, 1); w1[3] = ld_w(Uc, J1{}, IC<3>{}); ld_scales(Uc, IC<1>{}); BRQ_SLOT_END();
+            BRQ_STEP0(5, 2, 1); w1[3] = ld_w(Uc, J1{}, IC<3>{}); ld_scales(Uc, IC<1>{}); BRQ_DMA_HEAD(8);
+            if constexpr (U == 0) { producer_next(); p_buf ^= SCALE_BUF; }
+            BRQ_SLOT_END();
             BRQ_STEP0(6, 3, 0); ld_scales(Uc, IC<2>{}); BRQ_SLOT_END();
             BRQ_STEP0(7, 3, 1); ld_scales(Uc, IC<3>{}); BRQ_SLOT_END();
             if constexpr (MODE == 2) lds_wait_and_barrier();
-            else wait_vm_and_barrier<12>();      // as above, 6 code loads per stage
-            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); dma_step(Uc, IC<0>{});
+            else wait_vm_and_barrier<12>();
+            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_TAIL(0);
             if constexpr (MODE == 2) drain_slot(IC<NACC>{});
             BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); dma_step(Uc, IC<1>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); dma_step(Uc, IC<2>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); dma_step(Uc, IC<3>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); w0[2] = ld_w(N_{}, J0{}, IC<2>{}); dma_step(Uc, IC<4>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); dma_step(Uc, IC<5>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsw[0] = next_scale(srw[0], N_{}); nsw[1] = next_scale(srw[1], N_{}); dma_step(Uc, IC<6>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); BRQ_DMA_TAIL(1); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); BRQ_DMA_TAIL(2); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); w0[2] = ld_w(N_{}, J0{}, IC<2>{}); BRQ_DMA_TAIL(3); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsw[0] = next_scale(srw[0], N_{}); nsw[1] = next_scale(srw[1], N_{}); BRQ_DMA_TAIL(4); BRQ_SLOT_END();
             BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsw[2] = next_scale(srw[2], N_{}); nsw[3] = next_scale(srw[3], N_{});
-            nsa[0] = next_scale(sra[0], N_{}); nsa[1] = next_scale(sra[1], N_{}); dma_step(Uc, IC<8>{}); BRQ_SLOT_END();
+            nsa[0] = next_scale(sra[0], N_{}); nsa[1] = next_scale(sra[1], N_{}); BRQ_DMA_TAIL(5); BRQ_SLOT_END();
         }
 #undef BRQ_STEP0
     };
@@ -555,8 +566,6 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     dma_stage(IC<1>{});
     dma_stage(IC<2>{});
     dma_stage(IC<3>{});
-    producer_next();
-    p_buf ^= SCALE_BUF;
     wait_vm_and_barrier<0>();         // superstage 0 landed: the state every later tile starts from
     w0[0] = ld_w(IC<0>{}, IC<0>{}, IC<0>{}); w0[1] = ld_w(IC<0>{}, IC<0>{}, IC<1>{});
     w0[2] = ld_w(IC<0>{}, IC<0>{}, IC<2>{}); w0[3] = ld_w(IC<0>{}, IC<0>{}, IC<3>{});
@@ -574,8 +583,6 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         stage(IC<1>{}, IC<0>{});
         stage(IC<2>{}, IC<0>{});
         stage(IC<3>{}, IC<0>{});
-        producer_next();
-        p_buf ^= SCALE_BUF;
         c_buf ^= SCALE_BUF;
     };
     // The accumulators are one read-modify-write chain from here to the end (no instruction: each tile's
@@ -617,7 +624,8 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 
 #undef BRQ_MFMA
 #undef BRQ_SLOT_END
-#undef BRQ_DMA_SLOT
+#undef BRQ_DMA_TAIL
+#undef BRQ_DMA_HEAD
 
 }  // namespace tiled
 
