@@ -33,8 +33,9 @@
 // immediate offset.
 //
 // The output leaves through a 4 KB LDS block per wavefront that turns the accumulator layout
-// (neighbouring lanes = different rows) into whole 128-byte row segments per 8 lanes.  M may be
-// ragged: the last tile row clamps its A loads and masks its stores.
+// (neighbouring lanes = different rows) into whole 128-byte row segments per 8 lanes.  M and N
+// may be ragged: the last tile row (column) clamps its A (W) loads into the operand and masks its stores, rows
+// one by one and columns by 16-byte chunk (so N is a multiple of 8 for bf16 and of 4 for fp32 output).
 //
 // LDS map (bytes): [0, 128K) 4 stages x (W rows 16K | A rows 16K); [128K, 144K) 2 scale
 // buffers x (W 4K | A 4K); [144K, 160K) 4 epilogue blocks.
@@ -163,7 +164,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 
     TileWalk tw;
     tw.tiles_m = (M + TMv - 1) / TMv;            // the last tile row may be ragged: loads clamp, stores mask
-    tw.tiles_n = N / TN;
+    tw.tiles_n = (N + TN - 1) / TN;            // ... and so may the last tile column
     {
         const int T = tw.tiles_m * tw.tiles_n, G = gridDim.x;   // G is a multiple of 8
         const int per_xcd = (T + 7) / 8, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -193,9 +194,9 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
                          : (uint32_t)(((lane >> 2) + 16 * q) * cpitch) + swz16;
     }
     const int alane = lane & (ARW - 1);       // MB = 2: lanes 32..63 of the A scale load repeat rows 0..31
-    const uint32_t vscw = w_tiled ? (uint32_t)(lane * 16) : (uint32_t)(lane * spitch);
+    uint32_t vscw = w_tiled ? (uint32_t)(lane * 16) : (uint32_t)(lane * spitch);
     uint32_t vsca = a_tiled ? (uint32_t)(alane * 16) : (uint32_t)(alane * spitch);
-    bool a_clamped = false;   // row-major A: the per-lane offsets currently hold clamped rows
+    bool a_clamped = false, w_clamped = false;   // row-major operand: the per-lane offsets currently hold clamped rows
     // byte steps: stage to stage, superstage to superstage (codes), superstage to superstage (scales)
     const int w_stage = w_tiled ? 4096 : 64, w_super = w_tiled ? 16384 : 256, w_ssuper = w_tiled ? 1024 : 16;
     const int a_stage = a_tiled ? 4096 : 64, a_super = a_tiled ? 16384 : 256, a_ssuper = a_tiled ? 1024 : 16;
@@ -212,12 +213,28 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             int tm, tn;
             tw.tile(min(p_tile, ntiles - 1), tm, tn);
             const int64_t wrow = (int64_t)tn * TN + wave * 64, arow = (int64_t)tm * TMv + wave * ARW;   // slab rows
-            const uint8_t* bw = w_tiled ? wq + (wrow >> 6) * (cpitch / 64) * 4096 : wq + wrow * cpitch;
-            p_ws = uniform_ptr(w_tiled ? ws + (wrow >> 6) * (spitch / 16) * 1024 : ws + wrow * spitch);
-            // A slab of the ragged last tile row: rows past M - 1 are never stored, but their loads
-            // must stay inside the operand.  Tiled: the buffer has whole 64-row slabs, so a slab
-            // index past the last one is clamped.  Row-major: the slab base moves back to at most
+            // Slabs of the ragged last tile row / column: rows past M - 1 (N - 1) are never stored, but
+            // their loads must stay inside the operand.  Tiled: the buffer has whole 64-row slabs, so a
+            // slab index past the last one is clamped.  Row-major: the slab base moves back to at most
             // M - 64 and every lane clamps its row to M - 1.
+            const uint8_t *bw, *bws;
+            if (w_tiled) {
+                const int64_t slab = min(wrow >> 6, (int64_t)(N + 63) / 64 - 1);
+                bw = wq + slab * (cpitch / 64) * 4096;
+                bws = ws + slab * (spitch / 16) * 1024;
+            } else {
+                const int64_t wbase = min(wrow, max((int64_t)N - 64, (int64_t)0));
+                bw = wq + wbase * cpitch;
+                bws = ws + wbase * spitch;
+                if (wrow + 64 > N || w_clamped) {         // uniform; also restores the plain offsets afterwards
+                    w_clamped = wrow + 64 > N;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        vqw[q] = (uint32_t)((min(wrow + (lane >> 2) + 16 * q, (int64_t)N - 1) - wbase) * cpitch) + swz16;
+                    vscw = (uint32_t)((min(wrow + lane, (int64_t)N - 1) - wbase) * spitch);
+                }
+            }
+            p_ws = uniform_ptr(bws);
             const uint8_t *ba, *bas;
             if (a_tiled) {
                 // (for MB = 2 a wavefront's 32 rows are one half of a 64-row slab)
@@ -327,7 +344,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     uint8_t* const ybytes = reinterpret_cast<uint8_t*>(y);
     uint8_t* const ebuf = lds + EPI_BASE + wave * 4096;
     uint8_t* ytile = ybytes;        // the finished tile's corner for this wavefront
-    int mrem = 0;                   // this lane stores rows row + 8 j < mrem
+    int mrem = 0, nrem = 0;         // this lane stores rows row + 8 j < mrem of the blocks whose first column is < nrem
     uint32_t st_off = 0, wsw = 0;
     uint8_t* ewr = ebuf;
     const uint8_t* erd = ebuf;
@@ -349,6 +366,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         wsw = (uint32_t)((re & 7) ^ he) << 4;                    // its chunk swizzle, h folded in
         erd = ebuf + (le >> 3) * 128 + (((le & 7) ^ ((le >> 3) & 7)) << 4);
         mrem = M - (tm * TMv + wm * 32 * MB) - (le >> 3);
+        nrem = N - (tn * TN + wn * 128) - (le & 7) * (16 / ES);     // N is a multiple of the 16-byte chunk's columns
     };
     auto out_pack_write = [&](auto Xc) __attribute__((always_inline)) {
         constexpr int X = decltype(Xc)::value;
@@ -393,9 +411,10 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
         // whole 128-byte lines that this kernel never reads back: with the streaming hint the output does not
         // displace the operand panels that the other XCDs are about to fetch from the memory-side cache
         typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+        const int mr = (colbytes / ES < nrem) ? mrem : 0;     // a chunk past column N - 1 is not stored
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (row + 8 * j < mrem)
+            if (row + 8 * j < mr)
                 __builtin_nontemporal_store(u4{ob[Kb][j].x, ob[Kb][j].y, ob[Kb][j].z, ob[Kb][j].w}, reinterpret_cast<u4*>(dst + 8 * j * pitch));
     };
     // What the output path does after MFMA slot S of the next tile's first stage (S = -1: before slot 0;
@@ -633,7 +652,7 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 // quantizers, so with both operands tiled any K will do.
 bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy, bool both_tiled) {
     const int64_t Kp = (K + 511) / 512 * 512;
-    return M > 0 && N > 0 && N % tiled::TN == 0 && (K == Kp || both_tiled) &&
+    return M > 0 && N > 0 && N % (out_bf16 ? 8 : 4) == 0 && (K == Kp || both_tiled) &&
            (ldy * (out_bf16 ? 2 : 4)) % 16 == 0 && ldy * (out_bf16 ? 2 : 4) < (int64_t(1) << 28) &&
            (Kp / 2) * 64 < (int64_t(1) << 31);
 }
@@ -665,7 +684,7 @@ hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int6
     cus = cus >= 8 ? (cus & ~7) : 8;     // whole rounds of the 8 XCDs
     K = (K + 511) / 512 * 512;   // padded K of tiled operands (a no-op otherwise)
     // 256 x 256 tiles unless there are too few of them to give every CU one: then 128 x 256
-    const int64_t tn = N / tiled::TN;
+    const int64_t tn = (N + tiled::TN - 1) / tiled::TN;
     const int64_t T4 = ((M + 255) / 256) * tn, T2 = ((M + 127) / 128) * tn;
     const bool half = T4 < cus && T2 > T4;
     const int T = (int)(half ? T2 : T4);

@@ -187,6 +187,38 @@ def test_gemm_full_tiles_ragged_last_row(brq, orc):
     assert (buf[M:] == -7.0).all(), "wrote below the last row"
 
 
+# N not a multiple of 256 in the persistent tiled kernel: the last tile column clamps its W loads into the
+# operand (row-major: per-lane rows; tiled: the slab index) and masks its stores by 16-byte chunk.  bf16
+# output needs N % 8 == 0 and fp32 N % 4 == 0 (else the general kernel takes the call: N = 130 below).
+@pytest.mark.parametrize("M,N,K", [(300, 264, 512), (257, 8, 1024), (200, 64, 512), (1000, 1160, 1024), (513, 520, 1536),
+                                   (300, 260, 512), (129, 130, 512), (384, 248, 2048)])
+def test_gemm_ragged_last_tile_column(brq, orc, M, N, K):
+    from paper_2511_04214_amd import inputs
+    from test_gpu_layout import to_tiled
+    aq, as_ = inputs.random_mxfp4(M, K, seed=M * 5 + N)
+    wq, ws = inputs.random_mxfp4(N, K, seed=N * 11 + K)
+    y32 = check_gemm(brq, orc, aq, as_, wq, ws, ldy=N + 24)         # also: nothing written right of column N - 1
+    at, wt = [to_dev(t) for t in to_tiled(aq, as_)], [to_dev(t) for t in to_tiled(wq, ws)]
+    for dt in (torch.float32, torch.bfloat16):
+        buf = torch.full((M + 2, N + 16), -7.0, dtype=dt, device="cuda")
+        brq.mxfp4_gemm(at[0], at[1], wt[0], wt[1], out=buf[:M, :N], a_layout="tiled", w_layout="tiled", M=M, N=N, K=K)
+        got = to_host(buf[:M, :N])
+        assert np.array_equal(got, y32 if dt == torch.float32 else bf16_rne(y32))
+        assert (buf[M:] == -7.0).all() and (buf[:, N:] == -7.0).all(), "wrote outside the M x N block"
+
+
+def test_gemm_full_tiles_ragged_row_and_column(brq, orc):
+    """4100 x 4104: 17 x 17 = 289 tiles of 256 x 256 (the full-height kernel), 4 live rows in the last tile row
+    and 8 live columns in the last tile column; rows of every tile row, all columns."""
+    from paper_2511_04214_amd import inputs
+    M, N, K = 4100, 4104, 512
+    aq, as_ = inputs.random_mxfp4(M, K, seed=48)
+    wq, ws = inputs.random_mxfp4(N, K, seed=49)
+    rng = np.random.default_rng(50)
+    rows = sorted(set([r for t in range(0, 4096, 256) for r in (t, t + 255)] + [4096, 4099] + rng.integers(0, M, 6).tolist()))
+    check_gemm(brq, orc, aq, as_, wq, ws, rows=rows, ldy=N + 8)
+
+
 # 16 < M <= 128: the weight-streaming kernel that shares the activations through LDS (1 to 4 tiles of 32
 # rows, ragged M inside the last tile, ragged N inside the last workgroup and wavefront; K of 1 to 7
 # superstages, so that the main loop runs 0, 1 and 2 times with 0, 1 and 2 superstages left over);
