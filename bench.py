@@ -278,11 +278,11 @@ def main():
                     "traffic": traffic, "traffic_source": TRAFFIC_SOURCE if traffic else None}
 
     # ---- what the chip sustains on the block-scaled MFMA alone, fed from registers with bit patterns
-    # of this workload (the first 2 KB of quantized activations): the ceiling of any product kernel
+    # of this workload (the first 8 KB of quantized activations): the ceiling of any product kernel
     ncu = torch.cuda.get_device_properties(0).multi_processor_count
     with torch.cuda.stream(stream):
         sink = torch.empty((ncu * 256,), dtype=torch.float32, device="cuda")
-        ops = codes[0].flatten()[:2048].clone()
+        ops = codes[0].flatten()[:8192].clone()
         zops = torch.zeros_like(ops)
     c_iters = 2000
     c_flops = brq.diag_mfma_ceiling(ops, c_iters, ncu, sink=sink, stream=stream)
@@ -299,8 +299,9 @@ def main():
                "zero_operands_TFLOP/s": c_flops / float(z_ms.mean()) / 1e9,
                "zero_operands_frac_mxfp4_peak": c_flops / float(z_ms.mean()) / 1e9 / MXFP4_PEAK_TFLOPS,
                "product_kernel_frac_of_this_ceiling": (gemm_flops / gm_avg) / (c_flops / float(c_ms.mean())),
-               "note": "v_mfma_scale_f32_32x32x64 fp4 back to back from registers on every CU, operand "
-                       "bit patterns from this workload's quantized activations"}
+               "note": "v_mfma_scale_f32_32x32x64 fp4 back to back from registers on every CU: the product kernel's "
+                       "4 x 4 register tile (8 operand fragments, 16 accumulators) with nothing else in the loop, "
+                       "operand bit patterns from this workload's quantized activations"}
 
     # ---- context: the same product through the vendor library as PyTorch exposes it
     # (torch._scaled_mm on float4_e2m1fn_x2 operands with e8m0 group scales = hipBLASLt), on

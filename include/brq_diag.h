@@ -16,9 +16,11 @@ extern "C" {
  * `workgroups` workgroups of 4 wavefronts each issue
  * iters x 16 block-scaled fp4 MFMAs (v_mfma_scale_f32_32x32x64, the instruction of the product
  * kernels) back to back from registers, 2 * 32*32*64 flops apiece, i.e. a launch does
- * workgroups * 4 * iters * 16 * 131072 flops.  Operand fragments are read once from
- * `operands` (2048 bytes: 16 bytes per lane for each of the two operands, e.g. the first bytes
- * of a quantized matrix, so that the arithmetic sees realistic bit patterns); `sink` receives
+ * workgroups * 4 * iters * 16 * 131072 flops.  The 16 MFMAs of an iteration are the register tile of
+ * the large-shape product: 4 row-operand fragments x 4 column-operand fragments, read once from
+ * `operands` (8192 bytes: 16 bytes per lane and fragment, the four fragments of one operand first,
+ * e.g. the first bytes of a quantized matrix, so that the arithmetic sees realistic bit patterns
+ * and consecutive instructions see different ones); `sink` receives
  * workgroups * 256 floats, of which sink[0] is the number of shader-clock cycles and sink[1] the
  * number of 100 MHz reference-clock ticks that workgroup 0's first wavefront spent in the loop
  * (10 * sink[0] / sink[1] = the clock in MHz that the chip held), the rest without meaning.

@@ -388,8 +388,8 @@ def diag_mxfp4_gemm_clock(aq, as_, wq, ws, clock, **kw):
 def diag_mfma_ceiling(operands, iters, workgroups, sink=None, stream=None):
     """Launch the MFMA-only measurement loop (brq_diag_mfma_ceiling); returns the flops it does.  After the
     launch has finished, 0.1 * sink[0] / sink[1] is the shader clock in GHz that the chip held in the loop."""
-    if not (operands.is_cuda and operands.is_contiguous() and operands.dtype == torch.uint8 and operands.numel() >= 2048):
-        raise ValueError("operands must be a contiguous uint8 GPU tensor of at least 2048 bytes")
+    if not (operands.is_cuda and operands.is_contiguous() and operands.dtype == torch.uint8 and operands.numel() >= 8192):
+        raise ValueError("operands must be a contiguous uint8 GPU tensor of at least 8192 bytes")
     if sink is None:
         sink = torch.empty((workgroups * 256,), dtype=torch.float32, device=operands.device)
     if not (sink.is_cuda and sink.is_contiguous() and sink.dtype == torch.float32 and sink.numel() >= workgroups * 256):

@@ -444,19 +444,26 @@ __global__ void __launch_bounds__(256) k_gemm_decode_fused(const void* __restric
 }
 
 // ---- measurement aid: the block-scaled fp4 MFMA back to back from registers ------------------
-// 4 wavefronts per workgroup, one per SIMD, 16 independent 32x32 accumulators each; operands are
-// 16 bytes per lane from `operands` (W fragment from bytes [0, 1024), A fragment from [1024, 2048)),
-// scale bytes 127.  What a launch of this sustains is the ceiling of any product kernel on the
-// same operand bit patterns: it includes the instruction's own issue overhead and whatever clock
-// the chip holds under that load, and nothing else.
+// 4 wavefronts per workgroup, one per SIMD, the register tile of the large-shape product kernel: 4 W
+// fragments x 4 A fragments -> 16 independent 32x32 accumulators, every MFMA on another pair of fragments
+// (so that the operand registers switch between consecutive instructions as they do in the product).  The
+// fragments are 16 bytes per lane from `operands`: W fragment t from bytes [1024 t, 1024 t + 1024), A fragment
+// t from [4096 + 1024 t, ...); scale bytes 127.  What a launch of this sustains is the ceiling of any product
+// kernel on the same operand bit patterns: it includes the instruction's own issue overhead and whatever
+// clock the chip holds under that load, and nothing else.
 __global__ void __launch_bounds__(256, 1) k_mfma_ceiling(const uint8_t* __restrict__ operands, int iters,
                                                          float* __restrict__ sink) {
     const int lane = threadIdx.x & 63;
-    const v4i w = *reinterpret_cast<const v4i*>(operands + lane * 16);
-    const v4i a = *reinterpret_cast<const v4i*>(operands + 1024 + lane * 16);
-    v8i w8 = {}, a8 = {};
-    w8[0] = w[0]; w8[1] = w[1]; w8[2] = w[2]; w8[3] = w[3];
-    a8[0] = a[0]; a8[1] = a[1]; a8[2] = a[2]; a8[3] = a[3];
+    v8i w8[4], a8[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const v4i w = *reinterpret_cast<const v4i*>(operands + t * 1024 + lane * 16);
+        const v4i a = *reinterpret_cast<const v4i*>(operands + 4096 + t * 1024 + lane * 16);
+        w8[t] = v8i{};
+        a8[t] = v8i{};
+        w8[t][0] = w[0]; w8[t][1] = w[1]; w8[t][2] = w[2]; w8[t][3] = w[3];
+        a8[t][0] = a[0]; a8[t][1] = a[1]; a8[t][2] = a[2]; a8[t][3] = a[3];
+    }
     v16f acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = v16f{};
@@ -468,7 +475,7 @@ __global__ void __launch_bounds__(256, 1) k_mfma_ceiling(const uint8_t* __restri
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(w8, a8, acc[i], 4, 4, 0, 127, 0, 127);
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(w8[i >> 2], a8[i & 3], acc[i], 4, 4, 0, 127, 0, 127);
     }
     float t = 0.0f;
 #pragma unroll

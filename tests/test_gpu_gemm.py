@@ -249,7 +249,7 @@ def test_gemm_decode_full_size(brq, orc, M):
 
 def test_measurement_loop_reports_its_clock(brq):
     # the MFMA-only loop: sink[0] shader-clock cycles, sink[1] 100 MHz ticks of workgroup 0's loop
-    ops = torch.randint(0, 256, (2048,), dtype=torch.uint8, device="cuda")
+    ops = torch.randint(0, 256, (8192,), dtype=torch.uint8, device="cuda")
     sink = torch.zeros((8 * 256,), dtype=torch.float32, device="cuda")
     flops = brq.diag_mfma_ceiling(ops, 400, 8, sink=sink)
     torch.cuda.synchronize()
