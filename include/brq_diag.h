@@ -31,8 +31,9 @@ brq_status brq_diag_mfma_ceiling(const uint8_t* operands, int64_t iters, int64_t
                                  float* sink, void* stream);
 
 /*
- * brq_mxfp4_gemm on a shape that the persistent large-shape kernel takes (M > 128, N % 256 == 0,
- * K % 512 == 0 or both operands tiled; anything else: BRQ_ERR_SHAPE), which in addition writes to
+ * brq_mxfp4_gemm on a shape that the persistent large-shape kernel takes (M > 128; N a multiple of 8 for
+ * bf16 and of 4 for fp32 output; K % 512 == 0 or both operands tiled; the output pitch a multiple of 16
+ * bytes; anything else: BRQ_ERR_SHAPE), which in addition writes to
  * `clock` (device, 6 x uint64) what the first wavefront of the kernel's first workgroup measured:
  *   [0] shader-clock cycles and [1] 100 MHz reference-clock ticks from start to end
  *       (10 * [0] / [1] is the clock in MHz that the chip held during the product),

@@ -121,7 +121,7 @@ def test_argument_errors_before_any_launch(L):
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 256, 512, q(p), 0, 256, None, None) == NULL
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 256, 512, q(p), 0, 256, q(p + 4), None) == ALIGN
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 128, 256, 512, q(p), 0, 256, q(p), None) == SHAPE
-    assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 200, 512, q(p), 0, 200, q(p), None) == SHAPE
+    assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 202, 512, q(p), 0, 208, q(p), None) == SHAPE
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 256, 544, q(p), 0, 256, q(p), None) == SHAPE
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 0, 256, 512, q(p), 0, 256, q(p), None) == SHAPE
     # decode product with the online step inside: (x, xdt, M, K, ldx, B, signs, wq, ws, w_layout, N, y, ydt, ldy, stream)
