@@ -131,8 +131,12 @@ __device__ __forceinline__ void mfma_fp4_init(v16f& acc, const v4i& wf, const v4
 // texture-address unit takes ~27 cycles per load and the workgroup's four wavefronts issue theirs in the same
 // slot, so four loads keep it busy for most of four slots.  (Staggering the wavefronts over the slots instead
 // needs a branch per slot, and the taken branches cost more - 5% of the kernel - than the short queue does.)
-#define BRQ_DMA_TAIL(I) dma_step(Uc, IC<(I)>{})
-#define BRQ_DMA_HEAD(I) do { if constexpr (MODE != 1) dma_step(IC<PU>{}, IC<(I)>{}); } while (0)
+#define BRQ_DMA_TAIL(I) do { if constexpr (!LAST) dma_step(Uc, IC<(I)>{}); } while (0)
+#define BRQ_DMA_HEAD(I) do { if constexpr (MODE != 1 && !(LAST && U != 0)) dma_step(IC<PU>{}, IC<(I)>{}); } while (0)
+// (LAST = the last superstage of the workgroup: only its first stage still has loads to issue, the tail of its own
+// last stage's; no superstage follows, so nothing is loaded, no scale row and no next fragment is read for one)
+#define BRQ_N0(X) do { if constexpr (!(LAST && U == 3)) { X; } } while (0)
+#define BRQ_LD_SCALES(I) do { if constexpr (!LAST) ld_scales(Uc, IC<(I)>{}); } while (0)
 
 // Where the measurement instantiation reports its clock; the product instantiation's is empty.
 template <bool TIMED>
@@ -206,12 +210,12 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     int p_tile = 0, p_kq = 0;                                 // producer position: tile index, superstage in tile
     uint32_t p_buf = 0;                                       // byte offset of the scale buffer the producer fills next
     const uint8_t *p_w[4] = {}, *p_a[4] = {}, *p_ws = nullptr, *p_as = nullptr;   // [stage of the superstage]
-    // Past the end of the stream (p_tile >= ntiles) the last tile is loaded again: one throw-away
-    // superstage that nobody reads keeps the number of loads in flight the same in every iteration.
+    // The stream ends with the workgroup's last superstage: while the consumer works on that one the producer
+    // issues nothing (the LAST instantiation of the stages, whose waits count the fewer loads in flight).
     auto producer_next = [&]() {   // pointers of the next superstage; once per 128 MFMAs
         if (p_kq == 0) {
             int tm, tn;
-            tw.tile(min(p_tile, ntiles - 1), tm, tn);
+            tw.tile(min(p_tile, ntiles - 1), tm, tn);      // (K = 512: past the end the last tile again)
             const int64_t wrow = (int64_t)tn * TN + wave * 64, arow = (int64_t)tm * TMv + wave * ARW;   // slab rows
             // Slabs of the ragged last tile row / column: rows past M - 1 (N - 1) are never stored, but
             // their loads must stay inside the operand.  Tiled: the buffer has whole 64-row slabs, so a
@@ -465,9 +469,12 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     auto next_scale = [&](const v4i& row, auto Nc) __attribute__((always_inline)) -> int {
         return (int)((uint32_t)row[decltype(Nc)::value] >> hshift);
     };
-    auto stage = [&](auto Uc, auto Modec) __attribute__((always_inline)) {
+    auto stage = [&](auto Uc, auto Modec, auto Lastc) __attribute__((always_inline)) {
         constexpr int U = decltype(Uc)::value, P = U & 1, NU = (U + 1) & 3, PU = (U + 3) & 3;
         constexpr int MODE = decltype(Modec)::value;
+        constexpr bool LAST = decltype(Lastc)::value != 0;
+        // loads younger than the stage a wait is for: two stages' worth, fewer once the last superstage has stopped issuing
+        constexpr int VMW = (MB == 4) ? (!LAST || U == 0 ? 16 : U == 1 ? 8 : 0) : (!LAST || U == 0 ? 12 : U == 1 ? 6 : 0);
         static_assert(MODE == 0 || U == 0, "a tile starts with stage 0");
         using N_ = IC<NU>;
         using J0 = IC<0>;
@@ -504,12 +511,12 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             BRQ_STEP0(5, 1, 1); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
             BRQ_STEP0(6, 1, 2); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_SLOT_END();
             BRQ_STEP0(7, 1, 3); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_SLOT_END();
-            BRQ_STEP0(8, 2, 0); ld_scales(Uc, IC<0>{}); BRQ_DMA_HEAD(9);
-            if constexpr (U == 0) { producer_next(); p_buf ^= SCALE_BUF; }      // the previous superstage's loads are all issued
+            BRQ_STEP0(8, 2, 0); BRQ_LD_SCALES(0); BRQ_DMA_HEAD(9);
+            if constexpr (U == 0 && !LAST) { producer_next(); p_buf ^= SCALE_BUF; }      // the previous superstage's loads are all issued
             BRQ_SLOT_END();
-            BRQ_STEP0(9, 2, 1); ld_scales(Uc, IC<1>{}); BRQ_SLOT_END();
-            BRQ_STEP0(10, 2, 2); ld_scales(Uc, IC<2>{}); BRQ_SLOT_END();
-            BRQ_STEP0(11, 2, 3); ld_scales(Uc, IC<3>{}); BRQ_SLOT_END();
+            BRQ_STEP0(9, 2, 1); BRQ_LD_SCALES(1); BRQ_SLOT_END();
+            BRQ_STEP0(10, 2, 2); BRQ_LD_SCALES(2); BRQ_SLOT_END();
+            BRQ_STEP0(11, 2, 3); BRQ_LD_SCALES(3); BRQ_SLOT_END();
             // The next stage's loads have landed once at most 16 vector-memory operations are outstanding:
             // the LOADS younger than them are two stages' worth, 8 code loads each (this stage's buffer
             // was refilled by slots 12..31 of the stage three back and slots 0..8 of the one after it; since
@@ -521,21 +528,21 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             // flight only make the wait stricter, which is why MODE 2 has waited before its first store (there
             // with this stage's own 3 loads not yet issued: 13) and only meets the others here.
             if constexpr (MODE == 2) lds_wait_and_barrier();
-            else wait_vm_and_barrier<16>();
+            else wait_vm_and_barrier<VMW>();
             // refill of this stage's buffer: the scale rows first (stage 0; the wait two stages on then covers
             // them: 5 + 8 + 3 younger loads), a code load every fourth slot, the last three in the next stage
-            BRQ_STEP0(12, 3, 0); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_TAIL(0); BRQ_SLOT_END();
-            BRQ_STEP0(13, 3, 1); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_DMA_TAIL(1); BRQ_SLOT_END();
-            BRQ_STEP0(14, 3, 2); w0[2] = ld_w(N_{}, J0{}, IC<2>{}); BRQ_DMA_TAIL(2); BRQ_SLOT_END();
+            BRQ_STEP0(12, 3, 0); BRQ_N0(w0[0] = ld_w(N_{}, J0{}, IC<0>{})); BRQ_DMA_TAIL(0); BRQ_SLOT_END();
+            BRQ_STEP0(13, 3, 1); BRQ_N0(w0[1] = ld_w(N_{}, J0{}, IC<1>{})); BRQ_DMA_TAIL(1); BRQ_SLOT_END();
+            BRQ_STEP0(14, 3, 2); BRQ_N0(w0[2] = ld_w(N_{}, J0{}, IC<2>{})); BRQ_DMA_TAIL(2); BRQ_SLOT_END();
             BRQ_STEP0(15, 3, 3); BRQ_SLOT_END();
 
-            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[3] = ld_w(N_{}, J0{}, IC<3>{});
+            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); BRQ_N0(w0[3] = ld_w(N_{}, J0{}, IC<3>{}));
             if constexpr (MODE == 2) drain_slot(IC<NACC>{});
             BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][2], w1[0], a1[2], 1, csw[0], csa[2]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); BRQ_DMA_TAIL(3); BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][3], w1[0], a1[3], 1, csw[0], csa[3]); a0[2] = ld_a(N_{}, J0{}, IC<2>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[3] = ld_a(N_{}, J0{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); BRQ_N0(a0[0] = ld_a(N_{}, J0{}, IC<0>{})); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][2], w1[0], a1[2], 1, csw[0], csa[2]); BRQ_N0(a0[1] = ld_a(N_{}, J0{}, IC<1>{})); BRQ_DMA_TAIL(3); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][3], w1[0], a1[3], 1, csw[0], csa[3]); BRQ_N0(a0[2] = ld_a(N_{}, J0{}, IC<2>{})); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); BRQ_N0(a0[3] = ld_a(N_{}, J0{}, IC<3>{})); BRQ_SLOT_END();
             BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); BRQ_SLOT_END();
             BRQ_MFMA(acc[1][2], w1[1], a1[2], 1, csw[1], csa[2]); BRQ_DMA_TAIL(4); BRQ_SLOT_END();
             BRQ_MFMA(acc[1][3], w1[1], a1[3], 1, csw[1], csa[3]); BRQ_SLOT_END();
@@ -556,22 +563,22 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
             BRQ_STEP0(1, 0, 1); a1[0] = ld_a(Uc, J1{}, IC<0>{}); BRQ_DMA_HEAD(6); BRQ_SLOT_END();
             BRQ_STEP0(2, 1, 0); a1[1] = ld_a(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
             BRQ_STEP0(3, 1, 1); w1[1] = ld_w(Uc, J1{}, IC<1>{}); BRQ_SLOT_END();
-            BRQ_STEP0(4, 2, 0); w1[2] = ld_w(Uc, J1{}, IC<2>{}); ld_scales(Uc, IC<0>{}); BRQ_SLOT_END();
-            BRQ_STEP0(5, 2, 1); w1[3] = ld_w(Uc, J1{}, IC<3>{}); ld_scales(Uc, IC<1>{}); BRQ_DMA_HEAD(8);
-            if constexpr (U == 0) { producer_next(); p_buf ^= SCALE_BUF; }
+            BRQ_STEP0(4, 2, 0); w1[2] = ld_w(Uc, J1{}, IC<2>{}); BRQ_LD_SCALES(0); BRQ_SLOT_END();
+            BRQ_STEP0(5, 2, 1); w1[3] = ld_w(Uc, J1{}, IC<3>{}); BRQ_LD_SCALES(1); BRQ_DMA_HEAD(8);
+            if constexpr (U == 0 && !LAST) { producer_next(); p_buf ^= SCALE_BUF; }
             BRQ_SLOT_END();
-            BRQ_STEP0(6, 3, 0); ld_scales(Uc, IC<2>{}); BRQ_SLOT_END();
-            BRQ_STEP0(7, 3, 1); ld_scales(Uc, IC<3>{}); BRQ_SLOT_END();
+            BRQ_STEP0(6, 3, 0); BRQ_LD_SCALES(2); BRQ_SLOT_END();
+            BRQ_STEP0(7, 3, 1); BRQ_LD_SCALES(3); BRQ_SLOT_END();
             if constexpr (MODE == 2) lds_wait_and_barrier();
-            else wait_vm_and_barrier<12>();
-            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); w0[0] = ld_w(N_{}, J0{}, IC<0>{}); BRQ_DMA_TAIL(0);
+            else wait_vm_and_barrier<VMW>();
+            BRQ_MFMA(acc[0][0], w1[0], a1[0], 1, csw[0], csa[0]); BRQ_N0(w0[0] = ld_w(N_{}, J0{}, IC<0>{})); BRQ_DMA_TAIL(0);
             if constexpr (MODE == 2) drain_slot(IC<NACC>{});
             BRQ_SLOT_END();
-            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); a0[0] = ld_a(N_{}, J0{}, IC<0>{}); BRQ_DMA_TAIL(1); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); a0[1] = ld_a(N_{}, J0{}, IC<1>{}); BRQ_DMA_TAIL(2); BRQ_SLOT_END();
-            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); w0[1] = ld_w(N_{}, J0{}, IC<1>{}); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); w0[2] = ld_w(N_{}, J0{}, IC<2>{}); BRQ_DMA_TAIL(3); BRQ_SLOT_END();
-            BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); w0[3] = ld_w(N_{}, J0{}, IC<3>{}); BRQ_SLOT_END();
+            BRQ_MFMA(acc[0][1], w1[0], a1[1], 1, csw[0], csa[1]); BRQ_N0(a0[0] = ld_a(N_{}, J0{}, IC<0>{})); BRQ_DMA_TAIL(1); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][0], w1[1], a1[0], 1, csw[1], csa[0]); BRQ_N0(a0[1] = ld_a(N_{}, J0{}, IC<1>{})); BRQ_DMA_TAIL(2); BRQ_SLOT_END();
+            BRQ_MFMA(acc[1][1], w1[1], a1[1], 1, csw[1], csa[1]); BRQ_N0(w0[1] = ld_w(N_{}, J0{}, IC<1>{})); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][0], w1[2], a1[0], 1, csw[2], csa[0]); BRQ_N0(w0[2] = ld_w(N_{}, J0{}, IC<2>{})); BRQ_DMA_TAIL(3); BRQ_SLOT_END();
+            BRQ_MFMA(acc[2][1], w1[2], a1[1], 1, csw[2], csa[1]); BRQ_N0(w0[3] = ld_w(N_{}, J0{}, IC<3>{})); BRQ_SLOT_END();
             BRQ_MFMA(acc[3][0], w1[3], a1[0], 1, csw[3], csa[0]); nsw[0] = next_scale(srw[0], N_{}); nsw[1] = next_scale(srw[1], N_{}); BRQ_DMA_TAIL(4); BRQ_SLOT_END();
             BRQ_MFMA(acc[3][1], w1[3], a1[1], 1, csw[3], csa[1]); nsw[2] = next_scale(srw[2], N_{}); nsw[3] = next_scale(srw[3], N_{});
             nsa[0] = next_scale(sra[0], N_{}); nsa[1] = next_scale(sra[1], N_{}); BRQ_DMA_TAIL(5); BRQ_SLOT_END();
@@ -585,7 +592,10 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     dma_stage(IC<1>{});
     dma_stage(IC<2>{});
     dma_stage(IC<3>{});
-    wait_vm_and_barrier<0>();         // superstage 0 landed: the state every later tile starts from
+    // Stage 0 and the scale rows have landed once only the three later stages' loads are outstanding; the stages'
+    // own waits take it from there (their counts hold from the start: the prologue's later stages stand in for the
+    // loads a running ring would have issued).
+    wait_vm_and_barrier<(MB == 4 ? 24 : 18)>();
     w0[0] = ld_w(IC<0>{}, IC<0>{}, IC<0>{}); w0[1] = ld_w(IC<0>{}, IC<0>{}, IC<1>{});
     w0[2] = ld_w(IC<0>{}, IC<0>{}, IC<2>{}); w0[3] = ld_w(IC<0>{}, IC<0>{}, IC<3>{});
     a0[0] = ld_a(IC<0>{}, IC<0>{}, IC<0>{}); a0[1] = ld_a(IC<0>{}, IC<0>{}, IC<1>{});
@@ -597,11 +607,11 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 
     // One superstage = 4 stages of MFMAs on the consumer side, and the loads of the producer's
     // superstage (the next one of the stream) on the other.
-    auto superstage = [&](auto Modec) __attribute__((always_inline)) {
-        stage(IC<0>{}, Modec);
-        stage(IC<1>{}, IC<0>{});
-        stage(IC<2>{}, IC<0>{});
-        stage(IC<3>{}, IC<0>{});
+    auto superstage = [&](auto Modec, auto Lastc) __attribute__((always_inline)) {
+        stage(IC<0>{}, Modec, Lastc);
+        stage(IC<1>{}, IC<0>{}, Lastc);
+        stage(IC<2>{}, IC<0>{}, Lastc);
+        stage(IC<3>{}, IC<0>{}, Lastc);
         c_buf ^= SCALE_BUF;
     };
     // The accumulators are one read-modify-write chain from here to the end (no instruction: each tile's
@@ -613,12 +623,20 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     if constexpr (TIMED) { t_mark = __builtin_readcyclecounter(); t_pro = t_mark - t_c0; }
     // The workgroup's first tile has no predecessor to move out; every later tile's first stage carries the
     // output of the tile before it.
-    superstage(IC<1>{});
-    for (int kq = 1; kq < KQ; ++kq) superstage(IC<0>{});
-    for (int ti = 1; ti < ntiles; ++ti) {
-        out_begin(ti - 1);
-        superstage(IC<2>{});
-        for (int kq = 1; kq < KQ; ++kq) superstage(IC<0>{});
+    // The workgroup's superstages in order: tile 0 starts in mode 1, every later tile in mode 2 (after out_begin
+    // for the tile before it), all others are plain.  The very last one is peeled off and issues no loads for a
+    // successor (LAST) - unless K is a single superstage: then it is a tile's first stage as well, runs like any
+    // other, and the loads it issues for a successor that does not exist are waited for at the end.
+    {
+        const int peel = KQ > 1 ? 1 : 0;
+        superstage(IC<1>{}, IC<0>{});
+        for (int kq = 1; kq < KQ - (ntiles == 1 ? peel : 0); ++kq) superstage(IC<0>{}, IC<0>{});
+        for (int ti = 1; ti < ntiles; ++ti) {
+            out_begin(ti - 1);
+            superstage(IC<2>{}, IC<0>{});
+            for (int kq = 1; kq < KQ - (ti == ntiles - 1 ? peel : 0); ++kq) superstage(IC<0>{}, IC<0>{});
+        }
+        if (peel) superstage(IC<0>{}, IC<1>{});
     }
     if constexpr (TIMED) { const unsigned long long t = __builtin_readcyclecounter(); t_loop += t - t_mark; t_mark = t; }
     // ---- the last tile's output, with nothing to overlap it.  Its accumulators were last written by MFMAs
@@ -628,8 +646,9 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
     out_begin(ntiles - 1);
     static_for_drain(drain_slot, IC<NACC>{});
     if constexpr (TIMED) { const unsigned long long t = __builtin_readcyclecounter(); t_epi += t - t_mark; t_mark = t; }
-    // the throw-away superstage is still in flight: let it land before the LDS is released
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // K > 512: every load into LDS landed before the last superstage's third barrier; only output stores are in
+    // flight, and those may outlive the workgroup.  K = 512: the successor's loads must land before the LDS is released.
+    if (KQ == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if constexpr (TIMED) {
         if (blockIdx.x == 0) {
             const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
@@ -645,6 +664,8 @@ __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict
 #undef BRQ_SLOT_END
 #undef BRQ_DMA_TAIL
 #undef BRQ_DMA_HEAD
+#undef BRQ_N0
+#undef BRQ_LD_SCALES
 
 }  // namespace tiled
 
