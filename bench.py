@@ -124,6 +124,35 @@ def main():
             out.append(a.elapsed_time(b) / steps)
         return np.array(out)
 
+    # The same launches replayed from a HIP graph (n launches captured once): what a serving loop that replays a
+    # captured step sees.  For kernels of a few microseconds the eager train above is bound by the host's launch
+    # rate (the Python binding, 5-10 us a call), not by the GPU; the graph figure is reported next to it.
+    def train_graph(launch, n=16, reps=3):
+        stream.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for i in range(n):
+                launch(i)
+        t0 = time.perf_counter()
+        with torch.cuda.stream(stream):
+            while True:
+                for _ in range(4):
+                    g.replay()
+                stream.synchronize()
+                if (time.perf_counter() - t0) * 1e3 >= args.train_warm_ms:
+                    break
+            out = []
+            for _ in range(reps):
+                a, b = ev(), ev()
+                a.record(stream)
+                for _ in range(4):
+                    g.replay()
+                b.record(stream)
+                stream.synchronize()
+                out.append(a.elapsed_time(b) / (4 * n))
+        del g
+        return np.array(out)
+
     def hbm_leg(kernel, ms, alg_bytes, **extra):
         t = float(np.mean(ms))
         return {"kernel": kernel, "bound": "hbm", "avg_ms": t, "min_ms": float(np.min(ms)), "alg_bytes": alg_bytes,
@@ -377,9 +406,13 @@ def main():
                                    w_layout=LAY, M=cM, N=cN, K=cK)
                 r_ms = train(c_rq, reps=3)
                 g_ms = train(c_gemm, reps=3)
+                r_gr, g_gr = float(train_graph(c_rq).mean()), float(train_graph(c_gemm).mean())
                 entry["by_rotation_block"]["global_%d" % cB if cB == cK else str(cB)] = {
-                    "rotate_quantize_fused": hbm_leg("rotate_quantize_fused", r_ms, cM * cK * (c_es + 0.53125)),
-                    "mxfp4_gemm": mfma_leg(g_ms, cM, cN, cK, c_es)}
+                    "rotate_quantize_fused": hbm_leg("rotate_quantize_fused", r_ms, cM * cK * (c_es + 0.53125),
+                                                     graph_replay_avg_ms=r_gr,
+                                                     graph_replay_frac=cM * cK * (c_es + 0.53125) / r_gr / 1e6 / HBM_PEAK_GBS),
+                    "mxfp4_gemm": mfma_leg(g_ms, cM, cN, cK, c_es, graph_replay_avg_ms=g_gr,
+                                           graph_replay_frac=2.0 * cM * cN * cK / g_gr / 1e9 / MXFP4_PEAK_TFLOPS)}
                 stream.synchronize()
                 del w_sets
             configs[name] = entry
@@ -529,7 +562,8 @@ def main():
                                w_layout=LAY, M=dM, N=dN, K=dK)
             t = float(train(dgemm, reps=3).mean())
             by = (dN + dM) * dK * 0.53125 + dM * dN * 2
-            aux3["batches"][str(dM)] = {"avg_ms": t, "achieved": by / t / 1e6, "frac": by / t / 1e6 / HBM_PEAK_GBS}
+            aux3["batches"][str(dM)] = {"avg_ms": t, "achieved": by / t / 1e6, "frac": by / t / 1e6 / HBM_PEAK_GBS,
+                                        "graph_replay_avg_ms": float(train_graph(dgemm).mean())}
             if dM <= 16:
                 # the whole online path of a decode step (Sec. 4.3): rotate + quantize the bf16 activations, then the
                 # product - as two launches, and as the one launch that carries the online step in its prologue
@@ -545,6 +579,8 @@ def main():
                     brq.rotate_quantize_gemm_fused(dxm, B, dws[i % 2][0], dws[i % 2][1], dN, out=dy, stream=stream, w_layout=LAY)
                 aux3["batches"][str(dM)]["online_step_plus_product_two_launches_ms"] = float(train(two_launches, reps=3).mean())
                 aux3["batches"][str(dM)]["online_step_inside_the_product_ms"] = float(train(one_launch, reps=3).mean())
+                aux3["batches"][str(dM)]["graph_replay_two_launches_ms"] = float(train_graph(two_launches).mean())
+                aux3["batches"][str(dM)]["graph_replay_one_launch_ms"] = float(train_graph(one_launch).mean())
         stream.synchronize()
         del dws, dx
         torch.cuda.empty_cache()
