@@ -166,13 +166,16 @@ def test_gemm_half_tiles_several_per_workgroup(brq, orc):
         check_gemm(brq, orc, aq, as_, wq, ws, rows=rows)
 
 
-def test_gemm_full_tiles_ragged_last_row(brq, orc):
+@pytest.mark.parametrize("K", [512, 1024, 1536])
+def test_gemm_full_tiles_ragged_last_row(brq, orc, K):
     """4100 x 4096: 17 x 16 = 272 tiles of 256 x 256, enough for the full-height tile kernel, whose last
     tile row has 4 live rows: clamped A loads (row-major and tiled operands take different paths there)
-    and masked stores.  Rows next to the ragged edge, of every tile row, and random ones."""
+    and masked stores.  Rows next to the ragged edge, of every tile row, and random ones.  Sixteen workgroups
+    take two tiles: with K of one, two and three superstages the second tile's first stage (which carries
+    the first tile's output) is also, precedes, or is two before the workgroup's last superstage."""
     from paper_2511_04214_amd import inputs
     from test_gpu_layout import to_tiled
-    M, N, K = 4100, 4096, 512
+    M, N = 4100, 4096
     aq, as_ = inputs.random_mxfp4(M, K, seed=45)
     wq, ws = inputs.random_mxfp4(N, K, seed=46)
     rng = np.random.default_rng(47)
