@@ -271,6 +271,27 @@ def main():
         a_c, a_s = a_operand(zc, zs, gemm_M)
         gm_clock["constant_operands_shader_clock_GHz"] = clocked(a_c, a_s, zwc, zws, "constant_operands")
         gm_clock["cycle_split_first_wavefront"] = split
+        # the same kernel without its refill loads (a measurement instantiation whose output is not the product):
+        # what the product would take if moving its operands from the L2s into LDS cost nothing
+        if out_dtype == torch.bfloat16 and ((gemm_M + 255) // 256) * (N // 256) >= 1024:
+            a_c, a_s = a_operand(codes[0], scales[0], gemm_M)
+            with torch.cuda.stream(stream):
+                y_nl = torch.empty_like(ys[0])
+
+            def gemm_no_loads(i):
+                j = i % nsets
+                a_cj, a_sj = a_operand(codes[j], scales[j], gemm_M)
+                brq.mxfp4_gemm(a_cj, a_sj, wqs[j], wss[j], out=y_nl, stream=stream, a_layout=LAY, w_layout=LAY, M=gemm_M,
+                               N=N, K=K, clock=clk, no_loads=True)
+            nl_ms = float(train(gemm_no_loads, reps=3).mean())
+            stream.synchronize()
+            c, t = clk.tolist()[:2]
+            gm_clock["without_refill_loads"] = {"avg_ms": nl_ms, "frac_mxfp4_peak": 2.0 * gemm_M * N * K / nl_ms / 1e9 / MXFP4_PEAK_TFLOPS,
+                                                "shader_clock_GHz": 0.1 * c / max(t, 1), "total_cycles": c,
+                                                "note": "measurement instantiation: every MFMA, LDS read, barrier and output store "
+                                                        "of the product, no operand loads after the first 512 of K; its output "
+                                                        "is not the product"}
+            del y_nl
     stream.synchronize()
     del zc, zs, zwc, zws
 

@@ -23,7 +23,7 @@ extern "C" {
  * and consecutive instructions see different ones); `sink` receives
  * workgroups * 256 floats, of which sink[0] is the number of shader-clock cycles and sink[1] the
  * number of 100 MHz reference-clock ticks that workgroup 0's first wavefront spent in the loop
- * (10 * sink[0] / sink[1] = the clock in MHz that the chip held), the rest without meaning.
+ * (100 * sink[0] / sink[1] = the clock in MHz that the chip held), the rest without meaning.
  * Timing a launch gives the rate the chip sustains on this
  * instruction alone, the ceiling against which a product kernel's own losses can be read.
  */
@@ -36,7 +36,7 @@ brq_status brq_diag_mfma_ceiling(const uint8_t* operands, int64_t iters, int64_t
  * bytes; anything else: BRQ_ERR_SHAPE), which in addition writes to
  * `clock` (device, 6 x uint64) what the first wavefront of the kernel's first workgroup measured:
  *   [0] shader-clock cycles and [1] 100 MHz reference-clock ticks from start to end
- *       (10 * [0] / [1] is the clock in MHz that the chip held during the product),
+ *       (100 * [0] / [1] is the clock in MHz that the chip held during the product),
  *   [2] cycles inside the K loops of its output tiles, [3] cycles inside their epilogues,
  *   [4] the number of output tiles that workgroup processed, [5] cycles of the prologue.
  * y receives the product as usual.
@@ -45,6 +45,21 @@ brq_status brq_diag_mxfp4_gemm_clock(const uint8_t* aq, const uint8_t* as, brq_l
                                      const uint8_t* wq, const uint8_t* ws, brq_layout w_layout,
                                      int64_t M, int64_t N, int64_t K, void* y, brq_dtype ydt,
                                      int64_t ldy, uint64_t* clock, void* stream);
+
+/*
+ * The large-shape product kernel WITHOUT the loads that refill its operand ring: after the first 512
+ * elements of K the kernel keeps multiplying what it already holds in LDS, with every MFMA, LDS read,
+ * barrier and output store of the product.  y does NOT receive the product (it is written, with values
+ * without meaning).  What the launch takes is what the product would take if its operands cost nothing to
+ * move from the L2 into LDS; read next to brq_mxfp4_gemm's time and the MFMA-only loop's it prices that
+ * movement on a chip whose clock follows its power.  Same arguments and `clock` read-out as
+ * brq_diag_mxfp4_gemm_clock; bf16 output and at least 1024 output tiles of 256 x 256 only (anything
+ * else: BRQ_ERR_SHAPE).
+ */
+brq_status brq_diag_mxfp4_gemm_no_loads(const uint8_t* aq, const uint8_t* as, brq_layout a_layout,
+                                        const uint8_t* wq, const uint8_t* ws, brq_layout w_layout,
+                                        int64_t M, int64_t N, int64_t K, void* y, brq_dtype ydt,
+                                        int64_t ldy, uint64_t* clock, void* stream);
 
 #ifdef __cplusplus
 }

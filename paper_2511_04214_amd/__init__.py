@@ -18,7 +18,7 @@ BRQ_F32, BRQ_BF16 = 0, 1
 LAYOUTS = {"rowmajor": 0, "tiled": 1}
 EXPORTS = ["brq_init", "brq_block_rotate", "brq_operand_bytes", "brq_mxfp4_quantize", "brq_rotate_quantize_fused",
            "brq_swiglu", "brq_swiglu_rotate_quantize_fused", "brq_matrix_rotate",
-           "brq_matrix_rotate_quantize_fused", "brq_block_stats", "brq_block_stats_summary", "brq_mxfp4_gemm", "brq_rotate_quantize_gemm_fused", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_diag_mxfp4_gemm_clock", "brq_strerror", "brq_version"]
+           "brq_matrix_rotate_quantize_fused", "brq_block_stats", "brq_block_stats_summary", "brq_mxfp4_gemm", "brq_rotate_quantize_gemm_fused", "brq_to_rowmajor", "brq_diag_mfma_ceiling", "brq_diag_mxfp4_gemm_clock", "brq_diag_mxfp4_gemm_no_loads", "brq_strerror", "brq_version"]
 
 _lib = None
 
@@ -66,6 +66,8 @@ def lib():
         L.brq_to_rowmajor.restype = i32
         L.brq_diag_mxfp4_gemm_clock.argtypes = [vp, vp, i32, vp, vp, i32, i64, i64, i64, vp, i32, i64, vp, vp]
         L.brq_diag_mxfp4_gemm_clock.restype = i32
+        L.brq_diag_mxfp4_gemm_no_loads.argtypes = L.brq_diag_mxfp4_gemm_clock.argtypes
+        L.brq_diag_mxfp4_gemm_no_loads.restype = i32
         L.brq_diag_mfma_ceiling.argtypes = [vp, i64, i64, vp, vp]
         L.brq_diag_mfma_ceiling.restype = i32
         L.brq_init.restype = i32
@@ -318,13 +320,15 @@ def to_rowmajor(codes_tiled, scales_tiled, rows, K, stream=None):
 
 
 def mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.float32, out=None, stream=None, a_layout="rowmajor",
-               w_layout="rowmajor", M=None, N=None, K=None, clock=None):
+               w_layout="rowmajor", M=None, N=None, K=None, clock=None, no_loads=False):
     """Y[M, N] = deq(aq, as) @ deq(wq, ws)^T on the block-scaled MFMA (brq_mxfp4_gemm).
 
     Row-major operands are 2-D tensors that carry their shape; a tiled operand is a flat byte
     buffer, so its rows (M or N) and K must be given.  `clock` (an int64 GPU tensor of 6 elements;
     large shapes only, brq_diag_mxfp4_gemm_clock) receives the shader-clock cycles and the 100 MHz
     ticks that the kernel's first workgroup ran for, and their split over K loops and epilogues.
+    `no_loads` (with `clock`; brq_diag_mxfp4_gemm_no_loads) runs the measurement variant without refill
+    loads instead: `out` is written with values without meaning.
     """
     for t, n in ((aq, "aq"), (as_, "as"), (wq, "wq"), (ws, "ws")):
         if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.uint8):
@@ -351,9 +355,12 @@ def mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.float32, out=None, stream=None, 
     if clock is not None:
         if not (clock.is_cuda and clock.is_contiguous() and clock.dtype == torch.int64 and clock.numel() == 6):
             raise ValueError("clock must be a contiguous int64 GPU tensor of 6 elements")
-        _check(lib().brq_diag_mxfp4_gemm_clock(aq.data_ptr(), as_.data_ptr(), la, wq.data_ptr(), ws.data_ptr(), lw, M, N, K,
-                                               y.data_ptr(), _dtype_code(y), ldy, clock.data_ptr(), _stream(stream)))
+        fn = lib().brq_diag_mxfp4_gemm_no_loads if no_loads else lib().brq_diag_mxfp4_gemm_clock
+        _check(fn(aq.data_ptr(), as_.data_ptr(), la, wq.data_ptr(), ws.data_ptr(), lw, M, N, K,
+                  y.data_ptr(), _dtype_code(y), ldy, clock.data_ptr(), _stream(stream)))
         return y
+    if no_loads:
+        raise ValueError("no_loads is a measurement variant and needs `clock`")
     _check(lib().brq_mxfp4_gemm(aq.data_ptr(), as_.data_ptr(), la, wq.data_ptr(), ws.data_ptr(), lw, M, N, K,
                                 y.data_ptr(), _dtype_code(y), ldy, _stream(stream)))
     return y
@@ -383,6 +390,12 @@ def diag_mxfp4_gemm_clock(aq, as_, wq, ws, clock, **kw):
     """mxfp4_gemm on a large shape with the clock read-out (brq_diag_mxfp4_gemm_clock): after the launch has
     finished, 0.1 * clock[0] / clock[1] is the shader clock in GHz that the chip held during the product."""
     return mxfp4_gemm(aq, as_, wq, ws, clock=clock, **kw)
+
+
+def diag_mxfp4_gemm_no_loads(aq, as_, wq, ws, clock, **kw):
+    """The large-shape product kernel without its refill loads (brq_diag_mxfp4_gemm_no_loads): a timing aid, the
+    output is NOT the product."""
+    return mxfp4_gemm(aq, as_, wq, ws, clock=clock, no_loads=True, **kw)
 
 
 def diag_mfma_ceiling(operands, iters, workgroups, sink=None, stream=None):

@@ -271,6 +271,22 @@ brq_status brq_diag_mxfp4_gemm_clock(const uint8_t* aq, const uint8_t* as, brq_l
                                            reinterpret_cast<unsigned long long*>(clock)));
 }
 
+brq_status brq_diag_mxfp4_gemm_no_loads(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
+                                        const uint8_t* ws, brq_layout w_layout, int64_t M, int64_t N, int64_t K, void* y,
+                                        brq_dtype ydt, int64_t ldy, uint64_t* clock, void* stream) {
+    brq_status st = check_gemm(aq, as, a_layout, wq, ws, w_layout, M, N, K, y, ydt, ldy);
+    if (st != BRQ_OK) return st;
+    if (!clock) return BRQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(clock) & 7u) return BRQ_ERR_ALIGN;
+    const bool both = a_layout == BRQ_LAYOUT_TILED && w_layout == BRQ_LAYOUT_TILED;
+    // bf16 output and at least 256 tiles of 256 x 256 (whatever the device: the launcher then takes that tile)
+    if (ydt != BRQ_BF16 || M <= 128 || !brq::tiled_gemm_supported(M, N, K, true, ldy, both) ||
+        ((M + 255) / 256) * ((N + 255) / 256) < 1024) return BRQ_ERR_SHAPE;
+    const brq::Operand a{aq, as, a_layout == BRQ_LAYOUT_TILED}, w{wq, ws, w_layout == BRQ_LAYOUT_TILED};
+    return launched(brq::launch_gemm_tiled(a, w, M, N, K, y, true, ldy, static_cast<hipStream_t>(stream),
+                                           reinterpret_cast<unsigned long long*>(clock), true));
+}
+
 brq_status brq_mxfp4_gemm(const uint8_t* aq, const uint8_t* as, brq_layout a_layout, const uint8_t* wq,
                           const uint8_t* ws, brq_layout w_layout, int64_t M, int64_t N, int64_t K, void* y,
                           brq_dtype ydt, int64_t ldy, void* stream) {

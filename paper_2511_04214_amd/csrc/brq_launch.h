@@ -76,9 +76,12 @@ hipError_t launch_gemm_decode_fused(const void* x, bool in_bf16, int64_t M, int6
 // Persistent LDS-staged kernel for large shapes (N a multiple of 256, any M; K a multiple of 512,
 // or any K when both operands are tiled, whose K padding is zero).
 bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_t ldy, bool both_tiled);
-// clk (optional, device): receives {shader-clock cycles, 100 MHz ticks} that workgroup 0 ran for.
+// clk (optional, device): receives the clock read-out of workgroup 0's first wavefront (brq_diag.h).
+// no_loads: the measurement variant without refill loads (needs clk, bf16 out and 256 x 256 tiles).
+// True if the launcher would take 256 x 256 tiles for this shape on the current device.
 hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
-                             bool out_bf16, int64_t ldy, hipStream_t s, unsigned long long* clk = nullptr);
+                             bool out_bf16, int64_t ldy, hipStream_t s, unsigned long long* clk = nullptr,
+                             bool no_loads = false);
 
 // Tiled -> row-major copy of a quantized operand.
 hipError_t launch_to_rowmajor(const uint8_t* codes_t, const uint8_t* scales_t, int64_t rows, int64_t K,

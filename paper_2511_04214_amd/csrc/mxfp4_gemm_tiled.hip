@@ -131,8 +131,8 @@ __device__ __forceinline__ void mfma_fp4_init(v16f& acc, const v4i& wf, const v4
 // texture-address unit takes ~27 cycles per load and the workgroup's four wavefronts issue theirs in the same
 // slot, so four loads keep it busy for most of four slots.  (Staggering the wavefronts over the slots instead
 // needs a branch per slot, and the taken branches cost more - 5% of the kernel - than the short queue does.)
-#define BRQ_DMA_TAIL(I) do { if constexpr (!LAST) dma_step(Uc, IC<(I)>{}); } while (0)
-#define BRQ_DMA_HEAD(I) do { if constexpr (MODE != 1 && !(LAST && U != 0)) dma_step(IC<PU>{}, IC<(I)>{}); } while (0)
+#define BRQ_DMA_TAIL(I) do { if constexpr (!LAST && DIAG != 2) dma_step(Uc, IC<(I)>{}); } while (0)
+#define BRQ_DMA_HEAD(I) do { if constexpr (MODE != 1 && !(LAST && U != 0) && DIAG != 2) dma_step(IC<PU>{}, IC<(I)>{}); } while (0)
 // (LAST = the last superstage of the workgroup: only its first stage still has loads to issue, the tail of its own
 // last stage's; no superstage follows, so nothing is loaded, no scale row and no next fragment is read for one)
 #define BRQ_N0(X) do { if constexpr (!(LAST && U == 3)) { X; } } while (0)
@@ -146,14 +146,17 @@ struct ClockOut<true> { unsigned long long* p; };
 
 // MB = A tiles (32 rows) per wavefront: 4 -> 256 x 256 output tile, 2 -> 128 x 256 (for shapes
 // with too few 256 x 256 tiles to fill the chip; the stage is then 16 MFMA slots long).
-// TIMED = the measurement aid of brq_diag.h: workgroup 0 also reports the shader-clock cycles and the
-// 100 MHz ticks it ran for, and how the cycles split into prologue, K loops and epilogues.  The product
-// (TIMED = false) has no such code.
-template <bool OUT_BF16, int MB, bool TIMED>
+// DIAG != 0 = the measurement aids of brq_diag.h: workgroup 0 also reports the shader-clock cycles and the
+// 100 MHz ticks it ran for, and how the cycles split into prologue, K loops and epilogues.  DIAG == 2 in
+// addition issues no refill loads in the K loops: the ring keeps the first superstage the prologue brought, every
+// MFMA, LDS read, barrier and output store runs as in the product, and the result is NOT the product - what
+// the kernel would cost if its operands moved themselves.  The product (DIAG == 0) has no such code.
+template <bool OUT_BF16, int MB, int DIAG>
 __global__ void __launch_bounds__(256, 1) k_gemm_tiled(const uint8_t* __restrict__ aq, const uint8_t* __restrict__ as,
                                                        const uint8_t* __restrict__ wq, const uint8_t* __restrict__ ws,
                                                        int M, int N, int K, void* __restrict__ y, int64_t ldy, int a_tiled, int w_tiled,
-                                                       ClockOut<TIMED> clk) {
+                                                       ClockOut<DIAG != 0> clk) {
+    constexpr bool TIMED = DIAG != 0;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -678,28 +681,29 @@ bool tiled_gemm_supported(int64_t M, int64_t N, int64_t K, bool out_bf16, int64_
            (Kp / 2) * 64 < (int64_t(1) << 31);
 }
 
-template <bool OUT_BF16, int MB, bool TIMED>
+template <bool OUT_BF16, int MB, int DIAG>
 static void launch_one(dim3 g, hipStream_t s, const Operand& a, const Operand& w, int M, int N, int K, void* y, int64_t ldy,
                        unsigned long long* clk) {
-    tiled::ClockOut<TIMED> c;
-    if constexpr (TIMED) c.p = clk;
-    hipLaunchKernelGGL((tiled::k_gemm_tiled<OUT_BF16, MB, TIMED>), g, dim3(256), tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
+    tiled::ClockOut<DIAG != 0> c;
+    if constexpr (DIAG != 0) c.p = clk;
+    hipLaunchKernelGGL((tiled::k_gemm_tiled<OUT_BF16, MB, DIAG>), g, dim3(256), tiled::LDS_BYTES, s, a.codes, a.scales, w.codes,
                        w.scales, M, N, K, y, ldy, (int)a.tiled, (int)w.tiled, c);
 }
 
 // The kernels use all 160 KB of the CU's LDS: declared once per device.
 hipError_t setup_gemm_tiled() {
-    const void* kernels[8] = {(const void*)tiled::k_gemm_tiled<true, 4, false>, (const void*)tiled::k_gemm_tiled<false, 4, false>,
-                              (const void*)tiled::k_gemm_tiled<true, 2, false>, (const void*)tiled::k_gemm_tiled<false, 2, false>,
-                              (const void*)tiled::k_gemm_tiled<true, 4, true>, (const void*)tiled::k_gemm_tiled<false, 4, true>,
-                              (const void*)tiled::k_gemm_tiled<true, 2, true>, (const void*)tiled::k_gemm_tiled<false, 2, true>};
+    const void* kernels[9] = {(const void*)tiled::k_gemm_tiled<true, 4, 0>, (const void*)tiled::k_gemm_tiled<false, 4, 0>,
+                              (const void*)tiled::k_gemm_tiled<true, 2, 0>, (const void*)tiled::k_gemm_tiled<false, 2, 0>,
+                              (const void*)tiled::k_gemm_tiled<true, 4, 1>, (const void*)tiled::k_gemm_tiled<false, 4, 1>,
+                              (const void*)tiled::k_gemm_tiled<true, 2, 1>, (const void*)tiled::k_gemm_tiled<false, 2, 1>,
+                              (const void*)tiled::k_gemm_tiled<true, 4, 2>};
     for (const void* k : kernels)
         if (hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, tiled::LDS_BYTES); e != hipSuccess) return e;
     return hipSuccess;
 }
 
 hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int64_t N, int64_t K, void* y,
-                             bool out_bf16, int64_t ldy, hipStream_t s, unsigned long long* clk) {
+                             bool out_bf16, int64_t ldy, hipStream_t s, unsigned long long* clk, bool no_loads) {
     int cus = 0;
     if (hipError_t e = device_cus(&cus); e != hipSuccess) return e;
     cus = cus >= 8 ? (cus & ~7) : 8;     // whole rounds of the 8 XCDs
@@ -712,12 +716,15 @@ hipError_t launch_gemm_tiled(const Operand& a, const Operand& w, int64_t M, int6
     const int grid = T < cus ? ((T + 7) & ~7) : cus;
     const dim3 g(grid);
     const int Mi = (int)M, Ni = (int)N, Ki = (int)K;
-    if (clk) {     // the measurement instantiation (brq_diag_mxfp4_gemm_clock)
-        if (half) out_bf16 ? launch_one<true, 2, true>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk) : launch_one<false, 2, true>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk);
-        else out_bf16 ? launch_one<true, 4, true>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk) : launch_one<false, 4, true>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk);
+    if (no_loads) {    // brq_diag_mxfp4_gemm_no_loads: one instantiation only
+        if (!clk || half || !out_bf16) return hipErrorInvalidValue;
+        launch_one<true, 4, 2>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk);
+    } else if (clk) {     // the measurement instantiation (brq_diag_mxfp4_gemm_clock)
+        if (half) out_bf16 ? launch_one<true, 2, 1>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk) : launch_one<false, 2, 1>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk);
+        else out_bf16 ? launch_one<true, 4, 1>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk) : launch_one<false, 4, 1>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk);
     } else {
-        if (half) out_bf16 ? launch_one<true, 2, false>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk) : launch_one<false, 2, false>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk);
-        else out_bf16 ? launch_one<true, 4, false>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk) : launch_one<false, 4, false>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk);
+        if (half) out_bf16 ? launch_one<true, 2, 0>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk) : launch_one<false, 2, 0>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk);
+        else out_bf16 ? launch_one<true, 4, 0>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk) : launch_one<false, 4, 0>(g, s, a, w, Mi, Ni, Ki, y, ldy, clk);
     }
     return hipGetLastError();
 }

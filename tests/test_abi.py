@@ -124,6 +124,10 @@ def test_argument_errors_before_any_launch(L):
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 202, 512, q(p), 0, 208, q(p), None) == SHAPE
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 256, 256, 544, q(p), 0, 256, q(p), None) == SHAPE
     assert L.brq_diag_mxfp4_gemm_clock(q(p), q(p), 0, q(p), q(p), 0, 0, 256, 512, q(p), 0, 256, q(p), None) == SHAPE
+    # the variant without refill loads: bf16 output (dtype code 1) and >= 1024 tiles of 256 x 256 only
+    assert L.brq_diag_mxfp4_gemm_no_loads(q(p), q(p), 0, q(p), q(p), 0, 8192, 8192, 512, q(p), 1, 8192, None, None) == NULL
+    assert L.brq_diag_mxfp4_gemm_no_loads(q(p), q(p), 0, q(p), q(p), 0, 8192, 8192, 512, q(p), 0, 8192, q(p), None) == SHAPE
+    assert L.brq_diag_mxfp4_gemm_no_loads(q(p), q(p), 0, q(p), q(p), 0, 4096, 4096, 512, q(p), 1, 4096, q(p), None) == SHAPE
     # decode product with the online step inside: (x, xdt, M, K, ldx, B, signs, wq, ws, w_layout, N, y, ydt, ldy, stream)
     assert L.brq_rotate_quantize_gemm_fused(q(p), 1, 17, 512, 512, 32, None, q(p), q(p), 0, 64, q(p), 0, 64, None) == SHAPE   # M > 16
     assert L.brq_rotate_quantize_gemm_fused(q(p), 1, 4, 544, 544, 32, None, q(p), q(p), 0, 64, q(p), 0, 64, None) == SHAPE    # K % 512

@@ -281,3 +281,31 @@ def test_product_reports_its_clock(brq):
     with pytest.raises(brq.BrqError) as e:                # a shape that another kernel takes
         brq.mxfp4_gemm(ops[0][:64], ops[1][:64], ops[2], ops[3], clock=clk)
     assert e.value.status == 2
+
+
+def test_no_loads_variant_runs_and_leaves_the_product_alone(brq):
+    """The measurement instantiation without refill loads: accepted only for bf16 output and >= 1024 tiles of
+    256 x 256, reports a clock, runs in fewer cycles than the product, and a product launch after it is unchanged."""
+    from paper_2511_04214_amd import inputs
+    M, N, K = 8192, 8192, 1024
+    aq, as_ = [to_dev(t) for t in inputs.random_mxfp4(M, K, seed=91)]
+    wq, ws = [to_dev(t) for t in inputs.random_mxfp4(N, K, seed=92)]
+    y0 = brq.mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.bfloat16)
+    clk = torch.zeros(6, dtype=torch.int64, device="cuda")
+    brq.diag_mxfp4_gemm_clock(aq, as_, wq, ws, clk, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    full = clk.tolist()
+    scratch = torch.empty_like(y0)
+    brq.diag_mxfp4_gemm_no_loads(aq, as_, wq, ws, clk, out=scratch)
+    torch.cuda.synchronize()
+    nl = clk.tolist()
+    assert nl[4] == full[4] == 4 and 0 < nl[0] and 500 < 100.0 * nl[0] / nl[1] < 3000      # 4 tiles each; a plausible clock in MHz
+    assert nl[2] < full[2] * 1.05, (nl, full)
+    y1 = brq.mxfp4_gemm(aq, as_, wq, ws, out_dtype=torch.bfloat16)
+    assert torch.equal(y0, y1)
+    with pytest.raises(brq.BrqError) as err:
+        brq.diag_mxfp4_gemm_no_loads(aq, as_, wq, ws, clk, out_dtype=torch.float32)         # fp32 output
+    assert err.value.status == 2
+    with pytest.raises(brq.BrqError) as err:
+        brq.diag_mxfp4_gemm_no_loads(aq[:4096], as_[:4096], wq[:4096], ws[:4096], clk, out_dtype=torch.bfloat16)   # 256 tiles
+    assert err.value.status == 2
